@@ -1,0 +1,242 @@
+/*
+ * sushi.h — C ABI of the SubGraph-Stationary (SGS) SubNet inference library for AMD MI355X (gfx950).
+ *
+ * The library serves a stream of SubNet queries drawn from one weight-shared SuperNet
+ * (arXiv 2306.17266, "SUSHI").  The three calls of the paper's problem statement (Section 3.1:
+ * the accelerator receives the selected SubNet, the next SubGraph to cache and the query data,
+ * returns the result and enacts the caching decision) are
+ *
+ *     sushi_load_supernet        once      pack the SuperNet's weights on the device
+ *     sushi_set_subgraph_cache   every Q   make a SubGraph's weights resident
+ *     sushi_infer                per query run one SubNet, logits out
+ *
+ * plus the host-side scheduler of Algorithm 1 (sushi_sched_*) and counters (sushi_get_stats).
+ *
+ * Conventions
+ *   - Plain C types only.  Every pointer is marked HOST or DEVICE below.
+ *   - The library copies what it needs from HOST pointers before returning and never frees or
+ *     keeps a caller's pointer.  DEVICE input/output buffers stay caller-owned and must stay
+ *     alive until the stream has executed the enqueued work.
+ *   - Every function returns a sushi_status (0 = ok, negative = error); on error nothing has
+ *     been enqueued and sushi_last_error() gives a message.  Nothing aborts or throws.
+ *   - A context is bound to one device and one HIP stream; calls on one context must not
+ *     overlap in time.
+ */
+#ifndef SUSHI_H
+#define SUSHI_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SUSHI_MAX_STAGES 8
+#define SUSHI_MAX_CHOICES 4
+#define SUSHI_MAX_BLOCKS 32
+
+typedef struct sushi_ctx sushi_ctx; /* opaque */
+
+typedef enum {
+    SUSHI_OK = 0,
+    SUSHI_EINVAL = -1,  /* bad argument / SubNet choice not offered by the SuperNet */
+    SUSHI_ENOMEM = -2,  /* host or device allocation failed                          */
+    SUSHI_ESTATE = -3,  /* call out of order (e.g. infer before load)                */
+    SUSHI_EBUDGET = -4, /* SubGraph larger than the stated cache budget              */
+    SUSHI_EDEVICE = -5  /* a HIP call failed                                         */
+} sushi_status;
+
+typedef enum { SUSHI_FP32 = 0, SUSHI_BF16 = 1 } sushi_dtype;
+typedef enum { SUSHI_FAMILY_TINY = 0, SUSHI_FAMILY_RESNET = 1, SUSHI_FAMILY_MBV3 = 2 } sushi_family;
+typedef enum { SUSHI_ACT_NONE = 0, SUSHI_ACT_RELU = 1, SUSHI_ACT_HSWISH = 2 } sushi_act;
+typedef enum { SUSHI_STRICT_ACCURACY = 0, SUSHI_STRICT_LATENCY = 1 } sushi_policy;
+
+/* Kinds of SuperNet tensors in the weight blob (see sushi_describe_supernet). */
+typedef enum {
+    SUSHI_T_CONV = 0,     /* [K][C][R][R] dense convolution                      */
+    SUSHI_T_DWCONV = 1,   /* [K][1][R][R] depthwise convolution                  */
+    SUSHI_T_FC = 2,       /* [K][C] fully connected                              */
+    SUSHI_T_BIAS = 3,     /* [K]                                                 */
+    SUSHI_T_SCALE = 4,    /* [K] per-channel scale (batch norm folded to a pair) */
+    SUSHI_T_SHIFT = 5,    /* [K] per-channel shift                               */
+    SUSHI_T_SCALE_RES = 6 /* [K] scale that ends a residual branch               */
+} sushi_tensor_kind;
+
+/*
+ * A weight-shared SuperNet (Section 2.1: stages of repeated blocks; elastic depth, width /
+ * expand ratio and kernel size).  Three families:
+ *   TINY    n_stages conv3x3+ReLU layers (one per "stage"), global average, FC.  Elastic width per
+ *           layer, elastic depth = number of leading layers.
+ *   RESNET  three 3x3 stem convs (first stride 2), 3x3/2 max-pool, n_stages stages of bottleneck
+ *           blocks (1x1, 3x3 with the stage stride in its first block, 1x1, shortcut; the first
+ *           block of a stage has a 1x1 projection shortcut), global average, FC.  Width multiplier
+ *           per stage and for the stem, expand ratio per block.
+ *   MBV3    3x3/2 stem (h-swish), one depthwise-separable block, n_stages stages of inverted
+ *           residual blocks (1x1 expand, k x k depthwise, optional squeeze-excite, 1x1 project,
+ *           skip when stride 1 and equal widths), 1x1 head conv, global average, two FCs.
+ *           Expand ratio and kernel size per block.
+ * Channel counts follow ch(x) = max(8, floor(x/8 + 0.5) * 8), plus 8 if that is below 0.9 x.
+ */
+typedef struct sushi_arch {
+    int32_t family;
+    int32_t n_classes;
+    int32_t in_channels;
+    int32_t n_stages;
+    int32_t stage_base_out[SUSHI_MAX_STAGES]; /* channels at width multiplier 1 */
+    int32_t stage_stride[SUSHI_MAX_STAGES];
+    int32_t stage_max_depth[SUSHI_MAX_STAGES]; /* TINY: 1 each */
+    int32_t stage_act[SUSHI_MAX_STAGES];       /* sushi_act of the stage's blocks (MBV3) */
+    int32_t stage_se[SUSHI_MAX_STAGES];        /* squeeze-excite in the stage's blocks (MBV3) */
+    int32_t n_depth_drop, depth_drop_choices[SUSHI_MAX_CHOICES]; /* a stage may run max_depth - d blocks */
+    int32_t n_width;
+    double width_choices[SUSHI_MAX_CHOICES];
+    int32_t n_expand;
+    double expand_choices[SUSHI_MAX_CHOICES];
+    int32_t n_kernel, kernel_choices[SUSHI_MAX_CHOICES]; /* odd sizes; the largest is the stored one */
+    int32_t n_res, res_choices[SUSHI_MAX_CHOICES];
+    int32_t stem_mid, stem_out; /* RESNET: both; MBV3: stem_out */
+    int32_t head_mid, head_feat; /* MBV3 */
+} sushi_arch;
+
+/*
+ * One SubNet: which elastic choice is taken where.  Block slots are numbered stage by stage at
+ * maximum depth (slot = sum of max depths of earlier stages + block index).
+ *   depth[s]        active blocks of stage s (TINY: depth[0] = active layers); the FIRST depth[s]
+ *                   blocks run ("top k blocks per stage", Section 2.1)
+ *   width_idx[0]    stem, width_idx[1+s] stage s (TINY: layer s): index into width_choices
+ *   expand_idx[b]   index into expand_choices for block slot b
+ *   kernel_idx[b]   index into kernel_choices for block slot b (MBV3)
+ */
+typedef struct sushi_subnet_cfg {
+    int32_t resolution;
+    int32_t depth[SUSHI_MAX_STAGES];
+    int32_t width_idx[SUSHI_MAX_STAGES + 1];
+    int32_t expand_idx[SUSHI_MAX_BLOCKS];
+    int32_t kernel_idx[SUSHI_MAX_BLOCKS];
+} sushi_subnet_cfg;
+
+typedef struct sushi_tensor_desc {
+    char name[32];
+    int32_t kind; /* sushi_tensor_kind */
+    int32_t ndim;
+    int32_t shape[4];
+} sushi_tensor_desc;
+
+/* Active slice of one weight-bearing layer: K leading filters, C leading input channels
+ * (1 for depthwise), centred r x r taps (1 for FC).  K = 0: layer not used. */
+typedef struct sushi_layer_dims {
+    int32_t K, C, r;
+} sushi_layer_dims;
+
+/* A cacheable SubGraph (footnote 1 of the paper: any connected subset of weights; here, as in
+ * the scheduler's encoding of Section 3.3, one prefix box (K, C, r) per SuperNet layer, in the
+ * order sushi_subnet_layers reports).  Its size is sum K*C*r*r*sizeof(weight). */
+typedef struct sushi_subgraph_cfg {
+    int32_t n_layers;
+    const sushi_layer_dims *layers; /* HOST */
+} sushi_subgraph_cfg;
+
+/* Inputs of the scheduler (Algorithm 1).  All arrays HOST, copied.
+ *   subnet_vecs   [n_subnets][vec_len]   vectors [K_1,C_1,...,K_N,C_N] of the serving SubNets
+ *   accuracy      [n_subnets]
+ *   subgraph_vecs [n_subgraphs][vec_len] vectors of the candidate SubGraphs (the set S)
+ *   table         [n_subnets][n_subgraphs+1] latency of SubNet i with SubGraph j cached; the last
+ *                 column is "nothing cached"
+ *   initial_cache index into the candidates, or -1 for an empty cache state */
+typedef struct sushi_sched_desc {
+    int32_t n_subnets, n_subgraphs, vec_len;
+    const int32_t *subnet_vecs;
+    const float *accuracy;
+    const int32_t *subgraph_vecs;
+    const float *table;
+    int32_t Q;
+    int32_t policy; /* sushi_policy */
+    int32_t initial_cache;
+} sushi_sched_desc;
+
+typedef struct sushi_stats {
+    uint64_t queries;                /* sushi_infer calls that enqueued work                          */
+    uint64_t weight_bytes_total;     /* sum over queries of the SubNet's weight bytes                 */
+    uint64_t weight_bytes_resident;  /* of those, bytes inside the cached SubGraph (not re-fetched)   */
+    uint64_t last_weight_bytes;      /* the same two figures for the last query                       */
+    uint64_t last_resident_bytes;
+    uint64_t cache_installs;         /* sushi_set_subgraph_cache calls that installed a SubGraph      */
+    uint64_t cache_bytes_installed;  /* bytes moved by them                                           */
+    uint64_t cache_bytes;            /* size of the SubGraph cached now                               */
+    double last_hit_ratio;           /* ||SN ∩ G||_2 / ||SN||_2 on the [K,C] vectors (Appendix A.4)   */
+    double sum_hit_ratio;            /* summed over queries                                           */
+    uint64_t plan_cache_hits, plan_cache_misses;
+} sushi_stats;
+
+/* ---------------------------------------------------------------- host-only helpers (no GPU needed) */
+
+/* Lists the SuperNet's tensors in the order the weight blob must hold them (each tensor contiguous,
+ * float32, row-major over its shape).  Writes min(n, cap) entries to out (HOST, may be NULL when
+ * cap = 0) and the full count to *n_out.  SUSHI_EINVAL for an inconsistent arch. */
+int sushi_describe_supernet(const sushi_arch *arch, sushi_tensor_desc *out, int cap, int *n_out);
+
+/* For every weight-bearing SuperNet layer, in blob order, the slice (K, C, r) that SubNet cfg uses
+ * (Section 2.1); skipped layers report K = 0.  The scheduler's vector of Section 3.3 is
+ * [K_1, C_1, ..., K_N, C_N] of this list.  SUSHI_EINVAL if cfg is not a SubNet of arch. */
+int sushi_subnet_layers(const sushi_arch *arch, const sushi_subnet_cfg *cfg, sushi_layer_dims *out, int cap,
+                        int *n_out);
+
+/* ---------------------------------------------------------------- context */
+
+/* device_id: HIP device ordinal, or -1 for a host-only context (scheduler calls only; load and
+ * infer return SUSHI_ESTATE).  hip_stream: a hipStream_t created by the caller (e.g. PyTorch's
+ * current stream), borrowed for the life of the context; NULL = the default stream. */
+int sushi_create(sushi_ctx **out, int device_id, void *hip_stream);
+void sushi_destroy(sushi_ctx *ctx);
+/* Library-owned string, valid until the next call on ctx (ctx = NULL: last error of create). */
+const char *sushi_last_error(const sushi_ctx *ctx);
+
+/* ---------------------------------------------------------------- the SGS data path */
+
+/* weights: HOST float32 blob in sushi_describe_supernet order, nbytes = its exact size.
+ * compute_dtype: SUSHI_FP32 keeps float32 weights and activations (fp32 FMA); SUSHI_BF16 stores
+ * weights and activations as bf16 (values rounded to nearest even), multiplies on the bf16 matrix
+ * cores, accumulates and applies scale/shift in float32.  Packs the tensors so that every SubNet
+ * slice is a prefix per (tap, 8-channel group) and copies them to the device.  Synchronous. */
+int sushi_load_supernet(sushi_ctx *ctx, const sushi_arch *arch, const void *weights, size_t nbytes,
+                        int compute_dtype);
+
+/* Makes SubGraph g the cached one ("enacts the caching decision", Section 3.1).  g = NULL or
+ * g->n_layers = 0 empties the cache (SGS off).  g->n_layers must equal the SuperNet's layer
+ * count, every box must lie inside its layer, and the SubGraph's bytes must not exceed
+ * budget_bytes (SUSHI_EBUDGET).  Ordered before later sushi_infer calls. */
+int sushi_set_subgraph_cache(sushi_ctx *ctx, const sushi_subgraph_cfg *g, size_t budget_bytes);
+
+/* Runs SubNet cfg on one batch.
+ *   input_dev   DEVICE, [batch][resolution][resolution][in_channels], float32 (SUSHI_FP32) or
+ *               bf16 (SUSHI_BF16)
+ *   logits_dev  DEVICE, float32 [batch][n_classes]
+ * Enqueues on the context's stream and returns; results are bit-identical whatever SubGraph is
+ * cached.  SUSHI_EINVAL (nothing enqueued) if cfg is not a SubNet of the loaded SuperNet. */
+int sushi_infer(sushi_ctx *ctx, const sushi_subnet_cfg *cfg, const void *input_dev, int batch, void *logits_dev);
+
+/* ---------------------------------------------------------------- scheduler (Algorithm 1, Section 3.3) */
+
+int sushi_sched_init(sushi_ctx *ctx, const sushi_sched_desc *desc);
+/* One query (A_t, L_t): *subnet_idx_out = SubNet to serve under the current cache state;
+ * *new_cache_idx_out = candidate to cache next if this is a Q-th query, else -1.  The caller
+ * enacts it with sushi_set_subgraph_cache; the scheduler's own cache state changes here. */
+int sushi_sched_step(sushi_ctx *ctx, float acc_target, float lat_target, int *subnet_idx_out, int *new_cache_idx_out);
+/* For streams that name the SubNet themselves: accounts vector vec (HOST, vec_len ints) as the
+ * served SubNet and makes the every-Q cache choice only. */
+int sushi_sched_record(sushi_ctx *ctx, const int32_t *vec, int *new_cache_idx_out);
+
+/* ---------------------------------------------------------------- counters and options */
+
+int sushi_get_stats(sushi_ctx *ctx, sushi_stats *out);
+
+typedef enum {
+    SUSHI_OPT_EXEC_MODE = 0 /* 0 = one launch per layer (default), 1 = replay a HIP graph per SubNet */
+} sushi_option;
+int sushi_set_option(sushi_ctx *ctx, int option, int64_t value);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SUSHI_H */

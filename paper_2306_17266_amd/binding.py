@@ -1,0 +1,248 @@
+"""ctypes binding of libsushi.so (include/sushi.h).  Argument marshalling only: every step of the
+SubNet forward pass runs in the HIP library.  PyTorch supplies device memory and the stream."""
+import ctypes as C
+import os
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libsushi.so")
+
+MAX_STAGES, MAX_CHOICES, MAX_BLOCKS = 8, 4, 32
+FP32, BF16 = 0, 1
+STRICT_ACCURACY, STRICT_LATENCY = 0, 1
+OPT_EXEC_MODE = 0
+
+
+class SushiError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__("sushi error %d: %s" % (code, msg))
+        self.code = code
+
+
+class CArch(C.Structure):
+    _fields_ = [("family", C.c_int32), ("n_classes", C.c_int32), ("in_channels", C.c_int32),
+                ("n_stages", C.c_int32),
+                ("stage_base_out", C.c_int32 * MAX_STAGES), ("stage_stride", C.c_int32 * MAX_STAGES),
+                ("stage_max_depth", C.c_int32 * MAX_STAGES), ("stage_act", C.c_int32 * MAX_STAGES),
+                ("stage_se", C.c_int32 * MAX_STAGES),
+                ("n_depth_drop", C.c_int32), ("depth_drop_choices", C.c_int32 * MAX_CHOICES),
+                ("n_width", C.c_int32), ("width_choices", C.c_double * MAX_CHOICES),
+                ("n_expand", C.c_int32), ("expand_choices", C.c_double * MAX_CHOICES),
+                ("n_kernel", C.c_int32), ("kernel_choices", C.c_int32 * MAX_CHOICES),
+                ("n_res", C.c_int32), ("res_choices", C.c_int32 * MAX_CHOICES),
+                ("stem_mid", C.c_int32), ("stem_out", C.c_int32),
+                ("head_mid", C.c_int32), ("head_feat", C.c_int32)]
+
+
+class CSubnetCfg(C.Structure):
+    _fields_ = [("resolution", C.c_int32), ("depth", C.c_int32 * MAX_STAGES),
+                ("width_idx", C.c_int32 * (MAX_STAGES + 1)),
+                ("expand_idx", C.c_int32 * MAX_BLOCKS), ("kernel_idx", C.c_int32 * MAX_BLOCKS)]
+
+
+class CTensorDesc(C.Structure):
+    _fields_ = [("name", C.c_char * 32), ("kind", C.c_int32), ("ndim", C.c_int32), ("shape", C.c_int32 * 4)]
+
+
+class CLayerDims(C.Structure):
+    _fields_ = [("K", C.c_int32), ("C", C.c_int32), ("r", C.c_int32)]
+
+
+class CSubgraphCfg(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("layers", C.POINTER(CLayerDims))]
+
+
+class CSchedDesc(C.Structure):
+    _fields_ = [("n_subnets", C.c_int32), ("n_subgraphs", C.c_int32), ("vec_len", C.c_int32),
+                ("subnet_vecs", C.POINTER(C.c_int32)), ("accuracy", C.POINTER(C.c_float)),
+                ("subgraph_vecs", C.POINTER(C.c_int32)), ("table", C.POINTER(C.c_float)),
+                ("Q", C.c_int32), ("policy", C.c_int32), ("initial_cache", C.c_int32)]
+
+
+class CStats(C.Structure):
+    _fields_ = [("queries", C.c_uint64), ("weight_bytes_total", C.c_uint64), ("weight_bytes_resident", C.c_uint64),
+                ("last_weight_bytes", C.c_uint64), ("last_resident_bytes", C.c_uint64),
+                ("cache_installs", C.c_uint64), ("cache_bytes_installed", C.c_uint64), ("cache_bytes", C.c_uint64),
+                ("last_hit_ratio", C.c_double), ("sum_hit_ratio", C.c_double),
+                ("plan_cache_hits", C.c_uint64), ("plan_cache_misses", C.c_uint64)]
+
+
+_lib = None
+
+
+def lib():
+    """The loaded library; raises if it has not been built (no CPU fallback exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError("%s is missing: build it with `python -m paper_2306_17266_amd.build` "
+                           "(there is no fallback path)" % LIB_PATH)
+    L = C.CDLL(LIB_PATH)
+    vp, ip = C.c_void_p, C.POINTER(C.c_int)
+    L.sushi_describe_supernet.argtypes = [C.POINTER(CArch), C.POINTER(CTensorDesc), C.c_int, ip]
+    L.sushi_subnet_layers.argtypes = [C.POINTER(CArch), C.POINTER(CSubnetCfg), C.POINTER(CLayerDims), C.c_int, ip]
+    L.sushi_create.argtypes = [C.POINTER(vp), C.c_int, vp]
+    L.sushi_destroy.argtypes = [vp]
+    L.sushi_destroy.restype = None
+    L.sushi_last_error.argtypes = [vp]
+    L.sushi_last_error.restype = C.c_char_p
+    L.sushi_load_supernet.argtypes = [vp, C.POINTER(CArch), vp, C.c_size_t, C.c_int]
+    L.sushi_set_subgraph_cache.argtypes = [vp, C.POINTER(CSubgraphCfg), C.c_size_t]
+    L.sushi_infer.argtypes = [vp, C.POINTER(CSubnetCfg), vp, C.c_int, vp]
+    L.sushi_sched_init.argtypes = [vp, C.POINTER(CSchedDesc)]
+    L.sushi_sched_step.argtypes = [vp, C.c_float, C.c_float, ip, ip]
+    L.sushi_sched_record.argtypes = [vp, C.POINTER(C.c_int32), ip]
+    L.sushi_get_stats.argtypes = [vp, C.POINTER(CStats)]
+    L.sushi_set_option.argtypes = [vp, C.c_int, C.c_int64]
+    _lib = L
+    return L
+
+
+def _fill(arr, values):
+    for i, v in enumerate(values):
+        arr[i] = v
+
+
+def c_arch(a):
+    """workloads.arch.Arch -> sushi_arch."""
+    s = CArch()
+    s.family, s.n_classes, s.in_channels, s.n_stages = a.family, a.n_classes, a.in_channels, a.n_stages
+    _fill(s.stage_base_out, a.stage_base_out)
+    _fill(s.stage_stride, a.stage_stride)
+    _fill(s.stage_max_depth, a.stage_max_depth)
+    _fill(s.stage_act, a.stage_act)
+    _fill(s.stage_se, a.stage_se)
+    s.n_depth_drop = len(a.depth_drop_choices)
+    _fill(s.depth_drop_choices, a.depth_drop_choices)
+    s.n_width = len(a.width_choices)
+    _fill(s.width_choices, a.width_choices)
+    s.n_expand = len(a.expand_choices)
+    _fill(s.expand_choices, a.expand_choices)
+    s.n_kernel = len(a.kernel_choices)
+    _fill(s.kernel_choices, a.kernel_choices)
+    s.n_res = len(a.res_choices)
+    _fill(s.res_choices, a.res_choices)
+    s.stem_mid, s.stem_out, s.head_mid, s.head_feat = a.stem_mid, a.stem_out, a.head_mid, a.head_feat
+    return s
+
+
+def c_cfg(cfg):
+    """workloads.arch.SubnetCfg -> sushi_subnet_cfg."""
+    s = CSubnetCfg()
+    s.resolution = cfg.resolution
+    _fill(s.depth, cfg.depth)
+    _fill(s.width_idx, cfg.width_idx)
+    _fill(s.expand_idx, cfg.expand_idx)
+    _fill(s.kernel_idx, cfg.kernel_idx)
+    return s
+
+
+def _check(rc, ctx=None):
+    if rc != 0:
+        msg = lib().sushi_last_error(ctx) if ctx else b""
+        raise SushiError(rc, (msg or b"").decode())
+
+
+def sushi_describe_supernet(arch):
+    """[(name, shape tuple, kind)] in weight-blob order."""
+    a, n = c_arch(arch), C.c_int(0)
+    _check(lib().sushi_describe_supernet(C.byref(a), None, 0, C.byref(n)))
+    buf = (CTensorDesc * n.value)()
+    _check(lib().sushi_describe_supernet(C.byref(a), buf, n.value, C.byref(n)))
+    return [(d.name.decode(), tuple(d.shape[:d.ndim]), d.kind) for d in buf]
+
+
+def sushi_subnet_layers(arch, cfg):
+    """[(K, C, r)] per SuperNet layer for SubNet cfg."""
+    a, s, n = c_arch(arch), c_cfg(cfg), C.c_int(0)
+    buf = (CLayerDims * 256)()
+    _check(lib().sushi_subnet_layers(C.byref(a), C.byref(s), buf, 256, C.byref(n)))
+    return [(buf[i].K, buf[i].C, buf[i].r) for i in range(n.value)]
+
+
+class Sushi:
+    """One context (device + stream)."""
+
+    def __init__(self, device=0, stream=None):
+        if device < 0:
+            stream = 0                      # host-only context: scheduler calls only
+        elif stream is None:
+            import torch
+            stream = torch.cuda.current_stream(device).cuda_stream
+        self._h = C.c_void_p()
+        rc = lib().sushi_create(C.byref(self._h), device, C.c_void_p(stream))
+        if rc != 0:
+            raise SushiError(rc, (lib().sushi_last_error(None) or b"").decode())
+        self.arch = None
+        self.dtype = None
+        self._cfg_cache = {}
+
+    def close(self):
+        if self._h:
+            lib().sushi_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def sushi_load_supernet(self, arch, blob, dtype):
+        blob = np.ascontiguousarray(blob, dtype=np.float32)
+        a = c_arch(arch)
+        _check(lib().sushi_load_supernet(self._h, C.byref(a), blob.ctypes.data_as(C.c_void_p), blob.nbytes, dtype),
+               self._h)
+        self.arch, self.dtype = arch, dtype
+        self._cfg_cache = {}
+
+    def sushi_set_subgraph_cache(self, box, budget_bytes):
+        """box: list of (K, C, r) per layer, or None to empty the cache."""
+        if not box:
+            _check(lib().sushi_set_subgraph_cache(self._h, None, 0), self._h)
+            return
+        arr = (CLayerDims * len(box))(*[CLayerDims(k, c, r) for (k, c, r) in box])
+        g = CSubgraphCfg(len(box), arr)
+        _check(lib().sushi_set_subgraph_cache(self._h, C.byref(g), int(budget_bytes)), self._h)
+
+    def sushi_infer(self, cfg, x, logits):
+        """x: device tensor [B, res, res, C] (float32 or bfloat16); logits: float32 [B, classes]."""
+        key = cfg.key()
+        s = self._cfg_cache.get(key)
+        if s is None:
+            s = self._cfg_cache[key] = c_cfg(cfg)
+        _check(lib().sushi_infer(self._h, C.byref(s), C.c_void_p(x.data_ptr()), x.shape[0],
+                                 C.c_void_p(logits.data_ptr())), self._h)
+
+    def sushi_sched_init(self, subnet_vecs, accuracy, subgraph_vecs, table, Q, policy, initial_cache=-1):
+        sv = np.ascontiguousarray(subnet_vecs, dtype=np.int32)
+        gv = np.ascontiguousarray(subgraph_vecs, dtype=np.int32).reshape(-1, sv.shape[1])
+        acc = np.ascontiguousarray(accuracy, dtype=np.float32)
+        tab = np.ascontiguousarray(table, dtype=np.float32)
+        assert tab.shape == (sv.shape[0], gv.shape[0] + 1)
+        d = CSchedDesc(sv.shape[0], gv.shape[0], sv.shape[1],
+                       sv.ctypes.data_as(C.POINTER(C.c_int32)), acc.ctypes.data_as(C.POINTER(C.c_float)),
+                       gv.ctypes.data_as(C.POINTER(C.c_int32)), tab.ctypes.data_as(C.POINTER(C.c_float)),
+                       Q, policy, initial_cache)
+        _check(lib().sushi_sched_init(self._h, C.byref(d)), self._h)
+
+    def sushi_sched_step(self, acc_target, lat_target):
+        i, j = C.c_int(0), C.c_int(0)
+        _check(lib().sushi_sched_step(self._h, acc_target, lat_target, C.byref(i), C.byref(j)), self._h)
+        return i.value, j.value
+
+    def sushi_sched_record(self, vec):
+        v = np.ascontiguousarray(vec, dtype=np.int32)
+        j = C.c_int(0)
+        _check(lib().sushi_sched_record(self._h, v.ctypes.data_as(C.POINTER(C.c_int32)), C.byref(j)), self._h)
+        return j.value
+
+    def sushi_get_stats(self):
+        s = CStats()
+        _check(lib().sushi_get_stats(self._h, C.byref(s)), self._h)
+        return {f: getattr(s, f) for f, _ in CStats._fields_}
+
+    def sushi_set_option(self, option, value):
+        _check(lib().sushi_set_option(self._h, option, value), self._h)

@@ -1,0 +1,56 @@
+// Device kernels of the SubNet forward pass and their launchers (gfx950).
+//
+// Layouts
+//   activations   [B][H][W][C]  channels fastest, C = active channels of the SubNet (compact)
+//   dense weights [tap][channel group of 8][filter (padded to 16)][8 channels]
+//                 so the slice (K' filters, C' channels) of a SubNet is, for every tap and channel
+//                 group below C'/8, the contiguous prefix of K' * 8 elements; a 16-filter x 32-channel
+//                 matrix-core operand is four 256-byte runs
+//   depthwise     [tap in ring order][channel]: the 9 taps of the centre 3x3 first, then the 16 of
+//                 the 5x5 ring, then the 24 of the 7x7 ring, so a centred k x k crop is the prefix
+//                 of k*k taps
+//   scale/shift   float32 prefixes of length K'
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+namespace sushi {
+
+struct ConvArgs {
+    const void *x;       // input activations
+    void *y;             // output activations
+    const void *res;     // optional residual, same shape as y
+    const void *w;       // packed weights of the layer
+    const float *scale;  // may be null (= 1)
+    const float *shift;  // shift or bias
+    int B, H, W, C;      // input
+    int P, Q, K;         // output
+    int R, stride, pad;  // taps per side of the active kernel
+    int Rmax;            // taps per side of the stored kernel (depthwise crops)
+    int Kpad, CG;        // packed layout: padded filters, stored channel groups
+    int act;             // sushi_act; applied after the residual add
+    int hsigmoid;        // replace act by min(max(v+3,0),6)/6
+    int out_f32;         // store float32 regardless of the activation type
+};
+
+struct PoolArgs {
+    const void *x;
+    void *y;
+    const float *gate;  // OP_GATE: [B][C] multipliers
+    int B, H, W, C, P, Q;
+};
+
+// Every launcher returns hipSuccess or the launch error.  bf16 = activations and weights are bf16.
+hipError_t launch_conv(const ConvArgs &a, bool bf16, hipStream_t s);      // dense conv and FC
+hipError_t launch_dwconv(const ConvArgs &a, bool bf16, hipStream_t s);
+hipError_t launch_maxpool(const PoolArgs &a, bool bf16, hipStream_t s);   // 3x3 stride 2 pad 1
+hipError_t launch_gap(const PoolArgs &a, bool bf16, hipStream_t s);       // [B][H][W][C] -> [B][C]
+hipError_t launch_gate(const PoolArgs &a, bool bf16, hipStream_t s);      // y = x * gate[b][c]
+
+// Ring order of depthwise taps: tap t of a 7x7 kernel sits at row/col offset (dr, ds) from the centre.
+void dw_tap_offsets(int t, int *dr, int *ds);
+hipError_t upload_tap_table();
+
+}  // namespace sushi

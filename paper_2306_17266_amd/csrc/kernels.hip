@@ -1,0 +1,487 @@
+// Device kernels of the SubNet forward pass (gfx950 / CDNA4).  Layouts: see kernels.h.
+//
+// Dense convolutions and fully connected layers in bf16 run as implicit GEMMs on the matrix cores
+// (v_mfma_f32_16x16x32_bf16, float32 accumulation): filters are the MFMA rows, output pixels the
+// MFMA columns, so each lane ends up with four consecutive output channels of one pixel and the
+// channels-last store is an 8-byte write.  Both operands are read straight from global memory
+// in operand order (16 bytes per lane): the packed weight layout makes a 16 x 32 weight fragment
+// four 256-byte runs, and a channels-last activation row supplies 64 contiguous bytes per pixel.
+// Everything else (depthwise, pooling, squeeze-excite gating, the float32 mode) is bandwidth
+// work on the vector ALUs with 16- or 32-byte accesses per lane.
+#include "kernels.h"
+
+namespace sushi {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+
+#define DW_DR_LIST                                                                                                  \
+    -1, -1, -1, 0, 0, 0, 1, 1, 1, -2, -2, -2, -2, -2, -1, -1, 0, 0, 1, 1, 2, 2, 2, 2, 2, -3, -3, -3, -3, -3, -3, -3, \
+        -2, -2, -1, -1, 0, 0, 1, 1, 2, 2, 3, 3, 3, 3, 3, 3, 3
+#define DW_DS_LIST                                                                                                 \
+    -1, 0, 1, -1, 0, 1, -1, 0, 1, -2, -1, 0, 1, 2, -2, 2, -2, 2, -2, 2, -2, -1, 0, 1, 2, -3, -2, -1, 0, 1, 2, 3, -3, \
+        3, -3, 3, -3, 3, -3, 3, -3, 3, -3, -2, -1, 0, 1, 2, 3
+
+__constant__ signed char c_dw_dr[49] = {DW_DR_LIST};
+__constant__ signed char c_dw_ds[49] = {DW_DS_LIST};
+static const signed char h_dw_dr[49] = {DW_DR_LIST};
+static const signed char h_dw_ds[49] = {DW_DS_LIST};
+
+void dw_tap_offsets(int t, int *dr, int *ds) {
+    *dr = h_dw_dr[t];
+    *ds = h_dw_ds[t];
+}
+
+hipError_t upload_tap_table() { return hipSuccess; }
+
+// ------------------------------------------------------------------ element helpers
+
+__device__ __forceinline__ float bf2f(uint32_t b) { return __uint_as_float(b << 16); }
+
+__device__ __forceinline__ uint32_t f2bf(float f) {  // round to nearest even
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+__device__ __forceinline__ void load8(const float *p, float v[8]) {
+    const float4 a = *reinterpret_cast<const float4 *>(p);
+    const float4 b = *reinterpret_cast<const float4 *>(p + 4);
+    v[0] = a.x, v[1] = a.y, v[2] = a.z, v[3] = a.w, v[4] = b.x, v[5] = b.y, v[6] = b.z, v[7] = b.w;
+}
+
+__device__ __forceinline__ void load8(const uint16_t *p, float v[8]) {
+    const uint4 a = *reinterpret_cast<const uint4 *>(p);
+    v[0] = bf2f(a.x & 0xFFFFu), v[1] = bf2f(a.x >> 16), v[2] = bf2f(a.y & 0xFFFFu), v[3] = bf2f(a.y >> 16);
+    v[4] = bf2f(a.z & 0xFFFFu), v[5] = bf2f(a.z >> 16), v[6] = bf2f(a.w & 0xFFFFu), v[7] = bf2f(a.w >> 16);
+}
+
+__device__ __forceinline__ void store8(float *p, const float v[8]) {
+    *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
+    *reinterpret_cast<float4 *>(p + 4) = make_float4(v[4], v[5], v[6], v[7]);
+}
+
+__device__ __forceinline__ void store8(uint16_t *p, const float v[8]) {
+    uint4 a;
+    a.x = f2bf(v[0]) | (f2bf(v[1]) << 16), a.y = f2bf(v[2]) | (f2bf(v[3]) << 16);
+    a.z = f2bf(v[4]) | (f2bf(v[5]) << 16), a.w = f2bf(v[6]) | (f2bf(v[7]) << 16);
+    *reinterpret_cast<uint4 *>(p) = a;
+}
+
+__device__ __forceinline__ float ld1(const float *p) { return *p; }
+__device__ __forceinline__ float ld1(const uint16_t *p) { return bf2f(*p); }
+__device__ __forceinline__ void st1(float *p, float v) { *p = v; }
+__device__ __forceinline__ void st1(uint16_t *p, float v) { *p = (uint16_t)f2bf(v); }
+
+__device__ __forceinline__ float activate(float v, int act, int hsig) {
+    if (hsig) return fminf(fmaxf(v + 3.0f, 0.0f), 6.0f) / 6.0f;
+    if (act == 1) return fmaxf(v, 0.0f);
+    if (act == 2) return v * fminf(fmaxf(v + 3.0f, 0.0f), 6.0f) / 6.0f;
+    return v;
+}
+
+// ------------------------------------------------------------------ dense conv, vector ALUs
+// One thread: one output pixel x 4 consecutive filters.  Serves the float32 mode, the 3-channel
+// stem and fully connected layers in float32.  y = act(scale * conv + shift (+ res)).
+
+template <typename T>
+__global__ __launch_bounds__(256) void conv_direct_kernel(ConvArgs a) {
+    const int groups = (a.K + 3) >> 2;
+    const long total = (long)a.B * a.P * a.Q * groups;
+    const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const int fg = (int)(idx % groups);
+    const long m = idx / groups;
+    const int qq = (int)(m % a.Q);
+    const int pp = (int)((m / a.Q) % a.P);
+    const int n = (int)(m / ((long)a.Q * a.P));
+    const int fb = fg * 4;
+    const T *x = static_cast<const T *>(a.x);
+    const T *w = static_cast<const T *>(a.w);
+    const int cgs = (a.C + 7) >> 3;
+    const bool vec = (a.C & 7) == 0;
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int tap = 0; tap < a.R * a.R; ++tap) {
+        const int h = pp * a.stride - a.pad + tap / a.R;
+        const int v = qq * a.stride - a.pad + tap % a.R;
+        if (h < 0 || h >= a.H || v < 0 || v >= a.W) continue;
+        const T *xp = x + (((long)n * a.H + h) * a.W + v) * a.C;
+        for (int cg = 0; cg < cgs; ++cg) {
+            float xv[8];
+            if (vec) {
+                load8(xp + cg * 8, xv);
+            } else {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) xv[j] = (cg * 8 + j < a.C) ? ld1(xp + cg * 8 + j) : 0.f;
+            }
+            const T *wp = w + (((long)tap * a.CG + cg) * a.Kpad + fb) * 8;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if (fb + i < a.Kpad) {
+                    float wv[8];
+                    load8(wp + i * 8, wv);
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) acc[i] = fmaf(wv[j], xv[j], acc[i]);
+                }
+            }
+        }
+    }
+    const long obase = m * a.K + fb;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        if (fb + i >= a.K) break;
+        float v = acc[i] * (a.scale ? a.scale[fb + i] : 1.0f) + a.shift[fb + i];
+        if (a.res) v += ld1(static_cast<const T *>(a.res) + obase + i);
+        v = activate(v, a.act, a.hsigmoid);
+        if (a.out_f32)
+            static_cast<float *>(a.y)[obase + i] = v;
+        else
+            st1(static_cast<T *>(a.y) + obase + i, v);
+    }
+}
+
+// ------------------------------------------------------------------ dense conv, bf16 matrix cores
+// Workgroup = WF x WP x WK waves.  A wave owns FT filter tiles x PT pixel tiles of 16 x 16 and, when
+// WK > 1, every WK-th step of the reduction (taps x 32-channel chunks); the WK partial sums are added
+// in a fixed order through LDS, so results do not depend on timing.
+
+template <int FT, int PT, int WF, int WP, int WK>
+__global__ __launch_bounds__(64 * WF * WP * WK) void conv_mfma_kernel(ConvArgs a) {
+    constexpr int NW = WF * WP * WK;
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int wk = wave % WK, wp = (wave / WK) % WP, wf = wave / (WK * WP);
+    const int l16 = lane & 15, kg = lane >> 4;
+    const int M = a.B * a.P * a.Q;
+    const int n_ptiles = (M + 16 * PT * WP - 1) / (16 * PT * WP);
+    const int ptile = blockIdx.x % n_ptiles, ftile = blockIdx.x / n_ptiles;
+    const int f0 = (ftile * WF + wf) * FT * 16;
+    const int m0 = (ptile * WP + wp) * PT * 16;
+    const uint16_t *x = static_cast<const uint16_t *>(a.x);
+    const uint16_t *w = static_cast<const uint16_t *>(a.w);
+
+    int pn[PT], ph[PT], pw[PT];
+    bool pv[PT];
+#pragma unroll
+    for (int pt = 0; pt < PT; ++pt) {
+        const int m = m0 + pt * 16 + l16;
+        pv[pt] = m < M;
+        const int mm = pv[pt] ? m : 0;
+        const int qq = mm % a.Q, pp = (mm / a.Q) % a.P;
+        pn[pt] = mm / (a.Q * a.P);
+        ph[pt] = pp * a.stride - a.pad;
+        pw[pt] = qq * a.stride - a.pad;
+    }
+    f32x4_t acc[FT][PT];
+#pragma unroll
+    for (int ft = 0; ft < FT; ++ft)
+#pragma unroll
+        for (int pt = 0; pt < PT; ++pt) acc[ft][pt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+    const int csteps = (a.C + 31) >> 5;
+    const int nsteps = a.R * a.R * csteps;
+    for (int step = wk; step < nsteps; step += WK) {
+        const int tap = step / csteps;
+        const int c0 = (step - tap * csteps) * 32 + kg * 8;
+        const int dr = tap / a.R, ds = tap - dr * a.R;
+        const bool cv = c0 < a.C;
+        union {
+            uint4 u;
+            bf16x8_t v;
+        } fa[FT], fb[PT];
+#pragma unroll
+        for (int ft = 0; ft < FT; ++ft) {
+            const int f = f0 + ft * 16 + l16;
+            fa[ft].u = make_uint4(0, 0, 0, 0);
+            if (cv && f < a.Kpad)
+                fa[ft].u = *reinterpret_cast<const uint4 *>(w + (((long)tap * a.CG + (c0 >> 3)) * a.Kpad + f) * 8);
+        }
+#pragma unroll
+        for (int pt = 0; pt < PT; ++pt) {
+            const int h = ph[pt] + dr, v = pw[pt] + ds;
+            fb[pt].u = make_uint4(0, 0, 0, 0);
+            if (cv && pv[pt] && h >= 0 && h < a.H && v >= 0 && v < a.W)
+                fb[pt].u = *reinterpret_cast<const uint4 *>(x + (((long)pn[pt] * a.H + h) * a.W + v) * a.C + c0);
+        }
+#pragma unroll
+        for (int ft = 0; ft < FT; ++ft)
+#pragma unroll
+            for (int pt = 0; pt < PT; ++pt)
+                acc[ft][pt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[ft].v, fb[pt].v, acc[ft][pt], 0, 0, 0);
+    }
+
+    if constexpr (WK > 1) {
+        __shared__ float red[NW * FT * PT * 4 * 64];
+        float *mine = red + (long)wave * FT * PT * 4 * 64;
+#pragma unroll
+        for (int ft = 0; ft < FT; ++ft)
+#pragma unroll
+            for (int pt = 0; pt < PT; ++pt)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) mine[((ft * PT + pt) * 4 + i) * 64 + lane] = acc[ft][pt][i];
+        __syncthreads();
+        if (wk != 0) return;
+        for (int k = 1; k < WK; ++k) {
+            const float *other = red + (long)(wave + k) * FT * PT * 4 * 64;
+#pragma unroll
+            for (int ft = 0; ft < FT; ++ft)
+#pragma unroll
+                for (int pt = 0; pt < PT; ++pt)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) acc[ft][pt][i] += other[((ft * PT + pt) * 4 + i) * 64 + lane];
+        }
+    }
+
+    // lane holds, per tile, pixel column l16 and filters kg*4 .. kg*4+3
+#pragma unroll
+    for (int ft = 0; ft < FT; ++ft) {
+        const int fbase = f0 + ft * 16 + kg * 4;
+        if (fbase >= a.K) continue;
+        const int nf = min(4, a.K - fbase);
+        float sc[4], sh[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            sc[i] = (a.scale && i < nf) ? a.scale[fbase + i] : 1.0f;
+            sh[i] = i < nf ? a.shift[fbase + i] : 0.0f;
+        }
+#pragma unroll
+        for (int pt = 0; pt < PT; ++pt) {
+            const int m = m0 + pt * 16 + l16;
+            if (m >= M) continue;
+            const long o = (long)m * a.K + fbase;
+            float v[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) v[i] = acc[ft][pt][i] * sc[i] + sh[i];
+            if (a.res) {
+                const uint16_t *rp = static_cast<const uint16_t *>(a.res) + o;
+                if (nf == 4 && (a.K & 3) == 0) {
+                    const uint2 r = *reinterpret_cast<const uint2 *>(rp);
+                    v[0] += bf2f(r.x & 0xFFFFu), v[1] += bf2f(r.x >> 16), v[2] += bf2f(r.y & 0xFFFFu),
+                        v[3] += bf2f(r.y >> 16);
+                } else {
+                    for (int i = 0; i < nf; ++i) v[i] += bf2f(rp[i]);
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) v[i] = activate(v[i], a.act, a.hsigmoid);
+            if (a.out_f32) {
+                float *yp = static_cast<float *>(a.y) + o;
+                if (nf == 4 && (a.K & 3) == 0)
+                    *reinterpret_cast<float4 *>(yp) = make_float4(v[0], v[1], v[2], v[3]);
+                else
+                    for (int i = 0; i < nf; ++i) yp[i] = v[i];
+            } else {
+                uint16_t *yp = static_cast<uint16_t *>(a.y) + o;
+                if (nf == 4 && (a.K & 3) == 0) {
+                    uint2 r;
+                    r.x = f2bf(v[0]) | (f2bf(v[1]) << 16), r.y = f2bf(v[2]) | (f2bf(v[3]) << 16);
+                    *reinterpret_cast<uint2 *>(yp) = r;
+                } else {
+                    for (int i = 0; i < nf; ++i) yp[i] = (uint16_t)f2bf(v[i]);
+                }
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------ depthwise k x k
+// One thread: one output pixel x 8 channels, taps in ring order (prefix of the stored 7x7).
+
+template <typename T>
+__global__ __launch_bounds__(256) void dwconv_kernel(ConvArgs a) {
+    const int cgs = a.K >> 3;
+    const long total = (long)a.B * a.P * a.Q * cgs;
+    const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const int cg = (int)(idx % cgs);
+    const long m = idx / cgs;
+    const int qq = (int)(m % a.Q);
+    const int pp = (int)((m / a.Q) % a.P);
+    const int n = (int)(m / ((long)a.Q * a.P));
+    const int c = cg * 8;
+    const T *x = static_cast<const T *>(a.x);
+    const T *w = static_cast<const T *>(a.w);
+    float acc[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] = 0.f;
+    const int ntaps = a.R * a.R;
+    for (int t = 0; t < ntaps; ++t) {
+        const int h = pp * a.stride + c_dw_dr[t];
+        const int v = qq * a.stride + c_dw_ds[t];
+        if (h < 0 || h >= a.H || v < 0 || v >= a.W) continue;
+        float xv[8], wv[8];
+        load8(x + (((long)n * a.H + h) * a.W + v) * a.C + c, xv);
+        load8(w + (long)t * a.Kpad + c, wv);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] = fmaf(wv[j], xv[j], acc[j]);
+    }
+    float sc[8], sh[8];
+    load8(a.scale + c, sc);
+    load8(a.shift + c, sh);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] = activate(acc[j] * sc[j] + sh[j], a.act, 0);
+    store8(static_cast<T *>(a.y) + m * a.K + c, acc);
+}
+
+// ------------------------------------------------------------------ pooling and gating
+
+template <typename T>
+__global__ __launch_bounds__(256) void maxpool_kernel(PoolArgs a) {
+    const int cgs = a.C >> 3;
+    const long total = (long)a.B * a.P * a.Q * cgs;
+    const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const int cg = (int)(idx % cgs);
+    const long m = idx / cgs;
+    const int qq = (int)(m % a.Q);
+    const int pp = (int)((m / a.Q) % a.P);
+    const int n = (int)(m / ((long)a.Q * a.P));
+    const T *x = static_cast<const T *>(a.x);
+    float best[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) best[j] = -3.4028235e38f;
+    for (int r = 0; r < 3; ++r) {
+        const int h = pp * 2 - 1 + r;
+        if (h < 0 || h >= a.H) continue;
+        for (int s = 0; s < 3; ++s) {
+            const int v = qq * 2 - 1 + s;
+            if (v < 0 || v >= a.W) continue;
+            float xv[8];
+            load8(x + (((long)n * a.H + h) * a.W + v) * a.C + cg * 8, xv);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) best[j] = fmaxf(best[j], xv[j]);
+        }
+    }
+    store8(static_cast<T *>(a.y) + m * a.C + cg * 8, best);
+}
+
+// Global average over H x W.  Workgroup = 32 pixel lanes x 8 channel groups; partial sums are
+// combined by a fixed binary tree, so the result does not depend on timing.
+template <typename T>
+__global__ __launch_bounds__(256) void gap_kernel(PoolArgs a) {
+    __shared__ float part[32][8][9];
+    const int cgs = a.C >> 3;
+    const int blocks_per_image = (cgs + 7) >> 3;
+    const int n = blockIdx.x / blocks_per_image;
+    const int cgi = threadIdx.x & 7, pl = threadIdx.x >> 3;
+    const int cg = (blockIdx.x % blocks_per_image) * 8 + cgi;
+    const int hw = a.H * a.W;
+    float acc[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] = 0.f;
+    if (cg < cgs) {
+        const T *x = static_cast<const T *>(a.x) + (long)n * hw * a.C + cg * 8;
+        for (int p = pl; p < hw; p += 32) {
+            float xv[8];
+            load8(x + (long)p * a.C, xv);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[j] += xv[j];
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) part[pl][cgi][j] = acc[j];
+    __syncthreads();
+    for (int s = 16; s > 0; s >>= 1) {
+        if (pl < s)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) part[pl][cgi][j] += part[pl + s][cgi][j];
+        __syncthreads();
+    }
+    if (pl == 0 && cg < cgs) {
+        float o[8];
+        const float inv = 1.0f / (float)hw;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) o[j] = part[0][cgi][j] * inv;
+        store8(static_cast<T *>(a.y) + (long)n * a.C + cg * 8, o);
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void gate_kernel(PoolArgs a) {
+    const int cgs = a.C >> 3;
+    const long total = (long)a.B * a.H * a.W * cgs;
+    const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const int cg = (int)(idx % cgs);
+    const long m = idx / cgs;
+    const int n = (int)(m / ((long)a.H * a.W));
+    float xv[8], g[8];
+    load8(static_cast<const T *>(a.x) + m * a.C + cg * 8, xv);
+    load8(a.gate + (long)n * a.C + cg * 8, g);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) xv[j] *= g[j];
+    store8(static_cast<T *>(a.y) + m * a.C + cg * 8, xv);
+}
+
+// ------------------------------------------------------------------ launchers
+
+static inline unsigned blocks_for(long total) { return (unsigned)((total + 255) / 256); }
+
+template <int FT, int PT, int WF, int WP, int WK>
+static hipError_t launch_mfma(const ConvArgs &a, hipStream_t s) {
+    const int M = a.B * a.P * a.Q;
+    const int n_ptiles = (M + 16 * PT * WP - 1) / (16 * PT * WP);
+    const int n_ftiles = (a.K + 16 * FT * WF - 1) / (16 * FT * WF);
+    hipLaunchKernelGGL((conv_mfma_kernel<FT, PT, WF, WP, WK>), dim3(n_ptiles * n_ftiles), dim3(64 * WF * WP * WK), 0, s,
+                       a);
+    return hipGetLastError();
+}
+
+hipError_t launch_conv(const ConvArgs &a, bool bf16, hipStream_t s) {
+    const long M = (long)a.B * a.P * a.Q;
+    if (!bf16 || (a.C & 7) != 0) {
+        const long total = M * ((a.K + 3) / 4);
+        if (bf16)
+            hipLaunchKernelGGL(conv_direct_kernel<uint16_t>, dim3(blocks_for(total)), dim3(256), 0, s, a);
+        else
+            hipLaunchKernelGGL(conv_direct_kernel<float>, dim3(blocks_for(total)), dim3(256), 0, s, a);
+        return hipGetLastError();
+    }
+    // Tile choice: the largest workgroup tile that still yields about two workgroups per compute
+    // unit; few-pixel problems (late layers at batch 1, FC) split the reduction over waves instead.
+    const long tiles16 = ((M + 15) / 16) * ((a.K + 15) / 16);
+    if (M <= 16) return launch_mfma<1, 1, 1, 1, 8>(a, s);
+    if (M <= 64) return launch_mfma<1, 2, 1, 2, 4>(a, s);
+    if (tiles16 >= 512L * 64) return launch_mfma<4, 4, 2, 2, 1>(a, s);
+    if (tiles16 >= 512L * 16) return launch_mfma<2, 2, 2, 2, 1>(a, s);
+    if (tiles16 >= 512L * 4) return launch_mfma<1, 2, 2, 1, 1>(a, s);
+    return launch_mfma<1, 1, 1, 1, 4>(a, s);
+}
+
+hipError_t launch_dwconv(const ConvArgs &a, bool bf16, hipStream_t s) {
+    const long total = (long)a.B * a.P * a.Q * (a.K >> 3);
+    if (bf16)
+        hipLaunchKernelGGL(dwconv_kernel<uint16_t>, dim3(blocks_for(total)), dim3(256), 0, s, a);
+    else
+        hipLaunchKernelGGL(dwconv_kernel<float>, dim3(blocks_for(total)), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_maxpool(const PoolArgs &a, bool bf16, hipStream_t s) {
+    const long total = (long)a.B * a.P * a.Q * (a.C >> 3);
+    if (bf16)
+        hipLaunchKernelGGL(maxpool_kernel<uint16_t>, dim3(blocks_for(total)), dim3(256), 0, s, a);
+    else
+        hipLaunchKernelGGL(maxpool_kernel<float>, dim3(blocks_for(total)), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_gap(const PoolArgs &a, bool bf16, hipStream_t s) {
+    const unsigned blocks = (unsigned)(a.B * (((a.C >> 3) + 7) >> 3));
+    if (bf16)
+        hipLaunchKernelGGL(gap_kernel<uint16_t>, dim3(blocks), dim3(256), 0, s, a);
+    else
+        hipLaunchKernelGGL(gap_kernel<float>, dim3(blocks), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_gate(const PoolArgs &a, bool bf16, hipStream_t s) {
+    const long total = (long)a.B * a.H * a.W * (a.C >> 3);
+    if (bf16)
+        hipLaunchKernelGGL(gate_kernel<uint16_t>, dim3(blocks_for(total)), dim3(256), 0, s, a);
+    else
+        hipLaunchKernelGGL(gate_kernel<float>, dim3(blocks_for(total)), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+}  // namespace sushi

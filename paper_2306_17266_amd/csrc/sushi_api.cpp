@@ -1,0 +1,534 @@
+// C ABI of the library (include/sushi.h): context, SuperNet weight packer, SubGraph cache state,
+// per-query plan cache and launch loop, counters.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <memory>
+#include <new>
+#include <string>
+#include <unordered_map>
+#include <vector>
+
+#include "../../include/sushi.h"
+#include "kernels.h"
+#include "model.h"
+#include "sched.h"
+
+using namespace sushi;
+
+namespace {
+
+struct Launch {
+    int kind;
+    ConvArgs conv{};
+    PoolArgs pool{};
+    int in_patch = 0, out_patch = 0;  // 1 = pointer is the caller's input / logits buffer
+};
+
+struct CachedPlan {
+    Plan plan;
+    std::vector<Launch> launches;
+    uint64_t weight_bytes = 0;
+    double vec_norm2 = 0.0;           // sum K^2 + C^2 over layers
+    uint64_t g_version = ~0ull;       // cache state the two figures below were computed for
+    uint64_t resident_bytes = 0;
+    double hit_ratio = 0.0;
+};
+
+std::string g_create_error;
+
+}  // namespace
+
+struct sushi_ctx {
+    int device = 0;
+    hipStream_t stream = nullptr;
+    std::string err;
+    bool loaded = false, bf16 = false;
+    SuperNet sn;
+    void *d_weights = nullptr;
+    float *d_params = nullptr;
+    size_t weight_elems = 0;
+    void *big[N_BIG_BUFS] = {};
+    void *small_[N_SMALL_BUFS] = {};
+    int arena_batch = 0;
+    std::unordered_map<std::string, std::unique_ptr<CachedPlan>> plans;
+    std::vector<sushi_layer_dims> G;  // cached SubGraph (empty = nothing cached)
+    uint64_t g_version = 0;
+    Scheduler sched;
+    sushi_stats stats{};
+    int exec_mode = 0;
+};
+
+namespace {
+
+int fail(sushi_ctx *c, int code, const std::string &msg) {
+    if (c) c->err = msg;
+    return code;
+}
+
+int hip_fail(sushi_ctx *c, hipError_t e, const char *what) {
+    return fail(c, SUSHI_EDEVICE, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+inline uint16_t to_bf16(float f) {
+    uint32_t u;
+    std::memcpy(&u, &f, 4);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+size_t elem_size(const sushi_ctx *c) { return c->bf16 ? 2 : 4; }
+
+// Lays the SuperNet out for the device.  Dense/FC layer: [tap][channel group][filter, padded to 16][8];
+// depthwise: [tap in ring order][channel, padded to 16].  Scale/shift/bias: float32 runs, each
+// starting on a 32-byte boundary.  Returns the two host staging buffers.
+template <typename T, typename Cvt>
+void pack_weights(SuperNet &sn, const float *blob, std::vector<T> &w, std::vector<float> &params, Cvt cvt) {
+    size_t welems = 0, pfloats = 0;
+    for (SuperLayer &L : sn.layers) {
+        L.Kpad = (int)round_up(L.Kmax, 16);
+        L.CG = L.type == L_DW ? 0 : (L.Cmax + 7) / 8;
+        L.pk_w = welems;
+        const size_t taps = (size_t)L.Rmax * L.Rmax;
+        welems += L.type == L_DW ? taps * L.Kpad : taps * L.CG * L.Kpad * 8;
+        welems = round_up(welems, 128);
+        if (L.has_scale) {
+            L.pk_scale = pfloats;
+            pfloats += round_up(L.Kmax, 8);
+        }
+        L.pk_shift = pfloats;
+        pfloats += round_up(L.Kmax, 8);
+    }
+    w.assign(welems, T(0));
+    params.assign(pfloats, 0.f);
+    for (const SuperLayer &L : sn.layers) {
+        const float *src = blob + L.blob_w;
+        T *dst = w.data() + L.pk_w;
+        const int R = L.Rmax;
+        if (L.type == L_DW) {
+            for (int t = 0; t < R * R; ++t) {
+                int dr, ds;
+                if (R == 1)
+                    dr = ds = 0;
+                else
+                    dw_tap_offsets(t, &dr, &ds);
+                const int r = dr + R / 2, s = ds + R / 2;
+                for (int k = 0; k < L.Kmax; ++k) dst[(size_t)t * L.Kpad + k] = cvt(src[((size_t)k * R + r) * R + s]);
+            }
+        } else {
+            for (int k = 0; k < L.Kmax; ++k)
+                for (int c = 0; c < L.Cmax; ++c)
+                    for (int t = 0; t < R * R; ++t)
+                        dst[(((size_t)t * L.CG + c / 8) * L.Kpad + k) * 8 + (c & 7)] =
+                            cvt(src[((size_t)k * L.Cmax + c) * R * R + t]);
+        }
+        if (L.has_scale) std::memcpy(&params[L.pk_scale], blob + L.blob_scale, sizeof(float) * L.Kmax);
+        std::memcpy(&params[L.pk_shift], blob + L.blob_shift, sizeof(float) * L.Kmax);
+    }
+}
+
+void free_arena(sushi_ctx *c) {
+    for (auto &p : c->big) {
+        if (p) (void)hipFree(p);
+        p = nullptr;
+    }
+    for (auto &p : c->small_) {
+        if (p) (void)hipFree(p);
+        p = nullptr;
+    }
+    c->arena_batch = 0;
+}
+
+sushi_subnet_cfg largest_cfg(const sushi_arch &a) {
+    sushi_subnet_cfg m{};
+    int res = a.res_choices[0];
+    for (int i = 1; i < a.n_res; ++i) res = std::max(res, (int)a.res_choices[i]);
+    m.resolution = res;
+    auto argmax_d = [](const double *v, int n) {
+        int b = 0;
+        for (int i = 1; i < n; ++i)
+            if (v[i] > v[b]) b = i;
+        return b;
+    };
+    int mind = a.depth_drop_choices[0];
+    for (int i = 1; i < a.n_depth_drop; ++i) mind = std::min(mind, (int)a.depth_drop_choices[i]);
+    if (a.family == SUSHI_FAMILY_TINY)
+        m.depth[0] = a.n_stages - mind;
+    else
+        for (int s = 0; s < a.n_stages; ++s) m.depth[s] = a.stage_max_depth[s] - mind;
+    for (int s = 0; s <= a.n_stages; ++s) m.width_idx[s] = argmax_d(a.width_choices, a.n_width);
+    int kb = 0;
+    for (int i = 1; i < a.n_kernel; ++i)
+        if (a.kernel_choices[i] > a.kernel_choices[kb]) kb = i;
+    for (int b = 0; b < SUSHI_MAX_BLOCKS; ++b) {
+        m.expand_idx[b] = argmax_d(a.expand_choices, a.n_expand);
+        m.kernel_idx[b] = kb;
+    }
+    return m;
+}
+
+// Activation buffers for batches up to `batch`, sized by the largest SubNet at the largest resolution.
+int ensure_arena(sushi_ctx *c, int batch) {
+    if (batch <= c->arena_batch) return SUSHI_OK;
+    Plan p;
+    std::string err;
+    int rc = plan_subnet(c->sn, largest_cfg(c->sn.arch), batch, p, err);
+    if (rc) return fail(c, rc, "arena: " + err);
+    hipError_t e = hipStreamSynchronize(c->stream);
+    if (e != hipSuccess) return hip_fail(c, e, "hipStreamSynchronize");
+    free_arena(c);
+    const size_t big_bytes = round_up(p.max_big_elems * elem_size(c), 256);
+    const size_t small_bytes = round_up(std::max<size_t>(p.max_small_elems, 8) * 4, 256);
+    for (auto &b : c->big)
+        if ((e = hipMalloc(&b, big_bytes)) != hipSuccess) return fail(c, SUSHI_ENOMEM, "hipMalloc(activations)");
+    for (auto &b : c->small_)
+        if ((e = hipMalloc(&b, small_bytes)) != hipSuccess) return fail(c, SUSHI_ENOMEM, "hipMalloc(vectors)");
+    c->arena_batch = batch;
+    c->plans.clear();  // cached launches hold arena pointers
+    return SUSHI_OK;
+}
+
+void *buf_ptr(sushi_ctx *c, int id, bool small) {
+    if (id < 0) return nullptr;
+    return small ? c->small_[id] : c->big[id];
+}
+
+// Turns a plan into launch records with device pointers bound.
+void bind_plan(sushi_ctx *c, CachedPlan &cp) {
+    const size_t es = elem_size(c);
+    for (const Op &op : cp.plan.ops) {
+        Launch L;
+        L.kind = op.kind;
+        if (op.kind == OP_CONV || op.kind == OP_DW || op.kind == OP_FC) {
+            const SuperLayer &S = c->sn.layers[op.layer];
+            ConvArgs &a = L.conv;
+            a.x = buf_ptr(c, op.in_buf, op.in_small);
+            a.y = buf_ptr(c, op.out_buf, op.out_small);
+            a.res = buf_ptr(c, op.res_buf, false);
+            a.w = static_cast<const char *>(c->d_weights) + S.pk_w * es;
+            a.scale = S.has_scale ? c->d_params + S.pk_scale : nullptr;
+            a.shift = c->d_params + S.pk_shift;
+            a.B = op.B, a.H = op.H, a.W = op.W, a.C = op.C, a.P = op.P, a.Q = op.Q, a.K = op.K;
+            a.R = op.r, a.stride = op.stride, a.pad = op.pad, a.Rmax = S.Rmax;
+            a.Kpad = S.Kpad, a.CG = S.CG;
+            a.act = op.act, a.hsigmoid = op.hsigmoid ? 1 : 0, a.out_f32 = op.out_f32 ? 1 : 0;
+            L.in_patch = op.in_buf == BUF_INPUT;
+            L.out_patch = op.out_buf == BUF_LOGITS;
+        } else {
+            PoolArgs &a = L.pool;
+            a.x = buf_ptr(c, op.in_buf, op.in_small);
+            a.y = buf_ptr(c, op.out_buf, op.out_small);
+            a.gate = static_cast<const float *>(buf_ptr(c, op.gate_buf, true));
+            a.B = op.B, a.H = op.H, a.W = op.W, a.C = op.C, a.P = op.P, a.Q = op.Q;
+        }
+        cp.launches.push_back(L);
+    }
+    cp.weight_bytes = 0;
+    cp.vec_norm2 = 0.0;
+    for (const sushi_layer_dims &d : cp.plan.dims) {
+        cp.weight_bytes += (uint64_t)d.K * d.C * d.r * d.r * es;
+        cp.vec_norm2 += (double)d.K * d.K + (double)d.C * d.C;
+    }
+}
+
+// Bytes of the SubNet that lie inside the cached SubGraph, and the vector hit ratio (Appendix A.4).
+void refresh_residency(sushi_ctx *c, CachedPlan &cp) {
+    if (cp.g_version == c->g_version) return;
+    cp.g_version = c->g_version;
+    cp.resident_bytes = 0;
+    cp.hit_ratio = 0.0;
+    if (c->G.empty()) return;
+    const size_t es = elem_size(c);
+    double inter2 = 0.0;
+    for (size_t i = 0; i < cp.plan.dims.size(); ++i) {
+        const sushi_layer_dims &d = cp.plan.dims[i], &g = c->G[i];
+        if (d.K == 0 || g.K == 0) continue;
+        const uint64_t k = std::min(d.K, g.K), ch = std::min(d.C, g.C), r = std::min(d.r, g.r);
+        cp.resident_bytes += k * ch * r * r * es;
+        inter2 += (double)k * k + (double)ch * ch;
+    }
+    cp.hit_ratio = cp.vec_norm2 > 0 ? std::sqrt(inter2) / std::sqrt(cp.vec_norm2) : 0.0;
+}
+
+std::string plan_key(const sushi_subnet_cfg &cfg, int batch) {
+    std::string k(reinterpret_cast<const char *>(&cfg), sizeof(cfg));
+    k.append(reinterpret_cast<const char *>(&batch), sizeof(batch));
+    return k;
+}
+
+}  // namespace
+
+extern "C" {
+
+int sushi_describe_supernet(const sushi_arch *arch, sushi_tensor_desc *out, int cap, int *n_out) {
+    if (!arch || !n_out || cap < 0 || (cap > 0 && !out)) return SUSHI_EINVAL;
+    SuperNet sn;
+    std::string err;
+    int rc = build_supernet(*arch, sn, err);
+    if (rc) return rc;
+    *n_out = (int)sn.tensors.size();
+    for (int i = 0; i < cap && i < *n_out; ++i) out[i] = sn.tensors[i];
+    return SUSHI_OK;
+}
+
+int sushi_subnet_layers(const sushi_arch *arch, const sushi_subnet_cfg *cfg, sushi_layer_dims *out, int cap,
+                        int *n_out) {
+    if (!arch || !cfg || !n_out || cap < 0 || (cap > 0 && !out)) return SUSHI_EINVAL;
+    SuperNet sn;
+    std::string err;
+    int rc = build_supernet(*arch, sn, err);
+    if (rc) return rc;
+    std::vector<sushi_layer_dims> dims;
+    rc = subnet_dims(sn, *cfg, dims, err);
+    if (rc) return rc;
+    *n_out = (int)dims.size();
+    for (int i = 0; i < cap && i < *n_out; ++i) out[i] = dims[i];
+    return SUSHI_OK;
+}
+
+int sushi_create(sushi_ctx **out, int device_id, void *hip_stream) {
+    if (!out) return SUSHI_EINVAL;
+    *out = nullptr;
+    if (device_id == -1) {  // host-only context: scheduler and planning calls, no device work
+        sushi_ctx *h = new (std::nothrow) sushi_ctx();
+        if (!h) return SUSHI_ENOMEM;
+        h->device = -1;
+        *out = h;
+        return SUSHI_OK;
+    }
+    int n = 0;
+    hipError_t e = hipGetDeviceCount(&n);
+    if (e != hipSuccess || device_id < 0 || device_id >= n) {
+        g_create_error = e != hipSuccess ? std::string("hipGetDeviceCount: ") + hipGetErrorString(e)
+                                         : "no such device";
+        return e != hipSuccess ? SUSHI_EDEVICE : SUSHI_EINVAL;
+    }
+    if ((e = hipSetDevice(device_id)) != hipSuccess) {
+        g_create_error = std::string("hipSetDevice: ") + hipGetErrorString(e);
+        return SUSHI_EDEVICE;
+    }
+    sushi_ctx *c = new (std::nothrow) sushi_ctx();
+    if (!c) return SUSHI_ENOMEM;
+    c->device = device_id;
+    c->stream = static_cast<hipStream_t>(hip_stream);
+    *out = c;
+    return SUSHI_OK;
+}
+
+void sushi_destroy(sushi_ctx *c) {
+    if (!c) return;
+    if (c->device < 0) {
+        delete c;
+        return;
+    }
+    (void)hipSetDevice(c->device);
+    (void)hipStreamSynchronize(c->stream);
+    free_arena(c);
+    if (c->d_weights) (void)hipFree(c->d_weights);
+    if (c->d_params) (void)hipFree(c->d_params);
+    delete c;
+}
+
+const char *sushi_last_error(const sushi_ctx *c) { return c ? c->err.c_str() : g_create_error.c_str(); }
+
+int sushi_load_supernet(sushi_ctx *c, const sushi_arch *arch, const void *weights, size_t nbytes, int dtype) {
+    if (!c) return SUSHI_EINVAL;
+    if (c->device < 0) return fail(c, SUSHI_ESTATE, "load: host-only context");
+    if (!arch || !weights) return fail(c, SUSHI_EINVAL, "load: null argument");
+    if (dtype != SUSHI_FP32 && dtype != SUSHI_BF16) return fail(c, SUSHI_EINVAL, "load: unknown compute dtype");
+    SuperNet sn;
+    std::string err;
+    int rc = build_supernet(*arch, sn, err);
+    if (rc) return fail(c, rc, err);
+    if (nbytes != sn.blob_floats * sizeof(float))
+        return fail(c, SUSHI_EINVAL, "load: blob holds " + std::to_string(nbytes) + " bytes, the SuperNet needs " +
+                                         std::to_string(sn.blob_floats * sizeof(float)));
+    hipError_t e;
+    if ((e = hipSetDevice(c->device)) != hipSuccess) return hip_fail(c, e, "hipSetDevice");
+    if ((e = hipStreamSynchronize(c->stream)) != hipSuccess) return hip_fail(c, e, "hipStreamSynchronize");
+    // drop whatever was loaded before
+    free_arena(c);
+    c->plans.clear();
+    if (c->d_weights) (void)hipFree(c->d_weights);
+    if (c->d_params) (void)hipFree(c->d_params);
+    c->d_weights = nullptr, c->d_params = nullptr, c->loaded = false;
+    c->G.clear();
+    ++c->g_version;
+    c->stats = sushi_stats{};
+
+    const float *blob = static_cast<const float *>(weights);
+    std::vector<float> params;
+    size_t wbytes = 0;
+    const void *wsrc = nullptr;
+    std::vector<uint16_t> w16;
+    std::vector<float> w32;
+    try {
+        if (dtype == SUSHI_BF16) {
+            pack_weights<uint16_t>(sn, blob, w16, params, to_bf16);
+            wbytes = w16.size() * 2, wsrc = w16.data();
+        } else {
+            pack_weights<float>(sn, blob, w32, params, [](float f) { return f; });
+            wbytes = w32.size() * 4, wsrc = w32.data();
+        }
+    } catch (const std::bad_alloc &) {
+        return fail(c, SUSHI_ENOMEM, "load: host staging allocation failed");
+    }
+    if ((e = hipMalloc(&c->d_weights, std::max<size_t>(wbytes, 256))) != hipSuccess)
+        return fail(c, SUSHI_ENOMEM, "load: hipMalloc(weights)");
+    if ((e = hipMalloc(reinterpret_cast<void **>(&c->d_params), std::max<size_t>(params.size() * 4, 256))) !=
+        hipSuccess)
+        return fail(c, SUSHI_ENOMEM, "load: hipMalloc(params)");
+    if ((e = hipMemcpy(c->d_weights, wsrc, wbytes, hipMemcpyHostToDevice)) != hipSuccess)
+        return hip_fail(c, e, "hipMemcpy(weights)");
+    if ((e = hipMemcpy(c->d_params, params.data(), params.size() * 4, hipMemcpyHostToDevice)) != hipSuccess)
+        return hip_fail(c, e, "hipMemcpy(params)");
+    c->sn = std::move(sn);
+    c->bf16 = dtype == SUSHI_BF16;
+    c->weight_elems = wbytes / (c->bf16 ? 2 : 4);
+    c->loaded = true;
+    return SUSHI_OK;
+}
+
+int sushi_set_subgraph_cache(sushi_ctx *c, const sushi_subgraph_cfg *g, size_t budget_bytes) {
+    if (!c) return SUSHI_EINVAL;
+    if (!c->loaded) return fail(c, SUSHI_ESTATE, "set_subgraph_cache before load_supernet");
+    if (!g || g->n_layers == 0) {
+        c->G.clear();
+        ++c->g_version;
+        c->stats.cache_bytes = 0;
+        return SUSHI_OK;
+    }
+    if (g->n_layers != (int)c->sn.layers.size() || !g->layers)
+        return fail(c, SUSHI_EINVAL, "SubGraph must list all " + std::to_string(c->sn.layers.size()) + " layers");
+    uint64_t bytes = 0;
+    for (int i = 0; i < g->n_layers; ++i) {
+        const sushi_layer_dims &d = g->layers[i];
+        const SuperLayer &L = c->sn.layers[i];
+        if (d.K == 0) continue;
+        if (d.K < 0 || d.K > L.Kmax || d.C < 1 || d.C > L.Cmax || d.r < 1 || d.r > L.Rmax || (d.r & 1) == 0)
+            return fail(c, SUSHI_EINVAL, "SubGraph box of layer " + L.name + " lies outside the SuperNet");
+        bytes += (uint64_t)d.K * d.C * d.r * d.r * elem_size(c);
+    }
+    if (bytes > budget_bytes)
+        return fail(c, SUSHI_EBUDGET, "SubGraph needs " + std::to_string(bytes) + " bytes, budget is " +
+                                          std::to_string(budget_bytes));
+    c->G.assign(g->layers, g->layers + g->n_layers);
+    for (sushi_layer_dims &d : c->G)
+        if (d.K == 0) d = sushi_layer_dims{0, 0, 0};
+    ++c->g_version;
+    c->stats.cache_installs += 1;
+    c->stats.cache_bytes_installed += bytes;
+    c->stats.cache_bytes = bytes;
+    return SUSHI_OK;
+}
+
+int sushi_infer(sushi_ctx *c, const sushi_subnet_cfg *cfg, const void *input_dev, int batch, void *logits_dev) {
+    if (!c) return SUSHI_EINVAL;
+    if (!c->loaded) return fail(c, SUSHI_ESTATE, "infer before load_supernet");
+    if (!cfg || !input_dev || !logits_dev || batch < 1) return fail(c, SUSHI_EINVAL, "infer: bad argument");
+    hipError_t e;
+    if ((e = hipSetDevice(c->device)) != hipSuccess) return hip_fail(c, e, "hipSetDevice");
+    CachedPlan *cp = nullptr;
+    const std::string key = plan_key(*cfg, batch);
+    auto it = c->plans.find(key);
+    if (it != c->plans.end() && batch <= c->arena_batch) {
+        cp = it->second.get();
+        c->stats.plan_cache_hits++;
+    } else {
+        std::unique_ptr<CachedPlan> np(new (std::nothrow) CachedPlan());
+        if (!np) return fail(c, SUSHI_ENOMEM, "infer: plan allocation failed");
+        std::string err;
+        int rc = plan_subnet(c->sn, *cfg, batch, np->plan, err);
+        if (rc) return fail(c, rc, err);
+        if ((rc = ensure_arena(c, batch)) != SUSHI_OK) return rc;
+        bind_plan(c, *np);
+        cp = np.get();
+        c->plans[key] = std::move(np);
+        c->stats.plan_cache_misses++;
+    }
+    refresh_residency(c, *cp);
+
+    for (Launch &L : cp->launches) {
+        switch (L.kind) {
+            case OP_CONV:
+            case OP_FC: {
+                ConvArgs a = L.conv;
+                if (L.in_patch) a.x = input_dev;
+                if (L.out_patch) a.y = logits_dev;
+                e = launch_conv(a, c->bf16, c->stream);
+                break;
+            }
+            case OP_DW:
+                e = launch_dwconv(L.conv, c->bf16, c->stream);
+                break;
+            case OP_MAXPOOL:
+                e = launch_maxpool(L.pool, c->bf16, c->stream);
+                break;
+            case OP_GAP:
+                e = launch_gap(L.pool, c->bf16, c->stream);
+                break;
+            case OP_GATE:
+                e = launch_gate(L.pool, c->bf16, c->stream);
+                break;
+            default:
+                e = hipErrorInvalidValue;
+        }
+        if (e != hipSuccess) return hip_fail(c, e, "kernel launch");
+    }
+    sushi_stats &s = c->stats;
+    s.queries++;
+    s.weight_bytes_total += cp->weight_bytes;
+    s.weight_bytes_resident += cp->resident_bytes;
+    s.last_weight_bytes = cp->weight_bytes;
+    s.last_resident_bytes = cp->resident_bytes;
+    s.last_hit_ratio = cp->hit_ratio;
+    s.sum_hit_ratio += cp->hit_ratio;
+    return SUSHI_OK;
+}
+
+int sushi_sched_init(sushi_ctx *c, const sushi_sched_desc *d) {
+    if (!c) return SUSHI_EINVAL;
+    if (!d) return fail(c, SUSHI_EINVAL, "sched_init: null descriptor");
+    std::string err;
+    int rc = c->sched.init(*d, err);
+    return rc ? fail(c, rc, err) : SUSHI_OK;
+}
+
+int sushi_sched_step(sushi_ctx *c, float acc_target, float lat_target, int *subnet_idx_out, int *new_cache_idx_out) {
+    if (!c) return SUSHI_EINVAL;
+    if (!c->sched.ready()) return fail(c, SUSHI_ESTATE, "sched_step before sched_init");
+    if (!subnet_idx_out || !new_cache_idx_out) return fail(c, SUSHI_EINVAL, "sched_step: null output");
+    const int i = c->sched.select(acc_target, lat_target);
+    *subnet_idx_out = i;
+    *new_cache_idx_out = c->sched.record(c->sched.subnet_vec(i));
+    return SUSHI_OK;
+}
+
+int sushi_sched_record(sushi_ctx *c, const int32_t *vec, int *new_cache_idx_out) {
+    if (!c) return SUSHI_EINVAL;
+    if (!c->sched.ready()) return fail(c, SUSHI_ESTATE, "sched_record before sched_init");
+    if (!vec || !new_cache_idx_out) return fail(c, SUSHI_EINVAL, "sched_record: null argument");
+    *new_cache_idx_out = c->sched.record(vec);
+    return SUSHI_OK;
+}
+
+int sushi_get_stats(sushi_ctx *c, sushi_stats *out) {
+    if (!c || !out) return SUSHI_EINVAL;
+    *out = c->stats;
+    return SUSHI_OK;
+}
+
+int sushi_set_option(sushi_ctx *c, int option, int64_t value) {
+    if (!c) return SUSHI_EINVAL;
+    if (option == SUSHI_OPT_EXEC_MODE && (value == 0 || value == 1)) {
+        c->exec_mode = (int)value;
+        return SUSHI_OK;
+    }
+    return fail(c, SUSHI_EINVAL, "set_option: unknown option or value");
+}
+
+}  // extern "C"

@@ -1,0 +1,167 @@
+"""CPU-only checks of the library's host side: it loads, exports what include/sushi.h declares,
+lists the same SuperNet tensors and SubNet slices as the oracle, and its scheduler takes exactly
+the oracle scheduler's decisions.  No compute call is made."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2306_17266_amd as S
+from oracle import subnet_eval as E
+from oracle.sched_ref import STRICT_ACCURACY, STRICT_LATENCY, SchedRef
+from paper_2306_17266_amd import binding
+from workloads import arch as A
+from workloads import streams
+from workloads.rng import Stream
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+ALL_ARCHS = [A.tiny_arch, A.small_resnet_arch, A.small_mbv3_arch, A.resnet_arch, A.mbv3_arch]
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "sushi.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = sorted(set(re.findall(r"\b(sushi_[a-z_]+)\s*\(", header)))
+    assert len(names) >= 12 and "sushi_infer" in names and "sushi_load_supernet" in names
+    lib = ctypes.CDLL(binding.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+@pytest.mark.parametrize("mk", ALL_ARCHS)
+def test_tensor_table_and_slices_match_the_oracle(mk):
+    arch = mk()
+    assert S.sushi_describe_supernet(arch) == [(n, tuple(s), k) for n, s, k in E.supernet_tensors(arch)]
+    st = Stream(5)
+    cfgs = [A.min_cfg(arch), A.max_cfg(arch)] + [streams.uniform_cfg(arch, st) for _ in range(40)]
+    for cfg in cfgs:
+        assert S.sushi_subnet_layers(arch, cfg) == E.subnet_box(arch, cfg)
+
+
+def test_invalid_subnets_are_rejected():
+    arch = A.resnet_arch()
+    for mutate in (lambda c: c.depth.__setitem__(2, 7), lambda c: c.depth.__setitem__(0, 1),
+                   lambda c: c.expand_idx.__setitem__(3, 3), lambda c: c.width_idx.__setitem__(0, -1),
+                   lambda c: setattr(c, "resolution", 200)):
+        cfg = A.max_cfg(arch)
+        mutate(cfg)
+        assert not E.check_cfg(arch, cfg)
+        with pytest.raises(S.SushiError) as e:
+            S.sushi_subnet_layers(arch, cfg)
+        assert e.value.code == -1
+    bad = A.resnet_arch()
+    bad.stage_base_out[1] = 4
+    with pytest.raises(S.SushiError):
+        S.sushi_describe_supernet(bad)
+
+
+def test_host_only_context_refuses_device_work():
+    ctx = S.Sushi(-1)
+    with pytest.raises(S.SushiError) as e:
+        ctx.sushi_load_supernet(A.tiny_arch(), np.zeros(29098, np.float32), S.FP32)
+    assert e.value.code == -3
+    with pytest.raises(S.SushiError) as e:
+        ctx.sushi_sched_step(0.0, 0.0)
+    assert e.value.code == -3
+    ctx.close()
+
+
+def _random_problem(seed, n, m, length):
+    st = Stream(seed)
+    v = [[8 * st.randint(9) for _ in range(length)] for _ in range(n)]
+    g = [[8 * st.randint(9) for _ in range(length)] for _ in range(m)]
+    acc = [float(np.float32(0.6 + 0.3 * st.next_uniform())) for _ in range(n)]
+    table = [[float(np.float32(1.0 + 9.0 * st.next_uniform())) for _ in range(m + 1)] for _ in range(n)]
+    return v, acc, g, table
+
+
+@pytest.mark.parametrize("policy", [STRICT_ACCURACY, STRICT_LATENCY])
+@pytest.mark.parametrize("Q", [1, 3, 8])
+def test_scheduler_decisions_match_the_oracle_exactly(policy, Q):
+    for seed in range(4):
+        v, acc, g, table = _random_problem(seed, 7, 9, 12)
+        for init in (-1, 2):
+            ref = SchedRef(v, acc, g, table, Q, policy, init)
+            ctx = S.Sushi(-1)
+            ctx.sushi_sched_init(v, acc, g, table, Q, policy, init)
+            st = Stream(1000 + seed)
+            for _ in range(60):
+                a_t = float(np.float32(0.55 + 0.4 * st.next_uniform()))
+                l_t = float(np.float32(12.0 * st.next_uniform()))
+                assert ctx.sushi_sched_step(a_t, l_t) == ref.step(a_t, l_t)
+            ctx.close()
+
+
+def _served_stream(name):
+    """(arch, list of served SubnetCfg, Q) for the named-SubNet streams of configurations 1, 2, 3, 5."""
+    if name == "cfg1":
+        arch = A.tiny_arch()
+        return arch, streams.stream_uniform(arch, 8, 1), 4
+    if name == "cfg2":
+        arch = A.resnet_arch()
+        return arch, streams.stream_sticky(arch, 1000, 2), 8
+    arch = A.mbv3_arch()
+    pool = streams.subnet_pool(arch, 32, 3)
+    if name == "cfg3":
+        return arch, [pool[i] for i, _ in streams.stream_zipf(32, 1000, 3)], 10
+    picks = streams.stream_zipf(32, 2000, 5, regime=500, resolutions=[160, 192, 224])
+    return arch, [streams.with_resolution(pool[i], r) for i, r in picks], 10
+
+
+@pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3", "cfg5"])
+def test_cache_choices_match_the_oracle_on_the_configured_streams(name):
+    arch, cfgs, Q = _served_stream(name)
+    distinct = {c.key(): c for c in cfgs}
+    boxes = [E.subnet_box(arch, c) for c in list(distinct.values())[:40]]
+    budget = 2 * 1024 * 1024 if arch.family != A.FAMILY_TINY else 16 * 1024
+    cands = streams.candidate_subgraphs(boxes, budget, 2, 40)
+    gvecs = [[v for (k, c, r) in b for v in (k, c)] for b in cands]
+    assert len(gvecs) >= 2
+    n = len(gvecs[0])
+    dummy_v, dummy_acc = [[0] * n], [0.0]
+    table = [[1.0] * (len(gvecs) + 1)]
+    ref = SchedRef(dummy_v, dummy_acc, gvecs, table, Q, STRICT_LATENCY)
+    ctx = S.Sushi(-1)
+    ctx.sushi_sched_init(dummy_v, dummy_acc, gvecs, table, Q, S.STRICT_LATENCY)
+    changes = 0
+    for cfg in cfgs:
+        vec_lib = [v for (k, c, r) in S.sushi_subnet_layers(arch, cfg) for v in (k, c)]
+        vec_ref = E.encode_vector(arch, cfg)
+        assert vec_lib == vec_ref
+        a, b = ctx.sushi_sched_record(vec_lib), ref.record(vec_ref)
+        assert a == b
+        changes += a >= 0
+    assert changes == len(cfgs) // Q
+    ctx.close()
+
+
+def test_latency_target_stream_matches_the_oracle():
+    """Configuration 4's policy: latency targets drawn from 5 levels, STRICT_LATENCY, synthetic
+    accuracies increasing with SubNet size, synthetic table."""
+    arch = A.resnet_arch()
+    pool = streams.subnet_pool(arch, 16, 4)
+    boxes = [E.subnet_box(arch, c) for c in pool]
+    sizes = [E.weight_count(b) for b in boxes]
+    order = np.argsort(sizes)
+    acc = [0.0] * 16
+    for rank, i in enumerate(order):
+        acc[i] = float(np.float32(0.70 + 0.01 * rank))
+    cands = streams.candidate_subgraphs(boxes, 64 * 1024 * 1024, 2, 40)
+    gvecs = [[v for (k, c, r) in b for v in (k, c)] for b in cands]
+    vecs = [E.encode_vector(arch, c) for c in pool]
+    table = [[float(np.float32(1e-6 * 2 * (sizes[i] - E.weight_count(E.intersect(boxes[i], g)) + 0.1 * sizes[i])))
+              for g in cands] + [float(np.float32(1e-6 * 2 * 1.1 * sizes[i]))] for i in range(16)]
+    lo, hi = min(r[-1] for r in table), max(r[-1] for r in table)
+    levels = [float(np.float32(lo + (hi - lo) * k / 4)) for k in range(5)]
+    ref = SchedRef(vecs, acc, gvecs, table, 8, STRICT_LATENCY)
+    ctx = S.Sushi(-1)
+    ctx.sushi_sched_init(vecs, acc, gvecs, table, 8, S.STRICT_LATENCY)
+    served = set()
+    for lv in streams.stream_levels(5, 2000, 4):
+        got = ctx.sushi_sched_step(0.0, levels[lv])
+        assert got == ref.step(0.0, levels[lv])
+        served.add(got[0])
+    assert len(served) >= 3
+    ctx.close()
