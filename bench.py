@@ -1,0 +1,205 @@
+"""Benchmark of the SubNet-stream hot path on one MI355X.
+
+One step = one query: the scheduler's cache bookkeeping (sushi_sched_record, and
+sushi_set_subgraph_cache when the cached SubGraph changes) plus sushi_infer of the query's SubNet
+on one input batch that already sits in HBM.  The default workload is the ResNet50-shaped
+SuperNet at batch 1 with the sticky 1000-query stream (next SubNet repeats with p = 0.8).
+
+Prints ONE JSON line: queries/s over the timed steps, plus
+  roofline      the kernel family with the largest summed time, measured with HIP events around
+                every launch in a second, identical pass over the same steps;
+  cpu_baseline  the CPU oracle timed on a bounded sample of the same stream.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def build_workload(name):
+    from workloads import arch as A
+    from workloads import streams
+    if name == "resnet_bs1_sticky":
+        arch = A.resnet_arch()
+        return dict(arch=arch, batch=1, cfgs=streams.stream_sticky(arch, 1000, 2, 0.8, 224), Q=8,
+                    budget=16 << 20, desc="ResNet50-shaped SuperNet, bf16, batch 1, 224x224, 1000-query stream, "
+                    "next SubNet repeats with p=0.8 else uniform, cache re-chosen every 8 queries, budget 16 MiB")
+    if name == "mbv3_bs1_zipf":
+        arch = A.mbv3_arch()
+        pool = streams.subnet_pool(arch, 32, 3, 224)
+        cfgs = [pool[i] for i, _ in streams.stream_zipf(32, 1000, 3, 1.2)]
+        return dict(arch=arch, batch=1, cfgs=cfgs, Q=10, budget=4 << 20,
+                    desc="MobileNetV3-shaped SuperNet, bf16, batch 1, 224x224, 1000-query stream, Zipf(1.2) over a "
+                    "pool of 32 SubNets, cache re-chosen every 10 queries, budget 4 MiB")
+    if name == "resnet_bs16_levels":
+        arch = A.resnet_arch()
+        pool = streams.subnet_pool(arch, 16, 4, 224)
+        lv = streams.stream_levels(5, 2000, 4)
+        # without a measured latency table the level picks a SubNet of the pool by size rank
+        return dict(arch=arch, batch=16, cfgs=None, pool=pool, levels=lv, Q=8, budget=64 << 20,
+                    desc="ResNet50-shaped SuperNet, bf16, batch 16, 224x224, 2000-query stream, SubNet picked by "
+                    "a latency target drawn from 5 levels (table = weight bytes not cached), budget 64 MiB")
+    raise SystemExit("unknown workload %r" % name)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=50)
+    ap.add_argument("--workload", default="resnet_bs1_sticky")
+    ap.add_argument("--exec-mode", type=int, default=1, help="0 = launch per layer, 1 = HIP graph replay")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-roofline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        raise SystemExit("bench.py: this build runs on ONE GPU; --gpus %d is not supported "
+                         "(queries would shard by replica, see DESIGN.md)" % args.gpus)
+
+    import numpy as np
+    import torch
+
+    import paper_2306_17266_amd as S
+    from workloads import tensors as T
+
+    wl = build_workload(args.workload)
+    arch, batch, Q, budget = wl["arch"], wl["batch"], wl["Q"], wl["budget"]
+    table = S.sushi_describe_supernet(arch)
+    tensors = T.make_weights([(s, k) for _, s, k in table], 1, True)
+    ctx = S.Sushi(0)
+    ctx.sushi_load_supernet(arch, T.flatten(tensors), S.BF16)
+
+    # the stream, each SubNet's vector/box (library's encoder) and the candidate SubGraphs
+    from workloads import streams
+    if wl["cfgs"] is None:
+        pool = wl["pool"]
+        boxes = [S.sushi_subnet_layers(arch, c) for c in pool]
+        order = sorted(range(len(pool)), key=lambda i: streams.box_bytes(boxes[i], 2))
+        pick = [order[(lv * (len(pool) - 1)) // 4] for lv in range(5)]
+        cfgs = [pool[pick[lv]] for lv in wl["levels"]]
+    else:
+        cfgs = wl["cfgs"]
+    distinct = {}
+    for c in cfgs:
+        distinct.setdefault(c.key(), c)
+    box_of = {k: S.sushi_subnet_layers(arch, c) for k, c in distinct.items()}
+    vec_of = {k: np.array([v for (kk, cc, r) in b for v in (kk, cc)], dtype=np.int32) for k, b in box_of.items()}
+    cands = streams.candidate_subgraphs(list(box_of.values()), budget, 2, 40)
+    gvecs = [[v for (k, c, r) in b for v in (k, c)] for b in cands]
+    n = len(gvecs[0])
+    ctx.sushi_sched_init([[0] * n], [0.0], gvecs, [[1.0] * (len(gvecs) + 1)], Q, S.STRICT_LATENCY)
+
+    n_inputs = 8
+    res = cfgs[0].resolution
+    xs = [torch.from_numpy(T.make_input(11, t, batch, res, arch.in_channels, True)).cuda().to(torch.bfloat16)
+          for t in range(n_inputs)]
+    logits = torch.empty(batch, arch.n_classes, device="cuda", dtype=torch.float32)
+    state = {"cache": -1, "t": 0}
+
+    def step():
+        t = state["t"]
+        cfg = cfgs[t % len(cfgs)]
+        ctx.sushi_infer(cfg, xs[t % n_inputs], logits)
+        j = ctx.sushi_sched_record(vec_of[cfg.key()])
+        if j >= 0 and j != state["cache"]:
+            ctx.sushi_set_subgraph_cache(cands[j], budget)
+            state["cache"] = j
+        state["t"] = t + 1
+
+    ctx.sushi_set_option(S.OPT_EXEC_MODE, args.exec_mode)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t_start = state["t"]
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    elapsed = t1 - t0
+    stats = ctx.sushi_get_stats()
+
+    # p50 latency: the same steps one at a time, each followed by a synchronize
+    lat = []
+    state["t"] = t_start
+    for _ in range(min(args.steps, 300)):
+        a = time.perf_counter()
+        step()
+        torch.cuda.synchronize()
+        lat.append(time.perf_counter() - a)
+    p50_ms = float(np.median(lat) * 1e3)
+
+    roofline = None
+    if not args.no_roofline:
+        # identical pass with HIP events around every launch (launch-per-layer mode)
+        ctx.sushi_set_option(S.OPT_EXEC_MODE, 0)
+        state["t"] = t_start
+        for _ in range(20):
+            step()
+        torch.cuda.synchronize()
+        state["t"] = t_start
+        ctx.sushi_set_option(S.OPT_KERNEL_TIMING, 1)
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        ks = [k for k in ctx.sushi_get_kernel_stats() if k["launches"]]
+        ctx.sushi_set_option(S.OPT_KERNEL_TIMING, 0)
+        dom = max(ks, key=lambda k: k["total_ms"])
+        sec = dom["total_ms"] * 1e-3
+        ai = dom["flops"] / dom["bytes"]
+        if ai >= MFMA_BF16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9) and dom["name"].startswith("conv_mfma"):
+            achieved, peak, unit, bound = dom["flops"] / sec / 1e12, MFMA_BF16_PEAK_TFLOPS, "TFLOP/s", "mfma"
+        else:
+            achieved, peak, unit, bound = dom["bytes"] / sec / 1e9, HBM_PEAK_GBS, "GB/s", "hbm"
+        roofline = {"bound": bound, "achieved": achieved, "peak": peak, "unit": unit, "frac": achieved / peak,
+                    "traffic": None, "kernel": dom["name"], "launches": dom["launches"],
+                    "avg_launch_us": dom["total_ms"] * 1e3 / dom["launches"],
+                    "alg_bytes_per_launch": dom["bytes"] / dom["launches"],
+                    "alg_flops_per_launch": dom["flops"] / dom["launches"],
+                    "share_of_kernel_time": dom["total_ms"] / sum(k["total_ms"] for k in ks),
+                    "all_kernels": {k["name"]: {"launches": k["launches"], "avg_us": k["total_ms"] * 1e3 / k["launches"],
+                                                "GBps": k["bytes"] / (k["total_ms"] * 1e-3) / 1e9,
+                                                "TFLOPps": k["flops"] / (k["total_ms"] * 1e-3) / 1e12} for k in ks}}
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import subnet_eval as E
+        wts = E.name_weights(arch, tensors)
+        n_sample = 16 if batch == 1 else 2
+        sample = [cfgs[(t_start + i * 7) % len(cfgs)] for i in range(n_sample)]
+        x0 = np.ascontiguousarray(T.make_input(11, 0, batch, res, arch.in_channels, True).transpose(0, 3, 1, 2))
+        E.forward(arch, wts, sample[0], x0)
+        c0 = time.perf_counter()
+        for cfg in sample:
+            E.forward(arch, wts, cfg, x0)
+        c1 = time.perf_counter()
+        cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+        cpu = {"value": n_sample / (c1 - c0), "unit": "queries/s", "cores": cores, "kind": "oracle",
+               "sample": "%d queries of the same stream (every 7th from the first timed step), batch %d, "
+                         "%.1f s of CPU work" % (n_sample, batch, c1 - c0)}
+
+    out = {"metric": "SubNet queries/sec (batch %d)" % batch, "value": args.steps / elapsed, "unit": "queries/s",
+           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": elapsed / args.steps * 1e3,
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": args.workload, "description": wl["desc"], "exec_mode": args.exec_mode,
+                      "distinct_subnets": len(distinct), "candidate_subgraphs": len(cands)},
+           "p50_latency_ms": p50_ms,
+           "weight_bytes_per_query": stats["weight_bytes_total"] / max(1, stats["queries"]),
+           "weight_bytes_per_query_resident": stats["weight_bytes_resident"] / max(1, stats["queries"]),
+           "mean_hit_ratio": stats["sum_hit_ratio"] / max(1, stats["queries"]),
+           "cache_installs": stats["cache_installs"],
+           "roofline": roofline, "cpu_baseline": cpu}
+    print(json.dumps(out))
+    ctx.close()
+
+
+if __name__ == "__main__":
+    main()

@@ -232,9 +232,23 @@ int sushi_sched_record(sushi_ctx *ctx, const int32_t *vec, int *new_cache_idx_ou
 int sushi_get_stats(sushi_ctx *ctx, sushi_stats *out);
 
 typedef enum {
-    SUSHI_OPT_EXEC_MODE = 0 /* 0 = one launch per layer (default), 1 = replay a HIP graph per SubNet */
+    SUSHI_OPT_EXEC_MODE = 0,    /* 0 = one launch per layer (default), 1 = replay a HIP graph per SubNet */
+    SUSHI_OPT_KERNEL_TIMING = 1 /* 1 = bracket every launch with HIP events on the context's stream and
+                                   accumulate per kernel family (mode 0 only); setting 1 clears the totals */
 } sushi_option;
 int sushi_set_option(sushi_ctx *ctx, int option, int64_t value);
+
+/* Per kernel family: launches timed, their summed duration, and the algorithmic bytes and flops
+ * they processed (every input, output, residual, weight and scale/shift element of the active
+ * slice counted once).  Waits for outstanding timed launches.  Writes min(n, cap) entries. */
+typedef struct sushi_kernel_stats {
+    char name[32];
+    uint64_t launches;
+    double total_ms;
+    double bytes;
+    double flops;
+} sushi_kernel_stats;
+int sushi_get_kernel_stats(sushi_ctx *ctx, sushi_kernel_stats *out, int cap, int *n_out);
 
 #ifdef __cplusplus
 }

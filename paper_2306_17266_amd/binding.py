@@ -12,6 +12,7 @@ MAX_STAGES, MAX_CHOICES, MAX_BLOCKS = 8, 4, 32
 FP32, BF16 = 0, 1
 STRICT_ACCURACY, STRICT_LATENCY = 0, 1
 OPT_EXEC_MODE = 0
+OPT_KERNEL_TIMING = 1
 
 
 class SushiError(RuntimeError):
@@ -68,6 +69,11 @@ class CStats(C.Structure):
                 ("plan_cache_hits", C.c_uint64), ("plan_cache_misses", C.c_uint64)]
 
 
+class CKernelStats(C.Structure):
+    _fields_ = [("name", C.c_char * 32), ("launches", C.c_uint64), ("total_ms", C.c_double),
+                ("bytes", C.c_double), ("flops", C.c_double)]
+
+
 _lib = None
 
 
@@ -96,6 +102,7 @@ def lib():
     L.sushi_sched_record.argtypes = [vp, C.POINTER(C.c_int32), ip]
     L.sushi_get_stats.argtypes = [vp, C.POINTER(CStats)]
     L.sushi_set_option.argtypes = [vp, C.c_int, C.c_int64]
+    L.sushi_get_kernel_stats.argtypes = [vp, C.POINTER(CKernelStats), C.c_int, ip]
     _lib = L
     return L
 
@@ -246,3 +253,9 @@ class Sushi:
 
     def sushi_set_option(self, option, value):
         _check(lib().sushi_set_option(self._h, option, value), self._h)
+
+    def sushi_get_kernel_stats(self):
+        buf, n = (CKernelStats * 16)(), C.c_int(0)
+        _check(lib().sushi_get_kernel_stats(self._h, buf, 16, C.byref(n)), self._h)
+        return [dict(name=buf[i].name.decode(), launches=buf[i].launches, total_ms=buf[i].total_ms,
+                     bytes=buf[i].bytes, flops=buf[i].flops) for i in range(n.value)]

@@ -42,8 +42,22 @@ struct PoolArgs {
     int B, H, W, C, P, Q;
 };
 
+// Kernel families, for per-kernel accounting.
+enum KernelClass {
+    KC_CONV_DIRECT = 0,   // conv_direct_kernel
+    KC_CONV_MFMA = 1,     // conv_mfma_kernel (whole-reduction waves)
+    KC_CONV_SPLITK = 2,   // conv_mfma_splitk_kernel
+    KC_DWCONV = 3,
+    KC_MAXPOOL = 4,
+    KC_GAP = 5,
+    KC_GATE = 6,
+    KC_COUNT = 7
+};
+const char *kernel_class_name(int kc);
+
 // Every launcher returns hipSuccess or the launch error.  bf16 = activations and weights are bf16.
-hipError_t launch_conv(const ConvArgs &a, bool bf16, hipStream_t s);      // dense conv and FC
+// launch_conv reports the kernel family it picked in *kc (may be null).
+hipError_t launch_conv(const ConvArgs &a, bool bf16, hipStream_t s, int *kc);  // dense conv and FC
 hipError_t launch_dwconv(const ConvArgs &a, bool bf16, hipStream_t s);
 hipError_t launch_maxpool(const PoolArgs &a, bool bf16, hipStream_t s);   // 3x3 stride 2 pad 1
 hipError_t launch_gap(const PoolArgs &a, bool bf16, hipStream_t s);       // [B][H][W][C] -> [B][C]

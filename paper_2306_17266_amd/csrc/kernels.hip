@@ -10,6 +10,8 @@
 // work on the vector ALUs with 16- or 32-byte accesses per lane.
 #include "kernels.h"
 
+#include <algorithm>
+
 namespace sushi {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
@@ -141,16 +143,62 @@ __global__ __launch_bounds__(256) void conv_direct_kernel(ConvArgs a) {
 }
 
 // ------------------------------------------------------------------ dense conv, bf16 matrix cores
-// Workgroup = WF x WP x WK waves.  A wave owns FT filter tiles x PT pixel tiles of 16 x 16 and, when
-// WK > 1, every WK-th step of the reduction (taps x 32-channel chunks); the WK partial sums are added
-// in a fixed order through LDS, so results do not depend on timing.
 
-template <int FT, int PT, int WF, int WP, int WK>
-__global__ __launch_bounds__(64 * WF * WP * WK) void conv_mfma_kernel(ConvArgs a) {
-    constexpr int NW = WF * WP * WK;
+union Frag {
+    uint4 u;
+    bf16x8_t v;
+};
+
+// Epilogue of one 16 x 16 accumulator tile: the lane holds pixel m and filters fbase .. fbase+3.
+// y = act(scale * acc + shift (+ res)), stored channels-last as bf16 or float32.
+__device__ __forceinline__ void store_tile(const ConvArgs &a, const f32x4_t acc, int fbase, int m, int M) {
+    if (fbase >= a.K || m >= M) return;
+    const int nf = min(4, a.K - fbase);
+    const bool vec = nf == 4 && (a.K & 3) == 0;
+    const long o = (long)m * a.K + fbase;
+    float v[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const float sc = (a.scale && i < nf) ? a.scale[fbase + i] : 1.0f;
+        const float sh = i < nf ? a.shift[fbase + i] : 0.0f;
+        v[i] = acc[i] * sc + sh;
+    }
+    if (a.res) {
+        const uint16_t *rp = static_cast<const uint16_t *>(a.res) + o;
+        if (vec) {
+            const uint2 r = *reinterpret_cast<const uint2 *>(rp);
+            v[0] += bf2f(r.x & 0xFFFFu), v[1] += bf2f(r.x >> 16), v[2] += bf2f(r.y & 0xFFFFu), v[3] += bf2f(r.y >> 16);
+        } else {
+            for (int i = 0; i < nf; ++i) v[i] += bf2f(rp[i]);
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v[i] = activate(v[i], a.act, a.hsigmoid);
+    if (a.out_f32) {
+        float *yp = static_cast<float *>(a.y) + o;
+        if (vec)
+            *reinterpret_cast<float4 *>(yp) = make_float4(v[0], v[1], v[2], v[3]);
+        else
+            for (int i = 0; i < nf; ++i) yp[i] = v[i];
+    } else {
+        uint16_t *yp = static_cast<uint16_t *>(a.y) + o;
+        if (vec) {
+            uint2 r;
+            r.x = f2bf(v[0]) | (f2bf(v[1]) << 16), r.y = f2bf(v[2]) | (f2bf(v[3]) << 16);
+            *reinterpret_cast<uint2 *>(yp) = r;
+        } else {
+            for (int i = 0; i < nf; ++i) yp[i] = (uint16_t)f2bf(v[i]);
+        }
+    }
+}
+
+// Large problems (many pixels): workgroup = WF x WP waves, a wave owns FT x PT tiles of 16 x 16 and
+// walks the whole reduction (taps x 32-channel chunks).
+template <int FT, int PT, int WF, int WP>
+__global__ __launch_bounds__(64 * WF * WP) void conv_mfma_kernel(ConvArgs a) {
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
-    const int wk = wave % WK, wp = (wave / WK) % WP, wf = wave / (WK * WP);
+    const int wp = wave % WP, wf = wave / WP;
     const int l16 = lane & 15, kg = lane >> 4;
     const int M = a.B * a.P * a.Q;
     const int n_ptiles = (M + 16 * PT * WP - 1) / (16 * PT * WP);
@@ -179,108 +227,149 @@ __global__ __launch_bounds__(64 * WF * WP * WK) void conv_mfma_kernel(ConvArgs a
         for (int pt = 0; pt < PT; ++pt) acc[ft][pt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
     const int csteps = (a.C + 31) >> 5;
-    const int nsteps = a.R * a.R * csteps;
-    for (int step = wk; step < nsteps; step += WK) {
-        const int tap = step / csteps;
-        const int c0 = (step - tap * csteps) * 32 + kg * 8;
+    for (int tap = 0; tap < a.R * a.R; ++tap) {
         const int dr = tap / a.R, ds = tap - dr * a.R;
-        const bool cv = c0 < a.C;
-        union {
-            uint4 u;
-            bf16x8_t v;
-        } fa[FT], fb[PT];
-#pragma unroll
-        for (int ft = 0; ft < FT; ++ft) {
-            const int f = f0 + ft * 16 + l16;
-            fa[ft].u = make_uint4(0, 0, 0, 0);
-            if (cv && f < a.Kpad)
-                fa[ft].u = *reinterpret_cast<const uint4 *>(w + (((long)tap * a.CG + (c0 >> 3)) * a.Kpad + f) * 8);
-        }
+        const uint16_t *xp[PT];
+        bool ok[PT];
 #pragma unroll
         for (int pt = 0; pt < PT; ++pt) {
             const int h = ph[pt] + dr, v = pw[pt] + ds;
-            fb[pt].u = make_uint4(0, 0, 0, 0);
-            if (cv && pv[pt] && h >= 0 && h < a.H && v >= 0 && v < a.W)
-                fb[pt].u = *reinterpret_cast<const uint4 *>(x + (((long)pn[pt] * a.H + h) * a.W + v) * a.C + c0);
+            ok[pt] = pv[pt] && h >= 0 && h < a.H && v >= 0 && v < a.W;
+            xp[pt] = x + (((long)pn[pt] * a.H + (ok[pt] ? h : 0)) * a.W + (ok[pt] ? v : 0)) * a.C;
         }
+        for (int cs = 0; cs < csteps; ++cs) {
+            const int c0 = cs * 32 + kg * 8;
+            const bool cv = c0 < a.C;
+            const int cc = cv ? c0 : 0;
+            Frag fa[FT], fb[PT];
 #pragma unroll
-        for (int ft = 0; ft < FT; ++ft)
+            for (int ft = 0; ft < FT; ++ft) {
+                const int f = min(f0 + ft * 16 + l16, a.Kpad - 1);
+                fa[ft].u = *reinterpret_cast<const uint4 *>(w + (((long)tap * a.CG + (cc >> 3)) * a.Kpad + f) * 8);
+            }
 #pragma unroll
-            for (int pt = 0; pt < PT; ++pt)
-                acc[ft][pt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[ft].v, fb[pt].v, acc[ft][pt], 0, 0, 0);
-    }
-
-    if constexpr (WK > 1) {
-        __shared__ float red[NW * FT * PT * 4 * 64];
-        float *mine = red + (long)wave * FT * PT * 4 * 64;
-#pragma unroll
-        for (int ft = 0; ft < FT; ++ft)
-#pragma unroll
-            for (int pt = 0; pt < PT; ++pt)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) mine[((ft * PT + pt) * 4 + i) * 64 + lane] = acc[ft][pt][i];
-        __syncthreads();
-        if (wk != 0) return;
-        for (int k = 1; k < WK; ++k) {
-            const float *other = red + (long)(wave + k) * FT * PT * 4 * 64;
+            for (int pt = 0; pt < PT; ++pt) {
+                fb[pt].u = *reinterpret_cast<const uint4 *>(xp[pt] + cc);
+                if (!(ok[pt] && cv)) fb[pt].u = make_uint4(0, 0, 0, 0);
+            }
 #pragma unroll
             for (int ft = 0; ft < FT; ++ft)
 #pragma unroll
                 for (int pt = 0; pt < PT; ++pt)
+                    acc[ft][pt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[ft].v, fb[pt].v, acc[ft][pt], 0, 0, 0);
+        }
+    }
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) acc[ft][pt][i] += other[((ft * PT + pt) * 4 + i) * 64 + lane];
+    for (int ft = 0; ft < FT; ++ft)
+#pragma unroll
+        for (int pt = 0; pt < PT; ++pt) store_tile(a, acc[ft][pt], f0 + ft * 16 + kg * 4, m0 + pt * 16 + l16, M);
+}
+
+// Small problems (batch-1 layers, FC): latency decides, so the reduction is split over the WK waves
+// of the workgroup (WK = blockDim.x / 64, chosen by the host), every wave issues the loads of U steps
+// before the first MFMA, and the partial sums are added in a fixed order through LDS.  One
+// workgroup computes FT x PT tiles.  Loads are unconditional (addresses clamped into the tensor);
+// masked activations are zeroed afterwards, which also covers the spatial zero padding.
+template <int FT, int PT, int U, int MAXT>
+__global__ __launch_bounds__(MAXT) void conv_mfma_splitk_kernel(ConvArgs a) {
+    extern __shared__ float red[];  // [WK][FT*PT][4][64]
+    const int WK = blockDim.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wk = threadIdx.x >> 6;
+    const int l16 = lane & 15, kg = lane >> 4;
+    const int M = a.B * a.P * a.Q;
+    const int n_pgroups = (M + 16 * PT - 1) / (16 * PT);
+    const int pgroup = blockIdx.x % n_pgroups, ftile = blockIdx.x / n_pgroups;
+    const int f0 = ftile * FT * 16;
+    const int m0 = pgroup * PT * 16;
+    const uint16_t *x = static_cast<const uint16_t *>(a.x);
+    const uint16_t *w = static_cast<const uint16_t *>(a.w);
+
+    int pn[PT], ph[PT], pw[PT];
+    bool pv[PT];
+#pragma unroll
+    for (int pt = 0; pt < PT; ++pt) {
+        const int m = m0 + pt * 16 + l16;
+        pv[pt] = m < M;
+        const int mm = pv[pt] ? m : 0;
+        const int qq = mm % a.Q, pp = (mm / a.Q) % a.P;
+        pn[pt] = mm / (a.Q * a.P);
+        ph[pt] = pp * a.stride - a.pad;
+        pw[pt] = qq * a.stride - a.pad;
+    }
+    int fw[FT];
+#pragma unroll
+    for (int ft = 0; ft < FT; ++ft) fw[ft] = min(f0 + ft * 16 + l16, a.Kpad - 1) * 8;
+
+    f32x4_t acc[FT][PT];
+#pragma unroll
+    for (int ft = 0; ft < FT; ++ft)
+#pragma unroll
+        for (int pt = 0; pt < PT; ++pt) acc[ft][pt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+    const int csteps = (a.C + 31) >> 5;
+    const int nsteps = a.R * a.R * csteps;
+    for (int base = wk; base < nsteps; base += WK * U) {
+        Frag fa[U][FT], fb[U][PT];
+        bool ok[U][PT];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int step = base + u * WK;
+            const bool live = step < nsteps;
+            const int st = live ? step : 0;
+            const int tap = st / csteps;
+            const int c0 = (st - tap * csteps) * 32 + kg * 8;
+            const int dr = tap / a.R, ds = tap - dr * a.R;
+            const bool cv = live && c0 < a.C;
+            const int cc = cv ? c0 : 0;
+            const uint16_t *wp = w + ((long)tap * a.CG + (cc >> 3)) * a.Kpad * 8;
+#pragma unroll
+            for (int ft = 0; ft < FT; ++ft) fa[u][ft].u = *reinterpret_cast<const uint4 *>(wp + fw[ft]);
+#pragma unroll
+            for (int pt = 0; pt < PT; ++pt) {
+                const int h = ph[pt] + dr, v = pw[pt] + ds;
+                ok[u][pt] = cv && pv[pt] && h >= 0 && h < a.H && v >= 0 && v < a.W;
+                const int hh = ok[u][pt] ? h : 0, vv = ok[u][pt] ? v : 0;
+                fb[u][pt].u = *reinterpret_cast<const uint4 *>(x + (((long)pn[pt] * a.H + hh) * a.W + vv) * a.C + cc);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+#pragma unroll
+            for (int pt = 0; pt < PT; ++pt)
+                if (!ok[u][pt]) fb[u][pt].u = make_uint4(0, 0, 0, 0);
+#pragma unroll
+            for (int ft = 0; ft < FT; ++ft)
+#pragma unroll
+                for (int pt = 0; pt < PT; ++pt)
+                    acc[ft][pt] =
+                        __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[u][ft].v, fb[u][pt].v, acc[ft][pt], 0, 0, 0);
         }
     }
 
-    // lane holds, per tile, pixel column l16 and filters kg*4 .. kg*4+3
+    if (WK == 1) {
 #pragma unroll
-    for (int ft = 0; ft < FT; ++ft) {
-        const int fbase = f0 + ft * 16 + kg * 4;
-        if (fbase >= a.K) continue;
-        const int nf = min(4, a.K - fbase);
-        float sc[4], sh[4];
+        for (int ft = 0; ft < FT; ++ft)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            sc[i] = (a.scale && i < nf) ? a.scale[fbase + i] : 1.0f;
-            sh[i] = i < nf ? a.shift[fbase + i] : 0.0f;
-        }
+            for (int pt = 0; pt < PT; ++pt) store_tile(a, acc[ft][pt], f0 + ft * 16 + kg * 4, m0 + pt * 16 + l16, M);
+        return;
+    }
+    constexpr int NT = FT * PT;
 #pragma unroll
-        for (int pt = 0; pt < PT; ++pt) {
-            const int m = m0 + pt * 16 + l16;
-            if (m >= M) continue;
-            const long o = (long)m * a.K + fbase;
-            float v[4];
+    for (int ft = 0; ft < FT; ++ft)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) v[i] = acc[ft][pt][i] * sc[i] + sh[i];
-            if (a.res) {
-                const uint16_t *rp = static_cast<const uint16_t *>(a.res) + o;
-                if (nf == 4 && (a.K & 3) == 0) {
-                    const uint2 r = *reinterpret_cast<const uint2 *>(rp);
-                    v[0] += bf2f(r.x & 0xFFFFu), v[1] += bf2f(r.x >> 16), v[2] += bf2f(r.y & 0xFFFFu),
-                        v[3] += bf2f(r.y >> 16);
-                } else {
-                    for (int i = 0; i < nf; ++i) v[i] += bf2f(rp[i]);
-                }
-            }
+        for (int pt = 0; pt < PT; ++pt)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) v[i] = activate(v[i], a.act, a.hsigmoid);
-            if (a.out_f32) {
-                float *yp = static_cast<float *>(a.y) + o;
-                if (nf == 4 && (a.K & 3) == 0)
-                    *reinterpret_cast<float4 *>(yp) = make_float4(v[0], v[1], v[2], v[3]);
-                else
-                    for (int i = 0; i < nf; ++i) yp[i] = v[i];
-            } else {
-                uint16_t *yp = static_cast<uint16_t *>(a.y) + o;
-                if (nf == 4 && (a.K & 3) == 0) {
-                    uint2 r;
-                    r.x = f2bf(v[0]) | (f2bf(v[1]) << 16), r.y = f2bf(v[2]) | (f2bf(v[3]) << 16);
-                    *reinterpret_cast<uint2 *>(yp) = r;
-                } else {
-                    for (int i = 0; i < nf; ++i) yp[i] = (uint16_t)f2bf(v[i]);
-                }
-            }
-        }
+            for (int i = 0; i < 4; ++i) red[((wk * NT + ft * PT + pt) * 4 + i) * 64 + lane] = acc[ft][pt][i];
+    __syncthreads();
+    // wave t finishes tile t: partial sums of wave 0, 1, ... in that order
+    for (int t = wk; t < NT; t += WK) {
+        f32x4_t s = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        for (int k = 0; k < WK; ++k)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) s[i] += red[((k * NT + t) * 4 + i) * 64 + lane];
+        const int ft = t / PT, pt = t - ft * PT;
+        store_tile(a, s, f0 + ft * 16 + kg * 4, m0 + pt * 16 + l16, M);
     }
 }
 
@@ -417,18 +506,38 @@ __global__ __launch_bounds__(256) void gate_kernel(PoolArgs a) {
 
 static inline unsigned blocks_for(long total) { return (unsigned)((total + 255) / 256); }
 
-template <int FT, int PT, int WF, int WP, int WK>
+template <int FT, int PT, int WF, int WP>
 static hipError_t launch_mfma(const ConvArgs &a, hipStream_t s) {
     const int M = a.B * a.P * a.Q;
     const int n_ptiles = (M + 16 * PT * WP - 1) / (16 * PT * WP);
     const int n_ftiles = (a.K + 16 * FT * WF - 1) / (16 * FT * WF);
-    hipLaunchKernelGGL((conv_mfma_kernel<FT, PT, WF, WP, WK>), dim3(n_ptiles * n_ftiles), dim3(64 * WF * WP * WK), 0, s,
-                       a);
+    hipLaunchKernelGGL((conv_mfma_kernel<FT, PT, WF, WP>), dim3(n_ptiles * n_ftiles), dim3(64 * WF * WP), 0, s, a);
     return hipGetLastError();
 }
 
-hipError_t launch_conv(const ConvArgs &a, bool bf16, hipStream_t s) {
+template <int FT, int PT, int U, int MAXT>
+static hipError_t launch_splitk(const ConvArgs &a, int wk, hipStream_t s) {
+    const int M = a.B * a.P * a.Q;
+    const int n_pgroups = (M + 16 * PT - 1) / (16 * PT);
+    const int n_ftiles = (a.K + 16 * FT - 1) / (16 * FT);
+    wk = std::max(1, std::min(wk, MAXT / 64));
+    const size_t lds = wk > 1 ? (size_t)wk * FT * PT * 256 * sizeof(float) : 0;
+    hipLaunchKernelGGL((conv_mfma_splitk_kernel<FT, PT, U, MAXT>), dim3(n_pgroups * n_ftiles), dim3(64 * wk), lds, s, a);
+    return hipGetLastError();
+}
+
+const char *kernel_class_name(int kc) {
+    static const char *names[KC_COUNT] = {"conv_direct_kernel", "conv_mfma_kernel", "conv_mfma_splitk_kernel",
+                                          "dwconv_kernel",      "maxpool_kernel",   "gap_kernel",
+                                          "gate_kernel"};
+    return kc >= 0 && kc < KC_COUNT ? names[kc] : "?";
+}
+
+hipError_t launch_conv(const ConvArgs &a, bool bf16, hipStream_t s, int *kc) {
     const long M = (long)a.B * a.P * a.Q;
+    int dummy;
+    if (!kc) kc = &dummy;
+    *kc = KC_CONV_DIRECT;
     if (!bf16 || (a.C & 7) != 0) {
         const long total = M * ((a.K + 3) / 4);
         if (bf16)
@@ -437,15 +546,21 @@ hipError_t launch_conv(const ConvArgs &a, bool bf16, hipStream_t s) {
             hipLaunchKernelGGL(conv_direct_kernel<float>, dim3(blocks_for(total)), dim3(256), 0, s, a);
         return hipGetLastError();
     }
-    // Tile choice: the largest workgroup tile that still yields about two workgroups per compute
-    // unit; few-pixel problems (late layers at batch 1, FC) split the reduction over waves instead.
-    const long tiles16 = ((M + 15) / 16) * ((a.K + 15) / 16);
-    if (M <= 16) return launch_mfma<1, 1, 1, 1, 8>(a, s);
-    if (M <= 64) return launch_mfma<1, 2, 1, 2, 4>(a, s);
-    if (tiles16 >= 512L * 64) return launch_mfma<4, 4, 2, 2, 1>(a, s);
-    if (tiles16 >= 512L * 16) return launch_mfma<2, 2, 2, 2, 1>(a, s);
-    if (tiles16 >= 512L * 4) return launch_mfma<1, 2, 2, 1, 1>(a, s);
-    return launch_mfma<1, 1, 1, 1, 4>(a, s);
+    const long ptiles = (M + 15) / 16, ftiles = (a.K + 15) / 16;
+    const long tiles16 = ptiles * ftiles;
+    // Many tiles: whole-reduction waves with big workgroup tiles.
+    *kc = KC_CONV_MFMA;
+    if (tiles16 >= 512L * 64) return launch_mfma<4, 4, 2, 2>(a, s);
+    if (tiles16 >= 512L * 16) return launch_mfma<2, 2, 2, 2>(a, s);
+    *kc = KC_CONV_SPLITK;
+    // Few tiles: the widest pixel group that still leaves about one workgroup per compute unit, and
+    // about four reduction steps per wave.
+    const int nsteps = a.R * a.R * ((a.C + 31) / 32);
+    const int wk = (nsteps + 3) / 4;
+    if (ftiles * ((ptiles + 3) / 4) >= 256) return launch_splitk<1, 4, 4, 512>(a, wk, s);
+    if (ftiles * ((ptiles + 1) / 2) >= 256 || ptiles == 2) return launch_splitk<1, 2, 4, 1024>(a, wk, s);
+    if (ptiles >= 3 && ptiles <= 4) return launch_splitk<1, 4, 4, 512>(a, wk, s);
+    return launch_splitk<1, 1, 4, 1024>(a, wk, s);
 }
 
 hipError_t launch_dwconv(const ConvArgs &a, bool bf16, hipStream_t s) {

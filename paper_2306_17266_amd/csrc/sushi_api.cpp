@@ -35,6 +35,13 @@ struct CachedPlan {
     uint64_t g_version = ~0ull;       // cache state the two figures below were computed for
     uint64_t resident_bytes = 0;
     double hit_ratio = 0.0;
+    // exec mode 1: the launch sequence recorded as a HIP graph, for one (input, logits) pointer pair
+    hipGraphExec_t graph = nullptr;
+    const void *graph_in = nullptr;
+    void *graph_out = nullptr;
+    ~CachedPlan() {
+        if (graph) (void)hipGraphExecDestroy(graph);
+    }
 };
 
 std::string g_create_error;
@@ -59,6 +66,17 @@ struct sushi_ctx {
     Scheduler sched;
     sushi_stats stats{};
     int exec_mode = 0;
+    hipStream_t capture_stream = nullptr;  // graphs are recorded here and replayed on `stream`
+    // per-kernel timing (SUSHI_OPT_KERNEL_TIMING): event pairs around every launch
+    bool timing = false;
+    struct Pending {
+        hipEvent_t a, b;
+        int kc;
+        double bytes, flops;
+    };
+    std::vector<Pending> pending;
+    std::vector<hipEvent_t> free_events;
+    sushi_kernel_stats kstats[KC_COUNT] = {};
 };
 
 namespace {
@@ -254,6 +272,136 @@ void refresh_residency(sushi_ctx *c, CachedPlan &cp) {
     cp.hit_ratio = cp.vec_norm2 > 0 ? std::sqrt(inter2) / std::sqrt(cp.vec_norm2) : 0.0;
 }
 
+// Algorithmic traffic and arithmetic of one launch: every input, output, residual, weight and
+// scale/shift element of the active slice counted once.
+void launch_cost(const sushi_ctx *c, const Launch &L, double *bytes, double *flops) {
+    const double es = c->bf16 ? 2.0 : 4.0;
+    if (L.kind == OP_CONV || L.kind == OP_FC || L.kind == OP_DW) {
+        const ConvArgs &a = L.conv;
+        const double in = (double)a.B * a.H * a.W * a.C, out = (double)a.B * a.P * a.Q * a.K;
+        const double taps = (double)a.R * a.R;
+        const double wts = L.kind == OP_DW ? a.K * taps : (double)a.K * a.C * taps;
+        *bytes = (in + wts + (a.res ? out : 0.0)) * es + out * (a.out_f32 ? 4.0 : es) + 8.0 * a.K;
+        *flops = 2.0 * out * (L.kind == OP_DW ? taps : a.C * taps);
+    } else {
+        const PoolArgs &a = L.pool;
+        const double in = (double)a.B * a.H * a.W * a.C;
+        const double out = L.kind == OP_GATE ? in : (double)a.B * a.P * a.Q * a.C;
+        *bytes = (in + out) * es + (L.kind == OP_GATE ? 4.0 * a.B * a.C : 0.0);
+        *flops = L.kind == OP_MAXPOOL ? 9.0 * out : in;
+    }
+}
+
+hipError_t get_event(sushi_ctx *c, hipEvent_t *ev) {
+    if (!c->free_events.empty()) {
+        *ev = c->free_events.back();
+        c->free_events.pop_back();
+        return hipSuccess;
+    }
+    return hipEventCreate(ev);
+}
+
+// Waits for the recorded event pairs and adds their durations to the per-family totals.
+hipError_t drain_timing(sushi_ctx *c) {
+    hipError_t e = hipSuccess;
+    for (sushi_ctx::Pending &p : c->pending) {
+        float ms = 0.f;
+        if (e == hipSuccess) e = hipEventSynchronize(p.b);
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, p.a, p.b);
+        if (e == hipSuccess) {
+            sushi_kernel_stats &k = c->kstats[p.kc];
+            k.launches += 1, k.total_ms += ms, k.bytes += p.bytes, k.flops += p.flops;
+        }
+        c->free_events.push_back(p.a);
+        c->free_events.push_back(p.b);
+    }
+    c->pending.clear();
+    return e;
+}
+
+hipError_t issue_launches(sushi_ctx *c, CachedPlan &cp, const void *input_dev, void *logits_dev, hipStream_t st) {
+    const bool timed = c->timing && st == c->stream;
+    hipError_t e = hipSuccess;
+    for (Launch &L : cp.launches) {
+        sushi_ctx::Pending pend{};
+        if (timed) {
+            if ((e = get_event(c, &pend.a)) != hipSuccess || (e = get_event(c, &pend.b)) != hipSuccess) return e;
+            if ((e = hipEventRecord(pend.a, st)) != hipSuccess) return e;
+        }
+        int kc = KC_COUNT;
+        switch (L.kind) {
+            case OP_CONV:
+            case OP_FC: {
+                ConvArgs a = L.conv;
+                if (L.in_patch) a.x = input_dev;
+                if (L.out_patch) a.y = logits_dev;
+                e = launch_conv(a, c->bf16, st, &kc);
+                break;
+            }
+            case OP_DW:
+                kc = KC_DWCONV;
+                e = launch_dwconv(L.conv, c->bf16, st);
+                break;
+            case OP_MAXPOOL:
+                kc = KC_MAXPOOL;
+                e = launch_maxpool(L.pool, c->bf16, st);
+                break;
+            case OP_GAP:
+                kc = KC_GAP;
+                e = launch_gap(L.pool, c->bf16, st);
+                break;
+            case OP_GATE:
+                kc = KC_GATE;
+                e = launch_gate(L.pool, c->bf16, st);
+                break;
+            default:
+                e = hipErrorInvalidValue;
+        }
+        if (e != hipSuccess) return e;
+        if (timed) {
+            if ((e = hipEventRecord(pend.b, st)) != hipSuccess) return e;
+            pend.kc = kc;
+            launch_cost(c, L, &pend.bytes, &pend.flops);
+            c->pending.push_back(pend);
+        }
+    }
+    if (timed && c->pending.size() >= 4096) return drain_timing(c);
+    return hipSuccess;
+}
+
+// Exec mode 1: record the plan's launches once per (input, logits) pointer pair on a private stream,
+// then replay the instantiated graph on the context's stream.  No memset nodes are recorded.
+int replay_graph(sushi_ctx *c, CachedPlan &cp, const void *input_dev, void *logits_dev) {
+    hipError_t e;
+    if (!cp.graph || cp.graph_in != input_dev || cp.graph_out != logits_dev) {
+        if (cp.graph) {
+            (void)hipGraphExecDestroy(cp.graph);
+            cp.graph = nullptr;
+        }
+        if (!c->capture_stream &&
+            (e = hipStreamCreateWithFlags(&c->capture_stream, hipStreamNonBlocking)) != hipSuccess)
+            return hip_fail(c, e, "hipStreamCreateWithFlags");
+        if ((e = hipStreamBeginCapture(c->capture_stream, hipStreamCaptureModeThreadLocal)) != hipSuccess)
+            return hip_fail(c, e, "hipStreamBeginCapture");
+        hipError_t le = issue_launches(c, cp, input_dev, logits_dev, c->capture_stream);
+        hipGraph_t g = nullptr;
+        e = hipStreamEndCapture(c->capture_stream, &g);
+        if (le != hipSuccess || e != hipSuccess) {
+            if (g) (void)hipGraphDestroy(g);
+            return hip_fail(c, le != hipSuccess ? le : e, "graph capture");
+        }
+        e = hipGraphInstantiate(&cp.graph, g, nullptr, nullptr, 0);
+        (void)hipGraphDestroy(g);
+        if (e != hipSuccess) {
+            cp.graph = nullptr;
+            return hip_fail(c, e, "hipGraphInstantiate");
+        }
+        cp.graph_in = input_dev, cp.graph_out = logits_dev;
+    }
+    if ((e = hipGraphLaunch(cp.graph, c->stream)) != hipSuccess) return hip_fail(c, e, "hipGraphLaunch");
+    return SUSHI_OK;
+}
+
 std::string plan_key(const sushi_subnet_cfg &cfg, int batch) {
     std::string k(reinterpret_cast<const char *>(&cfg), sizeof(cfg));
     k.append(reinterpret_cast<const char *>(&batch), sizeof(batch));
@@ -327,6 +475,10 @@ void sushi_destroy(sushi_ctx *c) {
     }
     (void)hipSetDevice(c->device);
     (void)hipStreamSynchronize(c->stream);
+    c->plans.clear();
+    (void)drain_timing(c);
+    for (hipEvent_t ev : c->free_events) (void)hipEventDestroy(ev);
+    if (c->capture_stream) (void)hipStreamDestroy(c->capture_stream);
     free_arena(c);
     if (c->d_weights) (void)hipFree(c->d_weights);
     if (c->d_params) (void)hipFree(c->d_params);
@@ -452,31 +604,11 @@ int sushi_infer(sushi_ctx *c, const sushi_subnet_cfg *cfg, const void *input_dev
     }
     refresh_residency(c, *cp);
 
-    for (Launch &L : cp->launches) {
-        switch (L.kind) {
-            case OP_CONV:
-            case OP_FC: {
-                ConvArgs a = L.conv;
-                if (L.in_patch) a.x = input_dev;
-                if (L.out_patch) a.y = logits_dev;
-                e = launch_conv(a, c->bf16, c->stream);
-                break;
-            }
-            case OP_DW:
-                e = launch_dwconv(L.conv, c->bf16, c->stream);
-                break;
-            case OP_MAXPOOL:
-                e = launch_maxpool(L.pool, c->bf16, c->stream);
-                break;
-            case OP_GAP:
-                e = launch_gap(L.pool, c->bf16, c->stream);
-                break;
-            case OP_GATE:
-                e = launch_gate(L.pool, c->bf16, c->stream);
-                break;
-            default:
-                e = hipErrorInvalidValue;
-        }
+    if (c->exec_mode == 1) {
+        int rc = replay_graph(c, *cp, input_dev, logits_dev);
+        if (rc) return rc;
+    } else {
+        e = issue_launches(c, *cp, input_dev, logits_dev, c->stream);
         if (e != hipSuccess) return hip_fail(c, e, "kernel launch");
     }
     sushi_stats &s = c->stats;
@@ -522,8 +654,29 @@ int sushi_get_stats(sushi_ctx *c, sushi_stats *out) {
     return SUSHI_OK;
 }
 
+int sushi_get_kernel_stats(sushi_ctx *c, sushi_kernel_stats *out, int cap, int *n_out) {
+    if (!c || !n_out || cap < 0 || (cap > 0 && !out)) return SUSHI_EINVAL;
+    if (c->device >= 0) {
+        hipError_t e = drain_timing(c);
+        if (e != hipSuccess) return hip_fail(c, e, "kernel timing");
+    }
+    *n_out = KC_COUNT;
+    for (int i = 0; i < cap && i < KC_COUNT; ++i) {
+        out[i] = c->kstats[i];
+        std::snprintf(out[i].name, sizeof(out[i].name), "%s", kernel_class_name(i));
+    }
+    return SUSHI_OK;
+}
+
 int sushi_set_option(sushi_ctx *c, int option, int64_t value) {
     if (!c) return SUSHI_EINVAL;
+    if (option == SUSHI_OPT_KERNEL_TIMING && (value == 0 || value == 1)) {
+        if (c->device >= 0) (void)drain_timing(c);
+        if (value == 1)
+            for (auto &k : c->kstats) k = sushi_kernel_stats{};
+        c->timing = value == 1;
+        return SUSHI_OK;
+    }
     if (option == SUSHI_OPT_EXEC_MODE && (value == 0 || value == 1)) {
         c->exec_mode = (int)value;
         return SUSHI_OK;

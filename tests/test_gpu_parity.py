@@ -172,3 +172,41 @@ def test_errors_are_reported_not_raised_in_c():
         ctx.sushi_set_subgraph_cache([(64, 3, 3), (16, 16, 3), (16, 16, 3), (16, 16, 3), (0, 0, 0)], 1 << 30)
     assert e.value.code == -1                                  # outside the SuperNet
     ctx.close()
+
+
+def test_graph_replay_matches_eager_every_time():
+    """Exec mode 1 replays a recorded HIP graph per SubNet.  Several replays, with eager work and
+    synchronisations in between, different inputs in the same buffer, all equal to eager results."""
+    import paper_2306_17266_amd as S
+    arch = A.small_mbv3_arch()
+    ctx, wts = _ctx(arch, 7, True)
+    st = Stream(61)
+    cfgs = [streams.uniform_cfg(arch, st, 64) for _ in range(3)]
+    xbuf = torch.empty(2, 64, 64, 3, device="cuda", dtype=torch.bfloat16)
+    out = torch.empty(2, arch.n_classes, device="cuda", dtype=torch.float32)
+    eager = {}
+    for t in range(9):
+        x = torch.from_numpy(T.make_input(7, t, 2, 64, 3, True)).cuda().to(torch.bfloat16)
+        xbuf.copy_(x)
+        ctx.sushi_infer(cfgs[t % 3], xbuf, out)
+        torch.cuda.synchronize()
+        eager[t] = out.cpu().numpy().copy()
+    ctx.sushi_set_option(S.OPT_EXEC_MODE, 1)
+    for rep in range(2):
+        for t in range(9):
+            x = torch.from_numpy(T.make_input(7, t, 2, 64, 3, True)).cuda().to(torch.bfloat16)
+            xbuf.copy_(x)
+            out.fill_(float("nan"))
+            ctx.sushi_infer(cfgs[t % 3], xbuf, out)
+            torch.cuda.synchronize()
+            np.testing.assert_array_equal(out.cpu().numpy(), eager[t])
+            (xbuf.float().sum() + out.sum()).item()          # unrelated eager work between replays
+    # a different output buffer forces a re-record
+    out2 = torch.empty_like(out)
+    xbuf.copy_(torch.from_numpy(T.make_input(7, 4, 2, 64, 3, True)).cuda().to(torch.bfloat16))
+    ctx.sushi_infer(cfgs[4 % 3], xbuf, out2)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(out2.cpu().numpy(), eager[4])
+    want = oracle_logits(arch, wts, cfgs[1], T.make_input(7, 4, 2, 64, 3, True))
+    assert rel_l2(out2.cpu().numpy(), want) <= 1e-2
+    ctx.close()
