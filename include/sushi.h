@@ -167,6 +167,9 @@ typedef struct sushi_stats {
     double last_hit_ratio;           /* ||SN ∩ G||_2 / ||SN||_2 on the [K,C] vectors (Appendix A.4)   */
     double sum_hit_ratio;            /* summed over queries                                           */
     uint64_t plan_cache_hits, plan_cache_misses;
+    uint64_t weight_bytes_lds;       /* team kernel: weight bytes read from resident LDS slabs, summed   */
+    uint64_t last_lds_bytes;         /* the same for the last query                                    */
+    uint64_t cache_bytes_lds;        /* bytes of the cached SubGraph that fit the LDS stores (per XCD) */
 } sushi_stats;
 
 /* ---------------------------------------------------------------- host-only helpers (no GPU needed) */
@@ -216,6 +219,16 @@ int sushi_set_subgraph_cache(sushi_ctx *ctx, const sushi_subgraph_cfg *g, size_t
  * cached.  SUSHI_EINVAL (nothing enqueued) if cfg is not a SubNet of the loaded SuperNet. */
 int sushi_infer(sushi_ctx *ctx, const sushi_subnet_cfg *cfg, const void *input_dev, int batch, void *logits_dev);
 
+/* Waits until every query enqueued or posted through ctx has finished and its logits are visible
+ * to the host and to later work on any stream. */
+int sushi_synchronize(sushi_ctx *ctx);
+
+/* Team-kernel diagnostics.  enable = 1: from the next start of the team kernel, each team leader
+ * stamps a 100 MHz clock before the first op of a query and after the barrier of every op
+ * (slot 0, then slot i+1 for op i; 256 slots per team, 8 teams).  Each call first waits for all
+ * queries, stops the team kernel and, if out is not null, copies up to cap stamps to out (HOST). */
+int sushi_team_trace(sushi_ctx *ctx, int enable, uint64_t *out, int cap);
+
 /* ---------------------------------------------------------------- scheduler (Algorithm 1, Section 3.3) */
 
 int sushi_sched_init(sushi_ctx *ctx, const sushi_sched_desc *desc);
@@ -232,9 +245,27 @@ int sushi_sched_record(sushi_ctx *ctx, const int32_t *vec, int *new_cache_idx_ou
 int sushi_get_stats(sushi_ctx *ctx, sushi_stats *out);
 
 typedef enum {
-    SUSHI_OPT_EXEC_MODE = 0,    /* 0 = one launch per layer (default), 1 = replay a HIP graph per SubNet */
-    SUSHI_OPT_KERNEL_TIMING = 1 /* 1 = bracket every launch with HIP events on the context's stream and
+    SUSHI_OPT_EXEC_MODE = 0,    /* 0 = one launch per layer (default), 1 = replay a HIP graph per SubNet,
+                                   2 = stream kernel: one launch per query, layers separated by grid
+                                   barriers (bf16 mode only; a barrier wait that runs out is reported
+                                   by the next sushi_infer as SUSHI_EDEVICE),
+                                   3 = team kernel: a persistent kernel whose workgroups form one team per
+                                   XCD; each team serves one query at a time inside its XCD, so up to
+                                   eight queries are in flight.  bf16 mode only.  sushi_infer then waits
+                                   for the context's stream (the input must be complete), posts the
+                                   query to a team and returns; the logits are valid after
+                                   sushi_synchronize.  The kernel runs on a private stream and leaves by
+                                   itself when no query arrives for SUSHI_OPT_IDLE_US. */
+    SUSHI_OPT_KERNEL_TIMING = 1,/* 1 = bracket every launch with HIP events on the context's stream and
                                    accumulate per kernel family (mode 0 only); setting 1 clears the totals */
+    SUSHI_OPT_SPIN_LIMIT = 2,   /* polls a stream-/team-kernel workgroup makes at one barrier before it
+                                   gives up (default 400000, about a second) */
+    SUSHI_OPT_STREAM_WGS = 4,   /* workgroups of the stream kernel (multiple of 16; default: one per
+                                   compute unit); only before the first query in mode 2 */
+    SUSHI_OPT_TEAM_WGS_PER_CU = 5, /* workgroups of the team kernel per compute unit, 1 or 2 (default 2);
+                                   only before the first query in mode 3 */
+    SUSHI_OPT_IDLE_US = 3       /* microseconds without a query after which the team kernel leaves
+                                   (default 2000); the next query starts it again */
 } sushi_option;
 int sushi_set_option(sushi_ctx *ctx, int option, int64_t value);
 

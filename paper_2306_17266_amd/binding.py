@@ -13,6 +13,10 @@ FP32, BF16 = 0, 1
 STRICT_ACCURACY, STRICT_LATENCY = 0, 1
 OPT_EXEC_MODE = 0
 OPT_KERNEL_TIMING = 1
+OPT_SPIN_LIMIT = 2
+OPT_IDLE_US = 3
+OPT_STREAM_WGS = 4
+OPT_TEAM_WGS_PER_CU = 5
 
 
 class SushiError(RuntimeError):
@@ -66,7 +70,8 @@ class CStats(C.Structure):
                 ("last_weight_bytes", C.c_uint64), ("last_resident_bytes", C.c_uint64),
                 ("cache_installs", C.c_uint64), ("cache_bytes_installed", C.c_uint64), ("cache_bytes", C.c_uint64),
                 ("last_hit_ratio", C.c_double), ("sum_hit_ratio", C.c_double),
-                ("plan_cache_hits", C.c_uint64), ("plan_cache_misses", C.c_uint64)]
+                ("plan_cache_hits", C.c_uint64), ("plan_cache_misses", C.c_uint64),
+                ("weight_bytes_lds", C.c_uint64), ("last_lds_bytes", C.c_uint64), ("cache_bytes_lds", C.c_uint64)]
 
 
 class CKernelStats(C.Structure):
@@ -101,6 +106,8 @@ def lib():
     L.sushi_sched_step.argtypes = [vp, C.c_float, C.c_float, ip, ip]
     L.sushi_sched_record.argtypes = [vp, C.POINTER(C.c_int32), ip]
     L.sushi_get_stats.argtypes = [vp, C.POINTER(CStats)]
+    L.sushi_synchronize.argtypes = [vp]
+    L.sushi_team_trace.argtypes = [vp, C.c_int, C.POINTER(C.c_uint64), C.c_int]
     L.sushi_set_option.argtypes = [vp, C.c_int, C.c_int64]
     L.sushi_get_kernel_stats.argtypes = [vp, C.POINTER(CKernelStats), C.c_int, ip]
     _lib = L
@@ -222,6 +229,14 @@ class Sushi:
             s = self._cfg_cache[key] = c_cfg(cfg)
         _check(lib().sushi_infer(self._h, C.byref(s), C.c_void_p(x.data_ptr()), x.shape[0],
                                  C.c_void_p(logits.data_ptr())), self._h)
+
+    def sushi_synchronize(self):
+        _check(lib().sushi_synchronize(self._h), self._h)
+
+    def sushi_team_trace(self, enable):
+        buf = (C.c_uint64 * (8 * 256))()
+        _check(lib().sushi_team_trace(self._h, int(enable), buf, 8 * 256), self._h)
+        return np.array(buf[:], dtype=np.uint64).reshape(8, 256)
 
     def sushi_sched_init(self, subnet_vecs, accuracy, subgraph_vecs, table, Q, policy, initial_cache=-1):
         sv = np.ascontiguousarray(subnet_vecs, dtype=np.int32)

@@ -1,0 +1,134 @@
+// The stream kernel: one launch runs a whole SubNet query (all layers) on a fixed grid of
+// workgroups that synchronise between layers with a grid barrier, instead of one launch per layer.
+//
+// Activations written by one layer are read by other workgroups (on other XCDs, whose L2s are not
+// coherent with each other) in the next layer.  They are therefore stored write-through and loaded
+// around the L2 (agent-scope "sc1" accesses); weights, which never change, use ordinary cached
+// loads.  The barrier is two-level (groups of 16 workgroups, then the group leaders) on 64-bit
+// monotonic counters; every wait is bounded by a spin limit, after which the kernel raises an abort
+// flag and all workgroups leave.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include "kernels.h"
+
+namespace sushi {
+
+constexpr int STREAM_THREADS = 512;  // 8 waves per workgroup
+constexpr int STREAM_WAVES = STREAM_THREADS / 64;
+constexpr int BARRIER_GROUP = 16;    // workgroups per first-level barrier group
+constexpr int SYNC_WORDS = 64 * 16;  // 64-bit words in the barrier area (128-byte spacing)
+
+struct DevOp {
+    int kind;      // OpKind (model.h)
+    int pt, wk;    // dense conv: pixel tiles per unit (1, 2, 4) and waves sharing one unit (1, 2, 4, 8)
+    int n_units;   // dense conv: filter tiles x pixel groups
+    int n_p;       // dense conv: pixel groups
+    int in_patch;  // input pointer is the caller's input buffer
+    int out_patch; // output pointer is the caller's logits buffer
+    int relative;  // activation pointers hold (offset into the team's arena) + 1
+    int layer;     // SuperNet layer of a conv / FC op, -1 otherwise
+    int pad0;
+    ConvArgs conv;
+    PoolArgs pool;
+};
+
+struct StreamArgs {
+    const DevOp *prog;  // DEVICE
+    int n_ops;
+    const void *input;  // DEVICE, caller's
+    void *logits;       // DEVICE, caller's
+    unsigned long long *sync;       // DEVICE barrier area, SYNC_WORDS words, zero before first use
+    unsigned long long epoch_base;  // barriers already counted on `sync`
+    int spin_limit;
+    unsigned *abort_flag;  // pinned HOST memory, set to 1 when a wait ran out
+};
+
+// ---------------------------------------------------------------------------------------------
+// The team kernel: a persistent kernel in which the workgroups running on one XCD form a team.
+// A team serves one query at a time, entirely inside its XCD: activations go through that XCD's L2
+// (ordinary stores and loads, the vector L1 emptied at every barrier), layers are separated by a team barrier (32 arrivals instead of 256),
+// and up to eight queries are in flight on the chip.  Queries arrive through per-team mailboxes in
+// pinned host memory; a team leader that finds no post for `idle_ticks` (or sees `stop`) makes its
+// team leave, so the kernel always ends by itself.
+constexpr int MAX_TEAMS = 8;
+enum TeamCmd { TEAM_RUN = 0, TEAM_STOP = 1, TEAM_INSTALL = 2 };
+
+// SubGraph residency inside the team kernel (the persistent buffer of the paper, Section 4.2.2, kept
+// in LDS): every workgroup of a team owns RES_STORE_BYTES of LDS that survive from query to query.
+// The cached SubGraph is cut into slabs, one per 16-filter tile of a layer:
+// [tap][channel group < cg_res][16 filters][8 channels] bf16, i.e. 256 bytes per (tap, group).  Slab f
+// of a layer lives in the LDS of workgroup `owner` at byte offset `lds_off`; that workgroup computes
+// filter tile f of the layer for every query and reads those weights from LDS instead of memory.
+// Every team holds the same slabs.  Only layers that run as a single pixel group (at most 64 output
+// pixels per query: the late stages, squeeze-excite and classifier layers, which hold most of the
+// weights) use their slabs.
+constexpr int RES_STORE_BYTES = 120 * 1024;
+constexpr int RED_BYTES = STREAM_WAVES * 4 * 256 * 4;  // partial-sum scratch in front of the store
+
+struct ResEntry {
+    int owner;    // rank inside the team, -1 = not resident
+    int lds_off;  // byte offset inside the owner's store
+};
+
+struct ResLayer {
+    const void *w;  // packed weights of the layer (DEVICE)
+    int Kpad, CG, taps;
+    int cg_res;      // resident channel groups of every resident tile
+    int n_res;       // filter tiles 0 .. n_res-1 may be resident (see entries)
+    int first_entry; // index of tile 0's entry in ResTable::entries
+};
+
+struct ResTable {
+    int n_layers, team_size;  // team size the owners were assigned for
+    const ResLayer *layers;   // DEVICE, one per SuperNet layer
+    const ResEntry *entries;  // DEVICE
+};
+
+struct TeamPost {  // written by the host, one per team
+    unsigned long long seq;  // bumped last
+    int cmd, n_ops;
+    const DevOp *prog;  // DEVICE; activation pointers are arena offsets + 1 (TEAM_INSTALL: a ResTable)
+    const void *input;  // DEVICE
+    void *logits;       // DEVICE
+    unsigned long long pad[3];
+};
+
+struct TeamHostState {  // pinned HOST memory, device-visible
+    TeamPost post[MAX_TEAMS];
+    unsigned long long done[MAX_TEAMS * 8];  // done[8 t]: seq of team t's last finished post
+    unsigned team_size[MAX_TEAMS];
+    unsigned ready;       // kernel: teams are formed, sizes valid
+    unsigned stop;        // host: leave as soon as idle
+    unsigned abort_flag;  // kernel: a bounded wait ran out
+};
+
+struct TeamArgs {
+    TeamHostState *host;
+    unsigned long long *sync;  // DEVICE, SYNC_WORDS words, zero at launch
+    char *arena;               // DEVICE, MAX_TEAMS arenas
+    long arena_bytes;          // bytes per team arena
+    unsigned long long last_seq[MAX_TEAMS];  // posts each team has already finished
+    long idle_ticks;           // 100 MHz ticks a leader waits for a post before its team leaves
+    int spin_limit;
+    const ResTable *table;     // DEVICE or null: SubGraph to install when the kernel starts
+    unsigned long long *trace;  // DEVICE or null: [MAX_TEAMS][TRACE_SLOTS] 100 MHz timestamps, one after each op
+};
+constexpr int TRACE_SLOTS = 256;
+
+hipError_t launch_team_kernel(const TeamArgs &a, int nwg, hipStream_t s);
+// Sets the kernel's dynamic LDS limit; call once per device before the first launch.
+hipError_t prepare_team_kernel();
+// Workgroups of the team kernel that fit on one compute unit at the same time.
+hipError_t team_kernel_blocks_per_cu(int *n);
+
+// Chooses pt / wk / unit counts of a dense conv or FC op for a grid of nwg workgroups.
+void tile_dev_op(DevOp &op, int nwg, bool team);
+
+// Number of grid barriers the kernel executes for a program of n_ops ops.
+inline int stream_barriers(int n_ops) { return n_ops > 0 ? n_ops - 1 : 0; }
+
+hipError_t launch_stream_kernel(const StreamArgs &a, int nwg, hipStream_t s);
+
+}  // namespace sushi

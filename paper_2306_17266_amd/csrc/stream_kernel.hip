@@ -1,0 +1,808 @@
+// The stream kernel (see stream_kernel.h): a whole SubNet query in one launch, bf16 mode.
+#include "stream_kernel.h"
+
+#include <algorithm>
+
+#include "device_common.h"
+#include "model.h"
+
+namespace sushi {
+
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4_t;
+typedef __attribute__((ext_vector_type(2))) unsigned u32x2_t;
+
+// Cache policy bits of buffer accesses (gfx942/gfx950): sc0 = coherent within the XCD (skips the
+// compute unit's vector L1, served by the XCD's L2), sc1 = coherent across the device's XCDs
+// (stores write through the L2, loads do not hit stale lines there), both = system scope.
+constexpr int AUX_PLAIN = 0, AUX_SC0 = 1, AUX_SC1 = 16, AUX_SYS = 17;
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *p, long bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, (int)bytes, 0x00020000);
+}
+
+template <int AUX>
+__device__ __forceinline__ uint4 act_ld16(__amdgpu_buffer_rsrc_t r, int off) {
+    const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, AUX);
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+template <int AUX>
+__device__ __forceinline__ void act_st16(__amdgpu_buffer_rsrc_t r, int off, uint4 v) {
+    const u32x4_t d = {v.x, v.y, v.z, v.w};
+    __builtin_amdgcn_raw_buffer_store_b128(d, r, off, 0, AUX);
+}
+
+template <int AUX>
+__device__ __forceinline__ void act_st8(__amdgpu_buffer_rsrc_t r, int off, uint2 v) {
+    const u32x2_t d = {v.x, v.y};
+    __builtin_amdgcn_raw_buffer_store_b64(d, r, off, 0, AUX);
+}
+
+__device__ __forceinline__ void unpack8(const uint4 a, float v[8]) {
+    v[0] = bf2f(a.x & 0xFFFFu), v[1] = bf2f(a.x >> 16), v[2] = bf2f(a.y & 0xFFFFu), v[3] = bf2f(a.y >> 16);
+    v[4] = bf2f(a.z & 0xFFFFu), v[5] = bf2f(a.z >> 16), v[6] = bf2f(a.w & 0xFFFFu), v[7] = bf2f(a.w >> 16);
+}
+
+__device__ __forceinline__ uint4 pack8(const float v[8]) {
+    uint4 a;
+    a.x = f2bf(v[0]) | (f2bf(v[1]) << 16), a.y = f2bf(v[2]) | (f2bf(v[3]) << 16);
+    a.z = f2bf(v[4]) | (f2bf(v[5]) << 16), a.w = f2bf(v[6]) | (f2bf(v[7]) << 16);
+    return a;
+}
+
+// ------------------------------------------------------------------ grid barrier
+// sync[0] = abort, sync[16*(1+g)] = arrivals of group g, sync[16*40] = groups that arrived.
+// Counters only grow: barrier number e (counted from the first launch on this area) is complete
+// when the top counter reaches e * groups.  Returns false if the wait ran out or another
+// workgroup gave up; the caller must leave the kernel then.
+__device__ __forceinline__ bool grid_barrier(const StreamArgs &sa, unsigned long long e, int *lds_flag) {
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const unsigned nwg = gridDim.x;
+        const unsigned g = blockIdx.x / BARRIER_GROUP;
+        const unsigned gsize = min((unsigned)BARRIER_GROUP, nwg - g * BARRIER_GROUP);
+        const unsigned ngroups = (nwg + BARRIER_GROUP - 1) / BARRIER_GROUP;
+        unsigned long long *top = sa.sync + 16 * 40;
+        const unsigned long long old =
+            __hip_atomic_fetch_add(&sa.sync[16 * (1 + g)], 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (old + 1 == e * gsize) __hip_atomic_fetch_add(top, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned long long target = e * ngroups;
+        int spins = 0, good = 1;
+        while (__hip_atomic_load(top, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+            if (++spins > sa.spin_limit ||
+                __hip_atomic_load(&sa.sync[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
+                __hip_atomic_store(&sa.sync[0], 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(sa.abort_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+                good = 0;
+                break;
+            }
+            __builtin_amdgcn_s_sleep(1);
+        }
+        *lds_flag = good;
+    }
+    __syncthreads();
+    return *lds_flag != 0;
+}
+
+// ------------------------------------------------------------------ epilogue of one 16 x 16 tile
+
+// LD / ST: cache policy of activation loads / stores; sys_out: the output is the caller's buffer and
+// is written through to memory at system scope.
+template <int LD, int ST>
+__device__ __forceinline__ void store_tile_coherent(const ConvArgs &a, __amdgpu_buffer_rsrc_t ry,
+                                                    __amdgpu_buffer_rsrc_t rres, const f32x4_t acc, int fbase, int m,
+                                                    int M, bool sys_out) {
+    if (fbase >= a.K || m >= M) return;
+    const int nf = min(4, a.K - fbase);
+    const bool vec = nf == 4 && (a.K & 3) == 0;
+    const long o = (long)m * a.K + fbase;
+    float v[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const float sc = (a.scale && i < nf) ? a.scale[fbase + i] : 1.0f;
+        const float sh = i < nf ? a.shift[fbase + i] : 0.0f;
+        v[i] = acc[i] * sc + sh;
+    }
+    if (a.res) {
+        if (vec) {
+            const u32x2_t r = __builtin_amdgcn_raw_buffer_load_b64(rres, (int)(o * 2), 0, LD);
+            v[0] += bf2f(r.x & 0xFFFFu), v[1] += bf2f(r.x >> 16), v[2] += bf2f(r.y & 0xFFFFu), v[3] += bf2f(r.y >> 16);
+        } else {
+            const uint16_t *rp = static_cast<const uint16_t *>(a.res) + o;
+            for (int i = 0; i < nf; ++i)
+                v[i] += bf2f(__hip_atomic_load(rp + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v[i] = activate(v[i], a.act, a.hsigmoid);
+    if (a.out_f32) {
+        if (vec) {
+            const uint4 pk = make_uint4(__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]),
+                                        __float_as_uint(v[3]));
+            if (sys_out)
+                act_st16<AUX_SYS>(ry, (int)(o * 4), pk);
+            else
+                act_st16<ST>(ry, (int)(o * 4), pk);
+        } else {
+            float *yp = static_cast<float *>(a.y) + o;
+            for (int i = 0; i < nf; ++i) __hip_atomic_store(yp + i, v[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        }
+    } else {
+        if (vec) {
+            const uint2 pk = make_uint2(f2bf(v[0]) | (f2bf(v[1]) << 16), f2bf(v[2]) | (f2bf(v[3]) << 16));
+            if (sys_out)
+                act_st8<AUX_SYS>(ry, (int)(o * 2), pk);
+            else
+                act_st8<ST>(ry, (int)(o * 2), pk);
+        } else {
+            uint16_t *yp = static_cast<uint16_t *>(a.y) + o;
+            for (int i = 0; i < nf; ++i)
+                __hip_atomic_store(yp + i, (uint16_t)f2bf(v[i]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        }
+    }
+}
+
+// ------------------------------------------------------------------ dense conv / FC on the matrix cores
+// A unit = one 16-filter tile x PT 16-pixel tiles.  The workgroup's 8 waves form 8/wk slots of wk
+// waves; a slot computes one unit, its waves splitting the reduction steps (tap x 32 channels) and
+// each issuing the loads of U steps before the first MFMA.  Partial sums meet in LDS in a fixed order.
+
+// Residency (RES, team kernel only): an op that runs as one pixel group takes its filter tiles from
+// a per-workgroup list instead: the tiles whose slab this workgroup holds in LDS, plus its share of
+// the tiles nobody holds.  A resident tile reads the channel groups below cg_res from LDS and the
+// rest (the part of the SubNet outside the cached SubGraph) from memory; the order of the
+// reduction is the same either way, so the logits do not depend on what is cached.
+struct ResView {
+    const ResLayer *layer;    // null: the op has no resident tiles
+    const ResEntry *entries;  // entries of this layer
+    const char *store;        // this workgroup's LDS store
+    int *list;                // LDS scratch for the unit list (>= 130 ints)
+};
+
+template <int PT, int LD, int ST, bool RES>
+__device__ void conv_units(const DevOp &op, float *red, int rank, int nranks, const ResView rv) {
+    constexpr int U = PT == 4 ? 2 : 4;  // steps whose loads are in flight together (register budget)
+    const ConvArgs &a = op.conv;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wk = op.wk, slots = STREAM_WAVES / wk;
+    const int slot = wave / wk, ks = wave - slot * wk;
+    const int l16 = lane & 15, kg = lane >> 4;
+    const int M = a.B * a.P * a.Q;
+    const uint16_t *w = static_cast<const uint16_t *>(a.w);
+    const __amdgpu_buffer_rsrc_t rx = make_rsrc(a.x, (long)a.B * a.H * a.W * a.C * 2);
+    const long out_bytes = (long)M * a.K * (a.out_f32 ? 4 : 2);
+    const __amdgpu_buffer_rsrc_t ry = make_rsrc(a.y, out_bytes);
+    const __amdgpu_buffer_rsrc_t rres = make_rsrc(a.res ? a.res : a.y, (long)M * a.K * 2);
+    const int csteps = (a.C + 31) >> 5;
+    const int nsteps = a.R * a.R * csteps;
+    const int n_groups = (op.n_units + slots - 1) / slots;
+
+    const bool sys_out = op.out_patch != 0;
+    // unit list of a resident op: entries are (filter tile) | (resident ? 1 << 16 : 0)
+    const bool listed = RES && rv.layer != nullptr && op.n_p == 1 && slots == 1;
+    int n_listed = 0;
+    if (listed) {
+        const int n_f = op.n_units;
+        if (wave == 0) {
+            int count = 0;
+            for (int base = 0; base < n_f; base += 64) {
+                const int f = base + lane;
+                bool res = false, mine = false;
+                if (f < n_f) {
+                    res = f < rv.layer->n_res && rv.entries[f].owner >= 0;
+                    mine = res ? rv.entries[f].owner == rank : (f % nranks) == rank;
+                }
+                const unsigned long long mask = __ballot(mine);
+                const int pos = __popcll(mask & ((1ull << lane) - 1ull));
+                if (mine) rv.list[1 + count + pos] = f | (res ? 1 << 16 : 0);
+                count += __popcll(mask);
+            }
+            if (lane == 0) rv.list[0] = count;
+        }
+        __syncthreads();
+        n_listed = rv.list[0];
+    }
+    const int first = listed ? 0 : rank, limit = listed ? n_listed : n_groups, stride = listed ? 1 : nranks;
+    for (int g = first; g < limit; g += stride) {
+        const int unit = listed ? (rv.list[1 + g] & 0xFFFF) : g * slots + slot;
+        const bool active = unit < op.n_units;
+        const int ftile = active ? unit / op.n_p : 0, pgroup = active ? unit - ftile * op.n_p : 0;
+        const int f0 = ftile * 16, m0 = pgroup * PT * 16;
+        const bool resident = listed && (rv.list[1 + g] >> 16) != 0;
+        const int cg_res = resident ? rv.layer->cg_res : 0;
+        const char *slab = resident ? rv.store + rv.entries[ftile].lds_off : nullptr;
+        int pn[PT], ph[PT], pw[PT];
+        bool pv[PT];
+#pragma unroll
+        for (int pt = 0; pt < PT; ++pt) {
+            const int m = m0 + pt * 16 + l16;
+            pv[pt] = active && m < M;
+            const int mm = pv[pt] ? m : 0;
+            const int qq = mm % a.Q, pp = (mm / a.Q) % a.P;
+            pn[pt] = mm / (a.Q * a.P);
+            ph[pt] = pp * a.stride - a.pad;
+            pw[pt] = qq * a.stride - a.pad;
+        }
+        const int fw = min(f0 + l16, a.Kpad - 1) * 8;
+        f32x4_t acc[PT];
+#pragma unroll
+        for (int pt = 0; pt < PT; ++pt) acc[pt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+        if (active) {
+            for (int base = ks; base < nsteps; base += wk * U) {
+                Frag fa[U], fb[U][PT];
+                bool ok[U][PT];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int step = base + u * wk;
+                    const bool live = step < nsteps;
+                    const int st = live ? step : 0;
+                    const int tap = st / csteps;
+                    const int c0 = (st - tap * csteps) * 32 + kg * 8;
+                    const int dr = tap / a.R, ds = tap - dr * a.R;
+                    const bool cv = live && c0 < a.C;
+                    const int cc = cv ? c0 : 0;
+                    if (RES && (cc >> 3) < cg_res)
+                        fa[u].u = *reinterpret_cast<const uint4 *>(slab + ((tap * cg_res + (cc >> 3)) * 16 + l16) * 16);
+                    else
+                        fa[u].u = *reinterpret_cast<const uint4 *>(w + ((long)tap * a.CG + (cc >> 3)) * a.Kpad * 8 + fw);
+#pragma unroll
+                    for (int pt = 0; pt < PT; ++pt) {
+                        const int h = ph[pt] + dr, v = pw[pt] + ds;
+                        ok[u][pt] = cv && pv[pt] && h >= 0 && h < a.H && v >= 0 && v < a.W;
+                        const int hh = ok[u][pt] ? h : 0, vv = ok[u][pt] ? v : 0;
+                        fb[u][pt].u = act_ld16<LD>(rx, (((pn[pt] * a.H + hh) * a.W + vv) * a.C + cc) * 2);
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+#pragma unroll
+                    for (int pt = 0; pt < PT; ++pt) {
+                        if (!ok[u][pt]) fb[u][pt].u = make_uint4(0, 0, 0, 0);
+                        acc[pt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[u].v, fb[u][pt].v, acc[pt], 0, 0, 0);
+                    }
+            }
+        }
+        if (wk == 1) {
+            if (active)
+#pragma unroll
+                for (int pt = 0; pt < PT; ++pt)
+                    store_tile_coherent<LD, ST>(a, ry, rres, acc[pt], f0 + kg * 4, m0 + pt * 16 + l16, M, sys_out);
+            continue;
+        }
+        // red[wave][PT][4][64]
+#pragma unroll
+        for (int pt = 0; pt < PT; ++pt)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) red[((wave * PT + pt) * 4 + i) * 64 + lane] = acc[pt][i];
+        __syncthreads();
+        if (active)
+            for (int t = ks; t < PT; t += wk) {
+                f32x4_t s = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                for (int k = 0; k < wk; ++k)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) s[i] += red[(((slot * wk + k) * PT + t) * 4 + i) * 64 + lane];
+                store_tile_coherent<LD, ST>(a, ry, rres, s, f0 + kg * 4, m0 + t * 16 + l16, M, sys_out);
+            }
+        __syncthreads();
+    }
+}
+
+// ------------------------------------------------------------------ vector-ALU layers, grid-strided
+
+// Dense conv with a channel count that is not a multiple of 8 (the 3-channel stem): one thread per
+// output pixel x 4 filters.  The input is the caller's buffer (complete before the launch).
+template <int ST>
+__device__ void conv_direct_units(const ConvArgs &a, int rank, int nranks) {
+    const int groups = (a.K + 3) >> 2;
+    const long total = (long)a.B * a.P * a.Q * groups;
+    const uint16_t *x = static_cast<const uint16_t *>(a.x);
+    const uint16_t *w = static_cast<const uint16_t *>(a.w);
+    const int cgs = (a.C + 7) >> 3;
+    const __amdgpu_buffer_rsrc_t ry = make_rsrc(a.y, (long)a.B * a.P * a.Q * a.K * 2);
+    for (long idx = (long)rank * STREAM_THREADS + threadIdx.x; idx < total; idx += (long)nranks * STREAM_THREADS) {
+        const int fg = (int)(idx % groups);
+        const long m = idx / groups;
+        const int qq = (int)(m % a.Q), pp = (int)((m / a.Q) % a.P), n = (int)(m / ((long)a.Q * a.P));
+        const int fb = fg * 4;
+        float acc[4] = {0.f, 0.f, 0.f, 0.f};
+        for (int tap = 0; tap < a.R * a.R; ++tap) {
+            const int h = pp * a.stride - a.pad + tap / a.R, v = qq * a.stride - a.pad + tap % a.R;
+            if (h < 0 || h >= a.H || v < 0 || v >= a.W) continue;
+            const uint16_t *xp = x + (((long)n * a.H + h) * a.W + v) * a.C;
+            for (int cg = 0; cg < cgs; ++cg) {
+                float xv[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const int c = cg * 8 + j;
+                    xv[j] = 0.f;
+                    if (c < a.C) xv[j] = bf2f(__hip_atomic_load(xp + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM));
+                }
+                const uint16_t *wp = w + (((long)tap * a.CG + cg) * a.Kpad + fb) * 8;
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (fb + i < a.Kpad) {
+                        float wv[8];
+                        load8(wp + i * 8, wv);
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) acc[i] = fmaf(wv[j], xv[j], acc[i]);
+                    }
+            }
+        }
+        const long obase = m * a.K + fb;
+        float v4[4];
+        const int nf = min(4, a.K - fb);
+        for (int i = 0; i < 4; ++i)
+            v4[i] = i < nf ? activate(acc[i] * (a.scale ? a.scale[fb + i] : 1.0f) + a.shift[fb + i], a.act, a.hsigmoid)
+                           : 0.f;
+        uint16_t *yp = static_cast<uint16_t *>(a.y) + obase;
+        if (nf == 4 && (a.K & 3) == 0) {
+            act_st8<ST>(ry, (int)(obase * 2),
+                        make_uint2(f2bf(v4[0]) | (f2bf(v4[1]) << 16), f2bf(v4[2]) | (f2bf(v4[3]) << 16)));
+        } else {
+            for (int i = 0; i < nf; ++i)
+                __hip_atomic_store(yp + i, (uint16_t)f2bf(v4[i]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+}
+
+// Depthwise k x k: one thread per output pixel x 8 channels, taps in ring order.
+template <int LD, int ST>
+__device__ void dwconv_units(const ConvArgs &a, int rank, int nranks) {
+    const int cgs = a.K >> 3;
+    const long total = (long)a.B * a.P * a.Q * cgs;
+    const uint16_t *w = static_cast<const uint16_t *>(a.w);
+    const __amdgpu_buffer_rsrc_t rx = make_rsrc(a.x, (long)a.B * a.H * a.W * a.C * 2);
+    const __amdgpu_buffer_rsrc_t ry = make_rsrc(a.y, (long)a.B * a.P * a.Q * a.K * 2);
+    const int ntaps = a.R * a.R;
+    for (long idx = (long)rank * STREAM_THREADS + threadIdx.x; idx < total; idx += (long)nranks * STREAM_THREADS) {
+        const int cg = (int)(idx % cgs);
+        const long m = idx / cgs;
+        const int qq = (int)(m % a.Q), pp = (int)((m / a.Q) % a.P), n = (int)(m / ((long)a.Q * a.P));
+        const int c = cg * 8;
+        float acc[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] = 0.f;
+        for (int t = 0; t < ntaps; ++t) {
+            const int h = pp * a.stride + c_dw_dr[t], v = qq * a.stride + c_dw_ds[t];
+            if (h < 0 || h >= a.H || v < 0 || v >= a.W) continue;
+            float xv[8], wv[8];
+            unpack8(act_ld16<LD>(rx, (((n * a.H + h) * a.W + v) * a.C + c) * 2), xv);
+            load8(w + (long)t * a.Kpad + c, wv);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[j] = fmaf(wv[j], xv[j], acc[j]);
+        }
+        float sc[8], sh[8];
+        load8(a.scale + c, sc);
+        load8(a.shift + c, sh);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] = activate(acc[j] * sc[j] + sh[j], a.act, 0);
+        act_st16<ST>(ry, (int)((m * a.K + c) * 2), pack8(acc));
+    }
+}
+
+template <int LD, int ST>
+__device__ void maxpool_units(const PoolArgs &a, int rank, int nranks) {
+    const int cgs = a.C >> 3;
+    const long total = (long)a.B * a.P * a.Q * cgs;
+    const __amdgpu_buffer_rsrc_t rx = make_rsrc(a.x, (long)a.B * a.H * a.W * a.C * 2);
+    const __amdgpu_buffer_rsrc_t ry = make_rsrc(a.y, (long)a.B * a.P * a.Q * a.C * 2);
+    for (long idx = (long)rank * STREAM_THREADS + threadIdx.x; idx < total; idx += (long)nranks * STREAM_THREADS) {
+        const int cg = (int)(idx % cgs);
+        const long m = idx / cgs;
+        const int qq = (int)(m % a.Q), pp = (int)((m / a.Q) % a.P), n = (int)(m / ((long)a.Q * a.P));
+        float best[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) best[j] = -3.4028235e38f;
+        for (int r = 0; r < 3; ++r) {
+            const int h = pp * 2 - 1 + r;
+            if (h < 0 || h >= a.H) continue;
+            for (int s = 0; s < 3; ++s) {
+                const int v = qq * 2 - 1 + s;
+                if (v < 0 || v >= a.W) continue;
+                float xv[8];
+                unpack8(act_ld16<LD>(rx, (((n * a.H + h) * a.W + v) * a.C + cg * 8) * 2), xv);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) best[j] = fmaxf(best[j], xv[j]);
+            }
+        }
+        act_st16<ST>(ry, (int)((m * a.C + cg * 8) * 2), pack8(best));
+    }
+}
+
+// Global average: a workgroup takes (image, block of 8 channel groups); 64 pixel lanes x 8 channel
+// groups accumulate and a fixed binary tree in LDS combines them.
+template <int LD, int ST>
+__device__ void gap_units(const PoolArgs &a, float *lds, int rank, int nranks) {
+    float(*part)[8][9] = reinterpret_cast<float(*)[8][9]>(lds);  // [64][8][9]
+    const int cgs = a.C >> 3;
+    const int blocks_per_image = (cgs + 7) >> 3;
+    const int n_blocks = a.B * blocks_per_image;
+    const int cgi = threadIdx.x & 7, pl = threadIdx.x >> 3;
+    const int hw = a.H * a.W;
+    const __amdgpu_buffer_rsrc_t rx = make_rsrc(a.x, (long)a.B * hw * a.C * 2);
+    const __amdgpu_buffer_rsrc_t ry = make_rsrc(a.y, (long)a.B * a.C * 2);
+    for (int b = rank; b < n_blocks; b += nranks) {
+        const int n = b / blocks_per_image;
+        const int cg = (b - n * blocks_per_image) * 8 + cgi;
+        float acc[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] = 0.f;
+        if (cg < cgs)
+            for (int p = pl; p < hw; p += 64) {
+                float xv[8];
+                unpack8(act_ld16<LD>(rx, ((n * hw + p) * a.C + cg * 8) * 2), xv);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc[j] += xv[j];
+            }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) part[pl][cgi][j] = acc[j];
+        __syncthreads();
+        for (int s = 32; s > 0; s >>= 1) {
+            if (pl < s)
+#pragma unroll
+                for (int j = 0; j < 8; ++j) part[pl][cgi][j] += part[pl + s][cgi][j];
+            __syncthreads();
+        }
+        if (pl == 0 && cg < cgs) {
+            float o[8];
+            const float inv = 1.0f / (float)hw;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) o[j] = part[0][cgi][j] * inv;
+            act_st16<ST>(ry, (n * a.C + cg * 8) * 2, pack8(o));
+        }
+        __syncthreads();
+    }
+}
+
+template <int LD, int ST>
+__device__ void gate_units(const PoolArgs &a, int rank, int nranks) {
+    const int cgs = a.C >> 3;
+    const long total = (long)a.B * a.H * a.W * cgs;
+    const long bytes = (long)a.B * a.H * a.W * a.C * 2;
+    const __amdgpu_buffer_rsrc_t rx = make_rsrc(a.x, bytes);
+    const __amdgpu_buffer_rsrc_t ry = make_rsrc(a.y, bytes);
+    const __amdgpu_buffer_rsrc_t rg = make_rsrc(a.gate, (long)a.B * a.C * 4);
+    for (long idx = (long)rank * STREAM_THREADS + threadIdx.x; idx < total; idx += (long)nranks * STREAM_THREADS) {
+        const int cg = (int)(idx % cgs);
+        const long m = idx / cgs;
+        const int n = (int)(m / ((long)a.H * a.W));
+        float xv[8];
+        unpack8(act_ld16<LD>(rx, (int)((m * a.C + cg * 8) * 2)), xv);
+        const uint4 g0 = act_ld16<LD>(rg, (n * a.C + cg * 8) * 4), g1 = act_ld16<LD>(rg, (n * a.C + cg * 8) * 4 + 16);
+        xv[0] *= __uint_as_float(g0.x), xv[1] *= __uint_as_float(g0.y), xv[2] *= __uint_as_float(g0.z);
+        xv[3] *= __uint_as_float(g0.w), xv[4] *= __uint_as_float(g1.x), xv[5] *= __uint_as_float(g1.y);
+        xv[6] *= __uint_as_float(g1.z), xv[7] *= __uint_as_float(g1.w);
+        act_st16<ST>(ry, (int)((m * a.C + cg * 8) * 2), pack8(xv));
+    }
+}
+
+// Runs one op on the calling workgroup's share (rank of nranks).
+template <int LD, int ST, bool RES>
+__device__ void run_op(const DevOp &op, float *lds, int rank, int nranks, const ResView rv) {
+    switch (op.kind) {
+        case OP_CONV:
+        case OP_FC:
+            if ((op.conv.C & 7) != 0)
+                conv_direct_units<ST>(op.conv, rank, nranks);
+            else if (op.pt == 4)
+                conv_units<4, LD, ST, RES>(op, lds, rank, nranks, rv);
+            else if (op.pt == 2)
+                conv_units<2, LD, ST, RES>(op, lds, rank, nranks, rv);
+            else
+                conv_units<1, LD, ST, RES>(op, lds, rank, nranks, rv);
+            break;
+        case OP_DW:
+            dwconv_units<LD, ST>(op.conv, rank, nranks);
+            break;
+        case OP_MAXPOOL:
+            maxpool_units<LD, ST>(op.pool, rank, nranks);
+            break;
+        case OP_GAP:
+            gap_units<LD, ST>(op.pool, lds, rank, nranks);
+            break;
+        case OP_GATE:
+            gate_units<LD, ST>(op.pool, rank, nranks);
+            break;
+        default:
+            break;
+    }
+}
+
+// ------------------------------------------------------------------ the kernel
+
+__global__ __launch_bounds__(STREAM_THREADS) void sushi_stream_kernel(StreamArgs sa) {
+    __shared__ float lds[STREAM_WAVES * 4 * 256];  // conv partial sums; 64x8x9 floats for pooling fit too
+    __shared__ int barrier_ok;
+    __shared__ DevOp op;
+    unsigned long long epoch = sa.epoch_base;
+    for (int i = 0; i < sa.n_ops; ++i) {
+        // every thread needs the op's fields: stage the descriptor in LDS once per workgroup
+        {
+            const int *src = reinterpret_cast<const int *>(sa.prog + i);
+            int *dst = reinterpret_cast<int *>(&op);
+            for (int k = threadIdx.x; k < (int)(sizeof(DevOp) / sizeof(int)); k += STREAM_THREADS) dst[k] = src[k];
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            if (op.in_patch) op.conv.x = sa.input;
+            if (op.out_patch) op.conv.y = sa.logits;
+        }
+        __syncthreads();
+        run_op<AUX_SC1, AUX_SC1, false>(op, lds, (int)blockIdx.x, (int)gridDim.x, ResView{nullptr, nullptr, nullptr, nullptr});
+        if (i + 1 < sa.n_ops) {
+            epoch += 1;
+            if (!grid_barrier(sa, epoch, &barrier_ok)) return;
+        }
+    }
+}
+
+// ------------------------------------------------------------------ the team kernel
+// sync layout (64-bit words): [0] abort, [16*(1+t)] workgroups of team t, [16*(9+t)] barrier
+// arrivals of team t, [16*17] workgroups that joined, [16*(18+t)] go counter of team t,
+// [16*(26+t) .. +5] broadcast slot of team t (cmd/n_ops, prog, input, logits, seq).
+
+__device__ __forceinline__ unsigned long long ld_agent(const unsigned long long *p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_agent(unsigned long long *p, unsigned long long v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ unsigned long long ld_sys(const unsigned long long *p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
+__device__ __forceinline__ void raise_abort(const TeamArgs &ta) {
+    st_agent(&ta.sync[0], 1ull);
+    __hip_atomic_store(&ta.host->abort_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
+// Drops every line of this compute unit's vector L1.  A team's activations live in its XCD's L2:
+// stores reach the L2 (the L1 is write-through), but ordinary loads may be served by the L1, which
+// still holds the previous contents of a reused activation buffer.
+__device__ __forceinline__ void invalidate_vector_l1() {
+    asm volatile("buffer_inv sc1\n\ts_waitcnt vmcnt(0)" ::: "memory");
+}
+
+// Barrier among the workgroups of one team (all on one XCD); on return the compute unit's vector L1
+// is empty, so the loads of the next layer come from the L2.  Returns false when the wait ran out.
+__device__ __forceinline__ bool team_barrier(const TeamArgs &ta, int team, unsigned tsize, unsigned long long e,
+                                             int *lds_flag) {
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        unsigned long long *ctr = &ta.sync[16 * (9 + team)];
+        __hip_atomic_fetch_add(ctr, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned long long target = e * tsize;
+        int spins = 0, good = 1;
+        while (ld_agent(ctr) < target) {
+            if (++spins > ta.spin_limit || ld_agent(&ta.sync[0]) != 0) {
+                raise_abort(ta);
+                good = 0;
+                break;
+            }
+            __builtin_amdgcn_s_sleep(1);
+        }
+        invalidate_vector_l1();
+        *lds_flag = good;
+    }
+    __syncthreads();
+    return *lds_flag != 0;
+}
+
+// Copies the slabs this workgroup owns from the packed weights into its LDS store.
+__device__ void install_slabs(const ResTable *tab, int rank, char *store) {
+    for (int l = 0; l < tab->n_layers; ++l) {
+        const ResLayer &L = tab->layers[l];
+        if (L.n_res == 0) continue;
+        const uint16_t *w = static_cast<const uint16_t *>(L.w);
+        const int chunks = L.taps * L.cg_res * 16;  // 16-byte pieces of one slab
+        for (int f = 0; f < L.n_res; ++f) {
+            const ResEntry e = tab->entries[L.first_entry + f];
+            if (e.owner != rank) continue;
+            for (int i = threadIdx.x; i < chunks; i += STREAM_THREADS) {
+                const int j = i & 15, tc = i >> 4;
+                const int tap = tc / L.cg_res, cg = tc - tap * L.cg_res;
+                const uint4 v = *reinterpret_cast<const uint4 *>(w + (((long)tap * L.CG + cg) * L.Kpad + f * 16 + j) * 8);
+                *reinterpret_cast<uint4 *>(store + e.lds_off + (long)i * 16) = v;
+            }
+        }
+    }
+    __syncthreads();
+}
+
+__global__ __launch_bounds__(STREAM_THREADS) void sushi_team_kernel(TeamArgs ta) {
+    extern __shared__ __align__(16) char dyn_lds[];  // [RED_BYTES partial sums][RES_STORE_BYTES resident slabs]
+    float *lds = reinterpret_cast<float *>(dyn_lds);
+    char *store = dyn_lds + RED_BYTES;
+    __shared__ int unit_list[132];
+    __shared__ int flag;
+    __shared__ DevOp op;
+    __shared__ int s_team, s_rank, s_size;
+    __shared__ unsigned long long s_slot[5];
+
+    // ---- team formation: which XCD am I on, how many of us are there
+    if (threadIdx.x == 0) {
+        const int xcc = (int)(__builtin_amdgcn_s_getreg((3 << 11) | 20) & 7);  // XCC_ID, bits 3:0
+        s_team = xcc;
+        s_rank = (int)__hip_atomic_fetch_add(&ta.sync[16 * (1 + xcc)], 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_fetch_add(&ta.sync[16 * 17], 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        int spins = 0, good = 1;
+        while (ld_agent(&ta.sync[16 * 17]) < gridDim.x) {
+            if (++spins > ta.spin_limit || ld_agent(&ta.sync[0]) != 0) {
+                raise_abort(ta);
+                good = 0;
+                break;
+            }
+            __builtin_amdgcn_s_sleep(1);
+        }
+        s_size = (int)ld_agent(&ta.sync[16 * (1 + xcc)]);
+        flag = good;
+        if (good && blockIdx.x == 0) {
+            for (int t = 0; t < MAX_TEAMS; ++t)
+                __hip_atomic_store(&ta.host->team_size[t], (unsigned)ld_agent(&ta.sync[16 * (1 + t)]), __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_SYSTEM);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+            __hip_atomic_store(&ta.host->ready, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        }
+    }
+    __syncthreads();
+    if (!flag) return;
+    const int team = s_team, rank = s_rank, tsize = s_size;
+    const ResTable *table = nullptr;
+    if (ta.table && ta.table->team_size == tsize) {
+        table = ta.table;
+        install_slabs(table, rank, store);
+    }
+    char *arena = ta.arena + (long)team * ta.arena_bytes;
+    unsigned long long my_seq = ta.last_seq[team];
+    unsigned long long epoch = 0;
+    unsigned long long *go = &ta.sync[16 * (18 + team)];
+    unsigned long long *slot = &ta.sync[16 * (26 + team)];
+    const TeamPost *post = &ta.host->post[team];
+
+    for (unsigned long long iter = 1;; ++iter) {
+        // ---- wait for the next post: the leader polls the mailbox and hands the post to its team
+        if (threadIdx.x == 0) {
+            int good = 1;
+            if (rank == 0) {
+                const long long t0 = wall_clock64();
+                unsigned long long cmd = TEAM_STOP, n_ops = 0, seq = my_seq;
+                for (;;) {
+                    const unsigned long long sq = ld_sys(&post->seq);
+                    if (sq > my_seq) {
+                        seq = sq;
+                        cmd = (unsigned long long)__hip_atomic_load(&post->cmd, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+                        n_ops = (unsigned long long)__hip_atomic_load(&post->n_ops, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+                        break;
+                    }
+                    if (__hip_atomic_load(&ta.host->stop, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) != 0 ||
+                        ld_agent(&ta.sync[0]) != 0 || wall_clock64() - t0 > ta.idle_ticks)
+                        break;  // cmd stays TEAM_STOP
+                    __builtin_amdgcn_s_sleep(8);
+                }
+                st_agent(&slot[0], cmd | (n_ops << 32));
+                st_agent(&slot[1], ld_sys(reinterpret_cast<const unsigned long long *>(&post->prog)));
+                st_agent(&slot[2], ld_sys(reinterpret_cast<const unsigned long long *>(&post->input)));
+                st_agent(&slot[3], ld_sys(reinterpret_cast<const unsigned long long *>(&post->logits)));
+                st_agent(&slot[4], seq);
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // the slot is written before go moves
+                st_agent(go, iter);
+            } else {
+                const long long t0 = wall_clock64();
+                while (ld_agent(go) < iter) {
+                    if (ld_agent(&ta.sync[0]) != 0 || wall_clock64() - t0 > 4 * ta.idle_ticks + 100000000ll) {
+                        raise_abort(ta);
+                        good = 0;
+                        break;
+                    }
+                    __builtin_amdgcn_s_sleep(2);
+                }
+            }
+            if (good)
+                for (int k = 0; k < 5; ++k) s_slot[k] = ld_agent(&slot[k]);
+            invalidate_vector_l1();
+            flag = good;
+        }
+        __syncthreads();
+        if (!flag) return;
+        const int cmd = (int)(s_slot[0] & 0xFFFFFFFFull), n_ops = (int)(s_slot[0] >> 32);
+        if (cmd == TEAM_INSTALL) {
+            // a new cached SubGraph: refill the LDS store (a table made for another team size is ignored)
+            const ResTable *t = reinterpret_cast<const ResTable *>(s_slot[1]);
+            table = (t && t->team_size == tsize) ? t : nullptr;
+            if (table) install_slabs(table, rank, store);
+            epoch += 1;
+            if (!team_barrier(ta, team, tsize, epoch, &flag)) return;
+            if (rank == 0 && threadIdx.x == 0)
+                __hip_atomic_store(&ta.host->done[team * 8], s_slot[4], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+            my_seq = s_slot[4];
+            continue;
+        }
+        if (cmd != TEAM_RUN) return;
+        const DevOp *prog = reinterpret_cast<const DevOp *>(s_slot[1]);
+        const void *input = reinterpret_cast<const void *>(s_slot[2]);
+        void *logits = reinterpret_cast<void *>(s_slot[3]);
+        const unsigned long long seq = s_slot[4];
+
+        // ---- run the query inside this XCD
+        for (int i = 0; i < n_ops; ++i) {
+            {
+                const int *src = reinterpret_cast<const int *>(prog + i);
+                int *dst = reinterpret_cast<int *>(&op);
+                for (int k = threadIdx.x; k < (int)(sizeof(DevOp) / sizeof(int)); k += STREAM_THREADS) dst[k] = src[k];
+            }
+            __syncthreads();
+            if (threadIdx.x == 0) {
+                auto fix = [&](const void *p) -> const void * {
+                    return p ? static_cast<const void *>(arena + (reinterpret_cast<long>(p) - 1)) : nullptr;
+                };
+                op.conv.x = fix(op.conv.x), op.conv.y = const_cast<void *>(fix(op.conv.y)), op.conv.res = fix(op.conv.res);
+                op.pool.x = fix(op.pool.x), op.pool.y = const_cast<void *>(fix(op.pool.y));
+                op.pool.gate = static_cast<const float *>(fix(op.pool.gate));
+                if (op.in_patch) op.conv.x = input;
+                if (op.out_patch) op.conv.y = logits;
+            }
+            __syncthreads();
+            if (ta.trace && i == 0 && rank == 0 && threadIdx.x == 0) ta.trace[team * TRACE_SLOTS] = wall_clock64();
+            ResView rv{nullptr, nullptr, store, unit_list};
+            if (table && op.layer >= 0 && op.layer < table->n_layers && table->layers[op.layer].n_res > 0) {
+                rv.layer = &table->layers[op.layer];
+                rv.entries = table->entries + rv.layer->first_entry;
+            }
+            run_op<AUX_PLAIN, AUX_PLAIN, true>(op, lds, rank, tsize, rv);
+            epoch += 1;
+            if (!team_barrier(ta, team, tsize, epoch, &flag)) return;
+            if (ta.trace && rank == 0 && threadIdx.x == 0 && i + 1 < TRACE_SLOTS)
+                ta.trace[team * TRACE_SLOTS + i + 1] = wall_clock64();
+        }
+        // every workgroup's (write-through) logits stores have completed: report
+        if (rank == 0 && threadIdx.x == 0)
+            __hip_atomic_store(&ta.host->done[team * 8], seq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        my_seq = seq;
+    }
+}
+
+hipError_t prepare_team_kernel() {
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(sushi_team_kernel),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, RED_BYTES + RES_STORE_BYTES);
+}
+
+hipError_t team_kernel_blocks_per_cu(int *n) {
+    return hipOccupancyMaxActiveBlocksPerMultiprocessor(n, sushi_team_kernel, STREAM_THREADS,
+                                                        RED_BYTES + RES_STORE_BYTES);
+}
+
+hipError_t launch_team_kernel(const TeamArgs &a, int nwg, hipStream_t s) {
+    hipLaunchKernelGGL(sushi_team_kernel, dim3(nwg), dim3(STREAM_THREADS), RED_BYTES + RES_STORE_BYTES, s, a);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ host side
+
+void tile_dev_op(DevOp &op, int nwg, bool team) {
+    const ConvArgs &a = op.conv;
+    const long M = (long)a.B * a.P * a.Q;
+    const long ptiles = (M + 15) / 16, ftiles = (a.K + 15) / 16;
+    const int nsteps = a.R * a.R * ((a.C + 31) / 32);
+    int wk = 1;
+    while (wk < STREAM_WAVES && wk * 4 < nsteps) wk *= 2;  // about four reduction steps per wave
+    const int slots = STREAM_WAVES / wk;
+    // the widest pixel group that still gives every workgroup a unit group
+    int pt = 4;
+    while (pt > 1 && ftiles * ((ptiles + pt - 1) / pt) < (long)nwg * slots) pt /= 2;
+    if (ptiles <= 4 && ptiles > 2) pt = std::max(pt, 4);  // a handful of pixels: keep them in one unit
+    if (ptiles == 2) pt = std::max(pt, 2);
+    // team kernel: an op that is one pixel group may use resident slabs, which needs one unit per
+    // workgroup at a time (all eight waves on the same filter tile)
+    if (team && (ptiles + pt - 1) / pt == 1) wk = STREAM_WAVES;
+    op.pt = pt, op.wk = wk;
+    op.n_p = (int)((ptiles + pt - 1) / pt);
+    op.n_units = (int)(ftiles * op.n_p);
+}
+
+hipError_t launch_stream_kernel(const StreamArgs &a, int nwg, hipStream_t s) {
+    hipLaunchKernelGGL(sushi_stream_kernel, dim3(nwg), dim3(STREAM_THREADS), 0, s, a);
+    return hipGetLastError();
+}
+
+}  // namespace sushi

@@ -2,6 +2,7 @@
 // per-query plan cache and launch loop, counters.
 #include <hip/hip_runtime.h>
 
+#include <chrono>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -15,6 +16,7 @@
 #include "kernels.h"
 #include "model.h"
 #include "sched.h"
+#include "stream_kernel.h"
 
 using namespace sushi;
 
@@ -39,8 +41,18 @@ struct CachedPlan {
     hipGraphExec_t graph = nullptr;
     const void *graph_in = nullptr;
     void *graph_out = nullptr;
+    // exec mode 2: the plan as a device program for the stream kernel
+    DevOp *d_prog = nullptr;
+    int n_dev_ops = 0;
+    // exec mode 3: the same program with arena-relative activation pointers, for the team kernel
+    DevOp *d_team_prog = nullptr;
+    std::vector<DevOp> team_prog;     // host copy (tiling decides which ops can use resident slabs)
+    uint64_t table_version = ~0ull;   // residency table the figure below was computed for
+    uint64_t lds_bytes = 0;           // weight bytes this SubNet reads from resident LDS slabs
     ~CachedPlan() {
         if (graph) (void)hipGraphExecDestroy(graph);
+        if (d_prog) (void)hipFree(d_prog);
+        if (d_team_prog) (void)hipFree(d_team_prog);
     }
 };
 
@@ -67,6 +79,36 @@ struct sushi_ctx {
     sushi_stats stats{};
     int exec_mode = 0;
     hipStream_t capture_stream = nullptr;  // graphs are recorded here and replayed on `stream`
+    // exec mode 2 (stream kernel): barrier area, abort flag in pinned host memory, barriers counted so far
+    unsigned long long *d_sync = nullptr;
+    unsigned *h_abort = nullptr;
+    unsigned long long epoch_base = 0;
+    int stream_wgs = 0, stream_wgs_override = 0;
+    int team_wgs = 0, team_wgs_per_cu = 2;
+    int spin_limit = 400000;
+    // exec mode 3 (team kernel): mailboxes in pinned host memory, per-team arenas, private stream
+    TeamHostState *th = nullptr;
+    unsigned long long *d_tsync = nullptr;
+    char *d_tarena = nullptr;
+    long tarena_bytes = 0, tbig_bytes = 0, tsmall_bytes = 0;
+    int tarena_batch = 0;
+    hipStream_t pstream = nullptr;
+    bool team_launched = false;
+    unsigned long long posted[MAX_TEAMS] = {};
+    int next_team = 0;
+    long idle_ticks = 200000;  // 2 ms at 100 MHz
+    // residency table of the cached SubGraph (host copies + device generations)
+    struct ResGen {
+        ResTable *d_table = nullptr;
+        ResLayer *d_layers = nullptr;
+        ResEntry *d_entries = nullptr;
+    };
+    ResGen res_cur, res_prev;
+    std::vector<ResLayer> h_res_layers;
+    std::vector<ResEntry> h_res_entries;
+    uint64_t table_version = 0;
+    uint64_t table_bytes = 0;  // bytes of the cached SubGraph that sit in LDS (per team)
+    unsigned long long *d_trace = nullptr;
     // per-kernel timing (SUSHI_OPT_KERNEL_TIMING): event pairs around every launch
     bool timing = false;
     struct Pending {
@@ -402,6 +444,369 @@ int replay_graph(sushi_ctx *c, CachedPlan &cp, const void *input_dev, void *logi
     return SUSHI_OK;
 }
 
+// Exec mode 2: builds (once per plan) the device program and launches the stream kernel.
+int ensure_stream_state(sushi_ctx *c) {
+    if (c->d_sync) return SUSHI_OK;
+    hipError_t e;
+    hipDeviceProp_t prop;
+    if ((e = hipGetDeviceProperties(&prop, c->device)) != hipSuccess) return hip_fail(c, e, "hipGetDeviceProperties");
+    c->stream_wgs = std::max(BARRIER_GROUP, prop.multiProcessorCount / BARRIER_GROUP * BARRIER_GROUP);
+    if (c->stream_wgs_override) c->stream_wgs = c->stream_wgs_override;
+    if ((e = hipMalloc(reinterpret_cast<void **>(&c->d_sync), SYNC_WORDS * 8)) != hipSuccess)
+        return fail(c, SUSHI_ENOMEM, "hipMalloc(barrier area)");
+    if ((e = hipMemset(c->d_sync, 0, SYNC_WORDS * 8)) != hipSuccess) return hip_fail(c, e, "hipMemset");
+    if ((e = hipHostMalloc(reinterpret_cast<void **>(&c->h_abort), 64, hipHostMallocDefault)) != hipSuccess)
+        return fail(c, SUSHI_ENOMEM, "hipHostMalloc(abort flag)");
+    *c->h_abort = 0;
+    c->epoch_base = 0;
+    return SUSHI_OK;
+}
+
+int run_stream_kernel(sushi_ctx *c, CachedPlan &cp, const void *input_dev, void *logits_dev) {
+    if (!c->bf16) return fail(c, SUSHI_ESTATE, "the stream kernel runs in bf16 mode only");
+    int rc = ensure_stream_state(c);
+    if (rc) return rc;
+    hipError_t e;
+    if (*c->h_abort) {
+        // a wait inside an earlier launch ran out: drain, reset the barrier area, report
+        (void)hipStreamSynchronize(c->stream);
+        (void)hipMemset(c->d_sync, 0, SYNC_WORDS * 8);
+        *c->h_abort = 0;
+        c->epoch_base = 0;
+        return fail(c, SUSHI_EDEVICE, "an earlier query timed out at a grid barrier; its logits are invalid");
+    }
+    if (!cp.d_prog) {
+        std::vector<DevOp> prog;
+        for (const Launch &L : cp.launches) {
+            DevOp op{};
+            op.kind = L.kind;
+            op.conv = L.conv, op.pool = L.pool;
+            op.in_patch = L.in_patch, op.out_patch = L.out_patch;
+            op.pt = op.wk = 1;
+            op.layer = -1;
+            if (L.kind == OP_CONV || L.kind == OP_FC) tile_dev_op(op, c->stream_wgs, false);
+            prog.push_back(op);
+        }
+        if ((e = hipMalloc(reinterpret_cast<void **>(&cp.d_prog), prog.size() * sizeof(DevOp))) != hipSuccess)
+            return fail(c, SUSHI_ENOMEM, "hipMalloc(program)");
+        if ((e = hipMemcpy(cp.d_prog, prog.data(), prog.size() * sizeof(DevOp), hipMemcpyHostToDevice)) != hipSuccess)
+            return hip_fail(c, e, "hipMemcpy(program)");
+        cp.n_dev_ops = (int)prog.size();
+    }
+    StreamArgs sa{};
+    sa.prog = cp.d_prog, sa.n_ops = cp.n_dev_ops;
+    sa.input = input_dev, sa.logits = logits_dev;
+    sa.sync = c->d_sync, sa.epoch_base = c->epoch_base, sa.spin_limit = c->spin_limit, sa.abort_flag = c->h_abort;
+    if ((e = launch_stream_kernel(sa, c->stream_wgs, c->stream)) != hipSuccess) return hip_fail(c, e, "stream kernel");
+    c->epoch_base += (unsigned long long)stream_barriers(cp.n_dev_ops);
+    return SUSHI_OK;
+}
+
+// ---------------------------------------------------------------- SubGraph residency (team kernel)
+
+void free_res_gen(sushi_ctx::ResGen &g) {
+    if (g.d_table) (void)hipFree(g.d_table);
+    if (g.d_layers) (void)hipFree(g.d_layers);
+    if (g.d_entries) (void)hipFree(g.d_entries);
+    g = sushi_ctx::ResGen();
+}
+
+// Cuts the cached SubGraph into slabs and assigns them to the workgroups of a team: layers from
+// the last to the first (the late, few-pixel layers hold most weights and are the ones that use
+// their slabs), tiles round-robin over the ranks, first rank with room wins.
+int build_res_table(sushi_ctx *c) {
+    const int team_size = c->team_wgs / MAX_TEAMS;
+    const size_t n_layers = c->sn.layers.size();
+    c->h_res_layers.assign(n_layers, ResLayer{});
+    c->h_res_entries.clear();
+    c->table_bytes = 0;
+    ++c->table_version;
+    if (c->G.empty() || team_size < 1) return SUSHI_OK;
+    std::vector<long> used(team_size, 0);
+    int cursor = 0;
+    for (int l = (int)n_layers - 1; l >= 0; --l) {
+        const SuperLayer &L = c->sn.layers[l];
+        const sushi_layer_dims &g = c->G[l];
+        if (L.type == L_DW || g.K == 0) continue;
+        const int taps = L.Rmax * L.Rmax;
+        const int cg_res = std::min(g.C / 8, RES_STORE_BYTES / (taps * 256));
+        if (cg_res < 1) continue;
+        const long slab = (long)taps * cg_res * 256;
+        ResLayer &R = c->h_res_layers[l];
+        R.w = static_cast<const char *>(c->d_weights) + L.pk_w * 2;
+        R.Kpad = L.Kpad, R.CG = L.CG, R.taps = taps, R.cg_res = cg_res;
+        R.n_res = (g.K + 15) / 16;
+        R.first_entry = (int)c->h_res_entries.size();
+        bool any = false;
+        for (int f = 0; f < R.n_res; ++f) {
+            ResEntry e{-1, 0};
+            for (int k = 0; k < team_size; ++k) {
+                const int r = (cursor + k) % team_size;
+                if (used[r] + slab <= RES_STORE_BYTES) {
+                    e.owner = r, e.lds_off = (int)used[r];
+                    used[r] += slab;
+                    cursor = (r + 1) % team_size;
+                    c->table_bytes += (uint64_t)taps * cg_res * 8 * std::min(16, g.K - 16 * f) * 2;
+                    any = true;
+                    break;
+                }
+            }
+            c->h_res_entries.push_back(e);
+        }
+        if (!any) R.n_res = 0;
+    }
+    return SUSHI_OK;
+}
+
+// Uploads the table as a new device generation; the one before the previous is released.
+int upload_res_table(sushi_ctx *c) {
+    free_res_gen(c->res_prev);
+    c->res_prev = c->res_cur;
+    c->res_cur = sushi_ctx::ResGen();
+    if (c->h_res_entries.empty()) return SUSHI_OK;
+    hipError_t e;
+    sushi_ctx::ResGen g;
+    const size_t lb = c->h_res_layers.size() * sizeof(ResLayer), eb = c->h_res_entries.size() * sizeof(ResEntry);
+    if ((e = hipMalloc(reinterpret_cast<void **>(&g.d_layers), lb)) != hipSuccess ||
+        (e = hipMalloc(reinterpret_cast<void **>(&g.d_entries), eb)) != hipSuccess ||
+        (e = hipMalloc(reinterpret_cast<void **>(&g.d_table), sizeof(ResTable))) != hipSuccess) {
+        free_res_gen(g);
+        return fail(c, SUSHI_ENOMEM, "hipMalloc(residency table)");
+    }
+    ResTable t{};
+    t.n_layers = (int)c->h_res_layers.size(), t.team_size = c->team_wgs / MAX_TEAMS;
+    t.layers = g.d_layers, t.entries = g.d_entries;
+    if ((e = hipMemcpy(g.d_layers, c->h_res_layers.data(), lb, hipMemcpyHostToDevice)) != hipSuccess ||
+        (e = hipMemcpy(g.d_entries, c->h_res_entries.data(), eb, hipMemcpyHostToDevice)) != hipSuccess ||
+        (e = hipMemcpy(g.d_table, &t, sizeof(t), hipMemcpyHostToDevice)) != hipSuccess) {
+        free_res_gen(g);
+        return hip_fail(c, e, "hipMemcpy(residency table)");
+    }
+    c->res_cur = g;
+    return SUSHI_OK;
+}
+
+// Weight bytes of one SubNet that come out of resident slabs.
+void refresh_lds_bytes(sushi_ctx *c, CachedPlan &cp) {
+    if (cp.table_version == c->table_version) return;
+    cp.table_version = c->table_version;
+    cp.lds_bytes = 0;
+    if (c->h_res_entries.empty()) return;
+    for (const DevOp &op : cp.team_prog) {
+        if ((op.kind != OP_CONV && op.kind != OP_FC) || op.n_p != 1 || op.wk != STREAM_WAVES || op.layer < 0) continue;
+        if ((op.conv.C & 7) != 0) continue;
+        const ResLayer &R = c->h_res_layers[op.layer];
+        const int n_f = (op.conv.K + 15) / 16;
+        const int cgs = std::min(R.cg_res, op.conv.C / 8);
+        for (int f = 0; f < std::min(R.n_res, n_f); ++f)
+            if (c->h_res_entries[R.first_entry + f].owner >= 0)
+                cp.lds_bytes += (uint64_t)R.taps * cgs * 8 * std::min(16, op.conv.K - 16 * f) * 2;
+    }
+}
+
+// ---------------------------------------------------------------- exec mode 3: the team kernel
+
+bool team_kernel_running(sushi_ctx *c) {
+    return c->team_launched && hipStreamQuery(c->pstream) == hipErrorNotReady;
+}
+
+// Makes the team kernel leave (teams finish the post they are working on first) and waits for it.
+int stop_team_kernel(sushi_ctx *c) {
+    if (!c->team_launched) return SUSHI_OK;
+    c->th->stop = 1;
+    hipError_t e = hipStreamSynchronize(c->pstream);
+    c->th->stop = 0;
+    c->team_launched = false;
+    if (e != hipSuccess) return hip_fail(c, e, "team kernel");
+    return SUSHI_OK;
+}
+
+int launch_teams(sushi_ctx *c) {
+    hipError_t e;
+    if (c->team_launched) {
+        if ((e = hipStreamSynchronize(c->pstream)) != hipSuccess) return hip_fail(c, e, "team kernel");
+        c->team_launched = false;
+    }
+    if (c->th->abort_flag) {
+        c->th->abort_flag = 0;
+        for (int t = 0; t < MAX_TEAMS; ++t) c->th->done[t * 8] = c->posted[t];  // drop what was in flight
+        return fail(c, SUSHI_EDEVICE, "a wait inside the team kernel ran out; queries in flight were dropped");
+    }
+    c->th->ready = 0;
+    if ((e = hipMemsetAsync(c->d_tsync, 0, SYNC_WORDS * 8, c->pstream)) != hipSuccess) return hip_fail(c, e, "hipMemsetAsync");
+    TeamArgs ta{};
+    ta.host = c->th, ta.sync = c->d_tsync, ta.arena = c->d_tarena, ta.arena_bytes = c->tarena_bytes;
+    for (int t = 0; t < MAX_TEAMS; ++t) ta.last_seq[t] = c->th->done[t * 8];
+    ta.idle_ticks = c->idle_ticks, ta.spin_limit = c->spin_limit;
+    ta.trace = c->d_trace;
+    ta.table = c->res_cur.d_table;
+    if ((e = launch_team_kernel(ta, c->team_wgs, c->pstream)) != hipSuccess) return hip_fail(c, e, "team kernel launch");
+    c->team_launched = true;
+    const auto t0 = std::chrono::steady_clock::now();
+    while (!*(volatile unsigned *)&c->th->ready) {
+        if (std::chrono::steady_clock::now() - t0 > std::chrono::seconds(5)) {
+            (void)stop_team_kernel(c);
+            return fail(c, SUSHI_EDEVICE, "the team kernel did not start");
+        }
+    }
+    return SUSHI_OK;
+}
+
+int ensure_team_state(sushi_ctx *c, int batch) {
+    hipError_t e;
+    if (!c->th) {
+        hipDeviceProp_t prop;
+        if ((e = hipGetDeviceProperties(&prop, c->device)) != hipSuccess) return hip_fail(c, e, "hipGetDeviceProperties");
+        if ((e = prepare_team_kernel()) != hipSuccess) return hip_fail(c, e, "hipFuncSetAttribute");
+        // every workgroup must be resident at once (they wait for each other)
+        int fit = 0;
+        if ((e = team_kernel_blocks_per_cu(&fit)) != hipSuccess) return hip_fail(c, e, "occupancy query");
+        const int per_cu = std::max(1, std::min(c->team_wgs_per_cu, fit));
+        c->team_wgs = per_cu * std::max(BARRIER_GROUP, prop.multiProcessorCount / BARRIER_GROUP * BARRIER_GROUP);
+        if ((e = hipHostMalloc(reinterpret_cast<void **>(&c->th), sizeof(TeamHostState), hipHostMallocDefault)) != hipSuccess)
+            return fail(c, SUSHI_ENOMEM, "hipHostMalloc(mailboxes)");
+        std::memset(c->th, 0, sizeof(TeamHostState));
+        if ((e = hipMalloc(reinterpret_cast<void **>(&c->d_tsync), SYNC_WORDS * 8)) != hipSuccess)
+            return fail(c, SUSHI_ENOMEM, "hipMalloc(team sync)");
+        if ((e = hipStreamCreateWithFlags(&c->pstream, hipStreamNonBlocking)) != hipSuccess)
+            return hip_fail(c, e, "hipStreamCreateWithFlags");
+        int rc = build_res_table(c);  // a SubGraph may have been cached before the first query
+        if (rc == SUSHI_OK) rc = upload_res_table(c);
+        if (rc) return rc;
+    }
+    if (batch > c->tarena_batch) {
+        int rc = stop_team_kernel(c);
+        if (rc) return rc;
+        Plan p;
+        std::string err;
+        rc = plan_subnet(c->sn, largest_cfg(c->sn.arch), batch, p, err);
+        if (rc) return fail(c, rc, "arena: " + err);
+        if (c->d_tarena) (void)hipFree(c->d_tarena);
+        c->d_tarena = nullptr;
+        c->tbig_bytes = (long)round_up(p.max_big_elems * 2, 256);
+        c->tsmall_bytes = (long)round_up(std::max<size_t>(p.max_small_elems, 8) * 4, 256);
+        c->tarena_bytes = N_BIG_BUFS * c->tbig_bytes + N_SMALL_BUFS * c->tsmall_bytes;
+        if ((e = hipMalloc(reinterpret_cast<void **>(&c->d_tarena), (size_t)c->tarena_bytes * MAX_TEAMS)) != hipSuccess)
+            return fail(c, SUSHI_ENOMEM, "hipMalloc(team arenas)");
+        c->tarena_batch = batch;
+        for (auto &kv : c->plans)
+            if (kv.second->d_team_prog) {
+                (void)hipFree(kv.second->d_team_prog);
+                kv.second->d_team_prog = nullptr;
+                kv.second->team_prog.clear();
+            }
+    }
+    return SUSHI_OK;
+}
+
+// Blocks until team t has finished everything posted to it (relaunching the kernel if it has left).
+int wait_team(sushi_ctx *c, int t) {
+    const auto t0 = std::chrono::steady_clock::now();
+    unsigned spins = 0;
+    while (*(volatile unsigned long long *)&c->th->done[t * 8] != c->posted[t]) {
+        if ((++spins & 0x3FF) == 0) {
+            if (!team_kernel_running(c)) {
+                int rc = launch_teams(c);
+                if (rc) return rc;
+            }
+            if (std::chrono::steady_clock::now() - t0 > std::chrono::seconds(20))
+                return fail(c, SUSHI_EDEVICE, "timed out waiting for a team");
+        }
+    }
+    return SUSHI_OK;
+}
+
+int post_team_query(sushi_ctx *c, CachedPlan &cp, const void *input_dev, void *logits_dev, int batch) {
+    if (!c->bf16) return fail(c, SUSHI_ESTATE, "the team kernel runs in bf16 mode only");
+    int rc = ensure_team_state(c, batch);
+    if (rc) return rc;
+    hipError_t e;
+    if (!cp.d_team_prog) {
+        std::vector<DevOp> prog;
+        for (size_t i = 0; i < cp.launches.size(); ++i) {
+            const Launch &L = cp.launches[i];
+            const Op &o = cp.plan.ops[i];
+            DevOp op{};
+            op.kind = L.kind;
+            op.conv = L.conv, op.pool = L.pool;
+            op.in_patch = L.in_patch, op.out_patch = L.out_patch;
+            op.relative = 1;
+            op.pt = op.wk = 1;
+            auto rel = [&](int id, bool small) -> void * {
+                if (id < 0) return nullptr;
+                const long off = small ? N_BIG_BUFS * c->tbig_bytes + id * c->tsmall_bytes : id * c->tbig_bytes;
+                return reinterpret_cast<void *>(off + 1);
+            };
+            op.conv.x = rel(o.in_buf, o.in_small), op.conv.y = rel(o.out_buf, o.out_small);
+            op.conv.res = rel(o.res_buf, false);
+            op.pool.x = op.conv.x, op.pool.y = op.conv.y;
+            op.pool.gate = static_cast<const float *>(rel(o.gate_buf, true));
+            op.layer = (L.kind == OP_CONV || L.kind == OP_FC) ? o.layer : -1;
+            if (L.kind == OP_CONV || L.kind == OP_FC) tile_dev_op(op, c->team_wgs / MAX_TEAMS, true);
+            prog.push_back(op);
+        }
+        cp.team_prog = prog;
+        cp.table_version = ~0ull;
+        if ((e = hipMalloc(reinterpret_cast<void **>(&cp.d_team_prog), prog.size() * sizeof(DevOp))) != hipSuccess)
+            return fail(c, SUSHI_ENOMEM, "hipMalloc(program)");
+        if ((e = hipMemcpy(cp.d_team_prog, prog.data(), prog.size() * sizeof(DevOp), hipMemcpyHostToDevice)) != hipSuccess)
+            return hip_fail(c, e, "hipMemcpy(program)");
+        cp.n_dev_ops = (int)prog.size();
+    }
+    // the input must be complete before a team may read it
+    if (hipStreamQuery(c->stream) != hipSuccess && (e = hipStreamSynchronize(c->stream)) != hipSuccess)
+        return hip_fail(c, e, "hipStreamSynchronize");
+    if (!c->team_launched && (rc = launch_teams(c)) != SUSHI_OK) return rc;
+    int t = -1;
+    for (int k = 0; k < MAX_TEAMS; ++k) {
+        const int cand = (c->next_team + k) % MAX_TEAMS;
+        if (c->th->team_size[cand] > 0) {
+            t = cand;
+            break;
+        }
+    }
+    if (t < 0) return fail(c, SUSHI_EDEVICE, "no team has any workgroup");
+    c->next_team = (t + 1) % MAX_TEAMS;
+    if ((rc = wait_team(c, t)) != SUSHI_OK) return rc;
+    refresh_lds_bytes(c, cp);
+    c->stats.weight_bytes_lds += cp.lds_bytes;
+    c->stats.last_lds_bytes = cp.lds_bytes;
+    TeamPost &p = c->th->post[t];
+    p.cmd = TEAM_RUN, p.n_ops = cp.n_dev_ops, p.prog = cp.d_team_prog, p.input = input_dev, p.logits = logits_dev;
+    __atomic_thread_fence(__ATOMIC_RELEASE);
+    *(volatile unsigned long long *)&p.seq = ++c->posted[t];
+    return SUSHI_OK;
+}
+
+// Makes the teams of a running kernel refill their LDS stores from the current table (in mailbox
+// order, so queries posted earlier still see the old slabs); a stopped kernel installs at its start.
+int install_on_teams(sushi_ctx *c) {
+    if (!c->th) return SUSHI_OK;  // the team kernel has never run: the table is built at its first start
+    int rc = build_res_table(c);
+    if (rc == SUSHI_OK) rc = upload_res_table(c);
+    if (rc) return rc;
+    if (!team_kernel_running(c)) return SUSHI_OK;
+    for (int t = 0; t < MAX_TEAMS; ++t) {
+        if (c->th->team_size[t] == 0) continue;
+        if ((rc = wait_team(c, t)) != SUSHI_OK) return rc;
+        TeamPost &p = c->th->post[t];
+        p.cmd = TEAM_INSTALL, p.n_ops = 0, p.prog = reinterpret_cast<const DevOp *>(c->res_cur.d_table);
+        p.input = nullptr, p.logits = nullptr;
+        __atomic_thread_fence(__ATOMIC_RELEASE);
+        *(volatile unsigned long long *)&p.seq = ++c->posted[t];
+    }
+    return SUSHI_OK;
+}
+
+int synchronize_teams(sushi_ctx *c) {
+    if (!c->th) return SUSHI_OK;
+    for (int t = 0; t < MAX_TEAMS; ++t) {
+        int rc = wait_team(c, t);
+        if (rc) return rc;
+    }
+    return SUSHI_OK;
+}
+
 std::string plan_key(const sushi_subnet_cfg &cfg, int batch) {
     std::string k(reinterpret_cast<const char *>(&cfg), sizeof(cfg));
     k.append(reinterpret_cast<const char *>(&batch), sizeof(batch));
@@ -479,6 +884,18 @@ void sushi_destroy(sushi_ctx *c) {
     (void)drain_timing(c);
     for (hipEvent_t ev : c->free_events) (void)hipEventDestroy(ev);
     if (c->capture_stream) (void)hipStreamDestroy(c->capture_stream);
+    if (c->th) {
+        (void)stop_team_kernel(c);
+        (void)hipStreamDestroy(c->pstream);
+        (void)hipFree(c->d_tsync);
+        if (c->d_trace) (void)hipFree(c->d_trace);
+        free_res_gen(c->res_cur);
+        free_res_gen(c->res_prev);
+        if (c->d_tarena) (void)hipFree(c->d_tarena);
+        (void)hipHostFree(c->th);
+    }
+    if (c->d_sync) (void)hipFree(c->d_sync);
+    if (c->h_abort) (void)hipHostFree(c->h_abort);
     free_arena(c);
     if (c->d_weights) (void)hipFree(c->d_weights);
     if (c->d_params) (void)hipFree(c->d_params);
@@ -503,6 +920,10 @@ int sushi_load_supernet(sushi_ctx *c, const sushi_arch *arch, const void *weight
     if ((e = hipSetDevice(c->device)) != hipSuccess) return hip_fail(c, e, "hipSetDevice");
     if ((e = hipStreamSynchronize(c->stream)) != hipSuccess) return hip_fail(c, e, "hipStreamSynchronize");
     // drop whatever was loaded before
+    if (c->th) {
+        (void)synchronize_teams(c);
+        (void)stop_team_kernel(c);
+    }
     free_arena(c);
     c->plans.clear();
     if (c->d_weights) (void)hipFree(c->d_weights);
@@ -510,6 +931,10 @@ int sushi_load_supernet(sushi_ctx *c, const sushi_arch *arch, const void *weight
     c->d_weights = nullptr, c->d_params = nullptr, c->loaded = false;
     c->G.clear();
     ++c->g_version;
+    free_res_gen(c->res_cur);
+    free_res_gen(c->res_prev);
+    c->h_res_layers.clear(), c->h_res_entries.clear();
+    ++c->table_version;
     c->stats = sushi_stats{};
 
     const float *blob = static_cast<const float *>(weights);
@@ -552,7 +977,7 @@ int sushi_set_subgraph_cache(sushi_ctx *c, const sushi_subgraph_cfg *g, size_t b
         c->G.clear();
         ++c->g_version;
         c->stats.cache_bytes = 0;
-        return SUSHI_OK;
+        return install_on_teams(c);
     }
     if (g->n_layers != (int)c->sn.layers.size() || !g->layers)
         return fail(c, SUSHI_EINVAL, "SubGraph must list all " + std::to_string(c->sn.layers.size()) + " layers");
@@ -575,7 +1000,9 @@ int sushi_set_subgraph_cache(sushi_ctx *c, const sushi_subgraph_cfg *g, size_t b
     c->stats.cache_installs += 1;
     c->stats.cache_bytes_installed += bytes;
     c->stats.cache_bytes = bytes;
-    return SUSHI_OK;
+    int rc = install_on_teams(c);
+    c->stats.cache_bytes_lds = c->table_bytes;
+    return rc;
 }
 
 int sushi_infer(sushi_ctx *c, const sushi_subnet_cfg *cfg, const void *input_dev, int batch, void *logits_dev) {
@@ -604,7 +1031,13 @@ int sushi_infer(sushi_ctx *c, const sushi_subnet_cfg *cfg, const void *input_dev
     }
     refresh_residency(c, *cp);
 
-    if (c->exec_mode == 1) {
+    if (c->exec_mode == 3) {
+        int rc = post_team_query(c, *cp, input_dev, logits_dev, batch);
+        if (rc) return rc;
+    } else if (c->exec_mode == 2) {
+        int rc = run_stream_kernel(c, *cp, input_dev, logits_dev);
+        if (rc) return rc;
+    } else if (c->exec_mode == 1) {
         int rc = replay_graph(c, *cp, input_dev, logits_dev);
         if (rc) return rc;
     } else {
@@ -648,6 +1081,37 @@ int sushi_sched_record(sushi_ctx *c, const int32_t *vec, int *new_cache_idx_out)
     return SUSHI_OK;
 }
 
+int sushi_team_trace(sushi_ctx *c, int enable, uint64_t *out, int cap) {
+    if (!c || c->device < 0) return SUSHI_EINVAL;
+    hipError_t e;
+    int rc = synchronize_teams(c);
+    if (rc) return rc;
+    if ((rc = stop_team_kernel(c)) != SUSHI_OK) return rc;
+    if (out && c->d_trace && cap > 0) {
+        const size_t n = std::min<size_t>((size_t)cap, (size_t)MAX_TEAMS * TRACE_SLOTS);
+        if ((e = hipMemcpy(out, c->d_trace, n * 8, hipMemcpyDeviceToHost)) != hipSuccess) return hip_fail(c, e, "hipMemcpy(trace)");
+    }
+    if (enable && !c->d_trace) {
+        if ((e = hipMalloc(reinterpret_cast<void **>(&c->d_trace), MAX_TEAMS * TRACE_SLOTS * 8)) != hipSuccess)
+            return fail(c, SUSHI_ENOMEM, "hipMalloc(trace)");
+        (void)hipMemset(c->d_trace, 0, MAX_TEAMS * TRACE_SLOTS * 8);
+    } else if (!enable && c->d_trace) {
+        (void)hipFree(c->d_trace);
+        c->d_trace = nullptr;
+    }
+    return SUSHI_OK;
+}
+
+int sushi_synchronize(sushi_ctx *c) {
+    if (!c) return SUSHI_EINVAL;
+    if (c->device < 0) return SUSHI_OK;
+    int rc = synchronize_teams(c);
+    if (rc) return rc;
+    hipError_t e = hipStreamSynchronize(c->stream);
+    if (e != hipSuccess) return hip_fail(c, e, "hipStreamSynchronize");
+    return SUSHI_OK;
+}
+
 int sushi_get_stats(sushi_ctx *c, sushi_stats *out) {
     if (!c || !out) return SUSHI_EINVAL;
     *out = c->stats;
@@ -677,8 +1141,31 @@ int sushi_set_option(sushi_ctx *c, int option, int64_t value) {
         c->timing = value == 1;
         return SUSHI_OK;
     }
-    if (option == SUSHI_OPT_EXEC_MODE && (value == 0 || value == 1)) {
+    if (option == SUSHI_OPT_SPIN_LIMIT && value >= 0 && value <= 100000000) {
+        c->spin_limit = (int)value;
+        return SUSHI_OK;
+    }
+    if (option == SUSHI_OPT_EXEC_MODE && value >= 0 && value <= 3) {
+        if (c->exec_mode == 3 && value != 3 && c->th) {
+            int rc = synchronize_teams(c);
+            if (rc) return rc;
+            if ((rc = stop_team_kernel(c)) != SUSHI_OK) return rc;
+        }
         c->exec_mode = (int)value;
+        return SUSHI_OK;
+    }
+    if (option == SUSHI_OPT_STREAM_WGS && value >= BARRIER_GROUP && value <= 1024 && value % BARRIER_GROUP == 0) {
+        if (c->d_sync || c->th) return fail(c, SUSHI_ESTATE, "set the workgroup count before the first query");
+        c->stream_wgs_override = (int)value;
+        return SUSHI_OK;
+    }
+    if (option == SUSHI_OPT_TEAM_WGS_PER_CU && value >= 1 && value <= 2) {
+        if (c->th) return fail(c, SUSHI_ESTATE, "set the workgroup count before the first query");
+        c->team_wgs_per_cu = (int)value;
+        return SUSHI_OK;
+    }
+    if (option == SUSHI_OPT_IDLE_US && value >= 10 && value <= 10000000) {
+        c->idle_ticks = (long)value * 100;
         return SUSHI_OK;
     }
     return fail(c, SUSHI_EINVAL, "set_option: unknown option or value");
