@@ -6,8 +6,9 @@ on one input batch that already sits in HBM.  The default workload is the ResNet
 SuperNet at batch 1 with the sticky 1000-query stream (next SubNet repeats with p = 0.8).
 
 Prints ONE JSON line: queries/s over the timed steps, plus
-  roofline      the kernel family with the largest summed time, measured with HIP events around
-                every launch in a second, identical pass over the same steps;
+  roofline      the kernel with the largest summed time, measured with HIP events on the stream it
+                runs on: for the persistent team kernel (default) and the stream kernel inside the
+                timed region itself, for the per-layer modes in a second, identical pass;
   cpu_baseline  the CPU oracle timed on a bounded sample of the same stream.
 """
 import argparse
@@ -56,7 +57,8 @@ def main():
     ap.add_argument("--steps", type=int, default=1000)
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="resnet_bs1_sticky")
-    ap.add_argument("--exec-mode", type=int, default=1, help="0 = launch per layer, 1 = HIP graph replay")
+    ap.add_argument("--exec-mode", type=int, default=3,
+                    help="0 = launch per layer, 1 = HIP graph replay, 2 = stream kernel, 3 = persistent XCD-team kernel")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-roofline", action="store_true")
     args = ap.parse_args()
@@ -97,65 +99,81 @@ def main():
     n = len(gvecs[0])
     ctx.sushi_sched_init([[0] * n], [0.0], gvecs, [[1.0] * (len(gvecs) + 1)], Q, S.STRICT_LATENCY)
 
-    n_inputs = 8
+    n_inputs, n_outputs = 8, 64
     res = cfgs[0].resolution
     xs = [torch.from_numpy(T.make_input(11, t, batch, res, arch.in_channels, True)).cuda().to(torch.bfloat16)
           for t in range(n_inputs)]
-    logits = torch.empty(batch, arch.n_classes, device="cuda", dtype=torch.float32)
+    outs = [torch.empty(batch, arch.n_classes, device="cuda", dtype=torch.float32) for _ in range(n_outputs)]
+    torch.cuda.synchronize()
     state = {"cache": -1, "t": 0}
 
     def step():
         t = state["t"]
         cfg = cfgs[t % len(cfgs)]
-        ctx.sushi_infer(cfg, xs[t % n_inputs], logits)
+        ctx.sushi_infer(cfg, xs[t % n_inputs], outs[t % n_outputs])
         j = ctx.sushi_sched_record(vec_of[cfg.key()])
         if j >= 0 and j != state["cache"]:
             ctx.sushi_set_subgraph_cache(cands[j], budget)
             state["cache"] = j
         state["t"] = t + 1
 
-    ctx.sushi_set_option(S.OPT_EXEC_MODE, args.exec_mode)
+    mode = args.exec_mode
+    ctx.sushi_set_option(S.OPT_EXEC_MODE, mode)
     for _ in range(args.warmup):
         step()
-    torch.cuda.synchronize()
+    ctx.sushi_synchronize()
     t_start = state["t"]
+    # The timed region.  Modes 2 and 3 are timed with their HIP events in place (one pair per query
+    # launch / one pair around the persistent kernel); modes 0 and 1 are timed bare and measured per
+    # kernel in a second pass below.
+    live_events = mode in (2, 3) and not args.no_roofline
+    if mode == 3:
+        ctx.sushi_quiesce()          # the timed region gets a kernel launch of its own
+    if live_events:
+        ctx.sushi_set_option(S.OPT_KERNEL_TIMING, 1)
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
-    torch.cuda.synchronize()
+    ctx.sushi_synchronize()
     t1 = time.perf_counter()
     elapsed = t1 - t0
     stats = ctx.sushi_get_stats()
+    ks = None
+    if live_events:
+        ks = [k for k in ctx.sushi_get_kernel_stats() if k["launches"]]
+        ctx.sushi_set_option(S.OPT_KERNEL_TIMING, 0)
 
-    # p50 latency: the same steps one at a time, each followed by a synchronize
+    # p50 latency of a lone query: post, wait, repeat (same steps as the timed region)
     lat = []
     state["t"] = t_start
-    for _ in range(min(args.steps, 300)):
+    for _ in range(min(args.steps, 200)):
         a = time.perf_counter()
         step()
-        torch.cuda.synchronize()
+        ctx.sushi_synchronize()
         lat.append(time.perf_counter() - a)
     p50_ms = float(np.median(lat) * 1e3)
 
     roofline = None
     if not args.no_roofline:
-        # identical pass with HIP events around every launch (launch-per-layer mode)
-        ctx.sushi_set_option(S.OPT_EXEC_MODE, 0)
-        state["t"] = t_start
-        for _ in range(20):
-            step()
-        torch.cuda.synchronize()
-        state["t"] = t_start
-        ctx.sushi_set_option(S.OPT_KERNEL_TIMING, 1)
-        for _ in range(args.steps):
-            step()
-        torch.cuda.synchronize()
-        ks = [k for k in ctx.sushi_get_kernel_stats() if k["launches"]]
-        ctx.sushi_set_option(S.OPT_KERNEL_TIMING, 0)
+        if ks is None:
+            # identical pass, one launch per layer, HIP events around every launch
+            ctx.sushi_set_option(S.OPT_EXEC_MODE, 0)
+            state["t"] = t_start
+            for _ in range(20):
+                step()
+            ctx.sushi_synchronize()
+            state["t"] = t_start
+            ctx.sushi_set_option(S.OPT_KERNEL_TIMING, 1)
+            for _ in range(args.steps):
+                step()
+            ctx.sushi_synchronize()
+            ks = [k for k in ctx.sushi_get_kernel_stats() if k["launches"]]
+            ctx.sushi_set_option(S.OPT_KERNEL_TIMING, 0)
+            ctx.sushi_set_option(S.OPT_EXEC_MODE, mode)
         dom = max(ks, key=lambda k: k["total_ms"])
         sec = dom["total_ms"] * 1e-3
         ai = dom["flops"] / dom["bytes"]
-        if ai >= MFMA_BF16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9) and dom["name"].startswith("conv_mfma"):
+        if ai >= MFMA_BF16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9):
             achieved, peak, unit, bound = dom["flops"] / sec / 1e12, MFMA_BF16_PEAK_TFLOPS, "TFLOP/s", "mfma"
         else:
             achieved, peak, unit, bound = dom["bytes"] / sec / 1e9, HBM_PEAK_GBS, "GB/s", "hbm"
@@ -164,6 +182,7 @@ def main():
                     "avg_launch_us": dom["total_ms"] * 1e3 / dom["launches"],
                     "alg_bytes_per_launch": dom["bytes"] / dom["launches"],
                     "alg_flops_per_launch": dom["flops"] / dom["launches"],
+                    "arithmetic_intensity": ai,
                     "share_of_kernel_time": dom["total_ms"] / sum(k["total_ms"] for k in ks),
                     "all_kernels": {k["name"]: {"launches": k["launches"], "avg_us": k["total_ms"] * 1e3 / k["launches"],
                                                 "GBps": k["bytes"] / (k["total_ms"] * 1e-3) / 1e9,
@@ -193,7 +212,8 @@ def main():
                       "distinct_subnets": len(distinct), "candidate_subgraphs": len(cands)},
            "p50_latency_ms": p50_ms,
            "weight_bytes_per_query": stats["weight_bytes_total"] / max(1, stats["queries"]),
-           "weight_bytes_per_query_resident": stats["weight_bytes_resident"] / max(1, stats["queries"]),
+           "weight_bytes_per_query_in_cached_subgraph": stats["weight_bytes_resident"] / max(1, stats["queries"]),
+           "weight_bytes_per_query_from_lds": stats["weight_bytes_lds"] / max(1, stats["queries"]),
            "mean_hit_ratio": stats["sum_hit_ratio"] / max(1, stats["queries"]),
            "cache_installs": stats["cache_installs"],
            "roofline": roofline, "cpu_baseline": cpu}

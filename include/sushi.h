@@ -223,6 +223,10 @@ int sushi_infer(sushi_ctx *ctx, const sushi_subnet_cfg *cfg, const void *input_d
  * to the host and to later work on any stream. */
 int sushi_synchronize(sushi_ctx *ctx);
 
+/* sushi_synchronize, then makes the persistent team kernel (mode 3) leave, so that the GPU is free
+ * for other work; the next query starts it again (and refills the LDS stores). */
+int sushi_quiesce(sushi_ctx *ctx);
+
 /* Team-kernel diagnostics.  enable = 1: from the next start of the team kernel, each team leader
  * stamps a 100 MHz clock before the first op of a query and after the barrier of every op
  * (slot 0, then slot i+1 for op i; 256 slots per team, 8 teams).  Each call first waits for all
@@ -257,7 +261,7 @@ typedef enum {
                                    sushi_synchronize.  The kernel runs on a private stream and leaves by
                                    itself when no query arrives for SUSHI_OPT_IDLE_US. */
     SUSHI_OPT_KERNEL_TIMING = 1,/* 1 = bracket every launch with HIP events on the context's stream and
-                                   accumulate per kernel family (mode 0 only); setting 1 clears the totals */
+                                   accumulate per kernel family (modes 0, 2, 3); setting 1 clears the totals */
     SUSHI_OPT_SPIN_LIMIT = 2,   /* polls a stream-/team-kernel workgroup makes at one barrier before it
                                    gives up (default 400000, about a second) */
     SUSHI_OPT_STREAM_WGS = 4,   /* workgroups of the stream kernel (multiple of 16; default: one per
@@ -271,7 +275,9 @@ int sushi_set_option(sushi_ctx *ctx, int option, int64_t value);
 
 /* Per kernel family: launches timed, their summed duration, and the algorithmic bytes and flops
  * they processed (every input, output, residual, weight and scale/shift element of the active
- * slice counted once).  Waits for outstanding timed launches.  Writes min(n, cap) entries. */
+ * slice counted once).  One launch of the stream kernel is one query; one launch of the persistent
+ * team kernel lasts from its start to its exit and covers every query posted meanwhile.  Waits for
+ * outstanding timed launches (and makes the team kernel leave).  Writes min(n, cap) entries. */
 typedef struct sushi_kernel_stats {
     char name[32];
     uint64_t launches;

@@ -107,6 +107,7 @@ def lib():
     L.sushi_sched_record.argtypes = [vp, C.POINTER(C.c_int32), ip]
     L.sushi_get_stats.argtypes = [vp, C.POINTER(CStats)]
     L.sushi_synchronize.argtypes = [vp]
+    L.sushi_quiesce.argtypes = [vp]
     L.sushi_team_trace.argtypes = [vp, C.c_int, C.POINTER(C.c_uint64), C.c_int]
     L.sushi_set_option.argtypes = [vp, C.c_int, C.c_int64]
     L.sushi_get_kernel_stats.argtypes = [vp, C.POINTER(CKernelStats), C.c_int, ip]
@@ -232,6 +233,9 @@ class Sushi:
 
     def sushi_synchronize(self):
         _check(lib().sushi_synchronize(self._h), self._h)
+
+    def sushi_quiesce(self):
+        _check(lib().sushi_quiesce(self._h), self._h)
 
     def sushi_team_trace(self, enable):
         buf = (C.c_uint64 * (8 * 256))()

@@ -51,7 +51,9 @@ enum KernelClass {
     KC_MAXPOOL = 4,
     KC_GAP = 5,
     KC_GATE = 6,
-    KC_COUNT = 7
+    KC_STREAM = 7,  // sushi_stream_kernel (one launch per query)
+    KC_TEAM = 8,    // sushi_team_kernel (persistent; one launch serves many queries)
+    KC_COUNT = 9
 };
 const char *kernel_class_name(int kc);
 

@@ -467,7 +467,7 @@ static hipError_t launch_splitk(const ConvArgs &a, int wk, hipStream_t s) {
 const char *kernel_class_name(int kc) {
     static const char *names[KC_COUNT] = {"conv_direct_kernel", "conv_mfma_kernel", "conv_mfma_splitk_kernel",
                                           "dwconv_kernel",      "maxpool_kernel",   "gap_kernel",
-                                          "gate_kernel"};
+                                          "gate_kernel",        "sushi_stream_kernel", "sushi_team_kernel"};
     return kc >= 0 && kc < KC_COUNT ? names[kc] : "?";
 }
 

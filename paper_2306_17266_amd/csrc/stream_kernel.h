@@ -86,8 +86,8 @@ struct ResTable {
     const ResEntry *entries;  // DEVICE
 };
 
-struct TeamPost {  // written by the host, one per team
-    unsigned long long seq;  // bumped last
+struct TeamPost {  // written by the host
+    unsigned long long seq;  // the post's number (1, 2, ...)
     int cmd, n_ops;
     const DevOp *prog;  // DEVICE; activation pointers are arena offsets + 1 (TEAM_INSTALL: a ResTable)
     const void *input;  // DEVICE
@@ -95,9 +95,12 @@ struct TeamPost {  // written by the host, one per team
     unsigned long long pad[3];
 };
 
+constexpr int POST_RING = 8;  // posts a team's mailbox holds (post number s sits in slot s % POST_RING)
+
 struct TeamHostState {  // pinned HOST memory, device-visible
-    TeamPost post[MAX_TEAMS];
-    unsigned long long done[MAX_TEAMS * 8];  // done[8 t]: seq of team t's last finished post
+    TeamPost post[MAX_TEAMS][POST_RING];
+    unsigned long long posted[MAX_TEAMS * 8];  // posted[8 t]: number of posts written for team t (host)
+    unsigned long long done[MAX_TEAMS * 8];    // done[8 t]: number of posts team t has finished (kernel)
     unsigned team_size[MAX_TEAMS];
     unsigned ready;       // kernel: teams are formed, sizes valid
     unsigned stop;        // host: leave as soon as idle

@@ -88,10 +88,39 @@ __device__ __forceinline__ bool grid_barrier(const StreamArgs &sa, unsigned long
 
 // LD / ST: cache policy of activation loads / stores; sys_out: the output is the caller's buffer and
 // is written through to memory at system scope.
+// Scale and shift of the lane's four filters (and optionally the residual of one tile), fetched at
+// the start of a unit so that their latency hides behind the reduction.
+struct Epilogue {
+    float sc[4], sh[4];
+    u32x2_t res;
+    bool have, have_res;
+};
+
+template <int LD>
+__device__ __forceinline__ Epilogue fetch_epilogue(const ConvArgs &a, __amdgpu_buffer_rsrc_t rres, int fbase, int m,
+                                                   int M, bool want_res) {
+    Epilogue e;
+    e.have = fbase + 4 <= a.K && (a.K & 3) == 0;
+    e.have_res = false;
+    e.res = u32x2_t{0u, 0u};
+    if (e.have) {
+        const float4 sh = *reinterpret_cast<const float4 *>(a.shift + fbase);
+        float4 sc = make_float4(1.f, 1.f, 1.f, 1.f);
+        if (a.scale) sc = *reinterpret_cast<const float4 *>(a.scale + fbase);
+        e.sc[0] = sc.x, e.sc[1] = sc.y, e.sc[2] = sc.z, e.sc[3] = sc.w;
+        e.sh[0] = sh.x, e.sh[1] = sh.y, e.sh[2] = sh.z, e.sh[3] = sh.w;
+        if (want_res && a.res && m < M) {
+            e.res = __builtin_amdgcn_raw_buffer_load_b64(rres, (int)(((long)m * a.K + fbase) * 2), 0, LD);
+            e.have_res = true;
+        }
+    }
+    return e;
+}
+
 template <int LD, int ST>
 __device__ __forceinline__ void store_tile_coherent(const ConvArgs &a, __amdgpu_buffer_rsrc_t ry,
                                                     __amdgpu_buffer_rsrc_t rres, const f32x4_t acc, int fbase, int m,
-                                                    int M, bool sys_out) {
+                                                    int M, bool sys_out, const Epilogue &epi, bool epi_res) {
     if (fbase >= a.K || m >= M) return;
     const int nf = min(4, a.K - fbase);
     const bool vec = nf == 4 && (a.K & 3) == 0;
@@ -99,13 +128,14 @@ __device__ __forceinline__ void store_tile_coherent(const ConvArgs &a, __amdgpu_
     float v[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        const float sc = (a.scale && i < nf) ? a.scale[fbase + i] : 1.0f;
-        const float sh = i < nf ? a.shift[fbase + i] : 0.0f;
+        const float sc = epi.have ? epi.sc[i] : ((a.scale && i < nf) ? a.scale[fbase + i] : 1.0f);
+        const float sh = epi.have ? epi.sh[i] : (i < nf ? a.shift[fbase + i] : 0.0f);
         v[i] = acc[i] * sc + sh;
     }
     if (a.res) {
         if (vec) {
-            const u32x2_t r = __builtin_amdgcn_raw_buffer_load_b64(rres, (int)(o * 2), 0, LD);
+            const u32x2_t r = (epi_res && epi.have_res) ? epi.res
+                                                        : __builtin_amdgcn_raw_buffer_load_b64(rres, (int)(o * 2), 0, LD);
             v[0] += bf2f(r.x & 0xFFFFu), v[1] += bf2f(r.x >> 16), v[2] += bf2f(r.y & 0xFFFFu), v[3] += bf2f(r.y >> 16);
         } else {
             const uint16_t *rp = static_cast<const uint16_t *>(a.res) + o;
@@ -224,6 +254,9 @@ __device__ void conv_units(const DevOp &op, float *red, int rank, int nranks, co
             pw[pt] = qq * a.stride - a.pad;
         }
         const int fw = min(f0 + l16, a.Kpad - 1) * 8;
+        // the tile this wave will finish first is tile `ks` (if there is one)
+        const Epilogue epi = fetch_epilogue<LD>(a, rres, f0 + kg * 4, m0 + (wk == 1 ? 0 : ks) * 16 + l16, M,
+                                                active && (wk == 1 || ks < PT));
         f32x4_t acc[PT];
 #pragma unroll
         for (int pt = 0; pt < PT; ++pt) acc[pt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
@@ -267,7 +300,8 @@ __device__ void conv_units(const DevOp &op, float *red, int rank, int nranks, co
             if (active)
 #pragma unroll
                 for (int pt = 0; pt < PT; ++pt)
-                    store_tile_coherent<LD, ST>(a, ry, rres, acc[pt], f0 + kg * 4, m0 + pt * 16 + l16, M, sys_out);
+                    store_tile_coherent<LD, ST>(a, ry, rres, acc[pt], f0 + kg * 4, m0 + pt * 16 + l16, M, sys_out, epi,
+                                                pt == 0);
             continue;
         }
         // red[wave][PT][4][64]
@@ -282,7 +316,7 @@ __device__ void conv_units(const DevOp &op, float *red, int rank, int nranks, co
                 for (int k = 0; k < wk; ++k)
 #pragma unroll
                     for (int i = 0; i < 4; ++i) s[i] += red[(((slot * wk + k) * PT + t) * 4 + i) * 64 + lane];
-                store_tile_coherent<LD, ST>(a, ry, rres, s, f0 + kg * 4, m0 + t * 16 + l16, M, sys_out);
+                store_tile_coherent<LD, ST>(a, ry, rres, s, f0 + kg * 4, m0 + t * 16 + l16, M, sys_out, epi, t == ks);
             }
         __syncthreads();
     }
@@ -658,7 +692,7 @@ __global__ __launch_bounds__(STREAM_THREADS) void sushi_team_kernel(TeamArgs ta)
     unsigned long long epoch = 0;
     unsigned long long *go = &ta.sync[16 * (18 + team)];
     unsigned long long *slot = &ta.sync[16 * (26 + team)];
-    const TeamPost *post = &ta.host->post[team];
+    const unsigned long long *posted = &ta.host->posted[team * 8];
 
     for (unsigned long long iter = 1;; ++iter) {
         // ---- wait for the next post: the leader polls the mailbox and hands the post to its team
@@ -667,10 +701,11 @@ __global__ __launch_bounds__(STREAM_THREADS) void sushi_team_kernel(TeamArgs ta)
             if (rank == 0) {
                 const long long t0 = wall_clock64();
                 unsigned long long cmd = TEAM_STOP, n_ops = 0, seq = my_seq;
+                const TeamPost *post = &ta.host->post[team][0];
                 for (;;) {
-                    const unsigned long long sq = ld_sys(&post->seq);
-                    if (sq > my_seq) {
-                        seq = sq;
+                    if (ld_sys(posted) > my_seq) {
+                        seq = my_seq + 1;
+                        post = &ta.host->post[team][seq % POST_RING];
                         cmd = (unsigned long long)__hip_atomic_load(&post->cmd, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
                         n_ops = (unsigned long long)__hip_atomic_load(&post->n_ops, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
                         break;
@@ -725,12 +760,14 @@ __global__ __launch_bounds__(STREAM_THREADS) void sushi_team_kernel(TeamArgs ta)
         const unsigned long long seq = s_slot[4];
 
         // ---- run the query inside this XCD
+        constexpr int OP_WORDS = (int)(sizeof(DevOp) / sizeof(int));
+        static_assert(OP_WORDS <= STREAM_THREADS, "one thread per descriptor word");
+        // thread k carries word k of the next op's descriptor, fetched one op ahead
+        int next_word = (threadIdx.x < OP_WORDS && n_ops > 0) ? reinterpret_cast<const int *>(prog)[threadIdx.x] : 0;
         for (int i = 0; i < n_ops; ++i) {
-            {
-                const int *src = reinterpret_cast<const int *>(prog + i);
-                int *dst = reinterpret_cast<int *>(&op);
-                for (int k = threadIdx.x; k < (int)(sizeof(DevOp) / sizeof(int)); k += STREAM_THREADS) dst[k] = src[k];
-            }
+            if (threadIdx.x < OP_WORDS) reinterpret_cast<int *>(&op)[threadIdx.x] = next_word;
+            if (threadIdx.x < OP_WORDS && i + 1 < n_ops)
+                next_word = reinterpret_cast<const int *>(prog + i + 1)[threadIdx.x];
             __syncthreads();
             if (threadIdx.x == 0) {
                 auto fix = [&](const void *p) -> const void * {

@@ -33,6 +33,7 @@ struct CachedPlan {
     Plan plan;
     std::vector<Launch> launches;
     uint64_t weight_bytes = 0;
+    double alg_bytes = 0.0, alg_flops = 0.0;  // algorithmic traffic and arithmetic of the whole query
     double vec_norm2 = 0.0;           // sum K^2 + C^2 over layers
     uint64_t g_version = ~0ull;       // cache state the two figures below were computed for
     uint64_t resident_bytes = 0;
@@ -52,7 +53,6 @@ struct CachedPlan {
     ~CachedPlan() {
         if (graph) (void)hipGraphExecDestroy(graph);
         if (d_prog) (void)hipFree(d_prog);
-        if (d_team_prog) (void)hipFree(d_team_prog);
     }
 };
 
@@ -102,8 +102,22 @@ struct sushi_ctx {
         ResTable *d_table = nullptr;
         ResLayer *d_layers = nullptr;
         ResEntry *d_entries = nullptr;
+        unsigned long long install_seq[MAX_TEAMS] = {};  // post that installs this generation on team t
     };
-    ResGen res_cur, res_prev;
+    // Device memory the team mode needs while its kernel runs is carved from pools made up front and
+    // filled by asynchronous copies on a copy stream: hipMalloc / hipFree / hipMemcpy can wait for the
+    // whole device, i.e. for the persistent kernel to leave.
+    static constexpr size_t PROG_POOL_BYTES = 96u << 20;
+    static constexpr size_t RES_MAX_ENTRIES = 16384, RES_MAX_LAYERS = 256;
+    char *d_prog_pool = nullptr;
+    size_t prog_pool_used = 0;
+    char *h_stage = nullptr;  // pinned staging for the copies
+    size_t h_stage_bytes = 0;
+    hipStream_t copy_stream = nullptr;
+    static constexpr int N_RES_GENS = 4;
+    ResGen res_gens[N_RES_GENS];  // device tables stay alive while an install post may still name them
+    bool gen_valid[N_RES_GENS] = {};  // slot holds a table (false: nothing cached)
+    int gen_cur = 0;
     std::vector<ResLayer> h_res_layers;
     std::vector<ResEntry> h_res_entries;
     uint64_t table_version = 0;
@@ -119,6 +133,9 @@ struct sushi_ctx {
     std::vector<Pending> pending;
     std::vector<hipEvent_t> free_events;
     sushi_kernel_stats kstats[KC_COUNT] = {};
+    // the running team kernel's launch, when timed: its event pair and what has been posted to it
+    bool team_timed = false;
+    Pending team_pending{};
 };
 
 namespace {
@@ -497,18 +514,62 @@ int run_stream_kernel(sushi_ctx *c, CachedPlan &cp, const void *input_dev, void 
     sa.prog = cp.d_prog, sa.n_ops = cp.n_dev_ops;
     sa.input = input_dev, sa.logits = logits_dev;
     sa.sync = c->d_sync, sa.epoch_base = c->epoch_base, sa.spin_limit = c->spin_limit, sa.abort_flag = c->h_abort;
+    sushi_ctx::Pending pend{};
+    if (c->timing) {
+        if ((e = get_event(c, &pend.a)) != hipSuccess || (e = get_event(c, &pend.b)) != hipSuccess ||
+            (e = hipEventRecord(pend.a, c->stream)) != hipSuccess)
+            return hip_fail(c, e, "kernel timing");
+    }
     if ((e = launch_stream_kernel(sa, c->stream_wgs, c->stream)) != hipSuccess) return hip_fail(c, e, "stream kernel");
+    if (c->timing) {
+        if ((e = hipEventRecord(pend.b, c->stream)) != hipSuccess) return hip_fail(c, e, "kernel timing");
+        pend.kc = KC_STREAM, pend.bytes = cp.alg_bytes, pend.flops = cp.alg_flops;
+        c->pending.push_back(pend);
+        if (c->pending.size() >= 4096 && (e = drain_timing(c)) != hipSuccess) return hip_fail(c, e, "kernel timing");
+    }
     c->epoch_base += (unsigned long long)stream_barriers(cp.n_dev_ops);
     return SUSHI_OK;
 }
 
 // ---------------------------------------------------------------- SubGraph residency (team kernel)
 
+bool team_kernel_running(sushi_ctx *c);
+int launch_teams(sushi_ctx *c);
+
 void free_res_gen(sushi_ctx::ResGen &g) {
     if (g.d_table) (void)hipFree(g.d_table);
     if (g.d_layers) (void)hipFree(g.d_layers);
     if (g.d_entries) (void)hipFree(g.d_entries);
     g = sushi_ctx::ResGen();
+}
+
+// Host -> device copy that does not wait for other streams: through pinned staging on the copy stream.
+int upload_async(sushi_ctx *c, void *dst, const void *src, size_t bytes) {
+    if (bytes > c->h_stage_bytes) return fail(c, SUSHI_ENOMEM, "staging buffer too small");
+    std::memcpy(c->h_stage, src, bytes);
+    hipError_t e = hipMemcpyAsync(dst, c->h_stage, bytes, hipMemcpyHostToDevice, c->copy_stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(c->copy_stream);
+    if (e != hipSuccess) return hip_fail(c, e, "hipMemcpyAsync");
+    return SUSHI_OK;
+}
+
+// Pools and table slots of the team mode; called once, before the kernel first runs.
+int make_team_pools(sushi_ctx *c) {
+    hipError_t e;
+    c->h_stage_bytes = 1u << 20;
+    if ((e = hipHostMalloc(reinterpret_cast<void **>(&c->h_stage), c->h_stage_bytes, hipHostMallocDefault)) != hipSuccess)
+        return fail(c, SUSHI_ENOMEM, "hipHostMalloc(staging)");
+    if ((e = hipStreamCreateWithFlags(&c->copy_stream, hipStreamNonBlocking)) != hipSuccess)
+        return hip_fail(c, e, "hipStreamCreateWithFlags");
+    if ((e = hipMalloc(reinterpret_cast<void **>(&c->d_prog_pool), sushi_ctx::PROG_POOL_BYTES)) != hipSuccess)
+        return fail(c, SUSHI_ENOMEM, "hipMalloc(program pool)");
+    for (auto &g : c->res_gens) {
+        if ((e = hipMalloc(reinterpret_cast<void **>(&g.d_layers), sushi_ctx::RES_MAX_LAYERS * sizeof(ResLayer))) != hipSuccess ||
+            (e = hipMalloc(reinterpret_cast<void **>(&g.d_entries), sushi_ctx::RES_MAX_ENTRIES * sizeof(ResEntry))) != hipSuccess ||
+            (e = hipMalloc(reinterpret_cast<void **>(&g.d_table), sizeof(ResTable))) != hipSuccess)
+            return fail(c, SUSHI_ENOMEM, "hipMalloc(residency tables)");
+    }
+    return SUSHI_OK;
 }
 
 // Cuts the cached SubGraph into slabs and assigns them to the workgroups of a team: layers from
@@ -532,6 +593,7 @@ int build_res_table(sushi_ctx *c) {
         const int cg_res = std::min(g.C / 8, RES_STORE_BYTES / (taps * 256));
         if (cg_res < 1) continue;
         const long slab = (long)taps * cg_res * 256;
+        if (c->h_res_entries.size() + (size_t)(g.K + 15) / 16 > sushi_ctx::RES_MAX_ENTRIES) break;
         ResLayer &R = c->h_res_layers[l];
         R.w = static_cast<const char *>(c->d_weights) + L.pk_w * 2;
         R.Kpad = L.Kpad, R.CG = L.CG, R.taps = taps, R.cg_res = cg_res;
@@ -558,31 +620,37 @@ int build_res_table(sushi_ctx *c) {
     return SUSHI_OK;
 }
 
-// Uploads the table as a new device generation; the one before the previous is released.
+// Uploads the table as a new device generation.  The slot it takes over held the generation from
+// three installs ago; every team must have got past that generation's install post first.
 int upload_res_table(sushi_ctx *c) {
-    free_res_gen(c->res_prev);
-    c->res_prev = c->res_cur;
-    c->res_cur = sushi_ctx::ResGen();
+    const int slot = (c->gen_cur + 1) % sushi_ctx::N_RES_GENS;
+    sushi_ctx::ResGen &g = c->res_gens[slot];
+    if (c->th)
+        for (int t = 0; t < MAX_TEAMS; ++t) {
+            const auto t0 = std::chrono::steady_clock::now();
+            unsigned spins = 0;
+            while (*(volatile unsigned long long *)&c->th->done[t * 8] < g.install_seq[t]) {
+                if ((++spins & 0x3FF) != 0) continue;
+                if (!team_kernel_running(c)) {  // the post is still in the mailbox: let a new launch serve it
+                    int rc = launch_teams(c);
+                    if (rc) return rc;
+                }
+                if (std::chrono::steady_clock::now() - t0 > std::chrono::seconds(20))
+                    return fail(c, SUSHI_EDEVICE, "timed out waiting for an install");
+            }
+        }
+    c->gen_cur = slot;
+    c->gen_valid[slot] = false;
     if (c->h_res_entries.empty()) return SUSHI_OK;
-    hipError_t e;
-    sushi_ctx::ResGen g;
-    const size_t lb = c->h_res_layers.size() * sizeof(ResLayer), eb = c->h_res_entries.size() * sizeof(ResEntry);
-    if ((e = hipMalloc(reinterpret_cast<void **>(&g.d_layers), lb)) != hipSuccess ||
-        (e = hipMalloc(reinterpret_cast<void **>(&g.d_entries), eb)) != hipSuccess ||
-        (e = hipMalloc(reinterpret_cast<void **>(&g.d_table), sizeof(ResTable))) != hipSuccess) {
-        free_res_gen(g);
-        return fail(c, SUSHI_ENOMEM, "hipMalloc(residency table)");
-    }
+    if (c->h_res_layers.size() > sushi_ctx::RES_MAX_LAYERS) return fail(c, SUSHI_ENOMEM, "too many layers for the table");
     ResTable t{};
     t.n_layers = (int)c->h_res_layers.size(), t.team_size = c->team_wgs / MAX_TEAMS;
     t.layers = g.d_layers, t.entries = g.d_entries;
-    if ((e = hipMemcpy(g.d_layers, c->h_res_layers.data(), lb, hipMemcpyHostToDevice)) != hipSuccess ||
-        (e = hipMemcpy(g.d_entries, c->h_res_entries.data(), eb, hipMemcpyHostToDevice)) != hipSuccess ||
-        (e = hipMemcpy(g.d_table, &t, sizeof(t), hipMemcpyHostToDevice)) != hipSuccess) {
-        free_res_gen(g);
-        return hip_fail(c, e, "hipMemcpy(residency table)");
-    }
-    c->res_cur = g;
+    int rc = upload_async(c, g.d_layers, c->h_res_layers.data(), c->h_res_layers.size() * sizeof(ResLayer));
+    if (rc == SUSHI_OK) rc = upload_async(c, g.d_entries, c->h_res_entries.data(), c->h_res_entries.size() * sizeof(ResEntry));
+    if (rc == SUSHI_OK) rc = upload_async(c, g.d_table, &t, sizeof(t));
+    if (rc) return rc;
+    c->gen_valid[slot] = true;
     return SUSHI_OK;
 }
 
@@ -606,6 +674,13 @@ void refresh_lds_bytes(sushi_ctx *c, CachedPlan &cp) {
 
 // ---------------------------------------------------------------- exec mode 3: the team kernel
 
+// Hands the finished (or finishing) team-kernel launch over to the timing totals.
+void close_team_timing(sushi_ctx *c) {
+    if (!c->team_timed) return;
+    c->pending.push_back(c->team_pending);
+    c->team_timed = false;
+}
+
 bool team_kernel_running(sushi_ctx *c) {
     return c->team_launched && hipStreamQuery(c->pstream) == hipErrorNotReady;
 }
@@ -617,6 +692,7 @@ int stop_team_kernel(sushi_ctx *c) {
     hipError_t e = hipStreamSynchronize(c->pstream);
     c->th->stop = 0;
     c->team_launched = false;
+    close_team_timing(c);
     if (e != hipSuccess) return hip_fail(c, e, "team kernel");
     return SUSHI_OK;
 }
@@ -639,8 +715,21 @@ int launch_teams(sushi_ctx *c) {
     for (int t = 0; t < MAX_TEAMS; ++t) ta.last_seq[t] = c->th->done[t * 8];
     ta.idle_ticks = c->idle_ticks, ta.spin_limit = c->spin_limit;
     ta.trace = c->d_trace;
-    ta.table = c->res_cur.d_table;
+    ta.table = c->gen_valid[c->gen_cur] ? c->res_gens[c->gen_cur].d_table : nullptr;
+    close_team_timing(c);
+    if (c->timing) {
+        sushi_ctx::Pending &tp = c->team_pending;
+        tp = sushi_ctx::Pending{};
+        if ((e = get_event(c, &tp.a)) != hipSuccess || (e = get_event(c, &tp.b)) != hipSuccess ||
+            (e = hipEventRecord(tp.a, c->pstream)) != hipSuccess)
+            return hip_fail(c, e, "kernel timing");
+        tp.kc = KC_TEAM;
+    }
     if ((e = launch_team_kernel(ta, c->team_wgs, c->pstream)) != hipSuccess) return hip_fail(c, e, "team kernel launch");
+    if (c->timing) {
+        if ((e = hipEventRecord(c->team_pending.b, c->pstream)) != hipSuccess) return hip_fail(c, e, "kernel timing");
+        c->team_timed = true;
+    }
     c->team_launched = true;
     const auto t0 = std::chrono::steady_clock::now();
     while (!*(volatile unsigned *)&c->th->ready) {
@@ -670,7 +759,9 @@ int ensure_team_state(sushi_ctx *c, int batch) {
             return fail(c, SUSHI_ENOMEM, "hipMalloc(team sync)");
         if ((e = hipStreamCreateWithFlags(&c->pstream, hipStreamNonBlocking)) != hipSuccess)
             return hip_fail(c, e, "hipStreamCreateWithFlags");
-        int rc = build_res_table(c);  // a SubGraph may have been cached before the first query
+        int rc = make_team_pools(c);
+        if (rc) return rc;
+        rc = build_res_table(c);  // a SubGraph may have been cached before the first query
         if (rc == SUSHI_OK) rc = upload_res_table(c);
         if (rc) return rc;
     }
@@ -691,7 +782,6 @@ int ensure_team_state(sushi_ctx *c, int batch) {
         c->tarena_batch = batch;
         for (auto &kv : c->plans)
             if (kv.second->d_team_prog) {
-                (void)hipFree(kv.second->d_team_prog);
                 kv.second->d_team_prog = nullptr;
                 kv.second->team_prog.clear();
             }
@@ -715,6 +805,32 @@ int wait_team(sushi_ctx *c, int t) {
     }
     return SUSHI_OK;
 }
+
+// Blocks until team t's mailbox has room for one more post and returns that slot.
+int reserve_post(sushi_ctx *c, int t, TeamPost **slot) {
+    const auto t0 = std::chrono::steady_clock::now();
+    unsigned spins = 0;
+    while (c->posted[t] - *(volatile unsigned long long *)&c->th->done[t * 8] >= (unsigned long long)POST_RING) {
+        if ((++spins & 0x3FF) == 0) {
+            if (!team_kernel_running(c)) {
+                int rc = launch_teams(c);
+                if (rc) return rc;
+            }
+            if (std::chrono::steady_clock::now() - t0 > std::chrono::seconds(20))
+                return fail(c, SUSHI_EDEVICE, "timed out waiting for a team");
+        }
+    }
+    *slot = &c->th->post[t][(c->posted[t] + 1) % POST_RING];
+    return SUSHI_OK;
+}
+
+void publish_post(sushi_ctx *c, int t, TeamPost *slot) {
+    slot->seq = c->posted[t] + 1;
+    __atomic_thread_fence(__ATOMIC_RELEASE);
+    *(volatile unsigned long long *)&c->th->posted[t * 8] = ++c->posted[t];
+}
+
+int synchronize_teams(sushi_ctx *c);
 
 int post_team_query(sushi_ctx *c, CachedPlan &cp, const void *input_dev, void *logits_dev, int batch) {
     if (!c->bf16) return fail(c, SUSHI_ESTATE, "the team kernel runs in bf16 mode only");
@@ -747,10 +863,17 @@ int post_team_query(sushi_ctx *c, CachedPlan &cp, const void *input_dev, void *l
         }
         cp.team_prog = prog;
         cp.table_version = ~0ull;
-        if ((e = hipMalloc(reinterpret_cast<void **>(&cp.d_team_prog), prog.size() * sizeof(DevOp))) != hipSuccess)
-            return fail(c, SUSHI_ENOMEM, "hipMalloc(program)");
-        if ((e = hipMemcpy(cp.d_team_prog, prog.data(), prog.size() * sizeof(DevOp), hipMemcpyHostToDevice)) != hipSuccess)
-            return hip_fail(c, e, "hipMemcpy(program)");
+        const size_t bytes = round_up(prog.size() * sizeof(DevOp), 256);
+        if (c->prog_pool_used + bytes > sushi_ctx::PROG_POOL_BYTES) {
+            // pool exhausted: forget every program (after the teams are done with them) and start over
+            if ((rc = synchronize_teams(c)) != SUSHI_OK) return rc;
+            for (auto &kv : c->plans) kv.second->d_team_prog = nullptr;
+            c->prog_pool_used = 0;
+        }
+        DevOp *dst = reinterpret_cast<DevOp *>(c->d_prog_pool + c->prog_pool_used);
+        if ((rc = upload_async(c, dst, prog.data(), prog.size() * sizeof(DevOp))) != SUSHI_OK) return rc;
+        c->prog_pool_used += bytes;
+        cp.d_team_prog = dst;
         cp.n_dev_ops = (int)prog.size();
     }
     // the input must be complete before a team may read it
@@ -767,14 +890,15 @@ int post_team_query(sushi_ctx *c, CachedPlan &cp, const void *input_dev, void *l
     }
     if (t < 0) return fail(c, SUSHI_EDEVICE, "no team has any workgroup");
     c->next_team = (t + 1) % MAX_TEAMS;
-    if ((rc = wait_team(c, t)) != SUSHI_OK) return rc;
+    TeamPost *slot = nullptr;
+    if ((rc = reserve_post(c, t, &slot)) != SUSHI_OK) return rc;
+    if (c->team_timed) c->team_pending.bytes += cp.alg_bytes, c->team_pending.flops += cp.alg_flops;
     refresh_lds_bytes(c, cp);
     c->stats.weight_bytes_lds += cp.lds_bytes;
     c->stats.last_lds_bytes = cp.lds_bytes;
-    TeamPost &p = c->th->post[t];
+    TeamPost &p = *slot;
     p.cmd = TEAM_RUN, p.n_ops = cp.n_dev_ops, p.prog = cp.d_team_prog, p.input = input_dev, p.logits = logits_dev;
-    __atomic_thread_fence(__ATOMIC_RELEASE);
-    *(volatile unsigned long long *)&p.seq = ++c->posted[t];
+    publish_post(c, t, slot);
     return SUSHI_OK;
 }
 
@@ -788,12 +912,13 @@ int install_on_teams(sushi_ctx *c) {
     if (!team_kernel_running(c)) return SUSHI_OK;
     for (int t = 0; t < MAX_TEAMS; ++t) {
         if (c->th->team_size[t] == 0) continue;
-        if ((rc = wait_team(c, t)) != SUSHI_OK) return rc;
-        TeamPost &p = c->th->post[t];
-        p.cmd = TEAM_INSTALL, p.n_ops = 0, p.prog = reinterpret_cast<const DevOp *>(c->res_cur.d_table);
+        TeamPost *slot = nullptr;
+        if ((rc = reserve_post(c, t, &slot)) != SUSHI_OK) return rc;
+        TeamPost &p = *slot;
+        p.cmd = TEAM_INSTALL, p.n_ops = 0, p.prog = reinterpret_cast<const DevOp *>(c->gen_valid[c->gen_cur] ? c->res_gens[c->gen_cur].d_table : nullptr);
         p.input = nullptr, p.logits = nullptr;
-        __atomic_thread_fence(__ATOMIC_RELEASE);
-        *(volatile unsigned long long *)&p.seq = ++c->posted[t];
+        publish_post(c, t, slot);
+        c->res_gens[c->gen_cur].install_seq[t] = c->posted[t];
     }
     return SUSHI_OK;
 }
@@ -816,6 +941,8 @@ std::string plan_key(const sushi_subnet_cfg &cfg, int batch) {
 }  // namespace
 
 extern "C" {
+
+int sushi_synchronize(sushi_ctx *c);
 
 int sushi_describe_supernet(const sushi_arch *arch, sushi_tensor_desc *out, int cap, int *n_out) {
     if (!arch || !n_out || cap < 0 || (cap > 0 && !out)) return SUSHI_EINVAL;
@@ -889,8 +1016,10 @@ void sushi_destroy(sushi_ctx *c) {
         (void)hipStreamDestroy(c->pstream);
         (void)hipFree(c->d_tsync);
         if (c->d_trace) (void)hipFree(c->d_trace);
-        free_res_gen(c->res_cur);
-        free_res_gen(c->res_prev);
+        for (auto &g : c->res_gens) free_res_gen(g);
+        if (c->d_prog_pool) (void)hipFree(c->d_prog_pool);
+        if (c->h_stage) (void)hipHostFree(c->h_stage);
+        if (c->copy_stream) (void)hipStreamDestroy(c->copy_stream);
         if (c->d_tarena) (void)hipFree(c->d_tarena);
         (void)hipHostFree(c->th);
     }
@@ -931,9 +1060,9 @@ int sushi_load_supernet(sushi_ctx *c, const sushi_arch *arch, const void *weight
     c->d_weights = nullptr, c->d_params = nullptr, c->loaded = false;
     c->G.clear();
     ++c->g_version;
-    free_res_gen(c->res_cur);
-    free_res_gen(c->res_prev);
+    for (bool &v : c->gen_valid) v = false;
     c->h_res_layers.clear(), c->h_res_entries.clear();
+    c->prog_pool_used = 0;
     ++c->table_version;
     c->stats = sushi_stats{};
 
@@ -977,6 +1106,7 @@ int sushi_set_subgraph_cache(sushi_ctx *c, const sushi_subgraph_cfg *g, size_t b
         c->G.clear();
         ++c->g_version;
         c->stats.cache_bytes = 0;
+        c->stats.cache_bytes_lds = 0;
         return install_on_teams(c);
     }
     if (g->n_layers != (int)c->sn.layers.size() || !g->layers)
@@ -1030,6 +1160,12 @@ int sushi_infer(sushi_ctx *c, const sushi_subnet_cfg *cfg, const void *input_dev
         c->stats.plan_cache_misses++;
     }
     refresh_residency(c, *cp);
+    if (cp->alg_bytes == 0.0)
+        for (const Launch &L : cp->launches) {
+            double b = 0.0, f = 0.0;
+            launch_cost(c, L, &b, &f);
+            cp->alg_bytes += b, cp->alg_flops += f;
+        }
 
     if (c->exec_mode == 3) {
         int rc = post_team_query(c, *cp, input_dev, logits_dev, batch);
@@ -1102,6 +1238,14 @@ int sushi_team_trace(sushi_ctx *c, int enable, uint64_t *out, int cap) {
     return SUSHI_OK;
 }
 
+int sushi_quiesce(sushi_ctx *c) {
+    if (!c) return SUSHI_EINVAL;
+    if (c->device < 0) return SUSHI_OK;
+    int rc = sushi_synchronize(c);
+    if (rc) return rc;
+    return c->th ? stop_team_kernel(c) : SUSHI_OK;
+}
+
 int sushi_synchronize(sushi_ctx *c) {
     if (!c) return SUSHI_EINVAL;
     if (c->device < 0) return SUSHI_OK;
@@ -1121,6 +1265,11 @@ int sushi_get_stats(sushi_ctx *c, sushi_stats *out) {
 int sushi_get_kernel_stats(sushi_ctx *c, sushi_kernel_stats *out, int cap, int *n_out) {
     if (!c || !n_out || cap < 0 || (cap > 0 && !out)) return SUSHI_EINVAL;
     if (c->device >= 0) {
+        if (c->th) {
+            int rc = synchronize_teams(c);
+            if (rc == SUSHI_OK) rc = stop_team_kernel(c);
+            if (rc) return rc;
+        }
         hipError_t e = drain_timing(c);
         if (e != hipSuccess) return hip_fail(c, e, "kernel timing");
     }
