@@ -59,6 +59,11 @@ def main():
     ap.add_argument("--workload", default="resnet_bs1_sticky")
     ap.add_argument("--exec-mode", type=int, default=3,
                     help="0 = launch per layer, 1 = HIP graph replay, 2 = stream kernel, 3 = persistent XCD-team kernel")
+    ap.add_argument("--sgs", choices=["sched", "off"], default="sched",
+                    help="sched = the scheduler re-chooses the cached SubGraph every Q queries; off = nothing is cached")
+    ap.add_argument("--Q", type=int, default=0, help="queries between cache re-choices (default: the workload's)")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="run one 256 MiB device-to-device copy first (reference dispatch for byte counters)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-roofline", action="store_true")
     args = ap.parse_args()
@@ -73,7 +78,7 @@ def main():
     from workloads import tensors as T
 
     wl = build_workload(args.workload)
-    arch, batch, Q, budget = wl["arch"], wl["batch"], wl["Q"], wl["budget"]
+    arch, batch, Q, budget = wl["arch"], wl["batch"], args.Q or wl["Q"], wl["budget"]
     table = S.sushi_describe_supernet(arch)
     tensors = T.make_weights([(s, k) for _, s, k in table], 1, True)
     ctx = S.Sushi(0)
@@ -112,11 +117,17 @@ def main():
         cfg = cfgs[t % len(cfgs)]
         ctx.sushi_infer(cfg, xs[t % n_inputs], outs[t % n_outputs])
         j = ctx.sushi_sched_record(vec_of[cfg.key()])
-        if j >= 0 and j != state["cache"]:
+        if args.sgs == "sched" and j >= 0 and j != state["cache"]:
             ctx.sushi_set_subgraph_cache(cands[j], budget)
             state["cache"] = j
         state["t"] = t + 1
 
+    if args.calibration_copy:
+        src = torch.zeros(256 << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     mode = args.exec_mode
     ctx.sushi_set_option(S.OPT_EXEC_MODE, mode)
     for _ in range(args.warmup):
@@ -208,7 +219,7 @@ def main():
     out = {"metric": "SubNet queries/sec (batch %d)" % batch, "value": args.steps / elapsed, "unit": "queries/s",
            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": elapsed / args.steps * 1e3,
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-           "config": {"workload": args.workload, "description": wl["desc"], "exec_mode": args.exec_mode,
+           "config": {"workload": args.workload, "description": wl["desc"], "exec_mode": args.exec_mode, "sgs": args.sgs, "Q": Q,
                       "distinct_subnets": len(distinct), "candidate_subgraphs": len(cands)},
            "p50_latency_ms": p50_ms,
            "weight_bytes_per_query": stats["weight_bytes_total"] / max(1, stats["queries"]),

@@ -574,7 +574,8 @@ __global__ __launch_bounds__(STREAM_THREADS) void sushi_stream_kernel(StreamArgs
 // ------------------------------------------------------------------ the team kernel
 // sync layout (64-bit words): [0] abort, [16*(1+t)] workgroups of team t, [16*(9+t)] barrier
 // arrivals of team t, [16*17] workgroups that joined, [16*(18+t)] go counter of team t,
-// [16*(26+t) .. +5] broadcast slot of team t (cmd/n_ops, prog, input, logits, seq).
+// [16*(26+t) .. +5] broadcast slot of team t (cmd/n_ops, prog, input, logits, seq), [16*34] clock of
+// the latest post any team received (a team leaves only when the whole kernel has been idle).
 
 __device__ __forceinline__ unsigned long long ld_agent(const unsigned long long *p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -704,14 +705,16 @@ __global__ __launch_bounds__(STREAM_THREADS) void sushi_team_kernel(TeamArgs ta)
                 const TeamPost *post = &ta.host->post[team][0];
                 for (;;) {
                     if (ld_sys(posted) > my_seq) {
+                        st_agent(&ta.sync[16 * 34], (unsigned long long)wall_clock64());  // any team's post keeps all teams alive
                         seq = my_seq + 1;
                         post = &ta.host->post[team][seq % POST_RING];
                         cmd = (unsigned long long)__hip_atomic_load(&post->cmd, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
                         n_ops = (unsigned long long)__hip_atomic_load(&post->n_ops, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
                         break;
                     }
+                    const long long last = std::max(t0, (long long)ld_agent(&ta.sync[16 * 34]));
                     if (__hip_atomic_load(&ta.host->stop, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) != 0 ||
-                        ld_agent(&ta.sync[0]) != 0 || wall_clock64() - t0 > ta.idle_ticks)
+                        ld_agent(&ta.sync[0]) != 0 || wall_clock64() - last > ta.idle_ticks)
                         break;  // cmd stays TEAM_STOP
                     __builtin_amdgcn_s_sleep(8);
                 }

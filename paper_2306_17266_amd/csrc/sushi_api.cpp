@@ -78,6 +78,7 @@ struct sushi_ctx {
     Scheduler sched;
     sushi_stats stats{};
     int exec_mode = 0;
+    bool stream_dirty = false;  // work was enqueued on `stream` since the last synchronize
     hipStream_t capture_stream = nullptr;  // graphs are recorded here and replayed on `stream`
     // exec mode 2 (stream kernel): barrier area, abort flag in pinned host memory, barriers counted so far
     unsigned long long *d_sync = nullptr;
@@ -1167,6 +1168,7 @@ int sushi_infer(sushi_ctx *c, const sushi_subnet_cfg *cfg, const void *input_dev
             cp->alg_bytes += b, cp->alg_flops += f;
         }
 
+    if (c->exec_mode != 3) c->stream_dirty = true;
     if (c->exec_mode == 3) {
         int rc = post_team_query(c, *cp, input_dev, logits_dev, batch);
         if (rc) return rc;
@@ -1251,8 +1253,12 @@ int sushi_synchronize(sushi_ctx *c) {
     if (c->device < 0) return SUSHI_OK;
     int rc = synchronize_teams(c);
     if (rc) return rc;
+    // Nothing of this library runs on the context's stream in mode 3, and a wait on the default
+    // stream may wait for the persistent kernel instead (until it idles out).
+    if (c->exec_mode == 3 && !c->stream_dirty) return SUSHI_OK;
     hipError_t e = hipStreamSynchronize(c->stream);
     if (e != hipSuccess) return hip_fail(c, e, "hipStreamSynchronize");
+    c->stream_dirty = false;
     return SUSHI_OK;
 }
 
