@@ -23,13 +23,13 @@ constexpr int SYNC_WORDS = 64 * 16;  // 64-bit words in the barrier area (128-by
 struct DevOp {
     int kind;      // OpKind (model.h)
     int pt, wk;    // dense conv: pixel tiles per unit (1, 2, 4) and waves sharing one unit (1, 2, 4, 8)
-    int n_units;   // dense conv: filter tiles x pixel groups
+    int n_units;   // dense conv: filter groups x pixel groups
     int n_p;       // dense conv: pixel groups
     int in_patch;  // input pointer is the caller's input buffer
     int out_patch; // output pointer is the caller's logits buffer
     int relative;  // activation pointers hold (offset into the team's arena) + 1
     int layer;     // SuperNet layer of a conv / FC op, -1 otherwise
-    int pad0;
+    int ft;        // dense conv: filter tiles per unit (1, 2, 4); ft * pt <= 4
     ConvArgs conv;
     PoolArgs pool;
 };

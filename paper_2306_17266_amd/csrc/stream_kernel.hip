@@ -189,9 +189,10 @@ struct ResView {
     int *list;                // LDS scratch for the unit list (>= 130 ints)
 };
 
-template <int PT, int LD, int ST, bool RES>
+template <int FT, int PT, int LD, int ST, bool RES>
 __device__ void conv_units(const DevOp &op, float *red, int rank, int nranks, const ResView rv) {
-    constexpr int U = PT == 4 ? 2 : 4;  // steps whose loads are in flight together (register budget)
+    constexpr int NT = FT * PT;                      // 16 x 16 tiles of one unit (at most 4)
+    constexpr int U = (FT + PT) >= 4 ? 2 : ((FT + PT) == 3 ? 3 : 4);  // steps in flight (register budget)
     const ConvArgs &a = op.conv;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wk = op.wk, slots = STREAM_WAVES / wk;
@@ -208,8 +209,8 @@ __device__ void conv_units(const DevOp &op, float *red, int rank, int nranks, co
     const int n_groups = (op.n_units + slots - 1) / slots;
 
     const bool sys_out = op.out_patch != 0;
-    // unit list of a resident op: entries are (filter tile) | (resident ? 1 << 16 : 0)
-    const bool listed = RES && rv.layer != nullptr && op.n_p == 1 && slots == 1;
+    // unit list of a resident op (FT = 1): entries are (filter tile) | (resident ? 1 << 16 : 0)
+    const bool listed = RES && FT == 1 && rv.layer != nullptr && op.n_p == 1 && slots == 1;
     int n_listed = 0;
     if (listed) {
         const int n_f = op.n_units;
@@ -236,11 +237,11 @@ __device__ void conv_units(const DevOp &op, float *red, int rank, int nranks, co
     for (int g = first; g < limit; g += stride) {
         const int unit = listed ? (rv.list[1 + g] & 0xFFFF) : g * slots + slot;
         const bool active = unit < op.n_units;
-        const int ftile = active ? unit / op.n_p : 0, pgroup = active ? unit - ftile * op.n_p : 0;
-        const int f0 = ftile * 16, m0 = pgroup * PT * 16;
+        const int fgroup = active ? unit / op.n_p : 0, pgroup = active ? unit - fgroup * op.n_p : 0;
+        const int f0 = fgroup * FT * 16, m0 = pgroup * PT * 16;
         const bool resident = listed && (rv.list[1 + g] >> 16) != 0;
         const int cg_res = resident ? rv.layer->cg_res : 0;
-        const char *slab = resident ? rv.store + rv.entries[ftile].lds_off : nullptr;
+        const char *slab = resident ? rv.store + rv.entries[fgroup].lds_off : nullptr;
         int pn[PT], ph[PT], pw[PT];
         bool pv[PT];
 #pragma unroll
@@ -253,17 +254,25 @@ __device__ void conv_units(const DevOp &op, float *red, int rank, int nranks, co
             ph[pt] = pp * a.stride - a.pad;
             pw[pt] = qq * a.stride - a.pad;
         }
-        const int fw = min(f0 + l16, a.Kpad - 1) * 8;
-        // the tile this wave will finish first is tile `ks` (if there is one)
-        const Epilogue epi = fetch_epilogue<LD>(a, rres, f0 + kg * 4, m0 + (wk == 1 ? 0 : ks) * 16 + l16, M,
-                                                active && (wk == 1 || ks < PT));
-        f32x4_t acc[PT];
+        int fw[FT];
 #pragma unroll
-        for (int pt = 0; pt < PT; ++pt) acc[pt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        for (int ft = 0; ft < FT; ++ft) fw[ft] = min(f0 + ft * 16 + l16, a.Kpad - 1) * 8;
+        // scale/shift of every filter tile now, and the residual of the tile this wave finishes first
+        const int t0 = wk == 1 ? 0 : ks;
+        Epilogue epi[FT];
+#pragma unroll
+        for (int ft = 0; ft < FT; ++ft)
+            epi[ft] = fetch_epilogue<LD>(a, rres, f0 + ft * 16 + kg * 4, m0 + (t0 % PT) * 16 + l16, M,
+                                         active && t0 < NT && t0 / PT == ft);
+        f32x4_t acc[FT][PT];
+#pragma unroll
+        for (int ft = 0; ft < FT; ++ft)
+#pragma unroll
+            for (int pt = 0; pt < PT; ++pt) acc[ft][pt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
         if (active) {
             for (int base = ks; base < nsteps; base += wk * U) {
-                Frag fa[U], fb[U][PT];
+                Frag fa[U][FT], fb[U][PT];
                 bool ok[U][PT];
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
@@ -275,10 +284,13 @@ __device__ void conv_units(const DevOp &op, float *red, int rank, int nranks, co
                     const int dr = tap / a.R, ds = tap - dr * a.R;
                     const bool cv = live && c0 < a.C;
                     const int cc = cv ? c0 : 0;
-                    if (RES && (cc >> 3) < cg_res)
-                        fa[u].u = *reinterpret_cast<const uint4 *>(slab + ((tap * cg_res + (cc >> 3)) * 16 + l16) * 16);
-                    else
-                        fa[u].u = *reinterpret_cast<const uint4 *>(w + ((long)tap * a.CG + (cc >> 3)) * a.Kpad * 8 + fw);
+                    if (RES && FT == 1 && (cc >> 3) < cg_res) {
+                        fa[u][0].u = *reinterpret_cast<const uint4 *>(slab + ((tap * cg_res + (cc >> 3)) * 16 + l16) * 16);
+                    } else {
+                        const uint16_t *wp = w + ((long)tap * a.CG + (cc >> 3)) * a.Kpad * 8;
+#pragma unroll
+                        for (int ft = 0; ft < FT; ++ft) fa[u][ft].u = *reinterpret_cast<const uint4 *>(wp + fw[ft]);
+                    }
 #pragma unroll
                     for (int pt = 0; pt < PT; ++pt) {
                         const int h = ph[pt] + dr, v = pw[pt] + ds;
@@ -288,35 +300,50 @@ __device__ void conv_units(const DevOp &op, float *red, int rank, int nranks, co
                     }
                 }
 #pragma unroll
-                for (int u = 0; u < U; ++u)
+                for (int u = 0; u < U; ++u) {
 #pragma unroll
-                    for (int pt = 0; pt < PT; ++pt) {
+                    for (int pt = 0; pt < PT; ++pt)
                         if (!ok[u][pt]) fb[u][pt].u = make_uint4(0, 0, 0, 0);
-                        acc[pt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[u].v, fb[u][pt].v, acc[pt], 0, 0, 0);
-                    }
+#pragma unroll
+                    for (int ft = 0; ft < FT; ++ft)
+#pragma unroll
+                        for (int pt = 0; pt < PT; ++pt)
+                            acc[ft][pt] =
+                                __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[u][ft].v, fb[u][pt].v, acc[ft][pt], 0, 0, 0);
+                }
             }
         }
         if (wk == 1) {
             if (active)
 #pragma unroll
-                for (int pt = 0; pt < PT; ++pt)
-                    store_tile_coherent<LD, ST>(a, ry, rres, acc[pt], f0 + kg * 4, m0 + pt * 16 + l16, M, sys_out, epi,
-                                                pt == 0);
+                for (int ft = 0; ft < FT; ++ft)
+#pragma unroll
+                    for (int pt = 0; pt < PT; ++pt)
+                        store_tile_coherent<LD, ST>(a, ry, rres, acc[ft][pt], f0 + ft * 16 + kg * 4, m0 + pt * 16 + l16, M,
+                                                    sys_out, epi[ft], ft == 0 && pt == 0);
             continue;
         }
-        // red[wave][PT][4][64]
+        // red[wave][NT][4][64]
 #pragma unroll
-        for (int pt = 0; pt < PT; ++pt)
+        for (int ft = 0; ft < FT; ++ft)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) red[((wave * PT + pt) * 4 + i) * 64 + lane] = acc[pt][i];
+            for (int pt = 0; pt < PT; ++pt)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) red[((wave * NT + ft * PT + pt) * 4 + i) * 64 + lane] = acc[ft][pt][i];
         __syncthreads();
         if (active)
-            for (int t = ks; t < PT; t += wk) {
+            for (int t = ks; t < NT; t += wk) {
                 f32x4_t s = f32x4_t{0.f, 0.f, 0.f, 0.f};
                 for (int k = 0; k < wk; ++k)
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) s[i] += red[(((slot * wk + k) * PT + t) * 4 + i) * 64 + lane];
-                store_tile_coherent<LD, ST>(a, ry, rres, s, f0 + kg * 4, m0 + t * 16 + l16, M, sys_out, epi, t == ks);
+                    for (int i = 0; i < 4; ++i) s[i] += red[(((slot * wk + k) * NT + t) * 4 + i) * 64 + lane];
+                const int ft = t / PT, pt = t - ft * PT;
+                Epilogue e = epi[0];
+#pragma unroll
+                for (int k = 1; k < FT; ++k)
+                    if (ft == k) e = epi[k];
+                store_tile_coherent<LD, ST>(a, ry, rres, s, f0 + ft * 16 + kg * 4, m0 + pt * 16 + l16, M, sys_out, e,
+                                            t == ks);
             }
         __syncthreads();
     }
@@ -519,12 +546,18 @@ __device__ void run_op(const DevOp &op, float *lds, int rank, int nranks, const 
         case OP_FC:
             if ((op.conv.C & 7) != 0)
                 conv_direct_units<ST>(op.conv, rank, nranks);
-            else if (op.pt == 4)
-                conv_units<4, LD, ST, RES>(op, lds, rank, nranks, rv);
-            else if (op.pt == 2)
-                conv_units<2, LD, ST, RES>(op, lds, rank, nranks, rv);
+            else if (op.ft == 1 && op.pt == 4)
+                conv_units<1, 4, LD, ST, RES>(op, lds, rank, nranks, rv);
+            else if (op.ft == 1 && op.pt == 2)
+                conv_units<1, 2, LD, ST, RES>(op, lds, rank, nranks, rv);
+            else if (op.ft == 2 && op.pt == 2)
+                conv_units<2, 2, LD, ST, RES>(op, lds, rank, nranks, rv);
+            else if (op.ft == 2 && op.pt == 1)
+                conv_units<2, 1, LD, ST, RES>(op, lds, rank, nranks, rv);
+            else if (op.ft == 4 && op.pt == 1)
+                conv_units<4, 1, LD, ST, RES>(op, lds, rank, nranks, rv);
             else
-                conv_units<1, LD, ST, RES>(op, lds, rank, nranks, rv);
+                conv_units<1, 1, LD, ST, RES>(op, lds, rank, nranks, rv);
             break;
         case OP_DW:
             dwconv_units<LD, ST>(op.conv, rank, nranks);
@@ -545,7 +578,7 @@ __device__ void run_op(const DevOp &op, float *lds, int rank, int nranks, const 
 
 // ------------------------------------------------------------------ the kernel
 
-__global__ __launch_bounds__(STREAM_THREADS) void sushi_stream_kernel(StreamArgs sa) {
+__global__ __launch_bounds__(STREAM_THREADS, 3) void sushi_stream_kernel(StreamArgs sa) {
     __shared__ float lds[STREAM_WAVES * 4 * 256];  // conv partial sums; 64x8x9 floats for pooling fit too
     __shared__ int barrier_ok;
     __shared__ DevOp op;
@@ -645,7 +678,7 @@ __device__ void install_slabs(const ResTable *tab, int rank, char *store) {
     __syncthreads();
 }
 
-__global__ __launch_bounds__(STREAM_THREADS) void sushi_team_kernel(TeamArgs ta) {
+__global__ __launch_bounds__(STREAM_THREADS, 3) void sushi_team_kernel(TeamArgs ta) {
     extern __shared__ __align__(16) char dyn_lds[];  // [RED_BYTES partial sums][RES_STORE_BYTES resident slabs]
     float *lds = reinterpret_cast<float *>(dyn_lds);
     char *store = dyn_lds + RED_BYTES;
@@ -819,25 +852,42 @@ hipError_t launch_team_kernel(const TeamArgs &a, int nwg, hipStream_t s) {
 
 // ------------------------------------------------------------------ host side
 
+// Picks the unit shape (ft x pt tiles of 16 x 16) and the waves per unit (wk) of a dense conv / FC op
+// for nwg cooperating workgroups from a small cost model, in units of one load round trip: a
+// workgroup runs ceil(groups / nwg) unit groups one after the other; a group costs one round trip
+// per batch of U reduction steps, plus the LDS reduction when waves share a unit, plus the epilogue.
 void tile_dev_op(DevOp &op, int nwg, bool team) {
     const ConvArgs &a = op.conv;
     const long M = (long)a.B * a.P * a.Q;
     const long ptiles = (M + 15) / 16, ftiles = (a.K + 15) / 16;
     const int nsteps = a.R * a.R * ((a.C + 31) / 32);
-    int wk = 1;
-    while (wk < STREAM_WAVES && wk * 4 < nsteps) wk *= 2;  // about four reduction steps per wave
-    const int slots = STREAM_WAVES / wk;
-    // the widest pixel group that still gives every workgroup a unit group
-    int pt = 4;
-    while (pt > 1 && ftiles * ((ptiles + pt - 1) / pt) < (long)nwg * slots) pt /= 2;
-    if (ptiles <= 4 && ptiles > 2) pt = std::max(pt, 4);  // a handful of pixels: keep them in one unit
-    if (ptiles == 2) pt = std::max(pt, 2);
-    // team kernel: an op that is one pixel group may use resident slabs, which needs one unit per
-    // workgroup at a time (all eight waves on the same filter tile)
-    if (team && (ptiles + pt - 1) / pt == 1) wk = STREAM_WAVES;
-    op.pt = pt, op.wk = wk;
-    op.n_p = (int)((ptiles + pt - 1) / pt);
-    op.n_units = (int)(ftiles * op.n_p);
+    static const int shapes[6][2] = {{1, 4}, {2, 2}, {1, 2}, {4, 1}, {2, 1}, {1, 1}};
+    double best = 1e30;
+    int bft = 1, bpt = 1, bwk = 1;
+    for (const auto &sh : shapes) {
+        const int ft = sh[0], pt = sh[1];
+        const int U = (ft + pt) >= 4 ? 2 : ((ft + pt) == 3 ? 3 : 4);
+        const long units = ((ftiles + ft - 1) / ft) * ((ptiles + pt - 1) / pt);
+        for (int wk = 1; wk <= STREAM_WAVES; wk *= 2) {
+            const int slots = STREAM_WAVES / wk;
+            const long groups = (units + slots - 1) / slots;
+            const long iters = (groups + nwg - 1) / nwg;
+            const int per_wave = (nsteps + wk - 1) / wk;
+            const int batches = (per_wave + U - 1) / U;
+            // padding waste: tiles computed beyond the real extent cost MFMA and load issue time
+            const double waste = (double)(((ftiles + ft - 1) / ft) * ft * ((ptiles + pt - 1) / pt) * pt) /
+                                 (double)(ftiles * ptiles);
+            const double group_cost = batches * 1.0 + 0.05 * per_wave * ft * pt + (wk > 1 ? 0.6 : 0.0) + 0.8;
+            const double cost = iters * group_cost * (0.9 + 0.1 * waste);
+            if (cost < best - 1e-9) best = cost, bft = ft, bpt = pt, bwk = wk;
+        }
+    }
+    // team kernel: an op that is one pixel group of at most 64 pixels may use resident slabs, which
+    // needs single-tile-row units worked on by all eight waves
+    if (team && ptiles <= 4) bft = 1, bpt = ptiles > 2 ? 4 : (int)ptiles, bwk = STREAM_WAVES;
+    op.ft = bft, op.pt = bpt, op.wk = bwk;
+    op.n_p = (int)((ptiles + bpt - 1) / bpt);
+    op.n_units = (int)(((ftiles + bft - 1) / bft) * op.n_p);
 }
 
 hipError_t launch_stream_kernel(const StreamArgs &a, int nwg, hipStream_t s) {

@@ -500,7 +500,7 @@ int run_stream_kernel(sushi_ctx *c, CachedPlan &cp, const void *input_dev, void 
             op.kind = L.kind;
             op.conv = L.conv, op.pool = L.pool;
             op.in_patch = L.in_patch, op.out_patch = L.out_patch;
-            op.pt = op.wk = 1;
+            op.pt = op.wk = op.ft = 1;
             op.layer = -1;
             if (L.kind == OP_CONV || L.kind == OP_FC) tile_dev_op(op, c->stream_wgs, false);
             prog.push_back(op);
@@ -662,7 +662,7 @@ void refresh_lds_bytes(sushi_ctx *c, CachedPlan &cp) {
     cp.lds_bytes = 0;
     if (c->h_res_entries.empty()) return;
     for (const DevOp &op : cp.team_prog) {
-        if ((op.kind != OP_CONV && op.kind != OP_FC) || op.n_p != 1 || op.wk != STREAM_WAVES || op.layer < 0) continue;
+        if ((op.kind != OP_CONV && op.kind != OP_FC) || op.n_p != 1 || op.ft != 1 || op.wk != STREAM_WAVES || op.layer < 0) continue;
         if ((op.conv.C & 7) != 0) continue;
         const ResLayer &R = c->h_res_layers[op.layer];
         const int n_f = (op.conv.K + 15) / 16;
@@ -848,7 +848,7 @@ int post_team_query(sushi_ctx *c, CachedPlan &cp, const void *input_dev, void *l
             op.conv = L.conv, op.pool = L.pool;
             op.in_patch = L.in_patch, op.out_patch = L.out_patch;
             op.relative = 1;
-            op.pt = op.wk = 1;
+            op.pt = op.wk = op.ft = 1;
             auto rel = [&](int id, bool small) -> void * {
                 if (id < 0) return nullptr;
                 const long off = small ? N_BIG_BUFS * c->tbig_bytes + id * c->tsmall_bytes : id * c->tbig_bytes;
