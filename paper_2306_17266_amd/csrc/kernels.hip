@@ -130,77 +130,146 @@ __device__ __forceinline__ void store_tile(const ConvArgs &a, const f32x4_t acc,
     }
 }
 
-// Large problems (many pixels): workgroup = WF x WP waves, a wave owns FT x PT tiles of 16 x 16 and
-// walks the whole reduction (taps x 32-channel chunks).
-template <int FT, int PT, int WF, int WP>
-__global__ __launch_bounds__(64 * WF * WP) void conv_mfma_kernel(ConvArgs a) {
-    const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
-    const int wp = wave % WP, wf = wave / WP;
-    const int l16 = lane & 15, kg = lane >> 4;
+// Large problems (many pixels and filters; batch 16): the classic shared-memory tiling.  A workgroup
+// of four waves (2 x 2) computes BN filters x BM pixels with 32 x 32 x 16 MFMAs.  Per reduction step
+// (one tap, 32 channels) the BN x 32 weight tile and the BM x 32 activation tile are staged in LDS as
+// [8-channel group][row] 16-byte cells, so a wave's operand read is four contiguous 512-byte runs;
+// the next step's global loads are in flight (registers) while the current step is multiplied, and
+// the two LDS buffers alternate with one barrier per step.  Consecutive workgroup ids land on
+// different XCDs, so tile t is served by workgroup id (t % per_xcd) * 8 + t / per_xcd: tiles that
+// share a weight tile run on the same XCD and meet in its L2.
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+
+template <int BN, int BM>
+__global__ __launch_bounds__(256) void conv_mfma_kernel(ConvArgs a, int tiles_f, int tiles_m) {
+    constexpr int TF = BN / 64, TM = BM / 64;  // 32 x 32 tiles per wave along filters / pixels
+    constexpr int NA = BN / 64, NB = BM / 64;  // 16-byte cells each thread stages per step
+    constexpr int SA = BN + 4, SB = BM + 4;    // padded row counts of one channel-group plane
+    __shared__ uint4 sA[2][4 * SA];
+    __shared__ uint4 sB[2][4 * SB];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wf = wave >> 1, wm = wave & 1;
     const int M = a.B * a.P * a.Q;
-    const int n_ptiles = (M + 16 * PT * WP - 1) / (16 * PT * WP);
-    const int ptile = blockIdx.x % n_ptiles, ftile = blockIdx.x / n_ptiles;
-    const int f0 = (ftile * WF + wf) * FT * 16;
-    const int m0 = (ptile * WP + wp) * PT * 16;
+    const int ntiles = tiles_f * tiles_m;
+    const int per_xcd = (ntiles + 7) >> 3;
+    int tile = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
+    if ((int)gridDim.x != per_xcd * 8) tile = blockIdx.x;
+    if (tile >= ntiles) return;
+    const int tf = tile / tiles_m, tm = tile - tf * tiles_m;
+    const int f0 = tf * BN, m0 = tm * BM;
     const uint16_t *x = static_cast<const uint16_t *>(a.x);
     const uint16_t *w = static_cast<const uint16_t *>(a.w);
 
-    int pn[PT], ph[PT], pw[PT];
-    bool pv[PT];
+    // what this thread stages: weight cells (group akg, filter af[i]) and activation cells (group bkg, pixel i)
+    int a_off[NA], a_kg[NA], a_lds[NA];
 #pragma unroll
-    for (int pt = 0; pt < PT; ++pt) {
-        const int m = m0 + pt * 16 + l16;
-        pv[pt] = m < M;
-        const int mm = pv[pt] ? m : 0;
+    for (int i = 0; i < NA; ++i) {
+        const int c = tid + 256 * i;
+        a_kg[i] = c / BN;
+        const int f = c - a_kg[i] * BN;
+        a_off[i] = min(f0 + f, a.Kpad - 1) * 8;
+        a_lds[i] = a_kg[i] * SA + f;
+    }
+    int b_kg[NB], b_lds[NB], pn[NB], ph[NB], pw[NB];
+    bool pv[NB];
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+        const int c = tid + 256 * i;
+        b_kg[i] = c & 3;
+        const int pix = c >> 2;
+        b_lds[i] = b_kg[i] * SB + pix;
+        const int m = m0 + pix;
+        pv[i] = m < M;
+        const int mm = pv[i] ? m : 0;
         const int qq = mm % a.Q, pp = (mm / a.Q) % a.P;
-        pn[pt] = mm / (a.Q * a.P);
-        ph[pt] = pp * a.stride - a.pad;
-        pw[pt] = qq * a.stride - a.pad;
+        pn[i] = mm / (a.Q * a.P);
+        ph[i] = pp * a.stride - a.pad;
+        pw[i] = qq * a.stride - a.pad;
     }
-    f32x4_t acc[FT][PT];
-#pragma unroll
-    for (int ft = 0; ft < FT; ++ft)
-#pragma unroll
-        for (int pt = 0; pt < PT; ++pt) acc[ft][pt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-
     const int csteps = (a.C + 31) >> 5;
-    for (int tap = 0; tap < a.R * a.R; ++tap) {
+    const int nsteps = a.R * a.R * csteps;
+    // Register sets for the steps in flight: set j holds the cells of the steps congruent to j modulo PD.
+    constexpr int PD = 1;
+    uint4 ra[PD][NA], rb[PD][NB];
+    auto gload = [&](int step, uint4 *qa, uint4 *qb) {
+        const int tap = step / csteps;
+        const int c0 = (step - tap * csteps) * 32;
         const int dr = tap / a.R, ds = tap - dr * a.R;
-        const uint16_t *xp[PT];
-        bool ok[PT];
 #pragma unroll
-        for (int pt = 0; pt < PT; ++pt) {
-            const int h = ph[pt] + dr, v = pw[pt] + ds;
-            ok[pt] = pv[pt] && h >= 0 && h < a.H && v >= 0 && v < a.W;
-            xp[pt] = x + (((long)pn[pt] * a.H + (ok[pt] ? h : 0)) * a.W + (ok[pt] ? v : 0)) * a.C;
+        for (int i = 0; i < NA; ++i) {
+            const int cg = min((c0 >> 3) + a_kg[i], a.CG - 1);
+            qa[i] = *reinterpret_cast<const uint4 *>(w + ((long)tap * a.CG + cg) * a.Kpad * 8 + a_off[i]);
         }
-        for (int cs = 0; cs < csteps; ++cs) {
-            const int c0 = cs * 32 + kg * 8;
-            const bool cv = c0 < a.C;
-            const int cc = cv ? c0 : 0;
-            Frag fa[FT], fb[PT];
 #pragma unroll
-            for (int ft = 0; ft < FT; ++ft) {
-                const int f = min(f0 + ft * 16 + l16, a.Kpad - 1);
-                fa[ft].u = *reinterpret_cast<const uint4 *>(w + (((long)tap * a.CG + (cc >> 3)) * a.Kpad + f) * 8);
+        for (int i = 0; i < NB; ++i) {
+            const int h = ph[i] + dr, v = pw[i] + ds, c = c0 + b_kg[i] * 8;
+            const bool ok = pv[i] && c < a.C && h >= 0 && h < a.H && v >= 0 && v < a.W;
+            const long off = (((long)pn[i] * a.H + (ok ? h : 0)) * a.W + (ok ? v : 0)) * a.C + (ok ? c : 0);
+            qb[i] = *reinterpret_cast<const uint4 *>(x + off);
+            if (!ok) qb[i] = make_uint4(0, 0, 0, 0);
+        }
+    };
+    auto sstore = [&](int buf, const uint4 *qa, const uint4 *qb) {
+#pragma unroll
+        for (int i = 0; i < NA; ++i) sA[buf][a_lds[i]] = qa[i];
+#pragma unroll
+        for (int i = 0; i < NB; ++i) sB[buf][b_lds[i]] = qb[i];
+    };
+
+    f32x16_t acc[TF][TM];
+#pragma unroll
+    for (int i = 0; i < TF; ++i)
+#pragma unroll
+        for (int j = 0; j < TM; ++j)
+#pragma unroll
+            for (int k = 0; k < 16; ++k) acc[i][j][k] = 0.f;
+
+    const int l32 = lane & 31, kh = lane >> 5;
+    // prologue: step 0 into LDS, steps 1 .. PD-1 on their way
+    gload(0, ra[0], rb[0]);
+    sstore(0, ra[0], rb[0]);
+#pragma unroll
+    for (int j = 1; j < PD; ++j)
+        if (j < nsteps) gload(j, ra[j], rb[j]);
+    __syncthreads();
+    for (int s0 = 0; s0 < nsteps; s0 += PD) {
+#pragma unroll
+        for (int j = 0; j < PD; ++j) {
+            const int step = s0 + j;
+            if (step >= nsteps) break;
+            const int buf = step & 1;
+            // set j is free (its step is in LDS): start the loads of step + PD
+            if (step + PD < nsteps) gload(step + PD, ra[j], rb[j]);
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                Frag fa[TF], fb[TM];
+#pragma unroll
+                for (int i = 0; i < TF; ++i) fa[i].u = sA[buf][(2 * h + kh) * SA + wf * (BN / 2) + i * 32 + l32];
+#pragma unroll
+                for (int jm = 0; jm < TM; ++jm) fb[jm].u = sB[buf][(2 * h + kh) * SB + wm * (BM / 2) + jm * 32 + l32];
+#pragma unroll
+                for (int i = 0; i < TF; ++i)
+#pragma unroll
+                    for (int jm = 0; jm < TM; ++jm)
+                        acc[i][jm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i].v, fb[jm].v, acc[i][jm], 0, 0, 0);
             }
-#pragma unroll
-            for (int pt = 0; pt < PT; ++pt) {
-                fb[pt].u = *reinterpret_cast<const uint4 *>(xp[pt] + cc);
-                if (!(ok[pt] && cv)) fb[pt].u = make_uint4(0, 0, 0, 0);
-            }
-#pragma unroll
-            for (int ft = 0; ft < FT; ++ft)
-#pragma unroll
-                for (int pt = 0; pt < PT; ++pt)
-                    acc[ft][pt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[ft].v, fb[pt].v, acc[ft][pt], 0, 0, 0);
+            // the next step's cells were requested PD-1 steps ago
+            if (step + 1 < nsteps) sstore(buf ^ 1, ra[(j + 1) % PD], rb[(j + 1) % PD]);
+            __syncthreads();
         }
     }
+    // a 32 x 32 accumulator: lane holds pixel column l32 and, for jj = 0..3, filters 8*jj + 4*kh .. +3
 #pragma unroll
-    for (int ft = 0; ft < FT; ++ft)
+    for (int i = 0; i < TF; ++i)
 #pragma unroll
-        for (int pt = 0; pt < PT; ++pt) store_tile(a, acc[ft][pt], f0 + ft * 16 + kg * 4, m0 + pt * 16 + l16, M);
+        for (int j = 0; j < TM; ++j) {
+            const int m = m0 + wm * (BM / 2) + j * 32 + l32;
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) {
+                const f32x4_t v = {acc[i][j][4 * jj], acc[i][j][4 * jj + 1], acc[i][j][4 * jj + 2], acc[i][j][4 * jj + 3]};
+                store_tile(a, v, f0 + wf * (BN / 2) + i * 32 + 8 * jj + 4 * kh, m, M);
+            }
+        }
 }
 
 // Small problems (batch-1 layers, FC): latency decides, so the reduction is split over the WK waves
@@ -444,12 +513,12 @@ __global__ __launch_bounds__(256) void gate_kernel(PoolArgs a) {
 
 static inline unsigned blocks_for(long total) { return (unsigned)((total + 255) / 256); }
 
-template <int FT, int PT, int WF, int WP>
+template <int BN, int BM>
 static hipError_t launch_mfma(const ConvArgs &a, hipStream_t s) {
     const int M = a.B * a.P * a.Q;
-    const int n_ptiles = (M + 16 * PT * WP - 1) / (16 * PT * WP);
-    const int n_ftiles = (a.K + 16 * FT * WF - 1) / (16 * FT * WF);
-    hipLaunchKernelGGL((conv_mfma_kernel<FT, PT, WF, WP>), dim3(n_ptiles * n_ftiles), dim3(64 * WF * WP), 0, s, a);
+    const int tiles_m = (M + BM - 1) / BM, tiles_f = (a.K + BN - 1) / BN;
+    const int per_xcd = (tiles_m * tiles_f + 7) / 8;
+    hipLaunchKernelGGL((conv_mfma_kernel<BN, BM>), dim3(per_xcd * 8), dim3(256), 0, s, a, tiles_f, tiles_m);
     return hipGetLastError();
 }
 
@@ -486,10 +555,11 @@ hipError_t launch_conv(const ConvArgs &a, bool bf16, hipStream_t s, int *kc) {
     }
     const long ptiles = (M + 15) / 16, ftiles = (a.K + 15) / 16;
     const long tiles16 = ptiles * ftiles;
-    // Many tiles: whole-reduction waves with big workgroup tiles.
+    // Many tiles: LDS-tiled workgroups; the largest tile that still yields two workgroups per compute unit.
     *kc = KC_CONV_MFMA;
-    if (tiles16 >= 512L * 64) return launch_mfma<4, 4, 2, 2>(a, s);
-    if (tiles16 >= 512L * 16) return launch_mfma<2, 2, 2, 2>(a, s);
+    if (a.K > 64 && ((M + 127) / 128) * ((a.K + 127) / 128) >= 512) return launch_mfma<128, 128>(a, s);
+    if (((M + 127) / 128) * ((a.K + 63) / 64) >= 512) return launch_mfma<64, 128>(a, s);
+    if (((M + 63) / 64) * ((a.K + 63) / 64) >= 384) return launch_mfma<64, 64>(a, s);
     *kc = KC_CONV_SPLITK;
     // Few tiles: the widest pixel group that still leaves about one workgroup per compute unit, and
     // about four reduction steps per wave.
