@@ -10,6 +10,9 @@ namespace sushi {
 
 typedef __attribute__((ext_vector_type(4))) unsigned u32x4_t;
 typedef __attribute__((ext_vector_type(2))) unsigned u32x2_t;
+// Pointers read from a descriptor are generic to the compiler; weights are known to be in device memory.
+typedef __attribute__((address_space(1))) u32x4_t global_u32x4;
+typedef __attribute__((address_space(1))) uint16_t global_u16;
 
 // Cache policy bits of buffer accesses (gfx942/gfx950): sc0 = coherent within the XCD (skips the
 // compute unit's vector L1, served by the XCD's L2), sc1 = coherent across the device's XCDs
@@ -190,7 +193,7 @@ struct ResView {
 };
 
 template <int FT, int PT, int LD, int ST, bool RES>
-__device__ void conv_units(const DevOp &op, float *red, int rank, int nranks, const ResView rv) {
+__device__ __forceinline__ void conv_units(const DevOp &op, float *red, int rank, int nranks, const ResView rv) {
     constexpr int NT = FT * PT;                      // 16 x 16 tiles of one unit (at most 4)
     constexpr int U = (FT + PT) >= 4 ? 2 : ((FT + PT) == 3 ? 3 : 4);  // steps in flight (register budget)
     const ConvArgs &a = op.conv;
@@ -349,12 +352,135 @@ __device__ void conv_units(const DevOp &op, float *red, int rank, int nranks, co
     }
 }
 
+// ------------------------------------------------------------------ dense conv with many pixels: weight tile shared in LDS
+// A unit = AT 16-filter tiles x (8 * BT) 16-pixel tiles.  The eight waves split the pixels; every
+// wave multiplies its BT pixel tiles with all AT filter tiles, so an activation fragment (loaded
+// straight from memory into the lane layout of the MFMA operand) is used AT times and the weight
+// tile of a reduction step (one tap, 32 channels: AT KiB) is fetched once per workgroup, by waves
+// 0 .. AT-1, and handed to the others through a two-stage LDS buffer.  Loads run D steps ahead of
+// the MFMAs in register rings; one workgroup barrier per step orders the LDS stages.
+// Activation cells outside the image, beyond the active channels or beyond the last pixel are
+// requested at an offset past the end of the buffer, which a buffer load answers with zeros.
+constexpr int TILE_D = 4;
+
+template <int AT, int BT, int LD, int ST>
+__device__ __forceinline__ void conv_tile_units(const DevOp &op, u32x4_t *stage, int rank, int nranks) {
+    constexpr int D = TILE_D;
+    static_assert(D == 4, "the step loop is written out for four register sets");
+    constexpr int OOB = 0x7FFFFFF0;
+    const ConvArgs &a = op.conv;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l16 = lane & 15, kg = lane >> 4;
+    const int M = a.B * a.P * a.Q;
+    const global_u16 *wg = (const global_u16 *)a.w;
+    const __amdgpu_buffer_rsrc_t rx = make_rsrc(a.x, (long)a.B * a.H * a.W * a.C * 2);
+    const __amdgpu_buffer_rsrc_t ry = make_rsrc(a.y, (long)M * a.K * (a.out_f32 ? 4 : 2));
+    const __amdgpu_buffer_rsrc_t rres = make_rsrc(a.res ? a.res : a.y, (long)M * a.K * 2);
+    const int csteps = (a.C + 31) >> 5;
+    const int nsteps = a.R * a.R * csteps;
+    const bool sys_out = op.out_patch != 0;
+    const bool stager = wave < AT;
+
+    for (int unit = rank; unit < op.n_units; unit += nranks) {
+        const int fgroup = unit / op.n_p, pgroup = unit - fgroup * op.n_p;
+        const int f0 = fgroup * AT * 16, m0 = (pgroup * STREAM_WAVES + wave) * BT * 16;
+        int pbase[BT], ph[BT], pw[BT];
+        bool pv[BT];
+#pragma unroll
+        for (int j = 0; j < BT; ++j) {
+            const int m = m0 + j * 16 + l16;
+            pv[j] = m < M;
+            const int mm = pv[j] ? m : 0;
+            const int qq = mm % a.Q, pp = (mm / a.Q) % a.P;
+            pbase[j] = (mm / (a.Q * a.P)) * a.H;
+            ph[j] = pp * a.stride - a.pad;
+            pw[j] = qq * a.stride - a.pad;
+        }
+        // this lane's cell of the weight tile it stages: filter tile `wave`, lane layout of the operand
+        const long a_lane = (long)(min(f0 + wave * 16 + l16, a.Kpad - 1)) * 8;
+
+        u32x4_t ra0, ra1, ra2, ra3;  // weight cells of the steps in flight (stager waves)
+        u32x4_t rb0[BT], rb1[BT], rb2[BT], rb3[BT];
+        ra0 = ra1 = ra2 = ra3 = u32x4_t{0u, 0u, 0u, 0u};
+        int i_tap = 0, i_c = 0, i_dr = 0, i_ds = 0;  // reduction step the next issue() fetches
+        auto issue = [&](u32x4_t &qa, u32x4_t *qb) {
+            const int c0 = i_c * 32 + kg * 8;
+            if (stager) {
+                const int cg = min(c0 >> 3, a.CG - 1);
+                qa = *reinterpret_cast<const global_u32x4 *>(wg + ((long)i_tap * a.CG + cg) * a.Kpad * 8 + a_lane);
+            }
+#pragma unroll
+            for (int j = 0; j < BT; ++j) {
+                const int h = ph[j] + i_dr, v = pw[j] + i_ds;
+                const bool ok = pv[j] && c0 < a.C && h >= 0 && h < a.H && v >= 0 && v < a.W;
+                const int off = (((pbase[j] + h) * a.W + v) * a.C + c0) * 2;
+                qb[j] = __builtin_amdgcn_raw_buffer_load_b128(rx, ok ? off : OOB, 0, LD);
+            }
+            if (++i_c == csteps) {
+                i_c = 0, ++i_tap;
+                if (++i_ds == a.R) i_ds = 0, ++i_dr;
+            }
+        };
+
+        f32x4_t acc[AT][BT];
+#pragma unroll
+        for (int i = 0; i < AT; ++i)
+#pragma unroll
+            for (int j = 0; j < BT; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+        // One reduction step: multiply stage (step & 1) with the activations in `b`, pass the next
+        // step's weight cell (`a_next`, requested D-1 steps ago) to the other stage, and reuse the
+        // registers of this step (`a_free`, `b`) for the loads of step + D.
+        auto run_step = [&](int step, u32x4_t &a_free, const u32x4_t &a_next, u32x4_t *b) {
+            const u32x4_t *cur = stage + (step & 1) * (AT * 64);
+            u32x4_t fa[AT];
+#pragma unroll
+            for (int i = 0; i < AT; ++i) fa[i] = cur[i * 64 + lane];
+            if (stager && step + 1 < nsteps) stage[((step + 1) & 1) * (AT * 64) + tid] = a_next;
+#pragma unroll
+            for (int j = 0; j < BT; ++j) {
+                Frag fb;
+                fb.u = make_uint4(b[j].x, b[j].y, b[j].z, b[j].w);
+#pragma unroll
+                for (int i = 0; i < AT; ++i) {
+                    Frag f;
+                    f.u = make_uint4(fa[i].x, fa[i].y, fa[i].z, fa[i].w);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.v, fb.v, acc[i][j], 0, 0, 0);
+                }
+            }
+            if (step + D < nsteps) issue(a_free, b);
+            __syncthreads();
+        };
+
+        issue(ra0, rb0);
+        if (1 < nsteps) issue(ra1, rb1);
+        if (2 < nsteps) issue(ra2, rb2);
+        if (3 < nsteps) issue(ra3, rb3);
+        if (stager) stage[tid] = ra0;
+        __syncthreads();
+        for (int s0 = 0; s0 < nsteps; s0 += D) {
+            run_step(s0, ra0, ra1, rb0);
+            if (s0 + 1 < nsteps) run_step(s0 + 1, ra1, ra2, rb1);
+            if (s0 + 2 < nsteps) run_step(s0 + 2, ra2, ra3, rb2);
+            if (s0 + 3 < nsteps) run_step(s0 + 3, ra3, ra0, rb3);
+        }
+#pragma unroll
+        for (int i = 0; i < AT; ++i) {
+            const int fbase = f0 + i * 16 + kg * 4;
+            const Epilogue use = fetch_epilogue<LD>(a, rres, fbase, 0, 0, false);
+#pragma unroll
+            for (int j = 0; j < BT; ++j)
+                store_tile_coherent<LD, ST>(a, ry, rres, acc[i][j], fbase, m0 + j * 16 + l16, M, sys_out, use, false);
+        }
+    }
+}
+
 // ------------------------------------------------------------------ vector-ALU layers, grid-strided
 
 // Dense conv with a channel count that is not a multiple of 8 (the 3-channel stem): one thread per
 // output pixel x 4 filters.  The input is the caller's buffer (complete before the launch).
 template <int ST>
-__device__ void conv_direct_units(const ConvArgs &a, int rank, int nranks) {
+__device__ __forceinline__ void conv_direct_units(const ConvArgs &a, int rank, int nranks) {
     const int groups = (a.K + 3) >> 2;
     const long total = (long)a.B * a.P * a.Q * groups;
     const uint16_t *x = static_cast<const uint16_t *>(a.x);
@@ -409,7 +535,7 @@ __device__ void conv_direct_units(const ConvArgs &a, int rank, int nranks) {
 
 // Depthwise k x k: one thread per output pixel x 8 channels, taps in ring order.
 template <int LD, int ST>
-__device__ void dwconv_units(const ConvArgs &a, int rank, int nranks) {
+__device__ __forceinline__ void dwconv_units(const ConvArgs &a, int rank, int nranks) {
     const int cgs = a.K >> 3;
     const long total = (long)a.B * a.P * a.Q * cgs;
     const uint16_t *w = static_cast<const uint16_t *>(a.w);
@@ -443,7 +569,7 @@ __device__ void dwconv_units(const ConvArgs &a, int rank, int nranks) {
 }
 
 template <int LD, int ST>
-__device__ void maxpool_units(const PoolArgs &a, int rank, int nranks) {
+__device__ __forceinline__ void maxpool_units(const PoolArgs &a, int rank, int nranks) {
     const int cgs = a.C >> 3;
     const long total = (long)a.B * a.P * a.Q * cgs;
     const __amdgpu_buffer_rsrc_t rx = make_rsrc(a.x, (long)a.B * a.H * a.W * a.C * 2);
@@ -474,7 +600,7 @@ __device__ void maxpool_units(const PoolArgs &a, int rank, int nranks) {
 // Global average: a workgroup takes (image, block of 8 channel groups); 64 pixel lanes x 8 channel
 // groups accumulate and a fixed binary tree in LDS combines them.
 template <int LD, int ST>
-__device__ void gap_units(const PoolArgs &a, float *lds, int rank, int nranks) {
+__device__ __forceinline__ void gap_units(const PoolArgs &a, float *lds, int rank, int nranks) {
     float(*part)[8][9] = reinterpret_cast<float(*)[8][9]>(lds);  // [64][8][9]
     const int cgs = a.C >> 3;
     const int blocks_per_image = (cgs + 7) >> 3;
@@ -517,7 +643,7 @@ __device__ void gap_units(const PoolArgs &a, float *lds, int rank, int nranks) {
 }
 
 template <int LD, int ST>
-__device__ void gate_units(const PoolArgs &a, int rank, int nranks) {
+__device__ __forceinline__ void gate_units(const PoolArgs &a, int rank, int nranks) {
     const int cgs = a.C >> 3;
     const long total = (long)a.B * a.H * a.W * cgs;
     const long bytes = (long)a.B * a.H * a.W * a.C * 2;
@@ -538,14 +664,48 @@ __device__ void gate_units(const PoolArgs &a, int rank, int nranks) {
     }
 }
 
+// The descriptor of the running op is staged in LDS, and what a lane reads from LDS counts as
+// lane-varying for the compiler: buffer descriptors built from it would be resolved lane by lane.
+// This copy moves every word to a scalar register.
+__device__ __forceinline__ DevOp uniform_op(const DevOp &src) {
+    constexpr int WORDS = (int)(sizeof(DevOp) / sizeof(int));
+    union {
+        DevOp o;
+        int w[WORDS];
+    } u;
+    const int *p = reinterpret_cast<const int *>(&src);
+#pragma unroll
+    for (int k = 0; k < WORDS; ++k) u.w[k] = __builtin_amdgcn_readfirstlane(p[k]);
+    return u.o;
+}
+
+// Tiled dense conv (wk == 0): ft = filter tiles, pt = pixel tiles per wave of a unit.
+template <int LD, int ST>
+__device__ __forceinline__ void run_tiled(const DevOp &op, u32x4_t *stage, int rank, int nranks) {
+    const int key = op.ft * 4 + op.pt;
+    switch (key) {
+        case 2 * 4 + 1: conv_tile_units<2, 1, LD, ST>(op, stage, rank, nranks); break;
+        case 2 * 4 + 2: conv_tile_units<2, 2, LD, ST>(op, stage, rank, nranks); break;
+        case 3 * 4 + 1: conv_tile_units<3, 1, LD, ST>(op, stage, rank, nranks); break;
+        case 3 * 4 + 2: conv_tile_units<3, 2, LD, ST>(op, stage, rank, nranks); break;
+        case 4 * 4 + 1: conv_tile_units<4, 1, LD, ST>(op, stage, rank, nranks); break;
+        case 4 * 4 + 2: conv_tile_units<4, 2, LD, ST>(op, stage, rank, nranks); break;
+        case 6 * 4 + 1: conv_tile_units<6, 1, LD, ST>(op, stage, rank, nranks); break;
+        case 6 * 4 + 2: conv_tile_units<6, 2, LD, ST>(op, stage, rank, nranks); break;
+        default: break;
+    }
+}
+
 // Runs one op on the calling workgroup's share (rank of nranks).
 template <int LD, int ST, bool RES>
-__device__ void run_op(const DevOp &op, float *lds, int rank, int nranks, const ResView rv) {
+__device__ __forceinline__ void run_op(const DevOp &op, float *lds, int rank, int nranks, const ResView rv) {
     switch (op.kind) {
         case OP_CONV:
         case OP_FC:
             if ((op.conv.C & 7) != 0)
                 conv_direct_units<ST>(op.conv, rank, nranks);
+            else if (op.wk == 0)
+                run_tiled<LD, ST>(op, reinterpret_cast<u32x4_t *>(lds), rank, nranks);
             else if (op.ft == 1 && op.pt == 4)
                 conv_units<1, 4, LD, ST, RES>(op, lds, rank, nranks, rv);
             else if (op.ft == 1 && op.pt == 2)
@@ -596,7 +756,8 @@ __global__ __launch_bounds__(STREAM_THREADS, 3) void sushi_stream_kernel(StreamA
             if (op.out_patch) op.conv.y = sa.logits;
         }
         __syncthreads();
-        run_op<AUX_SC1, AUX_SC1, false>(op, lds, (int)blockIdx.x, (int)gridDim.x, ResView{nullptr, nullptr, nullptr, nullptr});
+        run_op<AUX_SC1, AUX_SC1, false>(uniform_op(op), lds, (int)blockIdx.x, (int)gridDim.x,
+                                        ResView{nullptr, nullptr, nullptr, nullptr});
         if (i + 1 < sa.n_ops) {
             epoch += 1;
             if (!grid_barrier(sa, epoch, &barrier_ok)) return;
@@ -822,7 +983,7 @@ __global__ __launch_bounds__(STREAM_THREADS, 3) void sushi_team_kernel(TeamArgs 
                 rv.layer = &table->layers[op.layer];
                 rv.entries = table->entries + rv.layer->first_entry;
             }
-            run_op<AUX_PLAIN, AUX_PLAIN, true>(op, lds, rank, tsize, rv);
+            run_op<AUX_PLAIN, AUX_PLAIN, true>(uniform_op(op), lds, rank, tsize, rv);
             epoch += 1;
             if (!team_barrier(ta, team, tsize, epoch, &flag)) return;
             if (ta.trace && rank == 0 && threadIdx.x == 0 && i + 1 < TRACE_SLOTS)
@@ -881,6 +1042,25 @@ void tile_dev_op(DevOp &op, int nwg, bool team) {
             const double cost = iters * group_cost * (0.9 + 0.1 * waste);
             if (cost < best - 1e-9) best = cost, bft = ft, bpt = pt, bwk = wk;
         }
+    }
+    // tiled units (wk = 0): at filter tiles x 8 waves x bt pixel tiles, the weight tile shared in LDS
+    bool tiled = false;
+    if ((a.C & 7) == 0 && ptiles >= STREAM_WAVES) {
+        static const int ats[4] = {2, 3, 4, 6};
+        for (const int at : ats)
+            for (int bt = 1; bt <= 2; ++bt) {
+                const long n_f = (ftiles + at - 1) / at, n_p = (ptiles + STREAM_WAVES * bt - 1) / (STREAM_WAVES * bt);
+                const long iters = (n_f * n_p + nwg - 1) / nwg;
+                const double unit_cost = 1.5 + nsteps * (0.019 * at * bt + 0.06) + 0.8 + 0.1 * at * bt;
+                const double cost = iters * unit_cost;
+                if (cost < best - 1e-9) best = cost, bft = at, bpt = bt, bwk = 0, tiled = true;
+            }
+    }
+    if (tiled) {
+        op.ft = bft, op.pt = bpt, op.wk = 0;
+        op.n_p = (int)((ptiles + STREAM_WAVES * bpt - 1) / (STREAM_WAVES * bpt));
+        op.n_units = (int)(((ftiles + bft - 1) / bft) * op.n_p);
+        return;
     }
     // team kernel: an op that is one pixel group of at most 64 pixels may use resident slabs, which
     // needs single-tile-row units worked on by all eight waves
