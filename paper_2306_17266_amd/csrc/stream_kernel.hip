@@ -2,6 +2,7 @@
 #include "stream_kernel.h"
 
 #include <algorithm>
+#include <type_traits>
 
 #include "device_common.h"
 #include "model.h"
@@ -13,6 +14,7 @@ typedef __attribute__((ext_vector_type(2))) unsigned u32x2_t;
 // Pointers read from a descriptor are generic to the compiler; weights are known to be in device memory.
 typedef __attribute__((address_space(1))) u32x4_t global_u32x4;
 typedef __attribute__((address_space(1))) uint16_t global_u16;
+typedef __attribute__((address_space(1))) float global_f32;
 
 // Cache policy bits of buffer accesses (gfx942/gfx950): sc0 = coherent within the XCD (skips the
 // compute unit's vector L1, served by the XCD's L2), sc1 = coherent across the device's XCDs
@@ -173,6 +175,56 @@ __device__ __forceinline__ void store_tile_coherent(const ConvArgs &a, __amdgpu_
                 __hip_atomic_store(yp + i, (uint16_t)f2bf(v[i]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
         }
     }
+}
+
+// Straight-line epilogue for the common case (filters a multiple of 4, the lane's four filters inside
+// K): ACT = 0 none, 1 ReLU, 2 h-swish, 3 h-sigmoid is a template parameter so that no per-element
+// branch is left.
+template <int ACT>
+__device__ __forceinline__ float act_fast(float v) {
+    if (ACT == 1) return fmaxf(v, 0.0f);
+    if (ACT == 2) return v * fminf(fmaxf(v + 3.0f, 0.0f), 6.0f) * (1.0f / 6.0f);
+    if (ACT == 3) return fminf(fmaxf(v + 3.0f, 0.0f), 6.0f) * (1.0f / 6.0f);
+    return v;
+}
+
+template <int ACT, int ST>
+__device__ __forceinline__ void store_tile_fast(const ConvArgs &a, __amdgpu_buffer_rsrc_t ry, const f32x4_t acc,
+                                                const float4 sc, const float4 sh, const u32x2_t res, bool has_res,
+                                                int fbase, int m, int M, bool sys_out) {
+    if (fbase + 4 > a.K || m >= M) return;
+    float v[4] = {acc[0] * sc.x + sh.x, acc[1] * sc.y + sh.y, acc[2] * sc.z + sh.z, acc[3] * sc.w + sh.w};
+    if (has_res) v[0] += bf2f(res.x & 0xFFFFu), v[1] += bf2f(res.x >> 16), v[2] += bf2f(res.y & 0xFFFFu), v[3] += bf2f(res.y >> 16);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v[i] = act_fast<ACT>(v[i]);
+    const int o = m * a.K + fbase;
+    if (a.out_f32) {
+        const uint4 pk = make_uint4(__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3]));
+        if (sys_out)
+            act_st16<AUX_SYS>(ry, o * 4, pk);
+        else
+            act_st16<ST>(ry, o * 4, pk);
+    } else {
+        const uint2 pk = make_uint2(f2bf(v[0]) | (f2bf(v[1]) << 16), f2bf(v[2]) | (f2bf(v[3]) << 16));
+        if (sys_out)
+            act_st8<AUX_SYS>(ry, o * 2, pk);
+        else
+            act_st8<ST>(ry, o * 2, pk);
+    }
+}
+
+// Calls f(std::integral_constant<int, ACT>) for the activation of the op.
+template <typename F>
+__device__ __forceinline__ void with_activation(const ConvArgs &a, F f) {
+    const int mode = a.hsigmoid ? 3 : a.act;
+    if (mode == 1)
+        f(std::integral_constant<int, 1>{});
+    else if (mode == 2)
+        f(std::integral_constant<int, 2>{});
+    else if (mode == 3)
+        f(std::integral_constant<int, 3>{});
+    else
+        f(std::integral_constant<int, 0>{});
 }
 
 // ------------------------------------------------------------------ dense conv / FC on the matrix cores
@@ -369,57 +421,88 @@ __device__ __forceinline__ void conv_tile_units(const DevOp &op, u32x4_t *stage,
     static_assert(D == 4, "the step loop is written out for four register sets");
     constexpr int OOB = 0x7FFFFFF0;
     const ConvArgs &a = op.conv;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l16 = lane & 15, kg = lane >> 4;
     const int M = a.B * a.P * a.Q;
-    const global_u16 *wg = (const global_u16 *)a.w;
+    const int taps = a.R * a.R;
     const __amdgpu_buffer_rsrc_t rx = make_rsrc(a.x, (long)a.B * a.H * a.W * a.C * 2);
+    const __amdgpu_buffer_rsrc_t rw = make_rsrc(a.w, (long)taps * a.CG * a.Kpad * 16);
     const __amdgpu_buffer_rsrc_t ry = make_rsrc(a.y, (long)M * a.K * (a.out_f32 ? 4 : 2));
     const __amdgpu_buffer_rsrc_t rres = make_rsrc(a.res ? a.res : a.y, (long)M * a.K * 2);
     const int csteps = (a.C + 31) >> 5;
-    const int nsteps = a.R * a.R * csteps;
+    const int nsteps = taps * csteps;
     const bool sys_out = op.out_patch != 0;
     const bool stager = wave < AT;
+    // channel groups of the last 32-channel step of a tap: active ones (activations) and stored ones (weights)
+    const int tail_active = ((a.C + 7) >> 3) - (csteps - 1) * 4;
+    const int tail_stored = min(4, a.CG - (csteps - 1) * 4);
+    // scale and shift of the unit's filters wait in LDS behind the two weight stages
+    float *epi_lds = reinterpret_cast<float *>(stage + 2 * AT * 64);
 
     for (int unit = rank; unit < op.n_units; unit += nranks) {
         const int fgroup = unit / op.n_p, pgroup = unit - fgroup * op.n_p;
         const int f0 = fgroup * AT * 16, m0 = (pgroup * STREAM_WAVES + wave) * BT * 16;
-        int pbase[BT], ph[BT], pw[BT];
-        bool pv[BT];
+        // epilogue constants of filter f0 + tid: requested now, parked in LDS after the reduction
+        float e_sc = 1.0f, e_sh = 0.0f;
+        if (tid < AT * 16 && f0 + tid < a.K) {
+            if (a.scale) e_sc = ((const global_f32 *)a.scale)[f0 + tid];
+            e_sh = ((const global_f32 *)a.shift)[f0 + tid];
+        }
+        // Activation cell of this lane: byte offset of (pixel, channel group kg) at tap (0, 0); bit t
+        // of the mask says whether tap t falls inside the image.  The mask of the last channel step
+        // also drops the channel groups beyond the active channels.
+        int b_lane[BT];
+        unsigned mask_full[BT], mask_tail[BT];
 #pragma unroll
         for (int j = 0; j < BT; ++j) {
             const int m = m0 + j * 16 + l16;
-            pv[j] = m < M;
-            const int mm = pv[j] ? m : 0;
-            const int qq = mm % a.Q, pp = (mm / a.Q) % a.P;
-            pbase[j] = (mm / (a.Q * a.P)) * a.H;
-            ph[j] = pp * a.stride - a.pad;
-            pw[j] = qq * a.stride - a.pad;
-        }
-        // this lane's cell of the weight tile it stages: filter tile `wave`, lane layout of the operand
-        const long a_lane = (long)(min(f0 + wave * 16 + l16, a.Kpad - 1)) * 8;
-
-        u32x4_t ra0, ra1, ra2, ra3;  // weight cells of the steps in flight (stager waves)
-        u32x4_t rb0[BT], rb1[BT], rb2[BT], rb3[BT];
-        ra0 = ra1 = ra2 = ra3 = u32x4_t{0u, 0u, 0u, 0u};
-        int i_tap = 0, i_c = 0, i_dr = 0, i_ds = 0;  // reduction step the next issue() fetches
-        auto issue = [&](u32x4_t &qa, u32x4_t *qb) {
-            const int c0 = i_c * 32 + kg * 8;
-            if (stager) {
-                const int cg = min(c0 >> 3, a.CG - 1);
-                qa = *reinterpret_cast<const global_u32x4 *>(wg + ((long)i_tap * a.CG + cg) * a.Kpad * 8 + a_lane);
+            const bool pv = m < M;
+            const int mm = pv ? m : 0;
+            const int qq = mm % a.Q, pp = (mm / a.Q) % a.P, nn = mm / (a.Q * a.P);
+            const int h0 = pp * a.stride - a.pad, w0 = qq * a.stride - a.pad;
+            b_lane[j] = (((nn * a.H + h0) * a.W + w0) * a.C + kg * 8) * 2;
+            unsigned mk = 0;
+            for (int t = 0, dr = 0, ds = 0; t < taps; ++t) {
+                const int h = h0 + dr, v = w0 + ds;
+                if (pv && h >= 0 && h < a.H && v >= 0 && v < a.W) mk |= 1u << t;
+                if (++ds == a.R) ds = 0, ++dr;
             }
+            mask_full[j] = mk;
+            mask_tail[j] = kg < tail_active ? mk : 0u;
+        }
+        // Weight cell of this lane in the lane layout of the operand.  Every wave issues the load
+        // (waves beyond AT repeat the last tile and drop the result): the load sequence is then the
+        // same on every path through the loop, which lets the compiler wait for exactly the load a
+        // step needs instead of for all of them.
+        const int a_row = min(f0 + min(wave, AT - 1) * 16 + l16, a.Kpad - 1) * 16;
+        const int a_full = kg * a.Kpad * 16 + a_row;
+        const int a_tail = min(kg, tail_stored - 1) * a.Kpad * 16 + a_row;
+
+        u32x4_t ra0, ra1, ra2, ra3;  // weight cells of the steps in flight
+        u32x4_t rb0[BT], rb1[BT], rb2[BT], rb3[BT];
+        // reduction step the next issue() fetches: tap, channel step, and the offsets they imply
+        int i_tap = 0, i_c = 0, i_ds = 0;
+        int i_tap_b = 0;  // activations: bytes from tap (0, 0) to the tap
+        int i_tap_a = 0;  // weights: bytes to the tap's first channel group
+        auto issue = [&](u32x4_t &qa, u32x4_t *qb) {
+            const bool live = i_tap < taps;  // steps past the end (the loop runs in rounds of D) add zeros
+            const bool tail = i_c == csteps - 1;
+            qa = __builtin_amdgcn_raw_buffer_load_b128(rw, tail ? a_tail : a_full, live ? i_tap_a + i_c * 4 * a.Kpad * 16 : 0, 0);
+            const int b_step = i_tap_b + i_c * 64;
 #pragma unroll
             for (int j = 0; j < BT; ++j) {
-                const int h = ph[j] + i_dr, v = pw[j] + i_ds;
-                const bool ok = pv[j] && c0 < a.C && h >= 0 && h < a.H && v >= 0 && v < a.W;
-                const int off = (((pbase[j] + h) * a.W + v) * a.C + c0) * 2;
-                qb[j] = __builtin_amdgcn_raw_buffer_load_b128(rx, ok ? off : OOB, 0, LD);
+                const unsigned mk = tail ? mask_tail[j] : mask_full[j];
+                const bool ok = live && ((mk >> i_tap) & 1u) != 0;
+                qb[j] = __builtin_amdgcn_raw_buffer_load_b128(rx, ok ? b_lane[j] + b_step : OOB, 0, LD);
             }
-            if (++i_c == csteps) {
-                i_c = 0, ++i_tap;
-                if (++i_ds == a.R) i_ds = 0, ++i_dr;
-            }
+            const bool wrap = tail;
+            i_c = wrap ? 0 : i_c + 1;
+            i_tap += wrap ? 1 : 0;
+            i_tap_a += wrap ? a.CG * a.Kpad * 16 : 0;
+            const bool wrap_s = wrap && i_ds + 1 == a.R;
+            i_ds = wrap ? (wrap_s ? 0 : i_ds + 1) : i_ds;
+            i_tap_b += wrap ? (wrap_s ? (a.W - a.R + 1) * a.C * 2 : a.C * 2) : 0;
         };
 
         f32x4_t acc[AT][BT];
@@ -436,7 +519,7 @@ __device__ __forceinline__ void conv_tile_units(const DevOp &op, u32x4_t *stage,
             u32x4_t fa[AT];
 #pragma unroll
             for (int i = 0; i < AT; ++i) fa[i] = cur[i * 64 + lane];
-            if (stager && step + 1 < nsteps) stage[((step + 1) & 1) * (AT * 64) + tid] = a_next;
+            if (stager) stage[((step + 1) & 1) * (AT * 64) + tid] = a_next;
 #pragma unroll
             for (int j = 0; j < BT; ++j) {
                 Frag fb;
@@ -448,30 +531,63 @@ __device__ __forceinline__ void conv_tile_units(const DevOp &op, u32x4_t *stage,
                     acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.v, fb.v, acc[i][j], 0, 0, 0);
                 }
             }
-            if (step + D < nsteps) issue(a_free, b);
+            issue(a_free, b);
             __syncthreads();
         };
 
         issue(ra0, rb0);
-        if (1 < nsteps) issue(ra1, rb1);
-        if (2 < nsteps) issue(ra2, rb2);
-        if (3 < nsteps) issue(ra3, rb3);
+        issue(ra1, rb1);
+        issue(ra2, rb2);
+        issue(ra3, rb3);
         if (stager) stage[tid] = ra0;
         __syncthreads();
         for (int s0 = 0; s0 < nsteps; s0 += D) {
             run_step(s0, ra0, ra1, rb0);
-            if (s0 + 1 < nsteps) run_step(s0 + 1, ra1, ra2, rb1);
-            if (s0 + 2 < nsteps) run_step(s0 + 2, ra2, ra3, rb2);
-            if (s0 + 3 < nsteps) run_step(s0 + 3, ra3, ra0, rb3);
+            run_step(s0 + 1, ra1, ra2, rb1);
+            run_step(s0 + 2, ra2, ra3, rb2);
+            run_step(s0 + 3, ra3, ra0, rb3);
         }
+        // residuals are requested before the first store, so that they overlap instead of queueing
+        // behind one another
+        u32x2_t resid[AT][BT];
+        const bool vec_k = (a.K & 3) == 0;
 #pragma unroll
         for (int i = 0; i < AT; ++i) {
             const int fbase = f0 + i * 16 + kg * 4;
-            const Epilogue use = fetch_epilogue<LD>(a, rres, fbase, 0, 0, false);
 #pragma unroll
-            for (int j = 0; j < BT; ++j)
-                store_tile_coherent<LD, ST>(a, ry, rres, acc[i][j], fbase, m0 + j * 16 + l16, M, sys_out, use, false);
+            for (int j = 0; j < BT; ++j) {
+                const int m = m0 + j * 16 + l16;
+                resid[i][j] = u32x2_t{0u, 0u};
+                if (a.res && vec_k && fbase + 4 <= a.K && m < M)
+                    resid[i][j] = __builtin_amdgcn_raw_buffer_load_b64(rres, (int)(((long)m * a.K + fbase) * 2), 0, LD);
+            }
         }
+        if (tid < AT * 16) epi_lds[tid] = e_sc, epi_lds[AT * 16 + tid] = e_sh;
+        __syncthreads();
+        if (vec_k) {
+            with_activation(a, [&](auto tag) {
+                constexpr int ACT = decltype(tag)::value;
+#pragma unroll
+                for (int i = 0; i < AT; ++i) {
+                    const int fbase = f0 + i * 16 + kg * 4;
+                    const float4 sc = *reinterpret_cast<const float4 *>(epi_lds + i * 16 + kg * 4);
+                    const float4 sh = *reinterpret_cast<const float4 *>(epi_lds + AT * 16 + i * 16 + kg * 4);
+#pragma unroll
+                    for (int j = 0; j < BT; ++j)
+                        store_tile_fast<ACT, ST>(a, ry, acc[i][j], sc, sh, resid[i][j], a.res != nullptr, fbase,
+                                                 m0 + j * 16 + l16, M, sys_out);
+                }
+            });
+        } else {
+            for (int i = 0; i < AT; ++i) {
+                const int fbase = f0 + i * 16 + kg * 4;
+                Epilogue e;
+                e.have = false, e.have_res = false, e.res = u32x2_t{0u, 0u};
+                for (int j = 0; j < BT; ++j)
+                    store_tile_coherent<LD, ST>(a, ry, rres, acc[i][j], fbase, m0 + j * 16 + l16, M, sys_out, e, false);
+            }
+        }
+        // (the next unit passes several barriers before it writes the constants in LDS again)
     }
 }
 
@@ -691,7 +807,6 @@ __device__ __forceinline__ void run_tiled(const DevOp &op, u32x4_t *stage, int r
         case 4 * 4 + 1: conv_tile_units<4, 1, LD, ST>(op, stage, rank, nranks); break;
         case 4 * 4 + 2: conv_tile_units<4, 2, LD, ST>(op, stage, rank, nranks); break;
         case 6 * 4 + 1: conv_tile_units<6, 1, LD, ST>(op, stage, rank, nranks); break;
-        case 6 * 4 + 2: conv_tile_units<6, 2, LD, ST>(op, stage, rank, nranks); break;
         default: break;
     }
 }
@@ -1048,7 +1163,7 @@ void tile_dev_op(DevOp &op, int nwg, bool team) {
     if ((a.C & 7) == 0 && ptiles >= STREAM_WAVES) {
         static const int ats[4] = {2, 3, 4, 6};
         for (const int at : ats)
-            for (int bt = 1; bt <= 2; ++bt) {
+            for (int bt = 1; bt <= (at == 6 ? 1 : 2); ++bt) {  // 6 x 2 tiles per wave do not fit the register budget
                 const long n_f = (ftiles + at - 1) / at, n_p = (ptiles + STREAM_WAVES * bt - 1) / (STREAM_WAVES * bt);
                 const long iters = (n_f * n_p + nwg - 1) / nwg;
                 const double unit_cost = 1.5 + nsteps * (0.019 * at * bt + 0.06) + 0.8 + 0.1 * at * bt;
