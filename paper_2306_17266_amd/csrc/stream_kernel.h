@@ -48,7 +48,7 @@ struct StreamArgs {
 // ---------------------------------------------------------------------------------------------
 // The team kernel: a persistent kernel in which the workgroups running on one XCD form a team.
 // A team serves one query at a time, entirely inside its XCD: activations go through that XCD's L2
-// (ordinary stores and loads, the vector L1 emptied at every barrier), layers are separated by a team barrier (32 arrivals instead of 256),
+// (ordinary stores; loads that skip the vector L1, which is emptied once per query), layers are separated by a team barrier (32 arrivals instead of 256),
 // and up to eight queries are in flight on the chip.  Queries arrive through per-team mailboxes in
 // pinned host memory; a team leader that finds no post for `idle_ticks` (or sees `stop`) makes its
 // team leave, so the kernel always ends by itself.

@@ -409,16 +409,18 @@ __device__ __forceinline__ void conv_units(const DevOp &op, float *red, int rank
 // wave multiplies its BT pixel tiles with all AT filter tiles, so an activation fragment (loaded
 // straight from memory into the lane layout of the MFMA operand) is used AT times and the weight
 // tile of a reduction step (one tap, 32 channels: AT KiB) is fetched once per workgroup, by waves
-// 0 .. AT-1, and handed to the others through a two-stage LDS buffer.  Loads run D steps ahead of
-// the MFMAs in register rings; one workgroup barrier per step orders the LDS stages.
+// 0 .. AT-1, and handed to the others through a two-stage LDS buffer.  The reduction advances in
+// intervals of TILE_KS steps with one workgroup barrier per interval; loads run TILE_SETS intervals
+// ahead of the MFMAs in register sets.
 // Activation cells outside the image, beyond the active channels or beyond the last pixel are
 // requested at an offset past the end of the buffer, which a buffer load answers with zeros.
-constexpr int TILE_D = 4;
+constexpr int TILE_KS = 2;    // reduction steps per interval
+constexpr int TILE_SETS = 3;  // register sets = intervals in flight
 
 template <int AT, int BT, int LD, int ST>
 __device__ __forceinline__ void conv_tile_units(const DevOp &op, u32x4_t *stage, int rank, int nranks) {
-    constexpr int D = TILE_D;
-    static_assert(D == 4, "the step loop is written out for four register sets");
+    constexpr int KS = TILE_KS;
+    static_assert(TILE_SETS == 3, "the interval loop is written out for three register sets");
     constexpr int OOB = 0x7FFFFFF0;
     const ConvArgs &a = op.conv;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -437,8 +439,35 @@ __device__ __forceinline__ void conv_tile_units(const DevOp &op, u32x4_t *stage,
     // channel groups of the last 32-channel step of a tap: active ones (activations) and stored ones (weights)
     const int tail_active = ((a.C + 7) >> 3) - (csteps - 1) * 4;
     const int tail_stored = min(4, a.CG - (csteps - 1) * 4);
-    // scale and shift of the unit's filters wait in LDS behind the two weight stages
-    float *epi_lds = reinterpret_cast<float *>(stage + 2 * AT * 64);
+    // LDS behind the two weight stages: scale and shift of the unit's filters, then one entry per
+    // reduction step {weight bytes to the step's first cell, activation bytes from tap (0, 0), tap bit
+    // for a full channel step, tap bit for the last channel step of a tap}; steps past the end (the
+    // loop runs whole rounds of intervals) have no tap bit and so multiply zeros
+    float *epi_lds = reinterpret_cast<float *>(stage + 2 * KS * AT * 64);
+    u32x4_t *table = stage + 2 * KS * AT * 64 + AT * 8;
+    const int nsteps_pad = (nsteps + 3 * KS - 1) / (3 * KS) * (3 * KS);
+    for (int st = tid; st < nsteps_pad; st += STREAM_THREADS) {
+        const int tap = st / csteps, c = st - tap * csteps;
+        const int dr = tap / a.R, ds = tap - dr * a.R;
+        u32x4_t e = {0u, 0u, 0u, 0u};
+        if (st < nsteps) {
+            e.x = (unsigned)((tap * a.CG + c * 4) * a.Kpad * 16);
+            e.y = (unsigned)((dr * a.W + ds) * a.C * 2 + c * 64);
+            e.z = c == csteps - 1 ? 0u : 1u << tap;
+            e.w = c == csteps - 1 ? 1u << tap : 0u;
+        }
+        table[st] = e;
+    }
+    __syncthreads();
+    const float rcp_q = 1.0f / (float)a.Q, rcp_pq = 1.0f / (float)(a.P * a.Q);
+    // x / d for 0 <= x < 2^22 from the reciprocal, corrected by one either way
+    auto div_small = [](int x, int d, float rcp) {
+        int q = (int)((float)x * rcp);
+        const int r = x - q * d;
+        q += r >= d ? 1 : 0;
+        q -= r < 0 ? 1 : 0;
+        return q;
+    };
 
     for (int unit = rank; unit < op.n_units; unit += nranks) {
         const int fgroup = unit / op.n_p, pgroup = unit - fgroup * op.n_p;
@@ -459,15 +488,17 @@ __device__ __forceinline__ void conv_tile_units(const DevOp &op, u32x4_t *stage,
             const int m = m0 + j * 16 + l16;
             const bool pv = m < M;
             const int mm = pv ? m : 0;
-            const int qq = mm % a.Q, pp = (mm / a.Q) % a.P, nn = mm / (a.Q * a.P);
+            const int nn = div_small(mm, a.P * a.Q, rcp_pq);
+            const int rem = mm - nn * a.P * a.Q;
+            const int pp = div_small(rem, a.Q, rcp_q), qq = rem - pp * a.Q;
             const int h0 = pp * a.stride - a.pad, w0 = qq * a.stride - a.pad;
             b_lane[j] = (((nn * a.H + h0) * a.W + w0) * a.C + kg * 8) * 2;
-            unsigned mk = 0;
-            for (int t = 0, dr = 0, ds = 0; t < taps; ++t) {
-                const int h = h0 + dr, v = w0 + ds;
-                if (pv && h >= 0 && h < a.H && v >= 0 && v < a.W) mk |= 1u << t;
-                if (++ds == a.R) ds = 0, ++dr;
-            }
+            unsigned cols = 0, mk = 0;
+            for (int ds = 0; ds < a.R; ++ds)
+                if (w0 + ds >= 0 && w0 + ds < a.W) cols |= 1u << ds;
+            for (int dr = 0; dr < a.R; ++dr)
+                if (h0 + dr >= 0 && h0 + dr < a.H) mk |= cols << (dr * a.R);
+            mk = pv ? mk : 0u;
             mask_full[j] = mk;
             mask_tail[j] = kg < tail_active ? mk : 0u;
         }
@@ -479,30 +510,18 @@ __device__ __forceinline__ void conv_tile_units(const DevOp &op, u32x4_t *stage,
         const int a_full = kg * a.Kpad * 16 + a_row;
         const int a_tail = min(kg, tail_stored - 1) * a.Kpad * 16 + a_row;
 
-        u32x4_t ra0, ra1, ra2, ra3;  // weight cells of the steps in flight
-        u32x4_t rb0[BT], rb1[BT], rb2[BT], rb3[BT];
-        // reduction step the next issue() fetches: tap, channel step, and the offsets they imply
-        int i_tap = 0, i_c = 0, i_ds = 0;
-        int i_tap_b = 0;  // activations: bytes from tap (0, 0) to the tap
-        int i_tap_a = 0;  // weights: bytes to the tap's first channel group
+        // register sets: weight cell and activation cells of the KS steps of an interval in flight
+        u32x4_t ra0[KS], ra1[KS], ra2[KS];
+        u32x4_t rb0[KS][BT], rb1[KS][BT], rb2[KS][BT];
+        int i_step = 0;  // reduction step the next issue() fetches
         auto issue = [&](u32x4_t &qa, u32x4_t *qb) {
-            const bool live = i_tap < taps;  // steps past the end (the loop runs in rounds of D) add zeros
-            const bool tail = i_c == csteps - 1;
-            qa = __builtin_amdgcn_raw_buffer_load_b128(rw, tail ? a_tail : a_full, live ? i_tap_a + i_c * 4 * a.Kpad * 16 : 0, 0);
-            const int b_step = i_tap_b + i_c * 64;
+            const u32x4_t e = table[i_step++];
+            qa = __builtin_amdgcn_raw_buffer_load_b128(rw, (e.w != 0u ? a_tail : a_full) + (int)e.x, 0, 0);
 #pragma unroll
             for (int j = 0; j < BT; ++j) {
-                const unsigned mk = tail ? mask_tail[j] : mask_full[j];
-                const bool ok = live && ((mk >> i_tap) & 1u) != 0;
-                qb[j] = __builtin_amdgcn_raw_buffer_load_b128(rx, ok ? b_lane[j] + b_step : OOB, 0, LD);
+                const bool ok = ((mask_full[j] & e.z) | (mask_tail[j] & e.w)) != 0u;
+                qb[j] = __builtin_amdgcn_raw_buffer_load_b128(rx, ok ? b_lane[j] + (int)e.y : OOB, 0, LD);
             }
-            const bool wrap = tail;
-            i_c = wrap ? 0 : i_c + 1;
-            i_tap += wrap ? 1 : 0;
-            i_tap_a += wrap ? a.CG * a.Kpad * 16 : 0;
-            const bool wrap_s = wrap && i_ds + 1 == a.R;
-            i_ds = wrap ? (wrap_s ? 0 : i_ds + 1) : i_ds;
-            i_tap_b += wrap ? (wrap_s ? (a.W - a.R + 1) * a.C * 2 : a.C * 2) : 0;
         };
 
         f32x4_t acc[AT][BT];
@@ -511,41 +530,56 @@ __device__ __forceinline__ void conv_tile_units(const DevOp &op, u32x4_t *stage,
 #pragma unroll
             for (int j = 0; j < BT; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-        // One reduction step: multiply stage (step & 1) with the activations in `b`, pass the next
-        // step's weight cell (`a_next`, requested D-1 steps ago) to the other stage, and reuse the
-        // registers of this step (`a_free`, `b`) for the loads of step + D.
-        auto run_step = [&](int step, u32x4_t &a_free, const u32x4_t &a_next, u32x4_t *b) {
-            const u32x4_t *cur = stage + (step & 1) * (AT * 64);
-            u32x4_t fa[AT];
+        // One interval: multiply the weight stage `par` with the activations of set `b`, pass the
+        // next interval's weight cells (`a_next`, requested two intervals ago) to the other stage,
+        // and reuse the registers of this interval (`a_free`, `b`) for the loads three intervals on.
+        auto run_interval = [&](int par, u32x4_t *a_free, const u32x4_t *a_next, u32x4_t (*b)[BT]) {
+            const u32x4_t *cur = stage + par * (KS * AT * 64);
+            u32x4_t *nxt = stage + (par ^ 1) * (KS * AT * 64);
+            if (stager) {
 #pragma unroll
-            for (int i = 0; i < AT; ++i) fa[i] = cur[i * 64 + lane];
-            if (stager) stage[((step + 1) & 1) * (AT * 64) + tid] = a_next;
+                for (int k = 0; k < KS; ++k) nxt[k * AT * 64 + tid] = a_next[k];
+            }
 #pragma unroll
-            for (int j = 0; j < BT; ++j) {
-                Frag fb;
-                fb.u = make_uint4(b[j].x, b[j].y, b[j].z, b[j].w);
+            for (int k = 0; k < KS; ++k) {
+                u32x4_t fa[AT];
 #pragma unroll
-                for (int i = 0; i < AT; ++i) {
-                    Frag f;
-                    f.u = make_uint4(fa[i].x, fa[i].y, fa[i].z, fa[i].w);
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.v, fb.v, acc[i][j], 0, 0, 0);
+                for (int i = 0; i < AT; ++i) fa[i] = cur[(k * AT + i) * 64 + lane];
+#pragma unroll
+                for (int j = 0; j < BT; ++j) {
+                    Frag fb;
+                    fb.u = make_uint4(b[k][j].x, b[k][j].y, b[k][j].z, b[k][j].w);
+#pragma unroll
+                    for (int i = 0; i < AT; ++i) {
+                        Frag f;
+                        f.u = make_uint4(fa[i].x, fa[i].y, fa[i].z, fa[i].w);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.v, fb.v, acc[i][j], 0, 0, 0);
+                    }
                 }
             }
-            issue(a_free, b);
+#pragma unroll
+            for (int k = 0; k < KS; ++k) issue(a_free[k], b[k]);
             __syncthreads();
         };
 
-        issue(ra0, rb0);
-        issue(ra1, rb1);
-        issue(ra2, rb2);
-        issue(ra3, rb3);
-        if (stager) stage[tid] = ra0;
+#pragma unroll
+        for (int k = 0; k < KS; ++k) issue(ra0[k], rb0[k]);
+#pragma unroll
+        for (int k = 0; k < KS; ++k) issue(ra1[k], rb1[k]);
+#pragma unroll
+        for (int k = 0; k < KS; ++k) issue(ra2[k], rb2[k]);
+        if (stager) {
+#pragma unroll
+            for (int k = 0; k < KS; ++k) stage[k * AT * 64 + tid] = ra0[k];
+        }
         __syncthreads();
-        for (int s0 = 0; s0 < nsteps; s0 += D) {
-            run_step(s0, ra0, ra1, rb0);
-            run_step(s0 + 1, ra1, ra2, rb1);
-            run_step(s0 + 2, ra2, ra3, rb2);
-            run_step(s0 + 3, ra3, ra0, rb3);
+        // three intervals per round: the stage parity of a round's first interval alternates
+        int par = 0;
+        for (int s0 = 0; s0 < nsteps; s0 += 3 * KS) {
+            run_interval(par, ra0, ra1, rb0);
+            run_interval(par ^ 1, ra1, ra2, rb1);
+            run_interval(par, ra2, ra0, rb2);
+            par ^= 1;
         }
         // residuals are requested before the first store, so that they overlap instead of queueing
         // behind one another
@@ -908,8 +942,11 @@ __device__ __forceinline__ void invalidate_vector_l1() {
     asm volatile("buffer_inv sc1\n\ts_waitcnt vmcnt(0)" ::: "memory");
 }
 
-// Barrier among the workgroups of one team (all on one XCD); on return the compute unit's vector L1
-// is empty, so the loads of the next layer come from the L2.  Returns false when the wait ran out.
+// Barrier among the workgroups of one team (all on one XCD).  With INV the compute unit's vector L1
+// is empty on return, so that ordinary loads see what the team wrote; between the ops of a query the
+// activations are instead loaded around the L1 (sc1), which costs less than emptying it.
+// Returns false when the wait ran out.
+template <bool INV = true>
 __device__ __forceinline__ bool team_barrier(const TeamArgs &ta, int team, unsigned tsize, unsigned long long e,
                                              int *lds_flag) {
     __syncthreads();
@@ -926,7 +963,7 @@ __device__ __forceinline__ bool team_barrier(const TeamArgs &ta, int team, unsig
             }
             __builtin_amdgcn_s_sleep(1);
         }
-        invalidate_vector_l1();
+        if (INV) invalidate_vector_l1();
         *lds_flag = good;
     }
     __syncthreads();
@@ -1098,9 +1135,9 @@ __global__ __launch_bounds__(STREAM_THREADS, 3) void sushi_team_kernel(TeamArgs 
                 rv.layer = &table->layers[op.layer];
                 rv.entries = table->entries + rv.layer->first_entry;
             }
-            run_op<AUX_PLAIN, AUX_PLAIN, true>(uniform_op(op), lds, rank, tsize, rv);
+            run_op<AUX_SC1, AUX_PLAIN, true>(uniform_op(op), lds, rank, tsize, rv);
             epoch += 1;
-            if (!team_barrier(ta, team, tsize, epoch, &flag)) return;
+            if (!team_barrier<false>(ta, team, tsize, epoch, &flag)) return;
             if (ta.trace && rank == 0 && threadIdx.x == 0 && i + 1 < TRACE_SLOTS)
                 ta.trace[team * TRACE_SLOTS + i + 1] = wall_clock64();
         }
@@ -1166,7 +1203,15 @@ void tile_dev_op(DevOp &op, int nwg, bool team) {
             for (int bt = 1; bt <= (at == 6 ? 1 : 2); ++bt) {  // 6 x 2 tiles per wave do not fit the register budget
                 const long n_f = (ftiles + at - 1) / at, n_p = (ptiles + STREAM_WAVES * bt - 1) / (STREAM_WAVES * bt);
                 const long iters = (n_f * n_p + nwg - 1) / nwg;
-                const double unit_cost = 1.5 + nsteps * (0.019 * at * bt + 0.06) + 0.8 + 0.1 * at * bt;
+                // per reduction step the slower of the matrix cores (2 waves per SIMD x 16 clocks per
+                // MFMA) and the LDS (8 waves x at KiB at 128 bytes per clock), in round trips of
+                // about 2300 clocks; plus set-up, first loads and epilogue
+                const int round = TILE_KS * TILE_SETS;
+                const int steps_pad = (nsteps + round - 1) / round * round;
+                // LDS: two weight stages, the epilogue constants, one 16-byte entry per step
+                if (2 * TILE_KS * at * 1024 + at * 128 + steps_pad * 16 > RED_BYTES) continue;
+                const double step_cost = (std::max(32.0 * at * bt, 64.0 * at) + 120.0) / 2300.0;
+                const double unit_cost = 1.4 + steps_pad * step_cost + 0.4 + 0.3 * at * bt;
                 const double cost = iters * unit_cost;
                 if (cost < best - 1e-9) best = cost, bft = at, bpt = bt, bwk = 0, tiled = true;
             }
