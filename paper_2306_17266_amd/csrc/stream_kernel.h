@@ -126,6 +126,13 @@ hipError_t prepare_team_kernel();
 // Workgroups of the team kernel that fit on one compute unit at the same time.
 hipError_t team_kernel_blocks_per_cu(int *n);
 
+// The matrix-core paths of both kernels keep one table entry per reduction step (tap x 32 channels)
+// of the running op in LDS and one bit per tap in a 32-bit mask.
+constexpr int STEP_TABLE_MAX = 256;
+inline bool dense_op_fits(const ConvArgs &a) {
+    return a.R * a.R <= 32 && a.R * a.R * ((a.C + 31) / 32) + 1 <= STEP_TABLE_MAX;
+}
+
 // Chooses pt / wk / unit counts of a dense conv or FC op for a grid of nwg workgroups.
 void tile_dev_op(DevOp &op, int nwg, bool team);
 

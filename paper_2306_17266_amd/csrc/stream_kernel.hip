@@ -213,6 +213,20 @@ __device__ __forceinline__ void store_tile_fast(const ConvArgs &a, __amdgpu_buff
     }
 }
 
+// The same for a bf16 output inside the team's arena, without a branch: `offset` is the byte offset
+// of the lane's four values or OOB_STORE, which the buffer store drops; `res` is zero when the op has
+// no residual.
+constexpr int OOB_STORE = 0x7FFFFFF0;
+template <int ACT, int ST>
+__device__ __forceinline__ void store_tile_bf16(__amdgpu_buffer_rsrc_t ry, const f32x4_t acc, const float4 sc,
+                                                const float4 sh, const u32x2_t res, int offset) {
+    float v[4] = {acc[0] * sc.x + sh.x, acc[1] * sc.y + sh.y, acc[2] * sc.z + sh.z, acc[3] * sc.w + sh.w};
+    v[0] += bf2f(res.x & 0xFFFFu), v[1] += bf2f(res.x >> 16), v[2] += bf2f(res.y & 0xFFFFu), v[3] += bf2f(res.y >> 16);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v[i] = act_fast<ACT>(v[i]);
+    act_st8<ST>(ry, offset, make_uint2(f2bf(v[0]) | (f2bf(v[1]) << 16), f2bf(v[2]) | (f2bf(v[3]) << 16)));
+}
+
 // Calls f(std::integral_constant<int, ACT>) for the activation of the op.
 template <typename F>
 __device__ __forceinline__ void with_activation(const ConvArgs &a, F f) {
@@ -228,9 +242,9 @@ __device__ __forceinline__ void with_activation(const ConvArgs &a, F f) {
 }
 
 // ------------------------------------------------------------------ dense conv / FC on the matrix cores
-// A unit = one 16-filter tile x PT 16-pixel tiles.  The workgroup's 8 waves form 8/wk slots of wk
-// waves; a slot computes one unit, its waves splitting the reduction steps (tap x 32 channels) and
-// each issuing the loads of U steps before the first MFMA.  Partial sums meet in LDS in a fixed order.
+// A unit = FT 16-filter tiles x PT 16-pixel tiles.  The workgroup's 8 waves form 8/wk slots of wk
+// waves; a slot computes one unit, its waves splitting the reduction steps (tap x 32 channels).
+// Partial sums meet in LDS in a fixed order.
 
 // Residency (RES, team kernel only): an op that runs as one pixel group takes its filter tiles from
 // a per-workgroup list instead: the tiles whose slab this workgroup holds in LDS, plus its share of
@@ -244,37 +258,111 @@ struct ResView {
     int *list;                // LDS scratch for the unit list (>= 130 ints)
 };
 
+// Per-op tables in LDS, one entry per reduction step (tap, 32 channels) plus a null entry at index
+// nsteps that every step past the end maps to:
+//   steps[s] = {weight bytes to the step's first cell, activation bytes from tap (0, 0),
+//               tap bit if the step is a full channel step, tap bit if it is the last of its tap}
+//   slabs[s] = {byte offset of the step's first cell in a resident slab, first channel group}
+struct StepTables {
+    u32x4_t *steps;
+    u32x2_t *slabs;
+};
+constexpr unsigned OOB_OFFSET = 0x7FFFFFF0u;  // past the end of any buffer: a buffer load there returns zeros
+
+__device__ __forceinline__ void build_step_tables(const ConvArgs &a, int cg_res, StepTables tb) {
+    const int csteps = (a.C + 31) >> 5;
+    const int nsteps = a.R * a.R * csteps;
+    for (int st = threadIdx.x; st <= nsteps; st += STREAM_THREADS) {
+        u32x4_t e = {OOB_OFFSET, 0u, 0u, 0u};
+        u32x2_t r = {0u, OOB_OFFSET};
+        if (st < nsteps) {
+            const int tap = st / csteps, c = st - tap * csteps;
+            const int dr = tap / a.R, ds = tap - dr * a.R;
+            e.x = (unsigned)((tap * a.CG + c * 4) * a.Kpad * 16);
+            e.y = (unsigned)((dr * a.W + ds) * a.C * 2 + c * 64);
+            e.z = c == csteps - 1 ? 0u : 1u << tap;
+            e.w = c == csteps - 1 ? 1u << tap : 0u;
+            r.x = (unsigned)((tap * cg_res + c * 4) * 256);
+            r.y = (unsigned)(c * 4);
+        }
+        tb.steps[st] = e;
+        tb.slabs[st] = r;
+    }
+    __syncthreads();
+}
+
+// x / d for 0 <= x < 2^22 from the reciprocal, corrected by one either way
+__device__ __forceinline__ int div_small(int x, int d, float rcp) {
+    int q = (int)((float)x * rcp);
+    const int r = x - q * d;
+    q += r >= d ? 1 : 0;
+    q -= r < 0 ? 1 : 0;
+    return q;
+}
+
+// The lane's activation cell of output pixel m: byte offset of (pixel, channel group kg) at tap (0, 0)
+// and the mask whose bit t says that tap t falls inside the image (0 for m outside the output).
+__device__ __forceinline__ void pixel_cell(const ConvArgs &a, int m, bool valid, int kg, float rcp_q, float rcp_pq,
+                                           int *offset, unsigned *mask) {
+    const int mm = valid ? m : 0;
+    const int nn = div_small(mm, a.P * a.Q, rcp_pq);
+    const int rem = mm - nn * a.P * a.Q;
+    const int pp = div_small(rem, a.Q, rcp_q), qq = rem - pp * a.Q;
+    const int h0 = pp * a.stride - a.pad, w0 = qq * a.stride - a.pad;
+    *offset = (((nn * a.H + h0) * a.W + w0) * a.C + kg * 8) * 2;
+    unsigned cols = 0, mk = 0;
+    for (int ds = 0; ds < a.R; ++ds)
+        if (w0 + ds >= 0 && w0 + ds < a.W) cols |= 1u << ds;
+    for (int dr = 0; dr < a.R; ++dr)
+        if (h0 + dr >= 0 && h0 + dr < a.H) mk |= cols << (dr * a.R);
+    *mask = valid ? mk : 0u;
+}
+
+// The waves of a slot take the reduction steps ks, ks + wk, ...  Weight cells are requested DA steps
+// ahead (they come from memory and take longest), activation cells DB steps ahead, both into
+// register rings; the loop body is the same on every path, so the waits are exact.
 template <int FT, int PT, int LD, int ST, bool RES>
-__device__ __forceinline__ void conv_units(const DevOp &op, float *red, int rank, int nranks, const ResView rv) {
-    constexpr int NT = FT * PT;                      // 16 x 16 tiles of one unit (at most 4)
-    constexpr int U = (FT + PT) >= 4 ? 2 : ((FT + PT) == 3 ? 3 : 4);  // steps in flight (register budget)
+__device__ __forceinline__ void conv_units(const DevOp &op, float *red, int rank, int nranks, const ResView rv,
+                                           const StepTables tb) {
+    constexpr int NT = FT * PT;   // 16 x 16 tiles of one unit (at most 4)
+    constexpr int DA = 8 / FT;    // weight steps in flight per wave
+    constexpr int DB = 2;         // activation steps in flight per wave
     const ConvArgs &a = op.conv;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int wk = op.wk, slots = STREAM_WAVES / wk;
     const int slot = wave / wk, ks = wave - slot * wk;
     const int l16 = lane & 15, kg = lane >> 4;
     const int M = a.B * a.P * a.Q;
-    const uint16_t *w = static_cast<const uint16_t *>(a.w);
+    const int taps = a.R * a.R;
     const __amdgpu_buffer_rsrc_t rx = make_rsrc(a.x, (long)a.B * a.H * a.W * a.C * 2);
+    const __amdgpu_buffer_rsrc_t rw = make_rsrc(a.w, (long)taps * a.CG * a.Kpad * 16);
     const long out_bytes = (long)M * a.K * (a.out_f32 ? 4 : 2);
     const __amdgpu_buffer_rsrc_t ry = make_rsrc(a.y, out_bytes);
     const __amdgpu_buffer_rsrc_t rres = make_rsrc(a.res ? a.res : a.y, (long)M * a.K * 2);
     const int csteps = (a.C + 31) >> 5;
-    const int nsteps = a.R * a.R * csteps;
+    const int nsteps = taps * csteps;
     const int n_groups = (op.n_units + slots - 1) / slots;
-
+    const int tail_active = ((a.C + 7) >> 3) - (csteps - 1) * 4;
+    const int tail_stored = min(4, a.CG - (csteps - 1) * 4);
+    const float rcp_q = 1.0f / (float)a.Q, rcp_pq = 1.0f / (float)(a.P * a.Q);
     const bool sys_out = op.out_patch != 0;
-    // unit list of a resident op (FT = 1): entries are (filter tile) | (resident ? 1 << 16 : 0)
-    const bool listed = RES && FT == 1 && rv.layer != nullptr && op.n_p == 1 && slots == 1;
+
+    // unit list of a resident op (FT <= 2): entries are (filter tile) | (resident ? 1 << 16 : 0); a
+    // unit takes FT consecutive entries, which need not be neighbouring tiles
+    constexpr bool CAN_LIST = RES && FT <= 2;
+    const int ftiles = (a.K + 15) >> 4;
+    const bool listed = CAN_LIST && rv.layer != nullptr && M <= 64;
+    const int cg_res_op = listed ? __builtin_amdgcn_readfirstlane(rv.layer->cg_res) : 0;
+    build_step_tables(a, cg_res_op, tb);
     int n_listed = 0;
     if (listed) {
-        const int n_f = op.n_units;
         if (wave == 0) {
             int count = 0;
-            for (int base = 0; base < n_f; base += 64) {
+            for (int base = 0; base < ftiles; base += 64) {
                 const int f = base + lane;
                 bool res = false, mine = false;
-                if (f < n_f) {
+                if (f < ftiles) {
                     res = f < rv.layer->n_res && rv.entries[f].owner >= 0;
                     mine = res ? rv.entries[f].owner == rank : (f % nranks) == rank;
                 }
@@ -288,37 +376,62 @@ __device__ __forceinline__ void conv_units(const DevOp &op, float *red, int rank
         __syncthreads();
         n_listed = rv.list[0];
     }
-    const int first = listed ? 0 : rank, limit = listed ? n_listed : n_groups, stride = listed ? 1 : nranks;
+    // a listed op: this workgroup's units are (FT entries of its list) x (pixel group)
+    const int listed_units = ((n_listed + FT - 1) / FT) * op.n_p;
+    const int first = listed ? 0 : rank, limit = listed ? (listed_units + slots - 1) / slots : n_groups,
+              stride = listed ? 1 : nranks;
     for (int g = first; g < limit; g += stride) {
-        const int unit = listed ? (rv.list[1 + g] & 0xFFFF) : g * slots + slot;
-        const bool active = unit < op.n_units;
-        const int fgroup = active ? unit / op.n_p : 0, pgroup = active ? unit - fgroup * op.n_p : 0;
-        const int f0 = fgroup * FT * 16, m0 = pgroup * PT * 16;
-        const bool resident = listed && (rv.list[1 + g] >> 16) != 0;
-        const int cg_res = resident ? rv.layer->cg_res : 0;
-        const char *slab = resident ? rv.store + rv.entries[fgroup].lds_off : nullptr;
-        int pn[PT], ph[PT], pw[PT];
-        bool pv[PT];
+        // the unit's filter tiles
+        int ftile[FT], cg_res[FT];
+        bool fok[FT];
+        const char *slab[FT];
+        int pgroup = 0;
+        if (listed) {
+            const int unit = g * slots + slot;
+            const int tgroup = unit / op.n_p;
+            pgroup = unit - tgroup * op.n_p;
+#pragma unroll
+            for (int ft = 0; ft < FT; ++ft) {
+                const int idx = tgroup * FT + ft;
+                fok[ft] = unit < listed_units && idx < n_listed;
+                const int entry = fok[ft] ? __builtin_amdgcn_readfirstlane(rv.list[1 + idx]) : 0;
+                ftile[ft] = entry & 0xFFFF;
+                const bool res = fok[ft] && (entry >> 16) != 0;
+                cg_res[ft] = res ? cg_res_op : 0;
+                slab[ft] = res ? rv.store + rv.entries[ftile[ft]].lds_off + (kg * 16 + l16) * 16 : nullptr;
+            }
+        } else {
+            const int unit = g * slots + slot;
+            const bool in_range = unit < op.n_units;
+            const int fgroup = in_range ? unit / op.n_p : 0;
+            pgroup = in_range ? unit - fgroup * op.n_p : 0;
+#pragma unroll
+            for (int ft = 0; ft < FT; ++ft) ftile[ft] = fgroup * FT + ft, fok[ft] = in_range, cg_res[ft] = 0, slab[ft] = nullptr;
+        }
+        const bool active = fok[0];
+        const int m0 = pgroup * PT * 16;
+        int b_lane[PT];
+        unsigned mask_full[PT], mask_tail[PT];
 #pragma unroll
         for (int pt = 0; pt < PT; ++pt) {
             const int m = m0 + pt * 16 + l16;
-            pv[pt] = active && m < M;
-            const int mm = pv[pt] ? m : 0;
-            const int qq = mm % a.Q, pp = (mm / a.Q) % a.P;
-            pn[pt] = mm / (a.Q * a.P);
-            ph[pt] = pp * a.stride - a.pad;
-            pw[pt] = qq * a.stride - a.pad;
+            pixel_cell(a, m, active && m < M, kg, rcp_q, rcp_pq, &b_lane[pt], &mask_full[pt]);
+            mask_tail[pt] = kg < tail_active ? mask_full[pt] : 0u;
         }
-        int fw[FT];
+        unsigned a_full[FT], a_tail[FT];
 #pragma unroll
-        for (int ft = 0; ft < FT; ++ft) fw[ft] = min(f0 + ft * 16 + l16, a.Kpad - 1) * 8;
+        for (int ft = 0; ft < FT; ++ft) {
+            const unsigned row = (unsigned)min(ftile[ft] * 16 + l16, a.Kpad - 1) * 16u;
+            a_full[ft] = (unsigned)(kg * a.Kpad * 16) + row;
+            a_tail[ft] = (unsigned)(min(kg, tail_stored - 1) * a.Kpad * 16) + row;
+        }
         // scale/shift of every filter tile now, and the residual of the tile this wave finishes first
         const int t0 = wk == 1 ? 0 : ks;
         Epilogue epi[FT];
 #pragma unroll
         for (int ft = 0; ft < FT; ++ft)
-            epi[ft] = fetch_epilogue<LD>(a, rres, f0 + ft * 16 + kg * 4, m0 + (t0 % PT) * 16 + l16, M,
-                                         active && t0 < NT && t0 / PT == ft);
+            epi[ft] = fetch_epilogue<LD>(a, rres, ftile[ft] * 16 + kg * 4, m0 + (t0 % PT) * 16 + l16, M,
+                                         fok[ft] && t0 < NT && t0 / PT == ft);
         f32x4_t acc[FT][PT];
 #pragma unroll
         for (int ft = 0; ft < FT; ++ft)
@@ -326,45 +439,62 @@ __device__ __forceinline__ void conv_units(const DevOp &op, float *red, int rank
             for (int pt = 0; pt < PT; ++pt) acc[ft][pt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
         if (active) {
-            for (int base = ks; base < nsteps; base += wk * U) {
-                Frag fa[U][FT], fb[U][PT];
-                bool ok[U][PT];
+            const int per_wave = (nsteps - ks + wk - 1) / wk;  // steps ks, ks + wk, ... below nsteps
+            u32x4_t ra[DA][FT], rb[DB][PT];
+            int ia = ks, ib = ks, ic = ks;  // step of the next weight request, activation request, product
+            auto issue_a = [&](u32x4_t *q) {
+                const int idx = min(ia, nsteps);
+                ia += wk;
+                const u32x4_t e = tb.steps[idx];
+                unsigned cg_first = 0;
+                if (CAN_LIST) cg_first = tb.slabs[idx].y;
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int step = base + u * wk;
-                    const bool live = step < nsteps;
-                    const int st = live ? step : 0;
-                    const int tap = st / csteps;
-                    const int c0 = (st - tap * csteps) * 32 + kg * 8;
-                    const int dr = tap / a.R, ds = tap - dr * a.R;
-                    const bool cv = live && c0 < a.C;
-                    const int cc = cv ? c0 : 0;
-                    if (RES && FT == 1 && (cc >> 3) < cg_res) {
-                        fa[u][0].u = *reinterpret_cast<const uint4 *>(slab + ((tap * cg_res + (cc >> 3)) * 16 + l16) * 16);
-                    } else {
-                        const uint16_t *wp = w + ((long)tap * a.CG + (cc >> 3)) * a.Kpad * 8;
+                for (int ft = 0; ft < FT; ++ft) {
+                    unsigned off = (e.w != 0u ? a_tail[ft] : a_full[ft]) + e.x;
+                    // cells the slab holds are not fetched
+                    if (CAN_LIST && cg_first + (unsigned)kg < (unsigned)cg_res[ft]) off = OOB_OFFSET;
+                    q[ft] = __builtin_amdgcn_raw_buffer_load_b128(rw, (int)off, 0, 0);
+                }
+            };
+            auto issue_b = [&](u32x4_t *q) {
+                const int idx = min(ib, nsteps);
+                ib += wk;
+                const u32x4_t e = tb.steps[idx];
 #pragma unroll
-                        for (int ft = 0; ft < FT; ++ft) fa[u][ft].u = *reinterpret_cast<const uint4 *>(wp + fw[ft]);
+                for (int pt = 0; pt < PT; ++pt) {
+                    const bool ok = ((mask_full[pt] & e.z) | (mask_tail[pt] & e.w)) != 0u;
+                    q[pt] = __builtin_amdgcn_raw_buffer_load_b128(rx, ok ? b_lane[pt] + (int)e.y : (int)OOB_OFFSET, 0, LD);
+                }
+            };
+#pragma unroll
+            for (int d = 0; d < DA; ++d) issue_a(ra[d]);
+#pragma unroll
+            for (int d = 0; d < DB; ++d) issue_b(rb[d]);
+            for (int i0 = 0; i0 < per_wave; i0 += DA) {
+#pragma unroll
+                for (int u = 0; u < DA; ++u) {
+                    Frag fa[FT];
+#pragma unroll
+                    for (int ft = 0; ft < FT; ++ft) fa[ft].u = make_uint4(ra[u][ft].x, ra[u][ft].y, ra[u][ft].z, ra[u][ft].w);
+                    if (CAN_LIST) {
+                        const u32x2_t sl = tb.slabs[min(ic, nsteps)];
+#pragma unroll
+                        for (int ft = 0; ft < FT; ++ft)
+                            if (sl.y + (unsigned)kg < (unsigned)cg_res[ft])
+                                fa[ft].u = *reinterpret_cast<const uint4 *>(slab[ft] + sl.x);
                     }
+                    ic += wk;
 #pragma unroll
                     for (int pt = 0; pt < PT; ++pt) {
-                        const int h = ph[pt] + dr, v = pw[pt] + ds;
-                        ok[u][pt] = cv && pv[pt] && h >= 0 && h < a.H && v >= 0 && v < a.W;
-                        const int hh = ok[u][pt] ? h : 0, vv = ok[u][pt] ? v : 0;
-                        fb[u][pt].u = act_ld16<LD>(rx, (((pn[pt] * a.H + hh) * a.W + vv) * a.C + cc) * 2);
+                        Frag fb;
+                        const u32x4_t b = rb[u % DB][pt];
+                        fb.u = make_uint4(b.x, b.y, b.z, b.w);
+#pragma unroll
+                        for (int ft = 0; ft < FT; ++ft)
+                            acc[ft][pt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[ft].v, fb.v, acc[ft][pt], 0, 0, 0);
                     }
-                }
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-#pragma unroll
-                    for (int pt = 0; pt < PT; ++pt)
-                        if (!ok[u][pt]) fb[u][pt].u = make_uint4(0, 0, 0, 0);
-#pragma unroll
-                    for (int ft = 0; ft < FT; ++ft)
-#pragma unroll
-                        for (int pt = 0; pt < PT; ++pt)
-                            acc[ft][pt] =
-                                __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[u][ft].v, fb[u][pt].v, acc[ft][pt], 0, 0, 0);
+                    issue_a(ra[u]);
+                    issue_b(rb[u % DB]);
                 }
             }
         }
@@ -374,33 +504,59 @@ __device__ __forceinline__ void conv_units(const DevOp &op, float *red, int rank
                 for (int ft = 0; ft < FT; ++ft)
 #pragma unroll
                     for (int pt = 0; pt < PT; ++pt)
-                        store_tile_coherent<LD, ST>(a, ry, rres, acc[ft][pt], f0 + ft * 16 + kg * 4, m0 + pt * 16 + l16, M,
-                                                    sys_out, epi[ft], ft == 0 && pt == 0);
+                        if (fok[ft])
+                            store_tile_coherent<LD, ST>(a, ry, rres, acc[ft][pt], ftile[ft] * 16 + kg * 4, m0 + pt * 16 + l16,
+                                                        M, sys_out, epi[ft], ft == 0 && pt == 0);
             continue;
         }
-        // red[wave][NT][4][64]
+        if constexpr (NT <= 4) {
+            // red[wave][NT][4][64]
 #pragma unroll
-        for (int ft = 0; ft < FT; ++ft)
+            for (int ft = 0; ft < FT; ++ft)
 #pragma unroll
-            for (int pt = 0; pt < PT; ++pt)
+                for (int pt = 0; pt < PT; ++pt)
 #pragma unroll
-                for (int i = 0; i < 4; ++i) red[((wave * NT + ft * PT + pt) * 4 + i) * 64 + lane] = acc[ft][pt][i];
-        __syncthreads();
-        if (active)
-            for (int t = ks; t < NT; t += wk) {
-                f32x4_t s = f32x4_t{0.f, 0.f, 0.f, 0.f};
-                for (int k = 0; k < wk; ++k)
+                    for (int i = 0; i < 4; ++i) red[((wave * NT + ft * PT + pt) * 4 + i) * 64 + lane] = acc[ft][pt][i];
+            __syncthreads();
+            if (active)
+                for (int t = ks; t < NT; t += wk) {
+                    f32x4_t s = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                    for (int k = 0; k < wk; ++k)
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) s[i] += red[(((slot * wk + k) * NT + t) * 4 + i) * 64 + lane];
-                const int ft = t / PT, pt = t - ft * PT;
-                Epilogue e = epi[0];
+                        for (int i = 0; i < 4; ++i) s[i] += red[(((slot * wk + k) * NT + t) * 4 + i) * 64 + lane];
+                    const int ft = t / PT, pt = t - ft * PT;
+                    Epilogue e = epi[0];
+                    int tile = ftile[0];
+                    bool ok = fok[0];
 #pragma unroll
-                for (int k = 1; k < FT; ++k)
-                    if (ft == k) e = epi[k];
-                store_tile_coherent<LD, ST>(a, ry, rres, s, f0 + ft * 16 + kg * 4, m0 + pt * 16 + l16, M, sys_out, e,
-                                            t == ks);
+                    for (int k = 1; k < FT; ++k)
+                        if (ft == k) e = epi[k], tile = ftile[k], ok = fok[k];
+                    if (ok)
+                        store_tile_coherent<LD, ST>(a, ry, rres, s, tile * 16 + kg * 4, m0 + pt * 16 + l16, M, sys_out, e,
+                                                    t == ks);
+                }
+            __syncthreads();
+        } else {
+            // the scratch holds one filter tile's partial sums at a time: red[wave][PT][4][64]
+#pragma unroll
+            for (int ft = 0; ft < FT; ++ft) {
+#pragma unroll
+                for (int pt = 0; pt < PT; ++pt)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) red[((wave * PT + pt) * 4 + i) * 64 + lane] = acc[ft][pt][i];
+                __syncthreads();
+                if (fok[ft])
+                    for (int pt = ks; pt < PT; pt += wk) {
+                        f32x4_t s = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                        for (int k = 0; k < wk; ++k)
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) s[i] += red[(((slot * wk + k) * PT + pt) * 4 + i) * 64 + lane];
+                        store_tile_coherent<LD, ST>(a, ry, rres, s, ftile[ft] * 16 + kg * 4, m0 + pt * 16 + l16, M, sys_out,
+                                                    epi[ft], false);
+                    }
+                __syncthreads();
             }
-        __syncthreads();
+        }
     }
 }
 
@@ -591,14 +747,29 @@ __device__ __forceinline__ void conv_tile_units(const DevOp &op, u32x4_t *stage,
 #pragma unroll
             for (int j = 0; j < BT; ++j) {
                 const int m = m0 + j * 16 + l16;
-                resid[i][j] = u32x2_t{0u, 0u};
-                if (a.res && vec_k && fbase + 4 <= a.K && m < M)
-                    resid[i][j] = __builtin_amdgcn_raw_buffer_load_b64(rres, (int)(((long)m * a.K + fbase) * 2), 0, LD);
+                const bool want = a.res && vec_k && fbase + 4 <= a.K && m < M;  // else: past the end, reads zeros
+                resid[i][j] = __builtin_amdgcn_raw_buffer_load_b64(rres, want ? (m * a.K + fbase) * 2 : OOB_STORE, 0, LD);
             }
         }
         if (tid < AT * 16) epi_lds[tid] = e_sc, epi_lds[AT * 16 + tid] = e_sh;
         __syncthreads();
-        if (vec_k) {
+        if (vec_k && !a.out_f32 && !sys_out) {
+            with_activation(a, [&](auto tag) {
+                constexpr int ACT = decltype(tag)::value;
+#pragma unroll
+                for (int i = 0; i < AT; ++i) {
+                    const int fbase = f0 + i * 16 + kg * 4;
+                    const float4 sc = *reinterpret_cast<const float4 *>(epi_lds + i * 16 + kg * 4);
+                    const float4 sh = *reinterpret_cast<const float4 *>(epi_lds + AT * 16 + i * 16 + kg * 4);
+#pragma unroll
+                    for (int j = 0; j < BT; ++j) {
+                        const int m = m0 + j * 16 + l16;
+                        const bool ok = fbase + 4 <= a.K && m < M;
+                        store_tile_bf16<ACT, ST>(ry, acc[i][j], sc, sh, resid[i][j], ok ? (m * a.K + fbase) * 2 : OOB_STORE);
+                    }
+                }
+            });
+        } else if (vec_k) {
             with_activation(a, [&](auto tag) {
                 constexpr int ACT = decltype(tag)::value;
 #pragma unroll
@@ -847,7 +1018,8 @@ __device__ __forceinline__ void run_tiled(const DevOp &op, u32x4_t *stage, int r
 
 // Runs one op on the calling workgroup's share (rank of nranks).
 template <int LD, int ST, bool RES>
-__device__ __forceinline__ void run_op(const DevOp &op, float *lds, int rank, int nranks, const ResView rv) {
+__device__ __forceinline__ void run_op(const DevOp &op, float *lds, int rank, int nranks, const ResView rv,
+                                       const StepTables tb) {
     switch (op.kind) {
         case OP_CONV:
         case OP_FC:
@@ -855,18 +1027,20 @@ __device__ __forceinline__ void run_op(const DevOp &op, float *lds, int rank, in
                 conv_direct_units<ST>(op.conv, rank, nranks);
             else if (op.wk == 0)
                 run_tiled<LD, ST>(op, reinterpret_cast<u32x4_t *>(lds), rank, nranks);
+            else if (op.ft == 2 && op.pt == 4)
+                conv_units<2, 4, LD, ST, RES>(op, lds, rank, nranks, rv, tb);
             else if (op.ft == 1 && op.pt == 4)
-                conv_units<1, 4, LD, ST, RES>(op, lds, rank, nranks, rv);
+                conv_units<1, 4, LD, ST, RES>(op, lds, rank, nranks, rv, tb);
             else if (op.ft == 1 && op.pt == 2)
-                conv_units<1, 2, LD, ST, RES>(op, lds, rank, nranks, rv);
+                conv_units<1, 2, LD, ST, RES>(op, lds, rank, nranks, rv, tb);
             else if (op.ft == 2 && op.pt == 2)
-                conv_units<2, 2, LD, ST, RES>(op, lds, rank, nranks, rv);
+                conv_units<2, 2, LD, ST, RES>(op, lds, rank, nranks, rv, tb);
             else if (op.ft == 2 && op.pt == 1)
-                conv_units<2, 1, LD, ST, RES>(op, lds, rank, nranks, rv);
+                conv_units<2, 1, LD, ST, RES>(op, lds, rank, nranks, rv, tb);
             else if (op.ft == 4 && op.pt == 1)
-                conv_units<4, 1, LD, ST, RES>(op, lds, rank, nranks, rv);
+                conv_units<4, 1, LD, ST, RES>(op, lds, rank, nranks, rv, tb);
             else
-                conv_units<1, 1, LD, ST, RES>(op, lds, rank, nranks, rv);
+                conv_units<1, 1, LD, ST, RES>(op, lds, rank, nranks, rv, tb);
             break;
         case OP_DW:
             dwconv_units<LD, ST>(op.conv, rank, nranks);
@@ -891,6 +1065,9 @@ __global__ __launch_bounds__(STREAM_THREADS, 3) void sushi_stream_kernel(StreamA
     __shared__ float lds[STREAM_WAVES * 4 * 256];  // conv partial sums; 64x8x9 floats for pooling fit too
     __shared__ int barrier_ok;
     __shared__ DevOp op;
+    __shared__ u32x4_t step_entries[STEP_TABLE_MAX];
+    __shared__ u32x2_t slab_entries[STEP_TABLE_MAX];
+    const StepTables tb{step_entries, slab_entries};
     unsigned long long epoch = sa.epoch_base;
     for (int i = 0; i < sa.n_ops; ++i) {
         // every thread needs the op's fields: stage the descriptor in LDS once per workgroup
@@ -906,7 +1083,7 @@ __global__ __launch_bounds__(STREAM_THREADS, 3) void sushi_stream_kernel(StreamA
         }
         __syncthreads();
         run_op<AUX_SC1, AUX_SC1, false>(uniform_op(op), lds, (int)blockIdx.x, (int)gridDim.x,
-                                        ResView{nullptr, nullptr, nullptr, nullptr});
+                                        ResView{nullptr, nullptr, nullptr, nullptr}, tb);
         if (i + 1 < sa.n_ops) {
             epoch += 1;
             if (!grid_barrier(sa, epoch, &barrier_ok)) return;
@@ -996,6 +1173,9 @@ __global__ __launch_bounds__(STREAM_THREADS, 3) void sushi_team_kernel(TeamArgs 
     float *lds = reinterpret_cast<float *>(dyn_lds);
     char *store = dyn_lds + RED_BYTES;
     __shared__ int unit_list[132];
+    __shared__ u32x4_t step_entries[STEP_TABLE_MAX];
+    __shared__ u32x2_t slab_entries[STEP_TABLE_MAX];
+    const StepTables tb{step_entries, slab_entries};
     __shared__ int flag;
     __shared__ DevOp op;
     __shared__ int s_team, s_rank, s_size;
@@ -1135,7 +1315,7 @@ __global__ __launch_bounds__(STREAM_THREADS, 3) void sushi_team_kernel(TeamArgs 
                 rv.layer = &table->layers[op.layer];
                 rv.entries = table->entries + rv.layer->first_entry;
             }
-            run_op<AUX_SC1, AUX_PLAIN, true>(uniform_op(op), lds, rank, tsize, rv);
+            run_op<AUX_SC1, AUX_PLAIN, true>(uniform_op(op), lds, rank, tsize, rv, tb);
             epoch += 1;
             if (!team_barrier<false>(ta, team, tsize, epoch, &flag)) return;
             if (ta.trace && rank == 0 && threadIdx.x == 0 && i + 1 < TRACE_SLOTS)
@@ -1174,27 +1354,34 @@ void tile_dev_op(DevOp &op, int nwg, bool team) {
     const long M = (long)a.B * a.P * a.Q;
     const long ptiles = (M + 15) / 16, ftiles = (a.K + 15) / 16;
     const int nsteps = a.R * a.R * ((a.C + 31) / 32);
-    static const int shapes[6][2] = {{1, 4}, {2, 2}, {1, 2}, {4, 1}, {2, 1}, {1, 1}};
+    // In round trips of about one microsecond, fitted to timings of the layer shapes of a
+    // ResNet50-like SuperNet on one XCD: a group of units (one per slot) has a fixed cost (first loads,
+    // reduction across waves, epilogue) and a cost per reduction step of a wave that grows mostly with
+    // the activation tiles it loads.
+    static const int shapes[7][2] = {{2, 4}, {1, 4}, {2, 2}, {1, 2}, {4, 1}, {2, 1}, {1, 1}};
+    auto shape_cost = [&](int ft, int pt, int wk) {
+        const long n_f = (ftiles + ft - 1) / ft, n_p = (ptiles + pt - 1) / pt;
+        const long units = n_f * n_p;
+        const int slots = STREAM_WAVES / wk;
+        const long iters = ((units + slots - 1) / slots + nwg - 1) / nwg;
+        const int per_wave = (nsteps + wk - 1) / wk;
+        const double step = 0.08 + 0.16 * pt + 0.04 * ft;
+        const double fixed = 4.5 + (wk > 1 ? 0.5 : 0.0) + (ft * pt > 4 ? 1.0 : 0.0);
+        return iters * (fixed + per_wave * step);
+    };
+    // team kernel, at most 64 output pixels: units of at most two filter tiles can take their weights
+    // from resident slabs
+    const bool slab_shapes_only = team && ptiles <= 4;
     double best = 1e30;
     int bft = 1, bpt = 1, bwk = 1;
-    for (const auto &sh : shapes) {
-        const int ft = sh[0], pt = sh[1];
-        const int U = (ft + pt) >= 4 ? 2 : ((ft + pt) == 3 ? 3 : 4);
-        const long units = ((ftiles + ft - 1) / ft) * ((ptiles + pt - 1) / pt);
+    for (const auto &sh : shapes)
         for (int wk = 1; wk <= STREAM_WAVES; wk *= 2) {
-            const int slots = STREAM_WAVES / wk;
-            const long groups = (units + slots - 1) / slots;
-            const long iters = (groups + nwg - 1) / nwg;
-            const int per_wave = (nsteps + wk - 1) / wk;
-            const int batches = (per_wave + U - 1) / U;
-            // padding waste: tiles computed beyond the real extent cost MFMA and load issue time
-            const double waste = (double)(((ftiles + ft - 1) / ft) * ft * ((ptiles + pt - 1) / pt) * pt) /
-                                 (double)(ftiles * ptiles);
-            const double group_cost = batches * 1.0 + 0.05 * per_wave * ft * pt + (wk > 1 ? 0.6 : 0.0) + 0.8;
-            const double cost = iters * group_cost * (0.9 + 0.1 * waste);
-            if (cost < best - 1e-9) best = cost, bft = ft, bpt = pt, bwk = wk;
+            if (sh[0] * sh[1] > 4 && wk != STREAM_WAVES) continue;  // eight tiles only with all waves on one unit
+            if (slab_shapes_only && sh[0] > 2) continue;
+            if (sh[1] > ptiles && !(sh[1] == 4 && ptiles == 3)) continue;
+            const double cost = shape_cost(sh[0], sh[1], wk);
+            if (cost < best - 1e-9) best = cost, bft = sh[0], bpt = sh[1], bwk = wk;
         }
-    }
     // tiled units (wk = 0): at filter tiles x 8 waves x bt pixel tiles, the weight tile shared in LDS
     bool tiled = false;
     if ((a.C & 7) == 0 && ptiles >= STREAM_WAVES) {
@@ -1203,15 +1390,16 @@ void tile_dev_op(DevOp &op, int nwg, bool team) {
             for (int bt = 1; bt <= (at == 6 ? 1 : 2); ++bt) {  // 6 x 2 tiles per wave do not fit the register budget
                 const long n_f = (ftiles + at - 1) / at, n_p = (ptiles + STREAM_WAVES * bt - 1) / (STREAM_WAVES * bt);
                 const long iters = (n_f * n_p + nwg - 1) / nwg;
-                // per reduction step the slower of the matrix cores (2 waves per SIMD x 16 clocks per
-                // MFMA) and the LDS (8 waves x at KiB at 128 bytes per clock), in round trips of
-                // about 2300 clocks; plus set-up, first loads and epilogue
+                // fitted to timings of the layer shapes of a ResNet50-like SuperNet on one XCD: a step
+                // costs what its activation loads cost (the waves do not share those) plus a little per
+                // weight tile; a unit has a fixed cost for set-up, first loads and the epilogue of its
+                // at x bt tiles per wave.  In round trips of about 2300 clocks.
                 const int round = TILE_KS * TILE_SETS;
                 const int steps_pad = (nsteps + round - 1) / round * round;
                 // LDS: two weight stages, the epilogue constants, one 16-byte entry per step
                 if (2 * TILE_KS * at * 1024 + at * 128 + steps_pad * 16 > RED_BYTES) continue;
-                const double step_cost = (std::max(32.0 * at * bt, 64.0 * at) + 120.0) / 2300.0;
-                const double unit_cost = 1.4 + steps_pad * step_cost + 0.4 + 0.3 * at * bt;
+                const double step_cost = (60.0 + 300.0 * bt + 45.0 * at * (bt == 2 ? 1.3 : 1.0)) / 2300.0;
+                const double unit_cost = 2.5 + 0.5 * at * bt + steps_pad * step_cost;
                 const double cost = iters * unit_cost;
                 if (cost < best - 1e-9) best = cost, bft = at, bpt = bt, bwk = 0, tiled = true;
             }
@@ -1222,9 +1410,6 @@ void tile_dev_op(DevOp &op, int nwg, bool team) {
         op.n_units = (int)(((ftiles + bft - 1) / bft) * op.n_p);
         return;
     }
-    // team kernel: an op that is one pixel group of at most 64 pixels may use resident slabs, which
-    // needs single-tile-row units worked on by all eight waves
-    if (team && ptiles <= 4) bft = 1, bpt = ptiles > 2 ? 4 : (int)ptiles, bwk = STREAM_WAVES;
     op.ft = bft, op.pt = bpt, op.wk = bwk;
     op.n_p = (int)((ptiles + bpt - 1) / bpt);
     op.n_units = (int)(((ftiles + bft - 1) / bft) * op.n_p);

@@ -502,7 +502,11 @@ int run_stream_kernel(sushi_ctx *c, CachedPlan &cp, const void *input_dev, void 
             op.in_patch = L.in_patch, op.out_patch = L.out_patch;
             op.pt = op.wk = op.ft = 1;
             op.layer = -1;
-            if (L.kind == OP_CONV || L.kind == OP_FC) tile_dev_op(op, c->stream_wgs, false);
+            if (L.kind == OP_CONV || L.kind == OP_FC) {
+                if ((L.conv.C & 7) == 0 && !dense_op_fits(L.conv))
+                    return fail(c, SUSHI_ESTATE, "a dense layer has too many reduction steps or taps for the stream kernel");
+                tile_dev_op(op, c->stream_wgs, false);
+            }
             prog.push_back(op);
         }
         if ((e = hipMalloc(reinterpret_cast<void **>(&cp.d_prog), prog.size() * sizeof(DevOp))) != hipSuccess)
@@ -662,7 +666,7 @@ void refresh_lds_bytes(sushi_ctx *c, CachedPlan &cp) {
     cp.lds_bytes = 0;
     if (c->h_res_entries.empty()) return;
     for (const DevOp &op : cp.team_prog) {
-        if ((op.kind != OP_CONV && op.kind != OP_FC) || op.n_p != 1 || op.ft != 1 || op.wk != STREAM_WAVES || op.layer < 0) continue;
+        if ((op.kind != OP_CONV && op.kind != OP_FC) || op.wk == 0 || op.ft > 2 || (long)op.conv.B * op.conv.P * op.conv.Q > 64 || op.layer < 0) continue;
         if ((op.conv.C & 7) != 0) continue;
         const ResLayer &R = c->h_res_layers[op.layer];
         const int n_f = (op.conv.K + 15) / 16;
@@ -859,7 +863,11 @@ int post_team_query(sushi_ctx *c, CachedPlan &cp, const void *input_dev, void *l
             op.pool.x = op.conv.x, op.pool.y = op.conv.y;
             op.pool.gate = static_cast<const float *>(rel(o.gate_buf, true));
             op.layer = (L.kind == OP_CONV || L.kind == OP_FC) ? o.layer : -1;
-            if (L.kind == OP_CONV || L.kind == OP_FC) tile_dev_op(op, c->team_wgs / MAX_TEAMS, true);
+            if (L.kind == OP_CONV || L.kind == OP_FC) {
+                if ((L.conv.C & 7) == 0 && !dense_op_fits(L.conv))
+                    return fail(c, SUSHI_ESTATE, "a dense layer has too many reduction steps or taps for the team kernel");
+                tile_dev_op(op, c->team_wgs / MAX_TEAMS, true);
+            }
             prog.push_back(op);
         }
         cp.team_prog = prog;
