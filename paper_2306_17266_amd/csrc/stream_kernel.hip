@@ -854,6 +854,152 @@ __device__ __forceinline__ void conv_direct_units(const ConvArgs &a, int rank, i
     }
 }
 
+// The stem on the matrix cores (wk == -1): a dense conv whose few input channels make the whole
+// patch (taps x channels, at most 64 values) one or two reduction steps.  A unit is a band of
+// op.pt output rows of one image: the workgroup copies the input rows the band needs into LDS with
+// wide loads, then every wave gathers the patches of its 16-pixel tiles from LDS element by element
+// (lane = pixel x 8 consecutive patch values) and multiplies them with weight fragments it gathered
+// once.  SYS: the input is the caller's buffer and is read at system scope.
+constexpr int STEM_MAX_FT = 4, STEM_MAX_KS = 2;
+template <int LD, int ST, bool SYS>
+__device__ __forceinline__ void stem_units(const DevOp &op, float *lds, int rank, int nranks) {
+    constexpr int XLD = SYS ? AUX_SYS : LD;
+    const ConvArgs &a = op.conv;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l16 = lane & 15, kg = lane >> 4;
+    const int KK = a.R * a.R * a.C;      // patch length
+    const int ksteps = (KK + 31) >> 5;   // <= STEM_MAX_KS
+    const int ftiles = (a.K + 15) >> 4;  // <= STEM_MAX_FT
+    const int M = a.B * a.P * a.Q;
+    const int row_elems = a.W * a.C;     // even: rows are copied as 32-bit words
+    const __amdgpu_buffer_rsrc_t rx = make_rsrc(a.x, (long)a.B * a.H * a.W * a.C * 2);
+    const __amdgpu_buffer_rsrc_t ry = make_rsrc(a.y, (long)M * a.K * 2);
+    const global_u16 *wg = (const global_u16 *)a.w;
+    uint16_t *rows = reinterpret_cast<uint16_t *>(lds);
+
+    // patch value k = 32 * ks + 8 * kg + e of this lane: LDS element offset from the patch corner,
+    // column offset (for the image border), or -1 beyond the patch
+    int k_off[STEM_MAX_KS][8], k_ds[STEM_MAX_KS][8];
+    Frag fa[STEM_MAX_FT][STEM_MAX_KS];
+#pragma unroll
+    for (int ks = 0; ks < STEM_MAX_KS; ++ks)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int k = ks * 32 + kg * 8 + e;
+            const int tap = k / a.C, c = k - tap * a.C;
+            const int dr = tap / a.R, ds = tap - dr * a.R;
+            const bool in = k < KK;
+            k_off[ks][e] = in ? (dr * a.W + ds) * a.C + c : 0;
+            k_ds[ks][e] = in ? ds : -0x10000;
+        }
+    // weight fragments: filter 16 * ft + l16, the same patch values (stored as [tap][filter][8 channels])
+#pragma unroll
+    for (int ft = 0; ft < STEM_MAX_FT; ++ft)
+#pragma unroll
+        for (int ks = 0; ks < STEM_MAX_KS; ++ks) {
+            unsigned v[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int k = ks * 32 + kg * 8 + e;
+                const int tap = k / a.C, c = k - tap * a.C;
+                const int f = min(ft * 16 + l16, a.Kpad - 1);
+                v[e] = (ft < ftiles && ks < ksteps && k < KK) ? (unsigned)wg[((long)tap * a.CG * a.Kpad + f) * 8 + c] : 0u;
+            }
+            fa[ft][ks].u = make_uint4(v[0] | (v[1] << 16), v[2] | (v[3] << 16), v[4] | (v[5] << 16), v[6] | (v[7] << 16));
+        }
+
+    const int bands = (a.P + op.pt - 1) / op.pt;
+    for (int unit = rank; unit < op.n_units; unit += nranks) {
+        const int n = unit / bands, band = unit - n * bands;
+        const int p0 = band * op.pt, prows = min(op.pt, a.P - p0);
+        const int h_first = p0 * a.stride - a.pad, rows_in = (prows - 1) * a.stride + a.R;
+        // input rows h_first .. h_first + rows_in - 1 (zeros outside the image) -> LDS
+        __syncthreads();
+        if ((row_elems & 7) == 0) {
+            // rows are multiples of 16 bytes: two 16-byte cells per thread and pass, requested together
+            const int row_cells = row_elems >> 3, cells = rows_in * row_cells;
+            for (int base = tid; base < cells; base += 2 * STREAM_THREADS) {
+                u32x4_t v[2];
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    const int i = base + u * STREAM_THREADS;
+                    const int r = i / row_cells, cc = i - r * row_cells;
+                    const int h = h_first + r;
+                    const bool ok = i < cells && h >= 0 && h < a.H;
+                    v[u] = __builtin_amdgcn_raw_buffer_load_b128(rx, ok ? ((n * a.H + h) * row_elems + cc * 8) * 2 : (int)OOB_OFFSET, 0, XLD);
+                }
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    const int i = base + u * STREAM_THREADS;
+                    if (i < cells) reinterpret_cast<u32x4_t *>(rows)[i] = v[u];
+                }
+            }
+        } else {
+            const int row_words = row_elems >> 1, words = rows_in * row_words;
+            for (int base = tid; base < words; base += 8 * STREAM_THREADS) {
+                unsigned v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int i = base + u * STREAM_THREADS;
+                    const int r = i / row_words, cw = i - r * row_words;
+                    const int h = h_first + r;
+                    const bool ok = i < words && h >= 0 && h < a.H;
+                    v[u] = __builtin_amdgcn_raw_buffer_load_b32(rx, ok ? ((n * a.H + h) * row_elems + cw * 2) * 2 : (int)OOB_OFFSET, 0, XLD);
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int i = base + u * STREAM_THREADS;
+                    if (i < words) reinterpret_cast<unsigned *>(rows)[i] = v[u];
+                }
+            }
+        }
+        __syncthreads();
+        const int npix = prows * a.Q;
+        for (int t = wave; t * 16 < npix; t += STREAM_WAVES) {
+            const int i = t * 16 + l16;
+            const bool pv = i < npix;
+            const int pr = pv ? i / a.Q : 0, q = pv ? i - pr * a.Q : 0;
+            const int w0 = q * a.stride - a.pad;
+            const int corner = pr * a.stride * row_elems + w0 * a.C;
+            f32x4_t acc[STEM_MAX_FT];
+#pragma unroll
+            for (int ft = 0; ft < STEM_MAX_FT; ++ft) acc[ft] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < STEM_MAX_KS; ++ks) {
+                if (ks < ksteps) {
+                    unsigned v[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const int col = w0 + k_ds[ks][e];
+                        const bool ok = pv && col >= 0 && col < a.W;
+                        v[e] = ok ? (unsigned)rows[corner + k_off[ks][e]] : 0u;
+                    }
+                    Frag fb;
+                    fb.u = make_uint4(v[0] | (v[1] << 16), v[2] | (v[3] << 16), v[4] | (v[5] << 16), v[6] | (v[7] << 16));
+#pragma unroll
+                    for (int ft = 0; ft < STEM_MAX_FT; ++ft)
+                        if (ft < ftiles) acc[ft] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[ft][ks].v, fb.v, acc[ft], 0, 0, 0);
+                }
+            }
+            const int m = (n * a.P + p0) * a.Q + i;
+            with_activation(a, [&](auto tag) {
+                constexpr int ACT = decltype(tag)::value;
+#pragma unroll
+                for (int ft = 0; ft < STEM_MAX_FT; ++ft) {
+                    const int fbase = ft * 16 + kg * 4;
+                    if (ft < ftiles && fbase + 4 <= a.K && pv) {
+                        const float4 sh = *reinterpret_cast<const float4 *>(a.shift + fbase);
+                        float4 sc = make_float4(1.f, 1.f, 1.f, 1.f);
+                        if (a.scale) sc = *reinterpret_cast<const float4 *>(a.scale + fbase);
+                        store_tile_bf16<ACT, ST>(ry, acc[ft], sc, sh, u32x2_t{0u, 0u}, (m * a.K + fbase) * 2);
+                    }
+                }
+            });
+        }
+    }
+}
+
 // Depthwise k x k: one thread per output pixel x 8 channels, taps in ring order.
 template <int LD, int ST>
 __device__ __forceinline__ void dwconv_units(const ConvArgs &a, int rank, int nranks) {
@@ -1023,7 +1169,11 @@ __device__ __forceinline__ void run_op(const DevOp &op, float *lds, int rank, in
     switch (op.kind) {
         case OP_CONV:
         case OP_FC:
-            if ((op.conv.C & 7) != 0)
+            if (op.wk == -1 && op.in_patch)
+                stem_units<LD, ST, true>(op, lds, rank, nranks);
+            else if (op.wk == -1)
+                stem_units<LD, ST, false>(op, lds, rank, nranks);
+            else if ((op.conv.C & 7) != 0)
                 conv_direct_units<ST>(op.conv, rank, nranks);
             else if (op.wk == 0)
                 run_tiled<LD, ST>(op, reinterpret_cast<u32x4_t *>(lds), rank, nranks);
@@ -1413,6 +1563,22 @@ void tile_dev_op(DevOp &op, int nwg, bool team) {
     op.ft = bft, op.pt = bpt, op.wk = bwk;
     op.n_p = (int)((ptiles + bpt - 1) / bpt);
     op.n_units = (int)(((ftiles + bft - 1) / bft) * op.n_p);
+}
+
+bool tile_stem_op(DevOp &op, int nwg) {
+    const ConvArgs &a = op.conv;
+    if ((a.C & 7) == 0 || a.R * a.R * a.C > 32 * STEM_MAX_KS || a.K > 16 * STEM_MAX_FT || (a.K & 3) != 0 ||
+        ((a.W * a.C) & 1) != 0 || a.res != nullptr || a.out_f32)
+        return false;
+    // rows per band: as many as keep every workgroup busy, within the LDS the input rows may take
+    const int bands_wanted = std::max(1, nwg / std::max(1, a.B));
+    int rows = (a.P + bands_wanted - 1) / bands_wanted;
+    while (rows > 1 && (long)((rows - 1) * a.stride + a.R) * a.W * a.C * 2 > RED_BYTES) --rows;
+    if ((long)((rows - 1) * a.stride + a.R) * a.W * a.C * 2 > RED_BYTES) return false;
+    op.wk = -1, op.ft = (a.K + 15) / 16, op.pt = rows;
+    op.n_p = (a.P + rows - 1) / rows;
+    op.n_units = a.B * op.n_p;
+    return true;
 }
 
 hipError_t launch_stream_kernel(const StreamArgs &a, int nwg, hipStream_t s) {

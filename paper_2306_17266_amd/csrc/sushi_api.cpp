@@ -505,7 +505,10 @@ int run_stream_kernel(sushi_ctx *c, CachedPlan &cp, const void *input_dev, void 
             if (L.kind == OP_CONV || L.kind == OP_FC) {
                 if ((L.conv.C & 7) == 0 && !dense_op_fits(L.conv))
                     return fail(c, SUSHI_ESTATE, "a dense layer has too many reduction steps or taps for the stream kernel");
-                tile_dev_op(op, c->stream_wgs, false);
+                if ((L.conv.C & 7) == 0)
+                    tile_dev_op(op, c->stream_wgs, false);
+                else
+                    tile_stem_op(op, c->stream_wgs);
             }
             prog.push_back(op);
         }
@@ -866,7 +869,10 @@ int post_team_query(sushi_ctx *c, CachedPlan &cp, const void *input_dev, void *l
             if (L.kind == OP_CONV || L.kind == OP_FC) {
                 if ((L.conv.C & 7) == 0 && !dense_op_fits(L.conv))
                     return fail(c, SUSHI_ESTATE, "a dense layer has too many reduction steps or taps for the team kernel");
-                tile_dev_op(op, c->team_wgs / MAX_TEAMS, true);
+                if ((L.conv.C & 7) == 0)
+                    tile_dev_op(op, c->team_wgs / MAX_TEAMS, true);
+                else
+                    tile_stem_op(op, c->team_wgs / MAX_TEAMS);
             }
             prog.push_back(op);
         }
