@@ -1327,7 +1327,6 @@ __global__ __launch_bounds__(STREAM_THREADS, 3) void sushi_team_kernel(TeamArgs 
     __shared__ u32x2_t slab_entries[STEP_TABLE_MAX];
     const StepTables tb{step_entries, slab_entries};
     __shared__ int flag;
-    __shared__ DevOp op;
     __shared__ int s_team, s_rank, s_size;
     __shared__ unsigned long long s_slot[5];
 
@@ -1440,32 +1439,41 @@ __global__ __launch_bounds__(STREAM_THREADS, 3) void sushi_team_kernel(TeamArgs 
 
         // ---- run the query inside this XCD
         constexpr int OP_WORDS = (int)(sizeof(DevOp) / sizeof(int));
-        static_assert(OP_WORDS <= STREAM_THREADS, "one thread per descriptor word");
-        // thread k carries word k of the next op's descriptor, fetched one op ahead
-        int next_word = (threadIdx.x < OP_WORDS && n_ops > 0) ? reinterpret_cast<const int *>(prog)[threadIdx.x] : 0;
+        static_assert(OP_WORDS <= 64, "one lane per descriptor word");
+        // lane k of every wave carries word k of the next op's descriptor, fetched one op ahead; the
+        // words then move to scalar registers lane by lane, without a trip through LDS
+        const int dlane = (int)(threadIdx.x & 63);
+        int next_word = (dlane < OP_WORDS && n_ops > 0) ? reinterpret_cast<const int *>(prog)[dlane] : 0;
         for (int i = 0; i < n_ops; ++i) {
-            if (threadIdx.x < OP_WORDS) reinterpret_cast<int *>(&op)[threadIdx.x] = next_word;
-            if (threadIdx.x < OP_WORDS && i + 1 < n_ops)
-                next_word = reinterpret_cast<const int *>(prog + i + 1)[threadIdx.x];
-            __syncthreads();
-            if (threadIdx.x == 0) {
+            DevOp uop;
+            {
+                union {
+                    DevOp o;
+                    int w[OP_WORDS];
+                } u;
+#pragma unroll
+                for (int k = 0; k < OP_WORDS; ++k) u.w[k] = __builtin_amdgcn_readlane(next_word, k);
+                uop = u.o;
+            }
+            if (dlane < OP_WORDS && i + 1 < n_ops) next_word = reinterpret_cast<const int *>(prog + i + 1)[dlane];
+            {
                 auto fix = [&](const void *p) -> const void * {
                     return p ? static_cast<const void *>(arena + (reinterpret_cast<long>(p) - 1)) : nullptr;
                 };
-                op.conv.x = fix(op.conv.x), op.conv.y = const_cast<void *>(fix(op.conv.y)), op.conv.res = fix(op.conv.res);
-                op.pool.x = fix(op.pool.x), op.pool.y = const_cast<void *>(fix(op.pool.y));
-                op.pool.gate = static_cast<const float *>(fix(op.pool.gate));
-                if (op.in_patch) op.conv.x = input;
-                if (op.out_patch) op.conv.y = logits;
+                uop.conv.x = fix(uop.conv.x), uop.conv.y = const_cast<void *>(fix(uop.conv.y)), uop.conv.res = fix(uop.conv.res);
+                uop.pool.x = fix(uop.pool.x), uop.pool.y = const_cast<void *>(fix(uop.pool.y));
+                uop.pool.gate = static_cast<const float *>(fix(uop.pool.gate));
+                if (uop.in_patch) uop.conv.x = input;
+                if (uop.out_patch) uop.conv.y = logits;
             }
-            __syncthreads();
+            uop = uniform_op(uop);  // the arena and the caller's buffers came through LDS
             if (ta.trace && i == 0 && rank == 0 && threadIdx.x == 0) ta.trace[team * TRACE_SLOTS] = wall_clock64();
             ResView rv{nullptr, nullptr, store, unit_list};
-            if (table && op.layer >= 0 && op.layer < table->n_layers && table->layers[op.layer].n_res > 0) {
-                rv.layer = &table->layers[op.layer];
+            if (table && uop.layer >= 0 && uop.layer < table->n_layers && table->layers[uop.layer].n_res > 0) {
+                rv.layer = &table->layers[uop.layer];
                 rv.entries = table->entries + rv.layer->first_entry;
             }
-            run_op<AUX_SC1, AUX_PLAIN, true>(uniform_op(op), lds, rank, tsize, rv, tb);
+            run_op<AUX_SC1, AUX_PLAIN, true>(uop, lds, rank, tsize, rv, tb);
             epoch += 1;
             if (!team_barrier<false>(ta, team, tsize, epoch, &flag)) return;
             if (ta.trace && rank == 0 && threadIdx.x == 0 && i + 1 < TRACE_SLOTS)
