@@ -59,6 +59,8 @@ def main():
     ap.add_argument("--workload", default="resnet_bs1_sticky")
     ap.add_argument("--exec-mode", type=int, default=3,
                     help="0 = launch per layer, 1 = HIP graph replay, 2 = stream kernel, 3 = persistent XCD-team kernel")
+    ap.add_argument("--teams-per-xcd", type=int, default=4, choices=[1, 2, 4],
+                    help="mode 3: teams per XCD (2 = twice as many queries in flight, each on half the workgroups)")
     ap.add_argument("--sgs", choices=["sched", "off"], default="sched",
                     help="sched = the scheduler re-chooses the cached SubGraph every Q queries; off = nothing is cached")
     ap.add_argument("--Q", type=int, default=0, help="queries between cache re-choices (default: the workload's)")
@@ -130,6 +132,7 @@ def main():
         del src, dst
     mode = args.exec_mode
     ctx.sushi_set_option(S.OPT_EXEC_MODE, mode)
+    ctx.sushi_set_option(S.OPT_TEAMS_PER_XCD, args.teams_per_xcd)
     for _ in range(args.warmup):
         step()
     ctx.sushi_synchronize()
@@ -219,7 +222,7 @@ def main():
     out = {"metric": "SubNet queries/sec (batch %d)" % batch, "value": args.steps / elapsed, "unit": "queries/s",
            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": elapsed / args.steps * 1e3,
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-           "config": {"workload": args.workload, "description": wl["desc"], "exec_mode": args.exec_mode, "sgs": args.sgs, "Q": Q,
+           "config": {"workload": args.workload, "description": wl["desc"], "exec_mode": args.exec_mode, "teams_per_xcd": args.teams_per_xcd, "sgs": args.sgs, "Q": Q,
                       "distinct_subnets": len(distinct), "candidate_subgraphs": len(cands)},
            "p50_latency_ms": p50_ms,
            "weight_bytes_per_query": stats["weight_bytes_total"] / max(1, stats["queries"]),

@@ -17,6 +17,7 @@ OPT_SPIN_LIMIT = 2
 OPT_IDLE_US = 3
 OPT_STREAM_WGS = 4
 OPT_TEAM_WGS_PER_CU = 5
+OPT_TEAMS_PER_XCD = 6
 
 
 class SushiError(RuntimeError):
@@ -238,9 +239,9 @@ class Sushi:
         _check(lib().sushi_quiesce(self._h), self._h)
 
     def sushi_team_trace(self, enable):
-        buf = (C.c_uint64 * (8 * 256))()
-        _check(lib().sushi_team_trace(self._h, int(enable), buf, 8 * 256), self._h)
-        return np.array(buf[:], dtype=np.uint64).reshape(8, 256)
+        buf = (C.c_uint64 * (32 * 256))()
+        _check(lib().sushi_team_trace(self._h, int(enable), buf, 32 * 256), self._h)
+        return np.array(buf[:], dtype=np.uint64).reshape(32, 256)
 
     def sushi_sched_init(self, subnet_vecs, accuracy, subgraph_vecs, table, Q, policy, initial_cache=-1):
         sv = np.ascontiguousarray(subnet_vecs, dtype=np.int32)

@@ -1242,10 +1242,18 @@ __global__ __launch_bounds__(STREAM_THREADS, 3) void sushi_stream_kernel(StreamA
 }
 
 // ------------------------------------------------------------------ the team kernel
-// sync layout (64-bit words): [0] abort, [16*(1+t)] workgroups of team t, [16*(9+t)] barrier
-// arrivals of team t, [16*17] workgroups that joined, [16*(18+t)] go counter of team t,
-// [16*(26+t) .. +5] broadcast slot of team t (cmd/n_ops, prog, input, logits, seq), [16*34] clock of
-// the latest post any team received (a team leaves only when the whole kernel has been idle).
+// sync layout (64-bit words, 16 words apart): abort, workgroups that joined per XCD, barrier arrivals
+// per team, workgroups that joined in total, go counter per team, broadcast slot per team (cmd/n_ops,
+// prog, input, logits, seq), clock of the latest post any team received (a team leaves only when the
+// whole kernel has been idle).
+constexpr int SY_ABORT = 0;
+__host__ __device__ constexpr int sy_xcd(int x) { return 16 * (1 + x); }
+__host__ __device__ constexpr int sy_barrier(int t) { return 16 * (1 + MAX_XCDS + t); }
+constexpr int SY_JOINED = 16 * (1 + MAX_XCDS + MAX_TEAMS);
+__host__ __device__ constexpr int sy_go(int t) { return SY_JOINED + 16 * (1 + t); }
+__host__ __device__ constexpr int sy_slot(int t) { return SY_JOINED + 16 * (1 + MAX_TEAMS + t); }
+constexpr int SY_CLOCK = SY_JOINED + 16 * (1 + 2 * MAX_TEAMS);
+static_assert(SY_CLOCK + 16 <= SYNC_WORDS, "the barrier area holds the team kernel's words");
 
 __device__ __forceinline__ unsigned long long ld_agent(const unsigned long long *p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -1278,12 +1286,12 @@ __device__ __forceinline__ bool team_barrier(const TeamArgs &ta, int team, unsig
                                              int *lds_flag) {
     __syncthreads();
     if (threadIdx.x == 0) {
-        unsigned long long *ctr = &ta.sync[16 * (9 + team)];
+        unsigned long long *ctr = &ta.sync[sy_barrier(team)];
         __hip_atomic_fetch_add(ctr, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         const unsigned long long target = e * tsize;
         int spins = 0, good = 1;
         while (ld_agent(ctr) < target) {
-            if (++spins > ta.spin_limit || ld_agent(&ta.sync[0]) != 0) {
+            if (++spins > ta.spin_limit || ld_agent(&ta.sync[SY_ABORT]) != 0) {
                 raise_abort(ta);
                 good = 0;
                 break;
@@ -1333,24 +1341,35 @@ __global__ __launch_bounds__(STREAM_THREADS, 3) void sushi_team_kernel(TeamArgs 
     // ---- team formation: which XCD am I on, how many of us are there
     if (threadIdx.x == 0) {
         const int xcc = (int)(__builtin_amdgcn_s_getreg((3 << 11) | 20) & 7);  // XCC_ID, bits 3:0
-        s_team = xcc;
-        s_rank = (int)__hip_atomic_fetch_add(&ta.sync[16 * (1 + xcc)], 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_fetch_add(&ta.sync[16 * 17], 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const int per_xcd = ta.teams_per_xcd;
+        const int arrival = (int)__hip_atomic_fetch_add(&ta.sync[sy_xcd(xcc)], 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_fetch_add(&ta.sync[SY_JOINED], 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         int spins = 0, good = 1;
-        while (ld_agent(&ta.sync[16 * 17]) < gridDim.x) {
-            if (++spins > ta.spin_limit || ld_agent(&ta.sync[0]) != 0) {
+        while (ld_agent(&ta.sync[SY_JOINED]) < gridDim.x) {
+            if (++spins > ta.spin_limit || ld_agent(&ta.sync[SY_ABORT]) != 0) {
                 raise_abort(ta);
                 good = 0;
                 break;
             }
             __builtin_amdgcn_s_sleep(1);
         }
-        s_size = (int)ld_agent(&ta.sync[16 * (1 + xcc)]);
+        // arrival order inside the XCD deals the workgroups to its teams in turn
+        const int on_xcd = (int)ld_agent(&ta.sync[sy_xcd(xcc)]);
+        const int sub = arrival % per_xcd;
+        s_team = xcc * per_xcd + sub;
+        s_rank = arrival / per_xcd;
+        s_size = (on_xcd - sub + per_xcd - 1) / per_xcd;
         flag = good;
         if (good && blockIdx.x == 0) {
-            for (int t = 0; t < MAX_TEAMS; ++t)
-                __hip_atomic_store(&ta.host->team_size[t], (unsigned)ld_agent(&ta.sync[16 * (1 + t)]), __ATOMIC_RELAXED,
-                                   __HIP_MEMORY_SCOPE_SYSTEM);
+            for (int t = 0; t < MAX_TEAMS; ++t) {
+                const int x = t / per_xcd, k = t - x * per_xcd;
+                unsigned size = 0;
+                if (x < MAX_XCDS) {
+                    const int n = (int)ld_agent(&ta.sync[sy_xcd(x)]);
+                    size = (unsigned)((n - k + per_xcd - 1) / per_xcd);
+                }
+                __hip_atomic_store(&ta.host->team_size[t], size, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+            }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
             __hip_atomic_store(&ta.host->ready, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
         }
@@ -1366,8 +1385,8 @@ __global__ __launch_bounds__(STREAM_THREADS, 3) void sushi_team_kernel(TeamArgs 
     char *arena = ta.arena + (long)team * ta.arena_bytes;
     unsigned long long my_seq = ta.last_seq[team];
     unsigned long long epoch = 0;
-    unsigned long long *go = &ta.sync[16 * (18 + team)];
-    unsigned long long *slot = &ta.sync[16 * (26 + team)];
+    unsigned long long *go = &ta.sync[sy_go(team)];
+    unsigned long long *slot = &ta.sync[sy_slot(team)];
     const unsigned long long *posted = &ta.host->posted[team * 8];
 
     for (unsigned long long iter = 1;; ++iter) {
@@ -1380,16 +1399,16 @@ __global__ __launch_bounds__(STREAM_THREADS, 3) void sushi_team_kernel(TeamArgs 
                 const TeamPost *post = &ta.host->post[team][0];
                 for (;;) {
                     if (ld_sys(posted) > my_seq) {
-                        st_agent(&ta.sync[16 * 34], (unsigned long long)wall_clock64());  // any team's post keeps all teams alive
+                        st_agent(&ta.sync[SY_CLOCK], (unsigned long long)wall_clock64());  // any team's post keeps all teams alive
                         seq = my_seq + 1;
                         post = &ta.host->post[team][seq % POST_RING];
                         cmd = (unsigned long long)__hip_atomic_load(&post->cmd, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
                         n_ops = (unsigned long long)__hip_atomic_load(&post->n_ops, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
                         break;
                     }
-                    const long long last = std::max(t0, (long long)ld_agent(&ta.sync[16 * 34]));
+                    const long long last = std::max(t0, (long long)ld_agent(&ta.sync[SY_CLOCK]));
                     if (__hip_atomic_load(&ta.host->stop, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) != 0 ||
-                        ld_agent(&ta.sync[0]) != 0 || wall_clock64() - last > ta.idle_ticks)
+                        ld_agent(&ta.sync[SY_ABORT]) != 0 || wall_clock64() - last > ta.idle_ticks)
                         break;  // cmd stays TEAM_STOP
                     __builtin_amdgcn_s_sleep(8);
                 }
@@ -1403,7 +1422,7 @@ __global__ __launch_bounds__(STREAM_THREADS, 3) void sushi_team_kernel(TeamArgs 
             } else {
                 const long long t0 = wall_clock64();
                 while (ld_agent(go) < iter) {
-                    if (ld_agent(&ta.sync[0]) != 0 || wall_clock64() - t0 > 4 * ta.idle_ticks + 100000000ll) {
+                    if (ld_agent(&ta.sync[SY_ABORT]) != 0 || wall_clock64() - t0 > 4 * ta.idle_ticks + 100000000ll) {
                         raise_abort(ta);
                         good = 0;
                         break;

@@ -86,6 +86,8 @@ struct sushi_ctx {
     unsigned long long epoch_base = 0;
     int stream_wgs = 0, stream_wgs_override = 0;
     int team_wgs = 0, team_wgs_per_cu = 2;
+    int teams_per_xcd = 1;  // teams each XCD's workgroups are dealt to (1 or 2)
+    int team_size() const { return team_wgs / (MAX_XCDS * teams_per_xcd); }  // workgroups of a team, if they spread evenly
     int spin_limit = 400000;
     // exec mode 3 (team kernel): mailboxes in pinned host memory, per-team arenas, private stream
     TeamHostState *th = nullptr;
@@ -584,7 +586,7 @@ int make_team_pools(sushi_ctx *c) {
 // the last to the first (the late, few-pixel layers hold most weights and are the ones that use
 // their slabs), tiles round-robin over the ranks, first rank with room wins.
 int build_res_table(sushi_ctx *c) {
-    const int team_size = c->team_wgs / MAX_TEAMS;
+    const int team_size = c->team_size();
     const size_t n_layers = c->sn.layers.size();
     c->h_res_layers.assign(n_layers, ResLayer{});
     c->h_res_entries.clear();
@@ -652,7 +654,7 @@ int upload_res_table(sushi_ctx *c) {
     if (c->h_res_entries.empty()) return SUSHI_OK;
     if (c->h_res_layers.size() > sushi_ctx::RES_MAX_LAYERS) return fail(c, SUSHI_ENOMEM, "too many layers for the table");
     ResTable t{};
-    t.n_layers = (int)c->h_res_layers.size(), t.team_size = c->team_wgs / MAX_TEAMS;
+    t.n_layers = (int)c->h_res_layers.size(), t.team_size = c->team_size();
     t.layers = g.d_layers, t.entries = g.d_entries;
     int rc = upload_async(c, g.d_layers, c->h_res_layers.data(), c->h_res_layers.size() * sizeof(ResLayer));
     if (rc == SUSHI_OK) rc = upload_async(c, g.d_entries, c->h_res_entries.data(), c->h_res_entries.size() * sizeof(ResEntry));
@@ -720,6 +722,7 @@ int launch_teams(sushi_ctx *c) {
     if ((e = hipMemsetAsync(c->d_tsync, 0, SYNC_WORDS * 8, c->pstream)) != hipSuccess) return hip_fail(c, e, "hipMemsetAsync");
     TeamArgs ta{};
     ta.host = c->th, ta.sync = c->d_tsync, ta.arena = c->d_tarena, ta.arena_bytes = c->tarena_bytes;
+    ta.teams_per_xcd = c->teams_per_xcd;
     for (int t = 0; t < MAX_TEAMS; ++t) ta.last_seq[t] = c->th->done[t * 8];
     ta.idle_ticks = c->idle_ticks, ta.spin_limit = c->spin_limit;
     ta.trace = c->d_trace;
@@ -870,9 +873,9 @@ int post_team_query(sushi_ctx *c, CachedPlan &cp, const void *input_dev, void *l
                 if ((L.conv.C & 7) == 0 && !dense_op_fits(L.conv))
                     return fail(c, SUSHI_ESTATE, "a dense layer has too many reduction steps or taps for the team kernel");
                 if ((L.conv.C & 7) == 0)
-                    tile_dev_op(op, c->team_wgs / MAX_TEAMS, true);
+                    tile_dev_op(op, c->team_size(), true);
                 else
-                    tile_stem_op(op, c->team_wgs / MAX_TEAMS);
+                    tile_stem_op(op, c->team_size());
             }
             prog.push_back(op);
         }
@@ -1331,6 +1334,11 @@ int sushi_set_option(sushi_ctx *c, int option, int64_t value) {
     if (option == SUSHI_OPT_TEAM_WGS_PER_CU && value >= 1 && value <= 2) {
         if (c->th) return fail(c, SUSHI_ESTATE, "set the workgroup count before the first query");
         c->team_wgs_per_cu = (int)value;
+        return SUSHI_OK;
+    }
+    if (option == SUSHI_OPT_TEAMS_PER_XCD && (value == 1 || value == 2 || value == 4) && value <= MAX_TEAMS / MAX_XCDS) {
+        if (c->th) return fail(c, SUSHI_ESTATE, "set the number of teams before the first query");
+        c->teams_per_xcd = (int)value;
         return SUSHI_OK;
     }
     if (option == SUSHI_OPT_IDLE_US && value >= 10 && value <= 10000000) {

@@ -83,21 +83,22 @@ def test_a_wait_that_runs_out_is_reported_and_recovered():
 
 # ---------------------------------------------------------------- exec mode 3: the team kernel
 
-def _team_ctx(arch, seed):
+def _team_ctx(arch, seed, teams_per_xcd=1):
     import paper_2306_17266_amd as S
     blob, wts = make_problem(arch, seed, True)
     ctx = S.Sushi(0)
     ctx.sushi_load_supernet(arch, blob, S.BF16)
     ctx.sushi_set_option(S.OPT_EXEC_MODE, 3)
+    ctx.sushi_set_option(S.OPT_TEAMS_PER_XCD, teams_per_xcd)
     return ctx, wts
 
 
-@pytest.mark.parametrize("fam", ["tiny", "resnet", "mbv3"])
-def test_team_kernel_small_supernets(fam):
-    """Queries are posted without waiting (up to eight in flight, one per XCD team), then all
+@pytest.mark.parametrize("fam,teams", [("tiny", 1), ("resnet", 1), ("mbv3", 1), ("resnet", 2), ("mbv3", 4)])
+def test_team_kernel_small_supernets(fam, teams):
+    """Queries are posted without waiting (one in flight per team; 1, 2 or 4 teams per XCD), then all
     logits are checked against the oracle; a second pass must reproduce them bit for bit."""
     arch = {"tiny": A.tiny_arch, "resnet": A.small_resnet_arch, "mbv3": A.small_mbv3_arch}[fam]()
-    ctx, wts = _team_ctx(arch, 3)
+    ctx, wts = _team_ctx(arch, 3, teams)
     st = Stream(81)
     for res, batch in ((min(arch.res_choices), 1), (max(arch.res_choices), 3)):
         cfgs = [A.min_cfg(arch, res), A.max_cfg(arch, res)] + [streams.uniform_cfg(arch, st, res) for _ in range(14)]
@@ -118,10 +119,10 @@ def test_team_kernel_small_supernets(fam):
     ctx.close()
 
 
-@pytest.mark.parametrize("fam", ["resnet", "mbv3"])
-def test_team_kernel_full_size_batch1(fam):
+@pytest.mark.parametrize("fam,teams", [("resnet", 1), ("mbv3", 1), ("resnet", 4), ("mbv3", 2)])
+def test_team_kernel_full_size_batch1(fam, teams):
     arch = A.resnet_arch() if fam == "resnet" else A.mbv3_arch()
-    ctx, wts = _team_ctx(arch, 31)
+    ctx, wts = _team_ctx(arch, 31, teams)
     st = Stream(83)
     cfgs = [A.min_cfg(arch, 224), A.max_cfg(arch, 224)] + [streams.uniform_cfg(arch, st) for _ in range(3)]
     xs_np = [T.make_input(31, t, 1, c.resolution, 3, True) for t, c in enumerate(cfgs)]
@@ -169,14 +170,14 @@ def test_team_kernel_restarts_after_idling_and_after_mode_switches():
     ctx.close()
 
 
-@pytest.mark.parametrize("fam", ["resnet", "mbv3"])
-def test_team_kernel_logits_do_not_depend_on_resident_slabs(fam):
+@pytest.mark.parametrize("fam,teams", [("resnet", 1), ("mbv3", 1), ("resnet", 4)])
+def test_team_kernel_logits_do_not_depend_on_resident_slabs(fam, teams):
     """SubGraph residency in LDS is exact: the same logits, bit for bit, with nothing cached, with
     a SubGraph cached, after the cache changes in mid-stream and after it is emptied; and the
     library reports how many weight bytes came out of LDS."""
     from oracle import subnet_eval as E
     arch = A.small_resnet_arch() if fam == "resnet" else A.small_mbv3_arch()
-    ctx, wts = _team_ctx(arch, 9)
+    ctx, wts = _team_ctx(arch, 9, teams)
     st = Stream(91)
     res = 64
     # (the largest SubNet of the shrunken MBV3 net is left out as a query: its bf16 rounding error
