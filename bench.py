@@ -25,6 +25,32 @@ HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 
+def kernel_sources_digest():
+    """SHA-256 over the library's sources: a stored counter reading only describes the kernels it
+    was taken with."""
+    import glob
+    import hashlib
+    h = hashlib.sha256()
+    for path in sorted(glob.glob(os.path.join(ROOT, "paper_2306_17266_amd", "csrc", "*"))):
+        h.update(os.path.basename(path).encode())
+        h.update(open(path, "rb").read())
+    return h.hexdigest()
+
+
+def stored_traffic(workload, mode, teams_per_xcd, sgs, Q):
+    """HBM-side bytes per query (FETCH_SIZE + WRITE_SIZE, scaled by a copy of known size) from
+    profiles/team_kernel_traffic.txt, or None when that reading was taken for another configuration
+    or before the kernels last changed."""
+    path = os.path.join(ROOT, "profiles", "team_kernel_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    kv = dict(line.strip().split("=", 1) for line in open(path) if "=" in line and not line.startswith("#"))
+    want = {"workload": workload, "exec_mode": str(mode), "teams_per_xcd": str(teams_per_xcd), "sgs": sgs, "Q": str(Q)}
+    if any(kv.get(k) != v for k, v in want.items()) or kv.get("sources_sha256") != kernel_sources_digest():
+        return None
+    return float(kv["fetch_bytes_per_query"]) + float(kv["write_bytes_per_query"])
+
+
 def build_workload(name):
     from workloads import arch as A
     from workloads import streams
@@ -191,8 +217,15 @@ def main():
             achieved, peak, unit, bound = dom["flops"] / sec / 1e12, MFMA_BF16_PEAK_TFLOPS, "TFLOP/s", "mfma"
         else:
             achieved, peak, unit, bound = dom["bytes"] / sec / 1e9, HBM_PEAK_GBS, "GB/s", "hbm"
+        # measured bytes per launch of the dominant kernel: known only for the team kernel, whose one
+        # launch serves all timed queries
+        traffic = None
+        if mode == 3 and dom["launches"] == 1:
+            per_query = stored_traffic(args.workload, mode, args.teams_per_xcd, args.sgs, Q)
+            if per_query is not None:
+                traffic = per_query * args.steps
         roofline = {"bound": bound, "achieved": achieved, "peak": peak, "unit": unit, "frac": achieved / peak,
-                    "traffic": None, "kernel": dom["name"], "launches": dom["launches"],
+                    "traffic": traffic, "kernel": dom["name"], "launches": dom["launches"],
                     "avg_launch_us": dom["total_ms"] * 1e3 / dom["launches"],
                     "alg_bytes_per_launch": dom["bytes"] / dom["launches"],
                     "alg_flops_per_launch": dom["flops"] / dom["launches"],
