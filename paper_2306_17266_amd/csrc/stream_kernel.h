@@ -23,7 +23,7 @@ constexpr int SYNC_WORDS = 128 * 16;  // 64-bit words in the barrier area (128-b
 struct DevOp {
     int kind;      // OpKind (model.h)
     int pt, wk;    // dense conv: pixel tiles per unit (1, 2, 4) and waves sharing one unit (1, 2, 4, 8);
-                   // wk = 0: tiled units (ft x pt tiles per wave); wk = -1: stem units (pt output rows per band)
+                   // wk = 0: tiled units (ft x pt tiles per wave); wk = -1: stem units (pt output rows per band); wk = -2: depthwise through LDS
     int n_units;   // dense conv: filter groups x pixel groups
     int n_p;       // dense conv: pixel groups
     int in_patch;  // input pointer is the caller's input buffer
@@ -141,6 +141,9 @@ void tile_dev_op(DevOp &op, int nwg, bool team);
 // A dense conv with few input channels (the stem): sets wk = -1 and the band height in pt if the
 // layer qualifies for the matrix-core stem path, else leaves the op alone and returns false.
 bool tile_stem_op(DevOp &op, int nwg);
+// A depthwise conv: sets wk = -2, the channel groups per unit in ft and the band height in pt if the layer fits
+// the LDS-staged path, else leaves the op alone and returns false.
+bool tile_dw_op(DevOp &op, int nwg);
 
 // Number of grid barriers the kernel executes for a program of n_ops ops.
 inline int stream_barriers(int n_ops) { return n_ops > 0 ? n_ops - 1 : 0; }

@@ -1035,6 +1035,108 @@ __device__ __forceinline__ void dwconv_units(const ConvArgs &a, int rank, int nr
     }
 }
 
+// Depthwise k x k through LDS (wk == -2): a unit is op.ft channel groups (of 8 channels) x a band of
+// op.pt output rows of one image.  The workgroup copies the input rows the band needs (zeros outside
+// the image) and the taps' weights into LDS; a thread then computes up to DW_ITEMS outputs of 8
+// channels, converting a tap's weights once for all of them.
+constexpr int DW_ITEMS = 4;
+template <int LD, int ST>
+__device__ __forceinline__ void dw_tiled_units(const DevOp &op, float *lds, int rank, int nranks) {
+    const ConvArgs &a = op.conv;
+    const int tid = threadIdx.x;
+    const int CB = op.ft, rows_out = op.pt;
+    const int cgs = a.K >> 3, cblocks = (cgs + CB - 1) / CB, bands = (a.P + rows_out - 1) / rows_out;
+    const int ntaps = a.R * a.R, half = (a.R - 1) >> 1;
+    const __amdgpu_buffer_rsrc_t rx = make_rsrc(a.x, (long)a.B * a.H * a.W * a.C * 2);
+    const __amdgpu_buffer_rsrc_t ry = make_rsrc(a.y, (long)a.B * a.P * a.Q * a.K * 2);
+    const __amdgpu_buffer_rsrc_t rw = make_rsrc(a.w, (long)a.Rmax * a.Rmax * a.Kpad * 2);
+    u32x4_t *w_lds = reinterpret_cast<u32x4_t *>(lds);  // [tap][CB]
+    u32x4_t *x_lds = w_lds + ntaps * CB;                // [row][column][CB]
+    const int cb = tid % CB;                            // STREAM_THREADS is a multiple of CB: fixed per thread
+    for (int unit = rank; unit < op.n_units; unit += nranks) {
+        const int band = unit % bands, rest = unit / bands;
+        const int cblock = rest % cblocks, n = rest / cblocks;
+        const int cg0 = cblock * CB;
+        const int p0 = band * rows_out, prows = min(rows_out, a.P - p0);
+        const int h_first = p0 * a.stride - half, rows_in = (prows - 1) * a.stride + a.R;
+        __syncthreads();
+        for (int i = tid; i < ntaps * CB; i += STREAM_THREADS) {
+            const int t = i / CB, c = cg0 + (i - t * CB);
+            w_lds[i] = __builtin_amdgcn_raw_buffer_load_b128(rw, c < cgs ? (t * a.Kpad + c * 8) * 2 : (int)OOB_OFFSET, 0, 0);
+        }
+        const int cells = rows_in * a.W * CB;
+        for (int base = tid; base < cells; base += 4 * STREAM_THREADS) {
+            u32x4_t v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int i = base + u * STREAM_THREADS;
+                const int pix = i / CB, c = cg0 + (i - pix * CB);
+                const int r = pix / a.W, col = pix - r * a.W;
+                const int h = h_first + r;
+                const bool ok = i < cells && h >= 0 && h < a.H && c < cgs;
+                v[u] = __builtin_amdgcn_raw_buffer_load_b128(rx, ok ? (((n * a.H + h) * a.W + col) * a.C + c * 8) * 2 : (int)OOB_OFFSET, 0, LD);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int i = base + u * STREAM_THREADS;
+                if (i < cells) x_lds[i] = v[u];
+            }
+        }
+        __syncthreads();
+        const int items = prows * a.Q * CB;
+        const bool cvalid = cg0 + cb < cgs;
+        const int c = (cg0 + cb) * 8;
+        float sc[8], sh[8];
+        if (cvalid) {
+            load8(a.scale + c, sc);
+            load8(a.shift + c, sh);
+        }
+        for (int first = tid; first < items; first += DW_ITEMS * STREAM_THREADS) {
+            // this thread's outputs: items first, first + 512, ... (same channel group)
+            int corner[DW_ITEMS], w0[DW_ITEMS], m_out[DW_ITEMS];
+            bool live[DW_ITEMS];
+            float acc[DW_ITEMS][8];
+#pragma unroll
+            for (int k = 0; k < DW_ITEMS; ++k) {
+                const int it = first + k * STREAM_THREADS;
+                live[k] = it < items && cvalid;
+                const int pix = live[k] ? it / CB : 0;
+                const int pr = pix / a.Q, q = pix - pr * a.Q;
+                w0[k] = q * a.stride;
+                corner[k] = ((pr * a.stride + half) * a.W + w0[k]) * CB + cb;
+                m_out[k] = (n * a.P + p0 + pr) * a.Q + q;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc[k][j] = 0.f;
+            }
+            for (int t = 0; t < ntaps; ++t) {
+                const int dr = c_dw_dr[t], ds = c_dw_ds[t];
+                float wv[8];
+                const u32x4_t wq = w_lds[t * CB + cb];
+                unpack8(make_uint4(wq.x, wq.y, wq.z, wq.w), wv);
+                const int step = (dr * a.W + ds) * CB;
+#pragma unroll
+                for (int k = 0; k < DW_ITEMS; ++k) {
+                    const int col = w0[k] + ds;
+                    if (live[k] && col >= 0 && col < a.W) {
+                        float xv[8];
+                        const u32x4_t xq = x_lds[corner[k] + step];
+                        unpack8(make_uint4(xq.x, xq.y, xq.z, xq.w), xv);
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) acc[k][j] = fmaf(wv[j], xv[j], acc[k][j]);
+                    }
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < DW_ITEMS; ++k)
+                if (live[k]) {
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) acc[k][j] = activate(acc[k][j] * sc[j] + sh[j], a.act, 0);
+                    act_st16<ST>(ry, (m_out[k] * a.K + c) * 2, pack8(acc[k]));
+                }
+        }
+    }
+}
+
 template <int LD, int ST>
 __device__ __forceinline__ void maxpool_units(const PoolArgs &a, int rank, int nranks) {
     const int cgs = a.C >> 3;
@@ -1193,7 +1295,10 @@ __device__ __forceinline__ void run_op(const DevOp &op, float *lds, int rank, in
                 conv_units<1, 1, LD, ST, RES>(op, lds, rank, nranks, rv, tb);
             break;
         case OP_DW:
-            dwconv_units<LD, ST>(op.conv, rank, nranks);
+            if (op.wk == -2)
+                dw_tiled_units<LD, ST>(op, lds, rank, nranks);
+            else
+                dwconv_units<LD, ST>(op.conv, rank, nranks);
             break;
         case OP_MAXPOOL:
             maxpool_units<LD, ST>(op.pool, rank, nranks);
@@ -1590,6 +1695,35 @@ void tile_dev_op(DevOp &op, int nwg, bool team) {
     op.ft = bft, op.pt = bpt, op.wk = bwk;
     op.n_p = (int)((ptiles + bpt - 1) / bpt);
     op.n_units = (int)(((ftiles + bft - 1) / bft) * op.n_p);
+}
+
+bool tile_dw_op(DevOp &op, int nwg) {
+    const ConvArgs &a = op.conv;
+    const int cgs = a.K / 8;
+    if ((a.K & 7) != 0 || (a.R & 1) == 0 || a.C != a.K) return false;
+    auto lds_bytes = [&](int rows, int cb) { return ((long)((rows - 1) * a.stride + a.R) * a.W + a.R * a.R) * cb * 16; };
+    // time ~ rounds x (outputs per unit, in passes of the workgroup's threads, plus the input rows to
+    // copy and a fixed part)
+    int best_cb = 0, best_rows = 0;
+    double best = 1e30;
+    for (int cb = 1; cb <= 4; cb *= 2) {
+        const int cblocks = (cgs + cb - 1) / cb;
+        for (int rows = 1; rows <= a.P; ++rows) {
+            if (lds_bytes(rows, cb) > RED_BYTES) break;
+            const long units = (long)a.B * cblocks * ((a.P + rows - 1) / rows);
+            const long rounds = (units + nwg - 1) / nwg;
+            const long passes = ((long)rows * a.Q * cb + STREAM_THREADS - 1) / STREAM_THREADS;
+            const double copy = (double)((rows - 1) * a.stride + a.R) * a.W * cb / STREAM_THREADS;
+            const double cost = rounds * (passes * a.R * a.R + 4.0 * copy + 60.0);
+            if (cost < best) best = cost, best_cb = cb, best_rows = rows;
+        }
+    }
+    if (best_cb == 0) return false;
+    const int cblocks = (cgs + best_cb - 1) / best_cb;
+    op.wk = -2, op.ft = best_cb, op.pt = best_rows;
+    op.n_p = (a.P + best_rows - 1) / best_rows;
+    op.n_units = a.B * cblocks * op.n_p;
+    return true;
 }
 
 bool tile_stem_op(DevOp &op, int nwg) {

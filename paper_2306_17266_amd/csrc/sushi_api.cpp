@@ -511,6 +511,8 @@ int run_stream_kernel(sushi_ctx *c, CachedPlan &cp, const void *input_dev, void 
                     tile_dev_op(op, c->stream_wgs, false);
                 else
                     tile_stem_op(op, c->stream_wgs);
+            } else if (L.kind == OP_DW) {
+                tile_dw_op(op, c->stream_wgs);
             }
             prog.push_back(op);
         }
@@ -876,6 +878,8 @@ int post_team_query(sushi_ctx *c, CachedPlan &cp, const void *input_dev, void *l
                     tile_dev_op(op, c->team_size(), true);
                 else
                     tile_stem_op(op, c->team_size());
+            } else if (L.kind == OP_DW) {
+                tile_dw_op(op, c->team_size());
             }
             prog.push_back(op);
         }
