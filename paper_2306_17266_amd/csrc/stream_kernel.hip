@@ -796,6 +796,178 @@ __device__ __forceinline__ void conv_tile_units(const DevOp &op, u32x4_t *stage,
     }
 }
 
+// ------------------------------------------------------------------ dense conv with many pixels and few weights
+// Units as in conv_tile_units (AT filter tiles x 8 * BT pixel tiles), for layers whose weights for one
+// filter group fit in LDS whole (short reductions: the 1x1 convs of the early stages, the second and
+// third stem conv).  A workgroup loads the filter group's weights for every reduction step once, in
+// operand order, and keeps them while it works through the group's pixel blocks; inside a unit the
+// waves run without any barrier, each with its own ring of activation cells ARES_D steps ahead.
+constexpr int ARES_D = 4;
+
+template <int AT, int BT, int LD, int ST>
+__device__ __forceinline__ void conv_ares_units(const DevOp &op, u32x4_t *lds, int rank, int nranks) {
+    constexpr int D = ARES_D;
+    const ConvArgs &a = op.conv;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l16 = lane & 15, kg = lane >> 4;
+    const int M = a.B * a.P * a.Q;
+    const int taps = a.R * a.R;
+    const __amdgpu_buffer_rsrc_t rx = make_rsrc(a.x, (long)a.B * a.H * a.W * a.C * 2);
+    const __amdgpu_buffer_rsrc_t rw = make_rsrc(a.w, (long)taps * a.CG * a.Kpad * 16);
+    const __amdgpu_buffer_rsrc_t ry = make_rsrc(a.y, (long)M * a.K * (a.out_f32 ? 4 : 2));
+    const __amdgpu_buffer_rsrc_t rres = make_rsrc(a.res ? a.res : a.y, (long)M * a.K * 2);
+    const int csteps = (a.C + 31) >> 5;
+    const int nsteps = taps * csteps;
+    const int nsteps_pad = (nsteps + D - 1) / D * D;
+    const bool sys_out = op.out_patch != 0;
+    const int tail_active = ((a.C + 7) >> 3) - (csteps - 1) * 4;
+    const int tail_stored = min(4, a.CG - (csteps - 1) * 4);
+    // LDS: [step][AT][64] weight cells, scale and shift of the group's filters, one table entry per step
+    u32x4_t *wts = lds;
+    float *epi_lds = reinterpret_cast<float *>(lds + nsteps * AT * 64);
+    u32x4_t *table = lds + nsteps * AT * 64 + AT * 8;
+    for (int st = tid; st < nsteps_pad; st += STREAM_THREADS) {
+        const int tap = st / csteps, c = st - tap * csteps;
+        const int dr = tap / a.R, ds = tap - dr * a.R;
+        u32x4_t e = {0u, 0u, 0u, 0u};
+        if (st < nsteps) {
+            e.x = (unsigned)((tap * a.CG + c * 4) * a.Kpad * 16);
+            e.y = (unsigned)((dr * a.W + ds) * a.C * 2 + c * 64);
+            e.z = c == csteps - 1 ? 0u : 1u << tap;
+            e.w = c == csteps - 1 ? 1u << tap : 0u;
+        }
+        table[st] = e;
+    }
+    __syncthreads();
+    const float rcp_q = 1.0f / (float)a.Q, rcp_pq = 1.0f / (float)(a.P * a.Q);
+    const bool vec_k = (a.K & 3) == 0;
+
+    int loaded_group = -1;
+    for (int unit = rank; unit < op.n_units; unit += nranks) {
+        const int fgroup = unit / op.n_p, pgroup = unit - fgroup * op.n_p;
+        const int f0 = fgroup * AT * 16, m0 = (pgroup * STREAM_WAVES + wave) * BT * 16;
+        if (fgroup != loaded_group) {
+            // (re)load the filter group: cell (step, tile, lane) in the lane layout of the MFMA operand
+            loaded_group = fgroup;
+            __syncthreads();
+            const int cells = nsteps * AT * 64;
+            for (int base = tid; base < cells; base += 4 * STREAM_THREADS) {
+                u32x4_t v[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int i = min(base + u * STREAM_THREADS, cells - 1);
+                    const int st = i / (AT * 64), rem = i - st * (AT * 64);
+                    const int tile = rem >> 6, ln = rem & 63;
+                    const u32x4_t e = table[st];
+                    const int kgx = e.w != 0u ? min(ln >> 4, tail_stored - 1) : (ln >> 4);
+                    const int row = min(f0 + tile * 16 + (ln & 15), a.Kpad - 1);
+                    v[u] = __builtin_amdgcn_raw_buffer_load_b128(rw, (int)e.x + (kgx * a.Kpad + row) * 16, 0, 0);
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int i = base + u * STREAM_THREADS;
+                    if (i < cells) wts[i] = v[u];
+                }
+            }
+            if (tid < AT * 16) {
+                float e_sc = 1.0f, e_sh = 0.0f;
+                if (f0 + tid < a.K) {
+                    if (a.scale) e_sc = ((const global_f32 *)a.scale)[f0 + tid];
+                    e_sh = ((const global_f32 *)a.shift)[f0 + tid];
+                }
+                epi_lds[tid] = e_sc, epi_lds[AT * 16 + tid] = e_sh;
+            }
+            __syncthreads();
+        }
+        int b_lane[BT];
+        unsigned mask_full[BT], mask_tail[BT];
+#pragma unroll
+        for (int j = 0; j < BT; ++j) {
+            const int m = m0 + j * 16 + l16;
+            pixel_cell(a, m, m < M, kg, rcp_q, rcp_pq, &b_lane[j], &mask_full[j]);
+            mask_tail[j] = kg < tail_active ? mask_full[j] : 0u;
+        }
+        // residuals early: their latency hides behind the reduction
+        u32x2_t resid[AT][BT];
+#pragma unroll
+        for (int i = 0; i < AT; ++i) {
+            const int fbase = f0 + i * 16 + kg * 4;
+#pragma unroll
+            for (int j = 0; j < BT; ++j) {
+                const int m = m0 + j * 16 + l16;
+                const bool want = a.res && vec_k && fbase + 4 <= a.K && m < M;
+                resid[i][j] = __builtin_amdgcn_raw_buffer_load_b64(rres, want ? (m * a.K + fbase) * 2 : OOB_STORE, 0, LD);
+            }
+        }
+        u32x4_t rb[D][BT];
+        int i_step = 0;
+        auto issue = [&](u32x4_t *qb) {
+            const u32x4_t e = table[min(i_step, nsteps_pad - 1)];
+            const bool past = i_step >= nsteps_pad;
+            ++i_step;
+#pragma unroll
+            for (int j = 0; j < BT; ++j) {
+                const bool ok = !past && ((mask_full[j] & e.z) | (mask_tail[j] & e.w)) != 0u;
+                qb[j] = __builtin_amdgcn_raw_buffer_load_b128(rx, ok ? b_lane[j] + (int)e.y : (int)OOB_OFFSET, 0, LD);
+            }
+        };
+        f32x4_t acc[AT][BT];
+#pragma unroll
+        for (int i = 0; i < AT; ++i)
+#pragma unroll
+            for (int j = 0; j < BT; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int d = 0; d < D; ++d) issue(rb[d]);
+        for (int s0 = 0; s0 < nsteps_pad; s0 += D) {
+#pragma unroll
+            for (int d = 0; d < D; ++d) {
+                const int step = min(s0 + d, nsteps - 1);  // steps past the end multiply zeros with the last weights
+                u32x4_t fa[AT];
+#pragma unroll
+                for (int i = 0; i < AT; ++i) fa[i] = wts[(step * AT + i) * 64 + lane];
+#pragma unroll
+                for (int j = 0; j < BT; ++j) {
+                    Frag fb;
+                    fb.u = make_uint4(rb[d][j].x, rb[d][j].y, rb[d][j].z, rb[d][j].w);
+#pragma unroll
+                    for (int i = 0; i < AT; ++i) {
+                        Frag f;
+                        f.u = make_uint4(fa[i].x, fa[i].y, fa[i].z, fa[i].w);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.v, fb.v, acc[i][j], 0, 0, 0);
+                    }
+                }
+                issue(rb[d]);
+            }
+        }
+        if (vec_k && !a.out_f32 && !sys_out) {
+            with_activation(a, [&](auto tag) {
+                constexpr int ACT = decltype(tag)::value;
+#pragma unroll
+                for (int i = 0; i < AT; ++i) {
+                    const int fbase = f0 + i * 16 + kg * 4;
+                    const float4 sc = *reinterpret_cast<const float4 *>(epi_lds + i * 16 + kg * 4);
+                    const float4 sh = *reinterpret_cast<const float4 *>(epi_lds + AT * 16 + i * 16 + kg * 4);
+#pragma unroll
+                    for (int j = 0; j < BT; ++j) {
+                        const int m = m0 + j * 16 + l16;
+                        const bool ok = fbase + 4 <= a.K && m < M;
+                        store_tile_bf16<ACT, ST>(ry, acc[i][j], sc, sh, resid[i][j], ok ? (m * a.K + fbase) * 2 : OOB_STORE);
+                    }
+                }
+            });
+        } else {
+            for (int i = 0; i < AT; ++i) {
+                const int fbase = f0 + i * 16 + kg * 4;
+                Epilogue e;
+                e.have = false, e.have_res = false, e.res = u32x2_t{0u, 0u};
+                for (int j = 0; j < BT; ++j)
+                    store_tile_coherent<LD, ST>(a, ry, rres, acc[i][j], fbase, m0 + j * 16 + l16, M, sys_out, e, false);
+            }
+        }
+    }
+}
+
 // ------------------------------------------------------------------ vector-ALU layers, grid-strided
 
 // Dense conv with a channel count that is not a multiple of 8 (the 3-channel stem): one thread per
@@ -1248,6 +1420,20 @@ __device__ __forceinline__ DevOp uniform_op(const DevOp &src) {
     return u.o;
 }
 
+// Tiled dense conv with the weights held in LDS (wk == -3): ft, pt as for wk == 0.
+template <int LD, int ST>
+__device__ __forceinline__ void run_ares(const DevOp &op, u32x4_t *lds, int rank, int nranks) {
+    const int key = op.ft * 4 + op.pt;
+    switch (key) {
+        case 2 * 4 + 1: conv_ares_units<2, 1, LD, ST>(op, lds, rank, nranks); break;
+        case 2 * 4 + 2: conv_ares_units<2, 2, LD, ST>(op, lds, rank, nranks); break;
+        case 4 * 4 + 1: conv_ares_units<4, 1, LD, ST>(op, lds, rank, nranks); break;
+        case 4 * 4 + 2: conv_ares_units<4, 2, LD, ST>(op, lds, rank, nranks); break;
+        case 6 * 4 + 1: conv_ares_units<6, 1, LD, ST>(op, lds, rank, nranks); break;
+        default: break;
+    }
+}
+
 // Tiled dense conv (wk == 0): ft = filter tiles, pt = pixel tiles per wave of a unit.
 template <int LD, int ST>
 __device__ __forceinline__ void run_tiled(const DevOp &op, u32x4_t *stage, int rank, int nranks) {
@@ -1279,6 +1465,8 @@ __device__ __forceinline__ void run_op(const DevOp &op, float *lds, int rank, in
                 conv_direct_units<ST>(op.conv, rank, nranks);
             else if (op.wk == 0)
                 run_tiled<LD, ST>(op, reinterpret_cast<u32x4_t *>(lds), rank, nranks);
+            else if (op.wk == -3)
+                run_ares<LD, ST>(op, reinterpret_cast<u32x4_t *>(lds), rank, nranks);
             else if (op.ft == 2 && op.pt == 4)
                 conv_units<2, 4, LD, ST, RES>(op, lds, rank, nranks, rv, tb);
             else if (op.ft == 1 && op.pt == 4)
@@ -1672,19 +1860,44 @@ void tile_dev_op(DevOp &op, int nwg, bool team) {
             for (int bt = 1; bt <= (at == 6 ? 1 : 2); ++bt) {  // 6 x 2 tiles per wave do not fit the register budget
                 const long n_f = (ftiles + at - 1) / at, n_p = (ptiles + STREAM_WAVES * bt - 1) / (STREAM_WAVES * bt);
                 const long iters = (n_f * n_p + nwg - 1) / nwg;
-                // fitted to timings of the layer shapes of a ResNet50-like SuperNet on one XCD: a step
-                // costs what its activation loads cost (the waves do not share those) plus a little per
-                // weight tile; a unit has a fixed cost for set-up, first loads and the epilogue of its
-                // at x bt tiles per wave.  In round trips of about 2300 clocks.
+                // fitted to timings of the layer shapes of a ResNet50-like SuperNet on one XCD (teams of
+                // 8 and of 32 workgroups): a step costs a fixed part plus a little per weight tile, more
+                // with two pixel tiles per wave; a unit has a fixed cost for set-up, first loads and the
+                // epilogue of its at x bt tiles per wave.  In microseconds.
                 const int round = TILE_KS * TILE_SETS;
                 const int steps_pad = (nsteps + round - 1) / round * round;
                 // LDS: two weight stages, the epilogue constants, one 16-byte entry per step
                 if (2 * TILE_KS * at * 1024 + at * 128 + steps_pad * 16 > RED_BYTES) continue;
-                const double step_cost = (60.0 + 300.0 * bt + 45.0 * at * (bt == 2 ? 1.3 : 1.0)) / 2300.0;
-                const double unit_cost = 2.5 + 0.5 * at * bt + steps_pad * step_cost;
+                const double step_cost = (0.10 + 0.03 * at) * (bt == 2 ? 1.7 : 1.0);
+                const double unit_cost = 1.2 + 0.3 * at * bt + steps_pad * step_cost;
                 const double cost = iters * unit_cost;
                 if (cost < best - 1e-9) best = cost, bft = at, bpt = bt, bwk = 0, tiled = true;
             }
+    }
+    // the same units with the filter group's weights held in LDS (wk = -3): short reductions only
+    bool ares = false;
+    if ((a.C & 7) == 0 && ptiles >= STREAM_WAVES) {
+        static const int shapes_r[5][2] = {{2, 1}, {2, 2}, {4, 1}, {4, 2}, {6, 1}};
+        const int steps_pad = (nsteps + ARES_D - 1) / ARES_D * ARES_D;
+        for (const auto &sh : shapes_r) {
+            const int at = sh[0], bt = sh[1];
+            if ((long)nsteps * at * 1024 + at * 128 + steps_pad * 16 > RED_BYTES) continue;
+            const long n_f = (ftiles + at - 1) / at, n_p = (ptiles + STREAM_WAVES * bt - 1) / (STREAM_WAVES * bt);
+            const long iters = (n_f * n_p + nwg - 1) / nwg;
+            // filter groups a workgroup meets on its way through units rank, rank + nwg, ...
+            const long reloads = std::min<long>(iters, n_p >= nwg ? (iters * nwg + n_p - 1) / n_p + 1 : iters);
+            (void)reloads;  // (the fitted unit cost includes the reloads the timed shapes had)
+            const double unit_cost = (1.6 + 0.18 * at * bt * (a.res ? 1.3 : 1.0) + steps_pad * bt * (0.06 + 0.012 * at)) *
+                                     (bt == 2 ? 1.3 : 1.0);
+            const double cost = iters * unit_cost;
+            if (cost < best - 1e-9) best = cost, bft = at, bpt = bt, bwk = -3, ares = true;
+        }
+    }
+    if (ares) {
+        op.ft = bft, op.pt = bpt, op.wk = -3;
+        op.n_p = (int)((ptiles + STREAM_WAVES * bpt - 1) / (STREAM_WAVES * bpt));
+        op.n_units = (int)(((ftiles + bft - 1) / bft) * op.n_p);
+        return;
     }
     if (tiled) {
         op.ft = bft, op.pt = bpt, op.wk = 0;

@@ -673,7 +673,7 @@ void refresh_lds_bytes(sushi_ctx *c, CachedPlan &cp) {
     cp.lds_bytes = 0;
     if (c->h_res_entries.empty()) return;
     for (const DevOp &op : cp.team_prog) {
-        if ((op.kind != OP_CONV && op.kind != OP_FC) || op.wk == 0 || op.ft > 2 || (long)op.conv.B * op.conv.P * op.conv.Q > 64 || op.layer < 0) continue;
+        if ((op.kind != OP_CONV && op.kind != OP_FC) || op.wk <= 0 || op.ft > 2 || (long)op.conv.B * op.conv.P * op.conv.Q > 64 || op.layer < 0) continue;
         if ((op.conv.C & 7) != 0) continue;
         const ResLayer &R = c->h_res_layers[op.layer];
         const int n_f = (op.conv.K + 15) / 16;
