@@ -82,16 +82,24 @@ struct ResLayer {
     int first_entry; // index of tile 0's entry in ResTable::entries
 };
 
+// The host writes a table into pinned HOST memory; a team copies it into device memory of its own
+// before it uses it (see TeamArgs::team_mem), with `layers` and `entries` pointing into that copy.
 struct ResTable {
     int n_layers, team_size;  // team size the owners were assigned for
-    const ResLayer *layers;   // DEVICE, one per SuperNet layer
-    const ResEntry *entries;  // DEVICE
+    int n_entries, pad;
+    const ResLayer *layers;   // one per SuperNet layer
+    const ResEntry *entries;
 };
+constexpr int RES_MAX_LAYERS = 256, RES_MAX_ENTRIES = 16384;
+static_assert(sizeof(ResTable) == 32 && sizeof(ResLayer) % 8 == 0 && sizeof(ResEntry) == 8, "tables are copied in 8-byte words");
+
+// Device memory of one team: the program of the query it is running and its copy of the residency table.
+constexpr int TEAM_PROG_MAX_OPS = 512;
 
 struct TeamPost {  // written by the host
     unsigned long long seq;  // the post's number (1, 2, ...)
     int cmd, n_ops;
-    const DevOp *prog;  // DEVICE; activation pointers are arena offsets + 1 (TEAM_INSTALL: a ResTable)
+    const DevOp *prog;  // pinned HOST; activation pointers are arena offsets + 1 (TEAM_INSTALL: a ResTable, pinned HOST)
     const void *input;  // DEVICE
     void *logits;       // DEVICE
     unsigned long long pad[3];
@@ -118,10 +126,14 @@ struct TeamArgs {
     long idle_ticks;           // 100 MHz ticks a leader waits for a post before its team leaves
     int teams_per_xcd;         // 1: the workgroups of an XCD form one team; 2, 4: that many teams, each a share of them
     int spin_limit;
-    const ResTable *table;     // DEVICE or null: SubGraph to install when the kernel starts
+    const ResTable *table;     // pinned HOST or null: SubGraph to install when the kernel starts
+    char *team_mem;            // DEVICE, MAX_TEAMS areas of TEAM_MEM_BYTES: [program][residency table]
     unsigned long long *trace;  // DEVICE or null: [MAX_TEAMS][TRACE_SLOTS] 100 MHz timestamps, one after each op
 };
 constexpr int TRACE_SLOTS = 256;
+constexpr long TEAM_TABLE_OFFSET = (long)TEAM_PROG_MAX_OPS * sizeof(DevOp);
+constexpr long TEAM_MEM_BYTES = TEAM_TABLE_OFFSET + 64 + (long)RES_MAX_LAYERS * sizeof(ResLayer) + (long)RES_MAX_ENTRIES * sizeof(ResEntry);
+static_assert(sizeof(DevOp) % 8 == 0, "programs are copied in 8-byte words");
 
 hipError_t launch_team_kernel(const TeamArgs &a, int nwg, hipStream_t s);
 // Sets the kernel's dynamic LDS limit; call once per device before the first launch.

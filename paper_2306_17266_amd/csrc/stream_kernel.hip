@@ -1598,6 +1598,46 @@ __device__ __forceinline__ bool team_barrier(const TeamArgs &ta, int team, unsig
     return *lds_flag != 0;
 }
 
+// Copies n 8-byte words from pinned host memory into device memory; the workgroups of a team share
+// the work.  The team kernel takes everything the host hands it this way (programs, residency
+// tables): it fills every compute unit, so a copy kernel of the runtime could not start beside it.
+__device__ __forceinline__ void team_fetch(unsigned long long *dst, const unsigned long long *src, int n, int rank,
+                                           int tsize) {
+    for (int i = rank * STREAM_THREADS + (int)threadIdx.x; i < n; i += tsize * STREAM_THREADS) dst[i] = ld_sys(src + i);
+}
+
+// Brings the residency table `src` (pinned host memory) into the team's device memory `mem`; the
+// workgroups of the team share the copy and meet at a barrier before anyone reads it.  Returns the
+// device copy through `out`: null when there is no table or it was made for another team size.
+// False: the barrier's wait ran out.
+__device__ __forceinline__ bool fetch_table(const TeamArgs &ta, const ResTable *src, char *mem, int team, int rank,
+                                            int tsize, unsigned long long &epoch, unsigned long long *hdr, int *lds_flag,
+                                            const ResTable **out) {
+    *out = nullptr;
+    if (!src) return true;
+    if (threadIdx.x < 4) hdr[threadIdx.x] = ld_sys(reinterpret_cast<const unsigned long long *>(src) + threadIdx.x);
+    __syncthreads();
+    const int n_layers = min((int)(hdr[0] & 0xFFFFFFFFull), RES_MAX_LAYERS), team_size = (int)(hdr[0] >> 32);
+    const int n_entries = min((int)(hdr[1] & 0xFFFFFFFFull), RES_MAX_ENTRIES);
+    const unsigned long long *layers = reinterpret_cast<const unsigned long long *>(hdr[2]);
+    const unsigned long long *entries = reinterpret_cast<const unsigned long long *>(hdr[3]);
+    __syncthreads();  // hdr may be written again
+    if (team_size != tsize) return true;
+    ResTable *dst = reinterpret_cast<ResTable *>(mem);
+    ResLayer *dst_layers = reinterpret_cast<ResLayer *>(mem + 64);
+    ResEntry *dst_entries = reinterpret_cast<ResEntry *>(mem + 64 + (long)RES_MAX_LAYERS * sizeof(ResLayer));
+    if (rank == 0 && threadIdx.x == 0) {
+        dst->n_layers = n_layers, dst->team_size = team_size, dst->n_entries = n_entries, dst->pad = 0;
+        dst->layers = dst_layers, dst->entries = dst_entries;
+    }
+    team_fetch(reinterpret_cast<unsigned long long *>(dst_layers), layers, n_layers * (int)(sizeof(ResLayer) / 8), rank, tsize);
+    team_fetch(reinterpret_cast<unsigned long long *>(dst_entries), entries, n_entries, rank, tsize);
+    epoch += 1;
+    if (!team_barrier(ta, team, tsize, epoch, lds_flag)) return false;  // (empties the L1: an older table sat at these addresses)
+    *out = dst;
+    return true;
+}
+
 // Copies the slabs this workgroup owns from the packed weights into its LDS store.
 __device__ void install_slabs(const ResTable *tab, int rank, char *store) {
     for (int l = 0; l < tab->n_layers; ++l) {
@@ -1619,7 +1659,10 @@ __device__ void install_slabs(const ResTable *tab, int rank, char *store) {
     __syncthreads();
 }
 
-__global__ __launch_bounds__(STREAM_THREADS, 3) void sushi_team_kernel(TeamArgs ta) {
+// Two waves per SIMD (the 256-register budget): with one workgroup per compute unit there are never
+// more, and under the smaller budget of three the op loops spill.  No other kernel fits beside this
+// one while it runs.
+__global__ __launch_bounds__(STREAM_THREADS, 2) void sushi_team_kernel(TeamArgs ta) {
     extern __shared__ __align__(16) char dyn_lds[];  // [RED_BYTES partial sums][RES_STORE_BYTES resident slabs]
     float *lds = reinterpret_cast<float *>(dyn_lds);
     char *store = dyn_lds + RED_BYTES;
@@ -1630,6 +1673,7 @@ __global__ __launch_bounds__(STREAM_THREADS, 3) void sushi_team_kernel(TeamArgs 
     __shared__ int flag;
     __shared__ int s_team, s_rank, s_size;
     __shared__ unsigned long long s_slot[5];
+    __shared__ unsigned long long s_hdr[4];
 
     // ---- team formation: which XCD am I on, how many of us are there
     if (threadIdx.x == 0) {
@@ -1670,14 +1714,14 @@ __global__ __launch_bounds__(STREAM_THREADS, 3) void sushi_team_kernel(TeamArgs 
     __syncthreads();
     if (!flag) return;
     const int team = s_team, rank = s_rank, tsize = s_size;
-    const ResTable *table = nullptr;
-    if (ta.table && ta.table->team_size == tsize) {
-        table = ta.table;
-        install_slabs(table, rank, store);
-    }
     char *arena = ta.arena + (long)team * ta.arena_bytes;
+    char *team_mem = ta.team_mem + (long)team * TEAM_MEM_BYTES;
+    DevOp *prog = reinterpret_cast<DevOp *>(team_mem);
     unsigned long long my_seq = ta.last_seq[team];
     unsigned long long epoch = 0;
+    const ResTable *table = nullptr;
+    if (!fetch_table(ta, ta.table, team_mem + TEAM_TABLE_OFFSET, team, rank, tsize, epoch, s_hdr, &flag, &table)) return;
+    if (table) install_slabs(table, rank, store);
     unsigned long long *go = &ta.sync[sy_go(team)];
     unsigned long long *slot = &ta.sync[sy_slot(team)];
     const unsigned long long *posted = &ta.host->posted[team * 8];
@@ -1730,11 +1774,12 @@ __global__ __launch_bounds__(STREAM_THREADS, 3) void sushi_team_kernel(TeamArgs 
         }
         __syncthreads();
         if (!flag) return;
-        const int cmd = (int)(s_slot[0] & 0xFFFFFFFFull), n_ops = (int)(s_slot[0] >> 32);
+        const int cmd = (int)(s_slot[0] & 0xFFFFFFFFull), n_ops = min((int)(s_slot[0] >> 32), TEAM_PROG_MAX_OPS);
         if (cmd == TEAM_INSTALL) {
             // a new cached SubGraph: refill the LDS store (a table made for another team size is ignored)
-            const ResTable *t = reinterpret_cast<const ResTable *>(s_slot[1]);
-            table = (t && t->team_size == tsize) ? t : nullptr;
+            if (!fetch_table(ta, reinterpret_cast<const ResTable *>(s_slot[1]), team_mem + TEAM_TABLE_OFFSET, team, rank,
+                             tsize, epoch, s_hdr, &flag, &table))
+                return;
             if (table) install_slabs(table, rank, store);
             epoch += 1;
             if (!team_barrier(ta, team, tsize, epoch, &flag)) return;
@@ -1744,10 +1789,14 @@ __global__ __launch_bounds__(STREAM_THREADS, 3) void sushi_team_kernel(TeamArgs 
             continue;
         }
         if (cmd != TEAM_RUN) return;
-        const DevOp *prog = reinterpret_cast<const DevOp *>(s_slot[1]);
         const void *input = reinterpret_cast<const void *>(s_slot[2]);
         void *logits = reinterpret_cast<void *>(s_slot[3]);
         const unsigned long long seq = s_slot[4];
+        // the query's program comes from the host's pinned pool into the team's memory
+        team_fetch(reinterpret_cast<unsigned long long *>(prog), reinterpret_cast<const unsigned long long *>(s_slot[1]),
+                   n_ops * (int)(sizeof(DevOp) / 8), rank, tsize);
+        epoch += 1;
+        if (!team_barrier<false>(ta, team, tsize, epoch, &flag)) return;
 
         // ---- run the query inside this XCD
         constexpr int OP_WORDS = (int)(sizeof(DevOp) / sizeof(int));
@@ -1755,7 +1804,11 @@ __global__ __launch_bounds__(STREAM_THREADS, 3) void sushi_team_kernel(TeamArgs 
         // lane k of every wave carries word k of the next op's descriptor, fetched one op ahead; the
         // words then move to scalar registers lane by lane, without a trip through LDS
         const int dlane = (int)(threadIdx.x & 63);
-        int next_word = (dlane < OP_WORDS && n_ops > 0) ? reinterpret_cast<const int *>(prog)[dlane] : 0;
+        // (loaded around the L1, which may hold the previous query's program)
+        auto prog_word = [&](int i, int k) {
+            return __hip_atomic_load(reinterpret_cast<const int *>(prog + i) + k, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        };
+        int next_word = (dlane < OP_WORDS && n_ops > 0) ? prog_word(0, dlane) : 0;
         for (int i = 0; i < n_ops; ++i) {
             DevOp uop;
             {
@@ -1767,7 +1820,7 @@ __global__ __launch_bounds__(STREAM_THREADS, 3) void sushi_team_kernel(TeamArgs 
                 for (int k = 0; k < OP_WORDS; ++k) u.w[k] = __builtin_amdgcn_readlane(next_word, k);
                 uop = u.o;
             }
-            if (dlane < OP_WORDS && i + 1 < n_ops) next_word = reinterpret_cast<const int *>(prog + i + 1)[dlane];
+            if (dlane < OP_WORDS && i + 1 < n_ops) next_word = prog_word(i + 1, dlane);
             {
                 auto fix = [&](const void *p) -> const void * {
                     return p ? static_cast<const void *>(arena + (reinterpret_cast<long>(p) - 1)) : nullptr;

@@ -46,7 +46,7 @@ struct CachedPlan {
     DevOp *d_prog = nullptr;
     int n_dev_ops = 0;
     // exec mode 3: the same program with arena-relative activation pointers, for the team kernel
-    DevOp *d_team_prog = nullptr;
+    DevOp *h_team_prog = nullptr;
     std::vector<DevOp> team_prog;     // host copy (tiling decides which ops can use resident slabs)
     uint64_t table_version = ~0ull;   // residency table the figure below was computed for
     uint64_t lds_bytes = 0;           // weight bytes this SubNet reads from resident LDS slabs
@@ -100,25 +100,22 @@ struct sushi_ctx {
     unsigned long long posted[MAX_TEAMS] = {};
     int next_team = 0;
     long idle_ticks = 200000;  // 2 ms at 100 MHz
-    // residency table of the cached SubGraph (host copies + device generations)
+    // residency table of the cached SubGraph (host copies + pinned generations the teams copy from)
     struct ResGen {
-        ResTable *d_table = nullptr;
-        ResLayer *d_layers = nullptr;
-        ResEntry *d_entries = nullptr;
+        ResTable *table = nullptr;  // pinned HOST: header, then RES_MAX_LAYERS layers, then RES_MAX_ENTRIES entries
+        ResLayer *layers = nullptr;
+        ResEntry *entries = nullptr;
         unsigned long long install_seq[MAX_TEAMS] = {};  // post that installs this generation on team t
     };
-    // Device memory the team mode needs while its kernel runs is carved from pools made up front and
-    // filled by asynchronous copies on a copy stream: hipMalloc / hipFree / hipMemcpy can wait for the
-    // whole device, i.e. for the persistent kernel to leave.
+    // While the team kernel runs it fills every compute unit, and hipMalloc / hipFree / hipMemcpy may
+    // wait for it to leave.  What the host hands to a running kernel (programs, residency tables)
+    // therefore lives in pinned host memory made up front; the teams copy it themselves.
     static constexpr size_t PROG_POOL_BYTES = 96u << 20;
-    static constexpr size_t RES_MAX_ENTRIES = 16384, RES_MAX_LAYERS = 256;
-    char *d_prog_pool = nullptr;
+    char *h_prog_pool = nullptr;  // pinned HOST
     size_t prog_pool_used = 0;
-    char *h_stage = nullptr;  // pinned staging for the copies
-    size_t h_stage_bytes = 0;
-    hipStream_t copy_stream = nullptr;
+    char *d_team_mem = nullptr;   // DEVICE, MAX_TEAMS x TEAM_MEM_BYTES
     static constexpr int N_RES_GENS = 4;
-    ResGen res_gens[N_RES_GENS];  // device tables stay alive while an install post may still name them
+    ResGen res_gens[N_RES_GENS];  // a generation stays untouched while an install post may still name it
     bool gen_valid[N_RES_GENS] = {};  // slot holds a table (false: nothing cached)
     int gen_cur = 0;
     std::vector<ResLayer> h_res_layers;
@@ -549,37 +546,25 @@ bool team_kernel_running(sushi_ctx *c);
 int launch_teams(sushi_ctx *c);
 
 void free_res_gen(sushi_ctx::ResGen &g) {
-    if (g.d_table) (void)hipFree(g.d_table);
-    if (g.d_layers) (void)hipFree(g.d_layers);
-    if (g.d_entries) (void)hipFree(g.d_entries);
+    if (g.table) (void)hipHostFree(g.table);
     g = sushi_ctx::ResGen();
-}
-
-// Host -> device copy that does not wait for other streams: through pinned staging on the copy stream.
-int upload_async(sushi_ctx *c, void *dst, const void *src, size_t bytes) {
-    if (bytes > c->h_stage_bytes) return fail(c, SUSHI_ENOMEM, "staging buffer too small");
-    std::memcpy(c->h_stage, src, bytes);
-    hipError_t e = hipMemcpyAsync(dst, c->h_stage, bytes, hipMemcpyHostToDevice, c->copy_stream);
-    if (e == hipSuccess) e = hipStreamSynchronize(c->copy_stream);
-    if (e != hipSuccess) return hip_fail(c, e, "hipMemcpyAsync");
-    return SUSHI_OK;
 }
 
 // Pools and table slots of the team mode; called once, before the kernel first runs.
 int make_team_pools(sushi_ctx *c) {
     hipError_t e;
-    c->h_stage_bytes = 1u << 20;
-    if ((e = hipHostMalloc(reinterpret_cast<void **>(&c->h_stage), c->h_stage_bytes, hipHostMallocDefault)) != hipSuccess)
-        return fail(c, SUSHI_ENOMEM, "hipHostMalloc(staging)");
-    if ((e = hipStreamCreateWithFlags(&c->copy_stream, hipStreamNonBlocking)) != hipSuccess)
-        return hip_fail(c, e, "hipStreamCreateWithFlags");
-    if ((e = hipMalloc(reinterpret_cast<void **>(&c->d_prog_pool), sushi_ctx::PROG_POOL_BYTES)) != hipSuccess)
-        return fail(c, SUSHI_ENOMEM, "hipMalloc(program pool)");
+    if ((e = hipHostMalloc(reinterpret_cast<void **>(&c->h_prog_pool), sushi_ctx::PROG_POOL_BYTES, hipHostMallocDefault)) != hipSuccess)
+        return fail(c, SUSHI_ENOMEM, "hipHostMalloc(program pool)");
+    if ((e = hipMalloc(reinterpret_cast<void **>(&c->d_team_mem), (size_t)TEAM_MEM_BYTES * MAX_TEAMS)) != hipSuccess)
+        return fail(c, SUSHI_ENOMEM, "hipMalloc(team memory)");
+    const size_t gen_bytes = 64 + RES_MAX_LAYERS * sizeof(ResLayer) + RES_MAX_ENTRIES * sizeof(ResEntry);
     for (auto &g : c->res_gens) {
-        if ((e = hipMalloc(reinterpret_cast<void **>(&g.d_layers), sushi_ctx::RES_MAX_LAYERS * sizeof(ResLayer))) != hipSuccess ||
-            (e = hipMalloc(reinterpret_cast<void **>(&g.d_entries), sushi_ctx::RES_MAX_ENTRIES * sizeof(ResEntry))) != hipSuccess ||
-            (e = hipMalloc(reinterpret_cast<void **>(&g.d_table), sizeof(ResTable))) != hipSuccess)
-            return fail(c, SUSHI_ENOMEM, "hipMalloc(residency tables)");
+        char *base = nullptr;
+        if ((e = hipHostMalloc(reinterpret_cast<void **>(&base), gen_bytes, hipHostMallocDefault)) != hipSuccess)
+            return fail(c, SUSHI_ENOMEM, "hipHostMalloc(residency tables)");
+        g.table = reinterpret_cast<ResTable *>(base);
+        g.layers = reinterpret_cast<ResLayer *>(base + 64);
+        g.entries = reinterpret_cast<ResEntry *>(base + 64 + RES_MAX_LAYERS * sizeof(ResLayer));
     }
     return SUSHI_OK;
 }
@@ -605,7 +590,7 @@ int build_res_table(sushi_ctx *c) {
         const int cg_res = std::min(g.C / 8, RES_STORE_BYTES / (taps * 256));
         if (cg_res < 1) continue;
         const long slab = (long)taps * cg_res * 256;
-        if (c->h_res_entries.size() + (size_t)(g.K + 15) / 16 > sushi_ctx::RES_MAX_ENTRIES) break;
+        if (c->h_res_entries.size() + (size_t)(g.K + 15) / 16 > (size_t)RES_MAX_ENTRIES) break;
         ResLayer &R = c->h_res_layers[l];
         R.w = static_cast<const char *>(c->d_weights) + L.pk_w * 2;
         R.Kpad = L.Kpad, R.CG = L.CG, R.taps = taps, R.cg_res = cg_res;
@@ -654,14 +639,14 @@ int upload_res_table(sushi_ctx *c) {
     c->gen_cur = slot;
     c->gen_valid[slot] = false;
     if (c->h_res_entries.empty()) return SUSHI_OK;
-    if (c->h_res_layers.size() > sushi_ctx::RES_MAX_LAYERS) return fail(c, SUSHI_ENOMEM, "too many layers for the table");
+    if (c->h_res_layers.size() > (size_t)RES_MAX_LAYERS) return fail(c, SUSHI_ENOMEM, "too many layers for the table");
+    if (c->h_res_entries.size() > (size_t)RES_MAX_ENTRIES) return fail(c, SUSHI_ENOMEM, "too many slabs for the table");
+    std::memcpy(g.layers, c->h_res_layers.data(), c->h_res_layers.size() * sizeof(ResLayer));
+    std::memcpy(g.entries, c->h_res_entries.data(), c->h_res_entries.size() * sizeof(ResEntry));
     ResTable t{};
-    t.n_layers = (int)c->h_res_layers.size(), t.team_size = c->team_size();
-    t.layers = g.d_layers, t.entries = g.d_entries;
-    int rc = upload_async(c, g.d_layers, c->h_res_layers.data(), c->h_res_layers.size() * sizeof(ResLayer));
-    if (rc == SUSHI_OK) rc = upload_async(c, g.d_entries, c->h_res_entries.data(), c->h_res_entries.size() * sizeof(ResEntry));
-    if (rc == SUSHI_OK) rc = upload_async(c, g.d_table, &t, sizeof(t));
-    if (rc) return rc;
+    t.n_layers = (int)c->h_res_layers.size(), t.team_size = c->team_size(), t.n_entries = (int)c->h_res_entries.size();
+    t.layers = g.layers, t.entries = g.entries;
+    *g.table = t;
     c->gen_valid[slot] = true;
     return SUSHI_OK;
 }
@@ -728,7 +713,8 @@ int launch_teams(sushi_ctx *c) {
     for (int t = 0; t < MAX_TEAMS; ++t) ta.last_seq[t] = c->th->done[t * 8];
     ta.idle_ticks = c->idle_ticks, ta.spin_limit = c->spin_limit;
     ta.trace = c->d_trace;
-    ta.table = c->gen_valid[c->gen_cur] ? c->res_gens[c->gen_cur].d_table : nullptr;
+    ta.table = c->gen_valid[c->gen_cur] ? c->res_gens[c->gen_cur].table : nullptr;
+    ta.team_mem = c->d_team_mem;
     close_team_timing(c);
     if (c->timing) {
         sushi_ctx::Pending &tp = c->team_pending;
@@ -794,8 +780,8 @@ int ensure_team_state(sushi_ctx *c, int batch) {
             return fail(c, SUSHI_ENOMEM, "hipMalloc(team arenas)");
         c->tarena_batch = batch;
         for (auto &kv : c->plans)
-            if (kv.second->d_team_prog) {
-                kv.second->d_team_prog = nullptr;
+            if (kv.second->h_team_prog) {
+                kv.second->h_team_prog = nullptr;
                 kv.second->team_prog.clear();
             }
     }
@@ -850,7 +836,7 @@ int post_team_query(sushi_ctx *c, CachedPlan &cp, const void *input_dev, void *l
     int rc = ensure_team_state(c, batch);
     if (rc) return rc;
     hipError_t e;
-    if (!cp.d_team_prog) {
+    if (!cp.h_team_prog) {
         std::vector<DevOp> prog;
         for (size_t i = 0; i < cp.launches.size(); ++i) {
             const Launch &L = cp.launches[i];
@@ -883,19 +869,20 @@ int post_team_query(sushi_ctx *c, CachedPlan &cp, const void *input_dev, void *l
             }
             prog.push_back(op);
         }
+        if (prog.size() > (size_t)TEAM_PROG_MAX_OPS) return fail(c, SUSHI_ESTATE, "the SubNet has too many ops for the team kernel");
         cp.team_prog = prog;
         cp.table_version = ~0ull;
         const size_t bytes = round_up(prog.size() * sizeof(DevOp), 256);
         if (c->prog_pool_used + bytes > sushi_ctx::PROG_POOL_BYTES) {
             // pool exhausted: forget every program (after the teams are done with them) and start over
             if ((rc = synchronize_teams(c)) != SUSHI_OK) return rc;
-            for (auto &kv : c->plans) kv.second->d_team_prog = nullptr;
+            for (auto &kv : c->plans) kv.second->h_team_prog = nullptr;
             c->prog_pool_used = 0;
         }
-        DevOp *dst = reinterpret_cast<DevOp *>(c->d_prog_pool + c->prog_pool_used);
-        if ((rc = upload_async(c, dst, prog.data(), prog.size() * sizeof(DevOp))) != SUSHI_OK) return rc;
+        DevOp *dst = reinterpret_cast<DevOp *>(c->h_prog_pool + c->prog_pool_used);
+        std::memcpy(dst, prog.data(), prog.size() * sizeof(DevOp));
         c->prog_pool_used += bytes;
-        cp.d_team_prog = dst;
+        cp.h_team_prog = dst;
         cp.n_dev_ops = (int)prog.size();
     }
     // the input must be complete before a team may read it
@@ -919,7 +906,7 @@ int post_team_query(sushi_ctx *c, CachedPlan &cp, const void *input_dev, void *l
     c->stats.weight_bytes_lds += cp.lds_bytes;
     c->stats.last_lds_bytes = cp.lds_bytes;
     TeamPost &p = *slot;
-    p.cmd = TEAM_RUN, p.n_ops = cp.n_dev_ops, p.prog = cp.d_team_prog, p.input = input_dev, p.logits = logits_dev;
+    p.cmd = TEAM_RUN, p.n_ops = cp.n_dev_ops, p.prog = cp.h_team_prog, p.input = input_dev, p.logits = logits_dev;
     publish_post(c, t, slot);
     return SUSHI_OK;
 }
@@ -937,7 +924,7 @@ int install_on_teams(sushi_ctx *c) {
         TeamPost *slot = nullptr;
         if ((rc = reserve_post(c, t, &slot)) != SUSHI_OK) return rc;
         TeamPost &p = *slot;
-        p.cmd = TEAM_INSTALL, p.n_ops = 0, p.prog = reinterpret_cast<const DevOp *>(c->gen_valid[c->gen_cur] ? c->res_gens[c->gen_cur].d_table : nullptr);
+        p.cmd = TEAM_INSTALL, p.n_ops = 0, p.prog = reinterpret_cast<const DevOp *>(c->gen_valid[c->gen_cur] ? c->res_gens[c->gen_cur].table : nullptr);
         p.input = nullptr, p.logits = nullptr;
         publish_post(c, t, slot);
         c->res_gens[c->gen_cur].install_seq[t] = c->posted[t];
@@ -1039,9 +1026,8 @@ void sushi_destroy(sushi_ctx *c) {
         (void)hipFree(c->d_tsync);
         if (c->d_trace) (void)hipFree(c->d_trace);
         for (auto &g : c->res_gens) free_res_gen(g);
-        if (c->d_prog_pool) (void)hipFree(c->d_prog_pool);
-        if (c->h_stage) (void)hipHostFree(c->h_stage);
-        if (c->copy_stream) (void)hipStreamDestroy(c->copy_stream);
+        if (c->h_prog_pool) (void)hipHostFree(c->h_prog_pool);
+        if (c->d_team_mem) (void)hipFree(c->d_team_mem);
         if (c->d_tarena) (void)hipFree(c->d_tarena);
         (void)hipHostFree(c->th);
     }
