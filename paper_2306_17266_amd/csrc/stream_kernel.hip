@@ -566,16 +566,18 @@ __device__ __forceinline__ void conv_units(const DevOp &op, float *red, int rank
 // straight from memory into the lane layout of the MFMA operand) is used AT times and the weight
 // tile of a reduction step (one tap, 32 channels: AT KiB) is fetched once per workgroup, by waves
 // 0 .. AT-1, and handed to the others through a two-stage LDS buffer.  The reduction advances in
-// intervals of TILE_KS steps with one workgroup barrier per interval; loads run TILE_SETS intervals
+// intervals of tile_ks(BT) steps with one workgroup barrier per interval; loads run TILE_SETS intervals
 // ahead of the MFMAs in register sets.
 // Activation cells outside the image, beyond the active channels or beyond the last pixel are
 // requested at an offset past the end of the buffer, which a buffer load answers with zeros.
-constexpr int TILE_KS = 2;    // reduction steps per interval
+// Reduction steps per interval: two, or one where a wave holds four pixel tiles (the register sets
+// of the activations are what limits the shape).
+__host__ __device__ constexpr int tile_ks(int bt) { return bt >= 4 ? 1 : 2; }
 constexpr int TILE_SETS = 3;  // register sets = intervals in flight
 
 template <int AT, int BT, int LD, int ST>
 __device__ __forceinline__ void conv_tile_units(const DevOp &op, u32x4_t *stage, int rank, int nranks) {
-    constexpr int KS = TILE_KS;
+    constexpr int KS = tile_ks(BT);
     static_assert(TILE_SETS == 3, "the interval loop is written out for three register sets");
     constexpr int OOB = 0x7FFFFFF0;
     const ConvArgs &a = op.conv;
@@ -591,7 +593,10 @@ __device__ __forceinline__ void conv_tile_units(const DevOp &op, u32x4_t *stage,
     const int csteps = (a.C + 31) >> 5;
     const int nsteps = taps * csteps;
     const bool sys_out = op.out_patch != 0;
-    const bool stager = wave < AT;
+    // every wave passes its weight cell on to LDS: the waves beyond AT hold the last tile once more and
+    // write it to the same place, so no wave branches around loads or stores (a branch there makes the
+    // compiler move loads into it, and the counted waits then fall back to waiting for every load)
+    const int st_cell = min(wave, AT - 1) * 64 + lane;
     // channel groups of the last 32-channel step of a tap: active ones (activations) and stored ones (weights)
     const int tail_active = ((a.C + 7) >> 3) - (csteps - 1) * 4;
     const int tail_stored = min(4, a.CG - (csteps - 1) * 4);
@@ -602,7 +607,7 @@ __device__ __forceinline__ void conv_tile_units(const DevOp &op, u32x4_t *stage,
     float *epi_lds = reinterpret_cast<float *>(stage + 2 * KS * AT * 64);
     u32x4_t *table = stage + 2 * KS * AT * 64 + AT * 8;
     const int nsteps_pad = (nsteps + 3 * KS - 1) / (3 * KS) * (3 * KS);
-    for (int st = tid; st < nsteps_pad; st += STREAM_THREADS) {
+    for (int st = tid; st < nsteps_pad + 3 * KS; st += STREAM_THREADS) {  // (the loads run one round past the end)
         const int tap = st / csteps, c = st - tap * csteps;
         const int dr = tap / a.R, ds = tap - dr * a.R;
         u32x4_t e = {0u, 0u, 0u, 0u};
@@ -692,10 +697,8 @@ __device__ __forceinline__ void conv_tile_units(const DevOp &op, u32x4_t *stage,
         auto run_interval = [&](int par, u32x4_t *a_free, const u32x4_t *a_next, u32x4_t (*b)[BT]) {
             const u32x4_t *cur = stage + par * (KS * AT * 64);
             u32x4_t *nxt = stage + (par ^ 1) * (KS * AT * 64);
-            if (stager) {
 #pragma unroll
-                for (int k = 0; k < KS; ++k) nxt[k * AT * 64 + tid] = a_next[k];
-            }
+            for (int k = 0; k < KS; ++k) nxt[k * AT * 64 + st_cell] = a_next[k];
 #pragma unroll
             for (int k = 0; k < KS; ++k) {
                 u32x4_t fa[AT];
@@ -724,10 +727,8 @@ __device__ __forceinline__ void conv_tile_units(const DevOp &op, u32x4_t *stage,
         for (int k = 0; k < KS; ++k) issue(ra1[k], rb1[k]);
 #pragma unroll
         for (int k = 0; k < KS; ++k) issue(ra2[k], rb2[k]);
-        if (stager) {
 #pragma unroll
-            for (int k = 0; k < KS; ++k) stage[k * AT * 64 + tid] = ra0[k];
-        }
+        for (int k = 0; k < KS; ++k) stage[k * AT * 64 + st_cell] = ra0[k];
         __syncthreads();
         // three intervals per round: the stage parity of a round's first interval alternates
         int par = 0;
@@ -784,10 +785,12 @@ __device__ __forceinline__ void conv_tile_units(const DevOp &op, u32x4_t *stage,
                 }
             });
         } else {
+#pragma unroll
             for (int i = 0; i < AT; ++i) {
                 const int fbase = f0 + i * 16 + kg * 4;
                 Epilogue e;
                 e.have = false, e.have_res = false, e.res = u32x2_t{0u, 0u};
+#pragma unroll
                 for (int j = 0; j < BT; ++j)
                     store_tile_coherent<LD, ST>(a, ry, rres, acc[i][j], fbase, m0 + j * 16 + l16, M, sys_out, e, false);
             }
@@ -1437,15 +1440,18 @@ __device__ __forceinline__ void run_ares(const DevOp &op, u32x4_t *lds, int rank
 // Tiled dense conv (wk == 0): ft = filter tiles, pt = pixel tiles per wave of a unit.
 template <int LD, int ST>
 __device__ __forceinline__ void run_tiled(const DevOp &op, u32x4_t *stage, int rank, int nranks) {
-    const int key = op.ft * 4 + op.pt;
+    const int key = op.ft * 8 + op.pt;
     switch (key) {
-        case 2 * 4 + 1: conv_tile_units<2, 1, LD, ST>(op, stage, rank, nranks); break;
-        case 2 * 4 + 2: conv_tile_units<2, 2, LD, ST>(op, stage, rank, nranks); break;
-        case 3 * 4 + 1: conv_tile_units<3, 1, LD, ST>(op, stage, rank, nranks); break;
-        case 3 * 4 + 2: conv_tile_units<3, 2, LD, ST>(op, stage, rank, nranks); break;
-        case 4 * 4 + 1: conv_tile_units<4, 1, LD, ST>(op, stage, rank, nranks); break;
-        case 4 * 4 + 2: conv_tile_units<4, 2, LD, ST>(op, stage, rank, nranks); break;
-        case 6 * 4 + 1: conv_tile_units<6, 1, LD, ST>(op, stage, rank, nranks); break;
+        case 2 * 8 + 1: conv_tile_units<2, 1, LD, ST>(op, stage, rank, nranks); break;
+        case 2 * 8 + 2: conv_tile_units<2, 2, LD, ST>(op, stage, rank, nranks); break;
+        case 3 * 8 + 1: conv_tile_units<3, 1, LD, ST>(op, stage, rank, nranks); break;
+        case 3 * 8 + 2: conv_tile_units<3, 2, LD, ST>(op, stage, rank, nranks); break;
+        case 3 * 8 + 4: conv_tile_units<3, 4, LD, ST>(op, stage, rank, nranks); break;
+        case 4 * 8 + 1: conv_tile_units<4, 1, LD, ST>(op, stage, rank, nranks); break;
+        case 4 * 8 + 2: conv_tile_units<4, 2, LD, ST>(op, stage, rank, nranks); break;
+        case 4 * 8 + 4: conv_tile_units<4, 4, LD, ST>(op, stage, rank, nranks); break;
+        case 6 * 8 + 1: conv_tile_units<6, 1, LD, ST>(op, stage, rank, nranks); break;
+        case 6 * 8 + 2: conv_tile_units<6, 2, LD, ST>(op, stage, rank, nranks); break;
         default: break;
     }
 }
@@ -1504,7 +1510,8 @@ __device__ __forceinline__ void run_op(const DevOp &op, float *lds, int rank, in
 
 // ------------------------------------------------------------------ the kernel
 
-__global__ __launch_bounds__(STREAM_THREADS, 3) void sushi_stream_kernel(StreamArgs sa) {
+// (two waves per SIMD: see sushi_team_kernel)
+__global__ __launch_bounds__(STREAM_THREADS, 2) void sushi_stream_kernel(StreamArgs sa) {
     __shared__ float lds[STREAM_WAVES * 4 * 256];  // conv partial sums; 64x8x9 floats for pooling fit too
     __shared__ int barrier_ok;
     __shared__ DevOp op;
@@ -1908,24 +1915,27 @@ void tile_dev_op(DevOp &op, int nwg, bool team) {
     // tiled units (wk = 0): at filter tiles x 8 waves x bt pixel tiles, the weight tile shared in LDS
     bool tiled = false;
     if ((a.C & 7) == 0 && ptiles >= STREAM_WAVES) {
-        static const int ats[4] = {2, 3, 4, 6};
-        for (const int at : ats)
-            for (int bt = 1; bt <= (at == 6 ? 1 : 2); ++bt) {  // 6 x 2 tiles per wave do not fit the register budget
+        static const int tile_shapes[10][2] = {{2, 1}, {2, 2}, {3, 1}, {3, 2}, {3, 4}, {4, 1}, {4, 2}, {4, 4}, {6, 1}, {6, 2}};
+        for (const auto &tsh : tile_shapes) {
+            const int at = tsh[0], bt = tsh[1];
+            if (true) {
                 const long n_f = (ftiles + at - 1) / at, n_p = (ptiles + STREAM_WAVES * bt - 1) / (STREAM_WAVES * bt);
                 const long iters = (n_f * n_p + nwg - 1) / nwg;
-                // fitted to timings of the layer shapes of a ResNet50-like SuperNet on one XCD (teams of
-                // 8 and of 32 workgroups): a step costs a fixed part plus a little per weight tile, more
-                // with two pixel tiles per wave; a unit has a fixed cost for set-up, first loads and the
-                // epilogue of its at x bt tiles per wave.  In microseconds.
-                const int round = TILE_KS * TILE_SETS;
+                // least-squares fit to timings of the layer shapes of a ResNet50-like SuperNet with every
+                // team of the chip busy (teams of 8, 16 and 32 workgroups): a step costs mostly what the
+                // activation tiles of a wave cost to load, a unit has a fixed cost for set-up and first
+                // loads plus the epilogue of its at x bt tiles per wave, the op a constant.  In microseconds.
+                const int round = tile_ks(bt) * TILE_SETS;
                 const int steps_pad = (nsteps + round - 1) / round * round;
-                // LDS: two weight stages, the epilogue constants, one 16-byte entry per step
-                if (2 * TILE_KS * at * 1024 + at * 128 + steps_pad * 16 > RED_BYTES) continue;
-                const double step_cost = (0.10 + 0.03 * at) * (bt == 2 ? 1.7 : 1.0);
-                const double unit_cost = 1.2 + 0.3 * at * bt + steps_pad * step_cost;
-                const double cost = iters * unit_cost;
+                // LDS: two weight stages, the epilogue constants, one 16-byte entry per step (the loads
+                // run one round past the last step)
+                if (2 * tile_ks(bt) * at * 1024 + at * 128 + (steps_pad + round) * 16 > RED_BYTES) continue;
+                const double step_cost = 0.0193 + 0.0222 * at + 0.1487 * bt - 0.0112 * at * bt;
+                const double unit_cost = 0.80 + at * bt * (a.res ? 0.48 : 0.384) + steps_pad * step_cost;
+                const double cost = 2.67 + iters * unit_cost;
                 if (cost < best - 1e-9) best = cost, bft = at, bpt = bt, bwk = 0, tiled = true;
             }
+        }
     }
     // the same units with the filter group's weights held in LDS (wk = -3): short reductions only
     bool ares = false;
@@ -1940,9 +1950,9 @@ void tile_dev_op(DevOp &op, int nwg, bool team) {
             // filter groups a workgroup meets on its way through units rank, rank + nwg, ...
             const long reloads = std::min<long>(iters, n_p >= nwg ? (iters * nwg + n_p - 1) / n_p + 1 : iters);
             (void)reloads;  // (the fitted unit cost includes the reloads the timed shapes had)
-            const double unit_cost = (1.6 + 0.18 * at * bt * (a.res ? 1.3 : 1.0) + steps_pad * bt * (0.06 + 0.012 * at)) *
-                                     (bt == 2 ? 1.3 : 1.0);
-            const double cost = iters * unit_cost;
+            const double step_cost = std::max(0.02, 0.0608 - 0.0463 * at + 0.1156 * bt + 0.0115 * at * bt);
+            const double unit_cost = 1.09 + at * bt * (a.res ? 0.494 : 0.307) + steps_pad * step_cost;
+            const double cost = 3.86 + iters * unit_cost;
             if (cost < best - 1e-9) best = cost, bft = at, bpt = bt, bwk = -3, ares = true;
         }
     }
