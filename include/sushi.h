@@ -229,7 +229,7 @@ int sushi_quiesce(sushi_ctx *ctx);
 
 /* Team-kernel diagnostics.  enable = 1: from the next start of the team kernel, each team leader
  * stamps a 100 MHz clock before the first op of a query and after the barrier of every op
- * (slot 0, then slot i+1 for op i; 256 slots per team, 32 teams).  Each call first waits for all
+ * (slot 0, then slot i+1 for op i; 256 slots per team, 64 teams).  Each call first waits for all
  * queries, stops the team kernel and, if out is not null, copies up to cap stamps to out (HOST). */
 int sushi_team_trace(sushi_ctx *ctx, int enable, uint64_t *out, int cap);
 
@@ -268,7 +268,7 @@ typedef enum {
                                    compute unit); only before the first query in mode 2 */
     SUSHI_OPT_TEAM_WGS_PER_CU = 5, /* workgroups of the team kernel per compute unit, 1 or 2 (default 2);
                                    only before the first query in mode 3 */
-    SUSHI_OPT_TEAMS_PER_XCD = 6, /* mode 3: teams the workgroups of one XCD are dealt to: 1 (default), 2 or 4.
+    SUSHI_OPT_TEAMS_PER_XCD = 6, /* mode 3: teams the workgroups of one XCD are dealt to: 1 (default), 2, 4 or 8.
                                    More, smaller teams serve more queries at a time, each more slowly:
                                    more queries per second, longer latency of a lone query.
                                    Only before the first query in mode 3 */

@@ -18,7 +18,7 @@ namespace sushi {
 constexpr int STREAM_THREADS = 512;  // 8 waves per workgroup
 constexpr int STREAM_WAVES = STREAM_THREADS / 64;
 constexpr int BARRIER_GROUP = 16;    // workgroups per first-level barrier group
-constexpr int SYNC_WORDS = 128 * 16;  // 64-bit words in the barrier area (128-byte spacing)
+constexpr int SYNC_WORDS = 256 * 16;  // 64-bit words in the barrier area (128-byte spacing)
 
 struct DevOp {
     int kind;      // OpKind (model.h)
@@ -54,7 +54,7 @@ struct StreamArgs {
 // pinned host memory; a team leader that finds no post for `idle_ticks` (or sees `stop`) makes its
 // team leave, so the kernel always ends by itself.
 constexpr int MAX_XCDS = 8;
-constexpr int MAX_TEAMS = 32;  // up to four teams per XCD
+constexpr int MAX_TEAMS = 64;  // up to eight teams per XCD
 enum TeamCmd { TEAM_RUN = 0, TEAM_STOP = 1, TEAM_INSTALL = 2 };
 
 // SubGraph residency inside the team kernel (the persistent buffer of the paper, Section 4.2.2, kept
@@ -124,7 +124,7 @@ struct TeamArgs {
     long arena_bytes;          // bytes per team arena
     unsigned long long last_seq[MAX_TEAMS];  // posts each team has already finished
     long idle_ticks;           // 100 MHz ticks a leader waits for a post before its team leaves
-    int teams_per_xcd;         // 1: the workgroups of an XCD form one team; 2, 4: that many teams, each a share of them
+    int teams_per_xcd;         // 1: the workgroups of an XCD form one team; 2, 4, 8: that many teams, each a share of them
     int spin_limit;
     const ResTable *table;     // pinned HOST or null: SubGraph to install when the kernel starts
     char *team_mem;            // DEVICE, MAX_TEAMS areas of TEAM_MEM_BYTES: [program][residency table]

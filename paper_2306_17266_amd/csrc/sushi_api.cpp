@@ -86,7 +86,7 @@ struct sushi_ctx {
     unsigned long long epoch_base = 0;
     int stream_wgs = 0, stream_wgs_override = 0;
     int team_wgs = 0, team_wgs_per_cu = 2;
-    int teams_per_xcd = 1;  // teams each XCD's workgroups are dealt to (1 or 2)
+    int teams_per_xcd = 1;  // teams each XCD's workgroups are dealt to (1, 2, 4 or 8)
     int team_size() const { return team_wgs / (MAX_XCDS * teams_per_xcd); }  // workgroups of a team, if they spread evenly
     int spin_limit = 400000;
     // exec mode 3 (team kernel): mailboxes in pinned host memory, per-team arenas, private stream
@@ -1326,7 +1326,7 @@ int sushi_set_option(sushi_ctx *c, int option, int64_t value) {
         c->team_wgs_per_cu = (int)value;
         return SUSHI_OK;
     }
-    if (option == SUSHI_OPT_TEAMS_PER_XCD && (value == 1 || value == 2 || value == 4) && value <= MAX_TEAMS / MAX_XCDS) {
+    if (option == SUSHI_OPT_TEAMS_PER_XCD && (value == 1 || value == 2 || value == 4 || value == 8) && value <= MAX_TEAMS / MAX_XCDS) {
         if (c->th) return fail(c, SUSHI_ESTATE, "set the number of teams before the first query");
         c->teams_per_xcd = (int)value;
         return SUSHI_OK;

@@ -93,9 +93,9 @@ def _team_ctx(arch, seed, teams_per_xcd=1):
     return ctx, wts
 
 
-@pytest.mark.parametrize("fam,teams", [("tiny", 1), ("resnet", 1), ("mbv3", 1), ("resnet", 2), ("mbv3", 4)])
+@pytest.mark.parametrize("fam,teams", [("tiny", 1), ("resnet", 1), ("mbv3", 1), ("resnet", 2), ("mbv3", 4), ("resnet", 8)])
 def test_team_kernel_small_supernets(fam, teams):
-    """Queries are posted without waiting (one in flight per team; 1, 2 or 4 teams per XCD), then all
+    """Queries are posted without waiting (one in flight per team; 1, 2, 4 or 8 teams per XCD), then all
     logits are checked against the oracle; a second pass must reproduce them bit for bit."""
     arch = {"tiny": A.tiny_arch, "resnet": A.small_resnet_arch, "mbv3": A.small_mbv3_arch}[fam]()
     ctx, wts = _team_ctx(arch, 3, teams)
@@ -119,7 +119,7 @@ def test_team_kernel_small_supernets(fam, teams):
     ctx.close()
 
 
-@pytest.mark.parametrize("fam,teams", [("resnet", 1), ("mbv3", 1), ("resnet", 4), ("mbv3", 2)])
+@pytest.mark.parametrize("fam,teams", [("resnet", 1), ("mbv3", 1), ("resnet", 4), ("mbv3", 2), ("resnet", 8), ("mbv3", 8)])
 def test_team_kernel_full_size_batch1(fam, teams):
     arch = A.resnet_arch() if fam == "resnet" else A.mbv3_arch()
     ctx, wts = _team_ctx(arch, 31, teams)
@@ -170,7 +170,7 @@ def test_team_kernel_restarts_after_idling_and_after_mode_switches():
     ctx.close()
 
 
-@pytest.mark.parametrize("fam,teams", [("resnet", 1), ("mbv3", 1), ("resnet", 4)])
+@pytest.mark.parametrize("fam,teams", [("resnet", 1), ("mbv3", 1), ("resnet", 4), ("resnet", 8)])
 def test_team_kernel_logits_do_not_depend_on_resident_slabs(fam, teams):
     """SubGraph residency in LDS is exact: the same logits, bit for bit, with nothing cached, with
     a SubGraph cached, after the cache changes in mid-stream and after it is emptied; and the
