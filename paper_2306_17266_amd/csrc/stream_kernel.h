@@ -55,7 +55,7 @@ struct StreamArgs {
 // team leave, so the kernel always ends by itself.
 constexpr int MAX_XCDS = 8;
 constexpr int MAX_TEAMS = 64;  // up to eight teams per XCD
-enum TeamCmd { TEAM_RUN = 0, TEAM_STOP = 1, TEAM_INSTALL = 2 };
+enum TeamCmd { TEAM_RUN = 0, TEAM_STOP = 1, TEAM_INSTALL = 2, TEAM_SKIP = 3 };  // TEAM_SKIP: kernel-internal, an install the next post replaces
 
 // SubGraph residency inside the team kernel (the persistent buffer of the paper, Section 4.2.2, kept
 // in LDS): every workgroup of a team owns RES_STORE_BYTES of LDS that survive from query to query.

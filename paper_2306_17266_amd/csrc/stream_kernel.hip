@@ -1748,6 +1748,12 @@ __global__ __launch_bounds__(STREAM_THREADS, 2) void sushi_team_kernel(TeamArgs 
                         post = &ta.host->post[team][seq % POST_RING];
                         cmd = (unsigned long long)__hip_atomic_load(&post->cmd, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
                         n_ops = (unsigned long long)__hip_atomic_load(&post->n_ops, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+                        // an install directly followed by another install is void: the team refills its LDS
+                        // once, for the newest SubGraph, when installs have piled up behind a query
+                        if (cmd == TEAM_INSTALL && ld_sys(posted) > seq &&
+                            __hip_atomic_load(&ta.host->post[team][(seq + 1) % POST_RING].cmd, __ATOMIC_RELAXED,
+                                              __HIP_MEMORY_SCOPE_SYSTEM) == TEAM_INSTALL)
+                            cmd = TEAM_SKIP;
                         break;
                     }
                     const long long last = std::max(t0, (long long)ld_agent(&ta.sync[SY_CLOCK]));
@@ -1782,6 +1788,12 @@ __global__ __launch_bounds__(STREAM_THREADS, 2) void sushi_team_kernel(TeamArgs 
         __syncthreads();
         if (!flag) return;
         const int cmd = (int)(s_slot[0] & 0xFFFFFFFFull), n_ops = min((int)(s_slot[0] >> 32), TEAM_PROG_MAX_OPS);
+        if (cmd == TEAM_SKIP) {
+            if (rank == 0 && threadIdx.x == 0)
+                __hip_atomic_store(&ta.host->done[team * 8], s_slot[4], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+            my_seq = s_slot[4];
+            continue;
+        }
         if (cmd == TEAM_INSTALL) {
             // a new cached SubGraph: refill the LDS store (a table made for another team size is ignored)
             if (!fetch_table(ta, reinterpret_cast<const ResTable *>(s_slot[1]), team_mem + TEAM_TABLE_OFFSET, team, rank,
