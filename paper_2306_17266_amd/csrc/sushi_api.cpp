@@ -885,9 +885,13 @@ int post_team_query(sushi_ctx *c, CachedPlan &cp, const void *input_dev, void *l
         cp.h_team_prog = dst;
         cp.n_dev_ops = (int)prog.size();
     }
-    // the input must be complete before a team may read it
-    if (hipStreamQuery(c->stream) != hipSuccess && (e = hipStreamSynchronize(c->stream)) != hipSuccess)
-        return hip_fail(c, e, "hipStreamSynchronize");
+    // The input must be complete before a team may read it.  Work still pending on the caller's stream may be
+    // waiting for a compute unit, and the team kernel gives none up while it runs: make it leave first (the
+    // teams finish what is in their mailboxes) instead of letting the stream wait for it to idle out.
+    if (hipStreamQuery(c->stream) == hipErrorNotReady) {
+        if (team_kernel_running(c) && (rc = stop_team_kernel(c)) != SUSHI_OK) return rc;
+        if ((e = hipStreamSynchronize(c->stream)) != hipSuccess) return hip_fail(c, e, "hipStreamSynchronize");
+    }
     if (!c->team_launched && (rc = launch_teams(c)) != SUSHI_OK) return rc;
     int t = -1;
     for (int k = 0; k < MAX_TEAMS; ++k) {

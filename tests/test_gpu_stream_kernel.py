@@ -137,6 +137,30 @@ def test_team_kernel_full_size_batch1(fam, teams):
     ctx.close()
 
 
+def test_team_kernel_gives_way_to_the_callers_kernels():
+    """The team kernel fills every compute unit.  An input that a kernel of the caller is still producing
+    when the query is posted must be waited for without waiting for the team kernel to idle out: it
+    leaves, the caller's kernel runs, it starts again."""
+    import time
+    arch = A.small_resnet_arch()
+    ctx, wts = _team_ctx(arch, 5, 4)
+    st = Stream(17)
+    cfgs = [streams.uniform_cfg(arch, st, 64) for _ in range(6)]
+    xs_np = [T.make_input(5, t, 1, 64, 3, True) for t in range(len(cfgs))]
+    host = [torch.from_numpy(x).to(torch.bfloat16) for x in xs_np]
+    outs = [torch.full((1, arch.n_classes), float("nan"), device="cuda") for _ in cfgs]
+    torch.cuda.synchronize()
+    t0 = time.time()
+    for cfg, h, o in zip(cfgs, host, outs):
+        x = (h.cuda() * 1).contiguous()      # upload and a kernel on the current stream, not waited for
+        ctx.sushi_infer(cfg, x, o)
+    ctx.sushi_synchronize()
+    assert time.time() - t0 < 5.0
+    for t, cfg in enumerate(cfgs):
+        assert rel_l2(outs[t].cpu().numpy(), oracle_logits(arch, wts, cfg, xs_np[t])) <= 1e-2, (t, cfg)
+    ctx.close()
+
+
 def test_team_kernel_restarts_after_idling_and_after_mode_switches():
     import time
 
