@@ -23,7 +23,7 @@ constexpr int SYNC_WORDS = 256 * 16;  // 64-bit words in the barrier area (128-b
 struct DevOp {
     int kind;      // OpKind (model.h)
     int pt, wk;    // dense conv: pixel tiles per unit (1, 2, 4) and waves sharing one unit (1, 2, 4, 8);
-                   // wk = 0: tiled units (ft x pt tiles per wave); wk = -1: stem units (pt output rows per band); wk = -2: depthwise through LDS; wk = -3: tiled units with the weights held in LDS
+                   // wk = 0: tiled units (ft x pt tiles per wave); wk = -1: stem units (pt output rows per band); wk = -2: depthwise through LDS; wk = -3: tiled units with the weights held in LDS; wk = -4: depthwise straight from memory, neighbouring outputs per thread
     int n_units;   // dense conv: filter groups x pixel groups
     int n_p;       // dense conv: pixel groups
     int in_patch;  // input pointer is the caller's input buffer

@@ -1210,45 +1210,60 @@ __device__ __forceinline__ void dwconv_units(const ConvArgs &a, int rank, int nr
     }
 }
 
-// Depthwise k x k through LDS (wk == -2): a unit is op.ft channel groups (of 8 channels) x a band of
-// op.pt output rows of one image.  The workgroup copies the input rows the band needs (zeros outside
-// the image) and the taps' weights into LDS; a thread then computes up to DW_ITEMS outputs of 8
-// channels, converting a tap's weights once for all of them.
-constexpr int DW_ITEMS = 4;
-template <int LD, int ST>
+// Depthwise k x k through LDS (wk == -2), k in {3, 5, 7}, stride 1 or 2: a unit is op.ft channel groups
+// (of 8 channels) x a band of op.pt output rows of one image.  The workgroup copies the input rows the
+// band needs into LDS, in rows padded with zero cells left and right (and zero rows outside the image),
+// so the inner loop has no bounds checks, and the taps' weights as fp32 in row-major tap order.  A
+// thread computes DW_ITEMS neighbouring outputs of one row and channel group: for every tap row it
+// reads the row's k weights and the (DW_ITEMS - 1) * stride + k input cells the outputs share, each
+// cell once.  (An odd DW_ITEMS also keeps the lanes' 16-byte LDS reads on different banks at stride 1.)
+constexpr int DW_ITEMS = 5;
+__host__ __device__ constexpr int dw_padded_width(int W, int Q, int R, int stride) {
+    const int need = (((Q + DW_ITEMS - 1) / DW_ITEMS) * DW_ITEMS - 1) * stride + R;  // last block's last column
+    return need > W + (R - 1) ? need : W + (R - 1);
+}
+template <int R, int S, int LD, int ST>
 __device__ __forceinline__ void dw_tiled_units(const DevOp &op, float *lds, int rank, int nranks) {
+    constexpr int HALF = (R - 1) / 2, NT = R * R, IT = DW_ITEMS, NCOL = (IT - 1) * S + R;
     const ConvArgs &a = op.conv;
     const int tid = threadIdx.x;
     const int CB = op.ft, rows_out = op.pt;
     const int cgs = a.K >> 3, cblocks = (cgs + CB - 1) / CB, bands = (a.P + rows_out - 1) / rows_out;
-    const int ntaps = a.R * a.R, half = (a.R - 1) >> 1;
+    const int qblocks = (a.Q + IT - 1) / IT;
+    const int Wp = dw_padded_width(a.W, a.Q, R, S);
     const __amdgpu_buffer_rsrc_t rx = make_rsrc(a.x, (long)a.B * a.H * a.W * a.C * 2);
     const __amdgpu_buffer_rsrc_t ry = make_rsrc(a.y, (long)a.B * a.P * a.Q * a.K * 2);
     const __amdgpu_buffer_rsrc_t rw = make_rsrc(a.w, (long)a.Rmax * a.Rmax * a.Kpad * 2);
-    u32x4_t *w_lds = reinterpret_cast<u32x4_t *>(lds);  // [tap][CB]
-    u32x4_t *x_lds = w_lds + ntaps * CB;                // [row][column][CB]
-    const int cb = tid % CB;                            // STREAM_THREADS is a multiple of CB: fixed per thread
+    float4 *w_lds = reinterpret_cast<float4 *>(lds);                   // [tap row][tap column][CB][2]
+    u32x4_t *x_lds = reinterpret_cast<u32x4_t *>(w_lds + NT * CB * 2);  // [row][padded column][CB]
+    const int cb = tid % CB;  // STREAM_THREADS is a multiple of CB: fixed per thread
     for (int unit = rank; unit < op.n_units; unit += nranks) {
         const int band = unit % bands, rest = unit / bands;
         const int cblock = rest % cblocks, n = rest / cblocks;
         const int cg0 = cblock * CB;
         const int p0 = band * rows_out, prows = min(rows_out, a.P - p0);
-        const int h_first = p0 * a.stride - half, rows_in = (prows - 1) * a.stride + a.R;
+        const int h_first = p0 * S - HALF, rows_in = (prows - 1) * S + R;
         __syncthreads();
-        for (int i = tid; i < ntaps * CB; i += STREAM_THREADS) {
-            const int t = i / CB, c = cg0 + (i - t * CB);
-            w_lds[i] = __builtin_amdgcn_raw_buffer_load_b128(rw, c < cgs ? (t * a.Kpad + c * 8) * 2 : (int)OOB_OFFSET, 0, 0);
+        // taps are stored centre first, ring by ring; LDS takes them row by row
+        for (int i = tid; i < NT * CB; i += STREAM_THREADS) {
+            const int t = i / CB, ci = i - t * CB, c = cg0 + ci;
+            const u32x4_t wq = __builtin_amdgcn_raw_buffer_load_b128(rw, c < cgs ? (t * a.Kpad + c * 8) * 2 : (int)OOB_OFFSET, 0, 0);
+            float wv[8];
+            unpack8(make_uint4(wq.x, wq.y, wq.z, wq.w), wv);
+            const int slot = (((c_dw_dr[t] + HALF) * R + c_dw_ds[t] + HALF) * CB + ci) * 2;
+            w_lds[slot] = make_float4(wv[0], wv[1], wv[2], wv[3]);
+            w_lds[slot + 1] = make_float4(wv[4], wv[5], wv[6], wv[7]);
         }
-        const int cells = rows_in * a.W * CB;
+        const int cells = rows_in * Wp * CB;
         for (int base = tid; base < cells; base += 4 * STREAM_THREADS) {
             u32x4_t v[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const int i = base + u * STREAM_THREADS;
                 const int pix = i / CB, c = cg0 + (i - pix * CB);
-                const int r = pix / a.W, col = pix - r * a.W;
+                const int r = pix / Wp, col = pix - r * Wp - HALF;
                 const int h = h_first + r;
-                const bool ok = i < cells && h >= 0 && h < a.H && c < cgs;
+                const bool ok = i < cells && h >= 0 && h < a.H && col >= 0 && col < a.W && c < cgs;
                 v[u] = __builtin_amdgcn_raw_buffer_load_b128(rx, ok ? (((n * a.H + h) * a.W + col) * a.C + c * 8) * 2 : (int)OOB_OFFSET, 0, LD);
             }
 #pragma unroll
@@ -1258,7 +1273,7 @@ __device__ __forceinline__ void dw_tiled_units(const DevOp &op, float *lds, int 
             }
         }
         __syncthreads();
-        const int items = prows * a.Q * CB;
+        const int items = prows * qblocks * CB;
         const bool cvalid = cg0 + cb < cgs;
         const int c = (cg0 + cb) * 8;
         float sc[8], sh[8];
@@ -1266,48 +1281,140 @@ __device__ __forceinline__ void dw_tiled_units(const DevOp &op, float *lds, int 
             load8(a.scale + c, sc);
             load8(a.shift + c, sh);
         }
-        for (int first = tid; first < items; first += DW_ITEMS * STREAM_THREADS) {
-            // this thread's outputs: items first, first + 512, ... (same channel group)
-            int corner[DW_ITEMS], w0[DW_ITEMS], m_out[DW_ITEMS];
-            bool live[DW_ITEMS];
-            float acc[DW_ITEMS][8];
+        for (int it = tid; it < items; it += STREAM_THREADS) {
+            const int blk = it / CB;  // (it % CB == cb)
+            const int pr = blk / qblocks, qb = blk - pr * qblocks;
+            float acc[IT][8];
 #pragma unroll
-            for (int k = 0; k < DW_ITEMS; ++k) {
-                const int it = first + k * STREAM_THREADS;
-                live[k] = it < items && cvalid;
-                const int pix = live[k] ? it / CB : 0;
-                const int pr = pix / a.Q, q = pix - pr * a.Q;
-                w0[k] = q * a.stride;
-                corner[k] = ((pr * a.stride + half) * a.W + w0[k]) * CB + cb;
-                m_out[k] = (n * a.P + p0 + pr) * a.Q + q;
+            for (int k = 0; k < IT; ++k)
 #pragma unroll
                 for (int j = 0; j < 8; ++j) acc[k][j] = 0.f;
+            const u32x4_t *xrow = x_lds + ((pr * S) * Wp + qb * IT * S) * CB + cb;
+            const float4 *wrow = w_lds + cb * 2;
+#pragma unroll 1
+            for (int dr = 0; dr < R; ++dr) {
+                float wv[R][8];
+#pragma unroll
+                for (int ds = 0; ds < R; ++ds) {
+                    const float4 lo = wrow[ds * CB * 2], hi = wrow[ds * CB * 2 + 1];
+                    wv[ds][0] = lo.x, wv[ds][1] = lo.y, wv[ds][2] = lo.z, wv[ds][3] = lo.w;
+                    wv[ds][4] = hi.x, wv[ds][5] = hi.y, wv[ds][6] = hi.z, wv[ds][7] = hi.w;
+                }
+#pragma unroll
+                for (int col = 0; col < NCOL; ++col) {
+                    const u32x4_t xq = xrow[col * CB];
+                    float xv[8];
+                    unpack8(make_uint4(xq.x, xq.y, xq.z, xq.w), xv);
+#pragma unroll
+                    for (int k = 0; k < IT; ++k) {
+                        constexpr int dummy = 0;
+                        (void)dummy;
+                        const int ds = col - k * S;  // (a constant once the loops are unrolled)
+                        if (ds >= 0 && ds < R) {
+#pragma unroll
+                            for (int j = 0; j < 8; ++j) acc[k][j] = fmaf(wv[ds][j], xv[j], acc[k][j]);
+                        }
+                    }
+                }
+                xrow += Wp * CB;
+                wrow += R * CB * 2;
             }
-            for (int t = 0; t < ntaps; ++t) {
-                const int dr = c_dw_dr[t], ds = c_dw_ds[t];
-                float wv[8];
-                const u32x4_t wq = w_lds[t * CB + cb];
-                unpack8(make_uint4(wq.x, wq.y, wq.z, wq.w), wv);
-                const int step = (dr * a.W + ds) * CB;
+            if (cvalid) {
 #pragma unroll
-                for (int k = 0; k < DW_ITEMS; ++k) {
-                    const int col = w0[k] + ds;
-                    if (live[k] && col >= 0 && col < a.W) {
-                        float xv[8];
-                        const u32x4_t xq = x_lds[corner[k] + step];
-                        unpack8(make_uint4(xq.x, xq.y, xq.z, xq.w), xv);
+                for (int k = 0; k < IT; ++k) {
+                    const int q = qb * IT + k;
 #pragma unroll
-                        for (int j = 0; j < 8; ++j) acc[k][j] = fmaf(wv[j], xv[j], acc[k][j]);
+                    for (int j = 0; j < 8; ++j) acc[k][j] = activate(acc[k][j] * sc[j] + sh[j], a.act, 0);
+                    const int m = (n * a.P + p0 + pr) * a.Q + q;
+                    act_st16<ST>(ry, q < a.Q ? (m * a.K + c) * 2 : (int)OOB_OFFSET, pack8(acc[k]));
+                }
+            }
+        }
+    }
+}
+
+// Position of the tap at offset (dr, ds) from the centre in the ring order of the stored taps.
+__device__ __forceinline__ int dw_tap_index(int dr, int ds) {
+    const int r = max(abs(dr), abs(ds));
+    if (r <= 1) return (dr + 1) * 3 + ds + 1;
+    const int base = (2 * r - 1) * (2 * r - 1);
+    if (dr == -r) return base + ds + r;
+    if (dr == r) return base + (2 * r + 1) + 2 * (2 * r - 1) + ds + r;
+    return base + (2 * r + 1) + (dr + r - 1) * 2 + (ds == r ? 1 : 0);
+}
+
+// Depthwise k x k straight from memory (wk == -4), for layers whose bands in LDS would be too small to
+// keep a workgroup's threads busy (wide maps, stride 2): the same items as in dw_tiled_units (DW_ITEMS
+// neighbouring outputs of one row and channel group per thread, every input cell of a tap row loaded
+// once for all of them), spread over all threads of the team; no LDS, no barriers.  Cells outside the
+// image are requested past the end of the buffer and arrive as zeros.
+template <int R, int S, int LD, int ST>
+__device__ __forceinline__ void dw_direct_units(const DevOp &op, int rank, int nranks) {
+    constexpr int HALF = (R - 1) / 2, IT = DW_ITEMS, NCOL = (IT - 1) * S + R;
+    const ConvArgs &a = op.conv;
+    const int cgs = a.K >> 3, qblocks = (a.Q + IT - 1) / IT;
+    const long items = (long)a.B * a.P * qblocks * cgs;
+    const __amdgpu_buffer_rsrc_t rx = make_rsrc(a.x, (long)a.B * a.H * a.W * a.C * 2);
+    const __amdgpu_buffer_rsrc_t ry = make_rsrc(a.y, (long)a.B * a.P * a.Q * a.K * 2);
+    const __amdgpu_buffer_rsrc_t rw = make_rsrc(a.w, (long)a.Rmax * a.Rmax * a.Kpad * 2);
+    for (long it = (long)rank * STREAM_THREADS + threadIdx.x; it < items; it += (long)nranks * STREAM_THREADS) {
+        const int cg = (int)(it % cgs);
+        const long blk = it / cgs;
+        const int qb = (int)(blk % qblocks);
+        const long rowi = blk / qblocks;
+        const int pr = (int)(rowi % a.P), n = (int)(rowi / a.P);
+        const int c = cg * 8;
+        const int col0 = qb * IT * S - HALF;
+        float acc[IT][8];
+#pragma unroll
+        for (int k = 0; k < IT; ++k)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[k][j] = 0.f;
+        int col_off[NCOL];  // byte offset of the row's cells from the row start; past the end outside the image
+#pragma unroll
+        for (int cc = 0; cc < NCOL; ++cc) {
+            const int col = col0 + cc;
+            col_off[cc] = col >= 0 && col < a.W ? (col * a.C + c) * 2 : -1;
+        }
+#pragma unroll 1
+        for (int dr = 0; dr < R; ++dr) {
+            const int h = pr * S - HALF + dr;
+            const bool row_ok = h >= 0 && h < a.H;
+            const int row_base = ((n * a.H + h) * a.W) * a.C * 2;
+            u32x4_t wq[R], xq[NCOL];
+#pragma unroll
+            for (int ds = 0; ds < R; ++ds)
+                wq[ds] = __builtin_amdgcn_raw_buffer_load_b128(rw, (dw_tap_index(dr - HALF, ds - HALF) * a.Kpad + c) * 2, 0, 0);
+#pragma unroll
+            for (int cc = 0; cc < NCOL; ++cc)
+                xq[cc] = __builtin_amdgcn_raw_buffer_load_b128(rx, row_ok && col_off[cc] >= 0 ? row_base + col_off[cc] : (int)OOB_OFFSET, 0, LD);
+            float wv[R][8];
+#pragma unroll
+            for (int ds = 0; ds < R; ++ds) unpack8(make_uint4(wq[ds].x, wq[ds].y, wq[ds].z, wq[ds].w), wv[ds]);
+#pragma unroll
+            for (int cc = 0; cc < NCOL; ++cc) {
+                float xv[8];
+                unpack8(make_uint4(xq[cc].x, xq[cc].y, xq[cc].z, xq[cc].w), xv);
+#pragma unroll
+                for (int k = 0; k < IT; ++k) {
+                    const int ds = cc - k * S;  // (a constant once the loops are unrolled)
+                    if (ds >= 0 && ds < R) {
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) acc[k][j] = fmaf(wv[ds][j], xv[j], acc[k][j]);
                     }
                 }
             }
+        }
+        float sc[8], sh[8];
+        load8(a.scale + c, sc);
+        load8(a.shift + c, sh);
 #pragma unroll
-            for (int k = 0; k < DW_ITEMS; ++k)
-                if (live[k]) {
+        for (int k = 0; k < IT; ++k) {
+            const int q = qb * IT + k;
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) acc[k][j] = activate(acc[k][j] * sc[j] + sh[j], a.act, 0);
-                    act_st16<ST>(ry, (m_out[k] * a.K + c) * 2, pack8(acc[k]));
-                }
+            for (int j = 0; j < 8; ++j) acc[k][j] = activate(acc[k][j] * sc[j] + sh[j], a.act, 0);
+            const long m = ((long)n * a.P + pr) * a.Q + q;
+            act_st16<ST>(ry, q < a.Q ? (int)((m * a.K + c) * 2) : (int)OOB_OFFSET, pack8(acc[k]));
         }
     }
 }
@@ -1489,10 +1596,31 @@ __device__ __forceinline__ void run_op(const DevOp &op, float *lds, int rank, in
                 conv_units<1, 1, LD, ST, RES>(op, lds, rank, nranks, rv, tb);
             break;
         case OP_DW:
-            if (op.wk == -2)
-                dw_tiled_units<LD, ST>(op, lds, rank, nranks);
-            else
+            if (op.wk == -2) {
+                const int key = op.conv.R * 4 + op.conv.stride;
+                switch (key) {
+                    case 3 * 4 + 1: dw_tiled_units<3, 1, LD, ST>(op, lds, rank, nranks); break;
+                    case 3 * 4 + 2: dw_tiled_units<3, 2, LD, ST>(op, lds, rank, nranks); break;
+                    case 5 * 4 + 1: dw_tiled_units<5, 1, LD, ST>(op, lds, rank, nranks); break;
+                    case 5 * 4 + 2: dw_tiled_units<5, 2, LD, ST>(op, lds, rank, nranks); break;
+                    case 7 * 4 + 1: dw_tiled_units<7, 1, LD, ST>(op, lds, rank, nranks); break;
+                    case 7 * 4 + 2: dw_tiled_units<7, 2, LD, ST>(op, lds, rank, nranks); break;
+                    default: break;
+                }
+            } else if (op.wk == -4) {
+                const int key = op.conv.R * 4 + op.conv.stride;
+                switch (key) {
+                    case 3 * 4 + 1: dw_direct_units<3, 1, LD, ST>(op, rank, nranks); break;
+                    case 3 * 4 + 2: dw_direct_units<3, 2, LD, ST>(op, rank, nranks); break;
+                    case 5 * 4 + 1: dw_direct_units<5, 1, LD, ST>(op, rank, nranks); break;
+                    case 5 * 4 + 2: dw_direct_units<5, 2, LD, ST>(op, rank, nranks); break;
+                    case 7 * 4 + 1: dw_direct_units<7, 1, LD, ST>(op, rank, nranks); break;
+                    case 7 * 4 + 2: dw_direct_units<7, 2, LD, ST>(op, rank, nranks); break;
+                    default: break;
+                }
+            } else {
                 dwconv_units<LD, ST>(op.conv, rank, nranks);
+            }
             break;
         case OP_MAXPOOL:
             maxpool_units<LD, ST>(op.pool, rank, nranks);
@@ -1988,10 +2116,16 @@ void tile_dev_op(DevOp &op, int nwg, bool team) {
 bool tile_dw_op(DevOp &op, int nwg) {
     const ConvArgs &a = op.conv;
     const int cgs = a.K / 8;
-    if ((a.K & 7) != 0 || (a.R & 1) == 0 || a.C != a.K) return false;
-    auto lds_bytes = [&](int rows, int cb) { return ((long)((rows - 1) * a.stride + a.R) * a.W + a.R * a.R) * cb * 16; };
-    // time ~ rounds x (outputs per unit, in passes of the workgroup's threads, plus the input rows to
-    // copy and a fixed part)
+    if ((a.K & 7) != 0 || a.C != a.K) return false;
+    if ((a.R != 3 && a.R != 5 && a.R != 7) || (a.stride != 1 && a.stride != 2)) return false;
+    const int Wp = dw_padded_width(a.W, a.Q, a.R, a.stride);
+    const int qblocks = (a.Q + DW_ITEMS - 1) / DW_ITEMS;
+    const int ncol = (DW_ITEMS - 1) * a.stride + a.R;
+    auto lds_bytes = [&](int rows, int cb) {
+        return (long)a.R * a.R * cb * 32 + (long)((rows - 1) * a.stride + a.R) * Wp * cb * 16;
+    };
+    // clocks ~ rounds x (items per thread x instructions of an item, two waves per SIMD taking turns,
+    // plus the batches of four loads that copy the input rows and a fixed part for weights and barriers)
     int best_cb = 0, best_rows = 0;
     double best = 1e30;
     for (int cb = 1; cb <= 4; cb *= 2) {
@@ -2000,10 +2134,24 @@ bool tile_dw_op(DevOp &op, int nwg) {
             if (lds_bytes(rows, cb) > RED_BYTES) break;
             const long units = (long)a.B * cblocks * ((a.P + rows - 1) / rows);
             const long rounds = (units + nwg - 1) / nwg;
-            const long passes = ((long)rows * a.Q * cb + STREAM_THREADS - 1) / STREAM_THREADS;
-            const double copy = (double)((rows - 1) * a.stride + a.R) * a.W * cb / STREAM_THREADS;
-            const double cost = rounds * (passes * a.R * a.R + 4.0 * copy + 60.0);
+            const long passes = ((long)rows * qblocks * cb + STREAM_THREADS - 1) / STREAM_THREADS;
+            const double item = a.R * (ncol * 10.0 + DW_ITEMS * a.R * 8.0 + 30.0) + DW_ITEMS * 40.0;
+            const long cells = (long)((rows - 1) * a.stride + a.R) * Wp * cb;
+            const double copy = (double)((cells + 4 * STREAM_THREADS - 1) / (4 * STREAM_THREADS)) * 900.0;
+            const double cost = rounds * (passes * item * 8.0 + copy + 3000.0);
             if (cost < best) best = cost, best_cb = cb, best_rows = rows;
+        }
+    }
+    // straight from memory: every thread of the team takes items in turn; a tap row costs a load round trip
+    // (no other wave of the SIMD may be there to hide it) plus its instructions
+    {
+        const long items = (long)a.B * a.P * qblocks * cgs;
+        const long per_thread = (items + (long)nwg * STREAM_THREADS - 1) / ((long)nwg * STREAM_THREADS);
+        const double row = 2500.0 + (ncol * 10.0 + DW_ITEMS * a.R * 8.0 + a.R * 10.0 + 30.0) * 8.0;
+        const double direct = per_thread * (a.R * row + DW_ITEMS * 40.0 * 8.0) + 1000.0;
+        if (direct < best) {
+            op.wk = -4, op.ft = 1, op.pt = 1, op.n_p = 1, op.n_units = 1;
+            return true;
         }
     }
     if (best_cb == 0) return false;
