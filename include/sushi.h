@@ -185,6 +185,26 @@ int sushi_describe_supernet(const sushi_arch *arch, sushi_tensor_desc *out, int 
 int sushi_subnet_layers(const sushi_arch *arch, const sushi_subnet_cfg *cfg, sushi_layer_dims *out, int cap,
                         int *n_out);
 
+/* How exec mode 3 cuts one op of a SubNet's per-query plan (Section 3.1: a query activates one SubNet; Section 4.2:
+ * its layers run one after the other) into units for a team of workgroups.  kind: 0 dense conv, 1 depthwise conv,
+ * 2 max-pool, 3 global average pool, 4 fully connected, 5 channel gate.  layer: SuperNet layer (order of
+ * sushi_subnet_layers) or -1.  wk selects the unit variant (> 0: split units, that many waves per unit; 0: tiled units;
+ * -1: stem units; -2 depthwise through LDS; -3 tiled units with resident weights; -4 depthwise from memory), ft / pt its
+ * tile shape, n_units / n_p the unit counts, lds_bytes what the variant takes of the 32 KiB LDS scratch. */
+typedef struct sushi_team_op {
+    int32_t kind, layer;
+    int32_t B, H, W, C, P, Q, K, R, stride;
+    int32_t ft, pt, wk, n_units, n_p;
+    int32_t lds_bytes;
+} sushi_team_op;
+
+/* The ops of SubNet cfg at the given batch size as a team of team_wgs workgroups (4 .. 32) would run them, in order.
+ * Host only: needs no device and no weights.  Writes min(n, cap) entries to out (HOST, may be NULL when cap = 0) and
+ * the full count to *n_out.  SUSHI_EINVAL for an inconsistent arch or cfg, batch < 1 or team_wgs outside 1 .. 32;
+ * SUSHI_ESTATE if a layer does not fit the team kernel. */
+int sushi_team_plan(const sushi_arch *arch, const sushi_subnet_cfg *cfg, int batch, int team_wgs, sushi_team_op *out,
+                    int cap, int *n_out);
+
 /* ---------------------------------------------------------------- context */
 
 /* device_id: HIP device ordinal, or -1 for a host-only context (scheduler calls only; load and

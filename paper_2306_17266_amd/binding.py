@@ -55,6 +55,11 @@ class CLayerDims(C.Structure):
     _fields_ = [("K", C.c_int32), ("C", C.c_int32), ("r", C.c_int32)]
 
 
+class CTeamOp(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("kind", "layer", "B", "H", "W", "C", "P", "Q", "K", "R", "stride",
+                                          "ft", "pt", "wk", "n_units", "n_p", "lds_bytes")]
+
+
 class CSubgraphCfg(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("layers", C.POINTER(CLayerDims))]
 
@@ -95,6 +100,7 @@ def lib():
     vp, ip = C.c_void_p, C.POINTER(C.c_int)
     L.sushi_describe_supernet.argtypes = [C.POINTER(CArch), C.POINTER(CTensorDesc), C.c_int, ip]
     L.sushi_subnet_layers.argtypes = [C.POINTER(CArch), C.POINTER(CSubnetCfg), C.POINTER(CLayerDims), C.c_int, ip]
+    L.sushi_team_plan.argtypes = [C.POINTER(CArch), C.POINTER(CSubnetCfg), C.c_int, C.c_int, C.POINTER(CTeamOp), C.c_int, ip]
     L.sushi_create.argtypes = [C.POINTER(vp), C.c_int, vp]
     L.sushi_destroy.argtypes = [vp]
     L.sushi_destroy.restype = None
@@ -176,6 +182,14 @@ def sushi_subnet_layers(arch, cfg):
     buf = (CLayerDims * 256)()
     _check(lib().sushi_subnet_layers(C.byref(a), C.byref(s), buf, 256, C.byref(n)))
     return [(buf[i].K, buf[i].C, buf[i].r) for i in range(n.value)]
+
+
+def sushi_team_plan(arch, cfg, batch, team_wgs):
+    """[dict per op] of SubNet cfg as a team of team_wgs workgroups runs it (host only)."""
+    a, s, n = c_arch(arch), c_cfg(cfg), C.c_int(0)
+    buf = (CTeamOp * 512)()
+    _check(lib().sushi_team_plan(C.byref(a), C.byref(s), int(batch), int(team_wgs), buf, 512, C.byref(n)))
+    return [{f: getattr(buf[i], f) for f, _ in CTeamOp._fields_} for i in range(n.value)]
 
 
 class Sushi:

@@ -148,6 +148,9 @@ inline bool dense_op_fits(const ConvArgs &a) {
     return a.R * a.R <= 32 && a.R * a.R * ((a.C + 31) / 32) + 1 <= STEP_TABLE_MAX;
 }
 
+// Bytes of the 32 KiB LDS scratch (RED_BYTES) the unit variant chosen for `op` uses, from the kernels' layouts.
+long dev_op_lds_bytes(const DevOp &op);
+
 // Chooses pt / wk / unit counts of a dense conv or FC op for a grid of nwg workgroups.
 void tile_dev_op(DevOp &op, int nwg, bool team);
 // A dense conv with few input channels (the stem): sets wk = -1 and the band height in pt if the

@@ -2058,7 +2058,7 @@ void tile_dev_op(DevOp &op, int nwg, bool team) {
         static const int tile_shapes[10][2] = {{2, 1}, {2, 2}, {3, 1}, {3, 2}, {3, 4}, {4, 1}, {4, 2}, {4, 4}, {6, 1}, {6, 2}};
         for (const auto &tsh : tile_shapes) {
             const int at = tsh[0], bt = tsh[1];
-            if (true) {
+            {
                 const long n_f = (ftiles + at - 1) / at, n_p = (ptiles + STREAM_WAVES * bt - 1) / (STREAM_WAVES * bt);
                 const long iters = (n_f * n_p + nwg - 1) / nwg;
                 // least-squares fit to timings of the layer shapes of a ResNet50-like SuperNet with every
@@ -2160,6 +2160,32 @@ bool tile_dw_op(DevOp &op, int nwg) {
     op.n_p = (a.P + best_rows - 1) / best_rows;
     op.n_units = a.B * cblocks * op.n_p;
     return true;
+}
+
+long dev_op_lds_bytes(const DevOp &op) {
+    const ConvArgs &a = op.conv;
+    if (op.kind == OP_DW) {
+        if (op.wk != -2) return 0;
+        const long rows_in = (long)(op.pt - 1) * a.stride + a.R;
+        return (long)a.R * a.R * op.ft * 32 + rows_in * dw_padded_width(a.W, a.Q, a.R, a.stride) * op.ft * 16;
+    }
+    if (op.kind != OP_CONV && op.kind != OP_FC) return 0;
+    const long nsteps = (long)a.R * a.R * ((a.C + 31) / 32);
+    if (op.wk == -1) return ((long)(op.pt - 1) * a.stride + a.R) * a.W * a.C * 2;  // the band's input rows
+    if (op.wk == 0) {  // two weight stages, epilogue constants, step table (one round past the end)
+        const int ks = tile_ks(op.pt), round = ks * TILE_SETS;
+        const long steps_pad = (nsteps + round - 1) / round * round;
+        return 2L * ks * op.ft * 1024 + op.ft * 128 + (steps_pad + round) * 16;
+    }
+    if (op.wk == -3) {  // the filter group's weights for every step, epilogue constants, step table
+        const long steps_pad = (nsteps + ARES_D - 1) / ARES_D * ARES_D;
+        return nsteps * op.ft * 1024 + op.ft * 128 + steps_pad * 16;
+    }
+    if (op.wk > 1) {  // partial sums of the waves: all tiles of a unit, or one filter tile at a time
+        const int nt = op.ft * op.pt;
+        return (long)STREAM_WAVES * (nt <= 4 ? nt : op.pt) * 1024;
+    }
+    return 0;
 }
 
 bool tile_stem_op(DevOp &op, int nwg) {

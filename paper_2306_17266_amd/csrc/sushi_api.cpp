@@ -831,6 +831,22 @@ void publish_post(sushi_ctx *c, int t, TeamPost *slot) {
 
 int synchronize_teams(sushi_ctx *c);
 
+// Tiles one op of a plan for a team of nwg workgroups (dims only; the activation pointers stay as they are).
+// False: a dense layer does not fit the team kernel.
+static bool tile_team_op(DevOp &op, int nwg) {
+    op.pt = op.wk = op.ft = 1;
+    if (op.kind == OP_CONV || op.kind == OP_FC) {
+        if ((op.conv.C & 7) == 0 && !dense_op_fits(op.conv)) return false;
+        if ((op.conv.C & 7) == 0)
+            tile_dev_op(op, nwg, true);
+        else
+            tile_stem_op(op, nwg);
+    } else if (op.kind == OP_DW) {
+        tile_dw_op(op, nwg);
+    }
+    return true;
+}
+
 int post_team_query(sushi_ctx *c, CachedPlan &cp, const void *input_dev, void *logits_dev, int batch) {
     if (!c->bf16) return fail(c, SUSHI_ESTATE, "the team kernel runs in bf16 mode only");
     int rc = ensure_team_state(c, batch);
@@ -846,7 +862,6 @@ int post_team_query(sushi_ctx *c, CachedPlan &cp, const void *input_dev, void *l
             op.conv = L.conv, op.pool = L.pool;
             op.in_patch = L.in_patch, op.out_patch = L.out_patch;
             op.relative = 1;
-            op.pt = op.wk = op.ft = 1;
             auto rel = [&](int id, bool small) -> void * {
                 if (id < 0) return nullptr;
                 const long off = small ? N_BIG_BUFS * c->tbig_bytes + id * c->tsmall_bytes : id * c->tbig_bytes;
@@ -857,16 +872,8 @@ int post_team_query(sushi_ctx *c, CachedPlan &cp, const void *input_dev, void *l
             op.pool.x = op.conv.x, op.pool.y = op.conv.y;
             op.pool.gate = static_cast<const float *>(rel(o.gate_buf, true));
             op.layer = (L.kind == OP_CONV || L.kind == OP_FC) ? o.layer : -1;
-            if (L.kind == OP_CONV || L.kind == OP_FC) {
-                if ((L.conv.C & 7) == 0 && !dense_op_fits(L.conv))
-                    return fail(c, SUSHI_ESTATE, "a dense layer has too many reduction steps or taps for the team kernel");
-                if ((L.conv.C & 7) == 0)
-                    tile_dev_op(op, c->team_size(), true);
-                else
-                    tile_stem_op(op, c->team_size());
-            } else if (L.kind == OP_DW) {
-                tile_dw_op(op, c->team_size());
-            }
+            if (!tile_team_op(op, c->team_size()))
+                return fail(c, SUSHI_ESTATE, "a dense layer has too many reduction steps or taps for the team kernel");
             prog.push_back(op);
         }
         if (prog.size() > (size_t)TEAM_PROG_MAX_OPS) return fail(c, SUSHI_ESTATE, "the SubNet has too many ops for the team kernel");
@@ -980,6 +987,44 @@ int sushi_subnet_layers(const sushi_arch *arch, const sushi_subnet_cfg *cfg, sus
     if (rc) return rc;
     *n_out = (int)dims.size();
     for (int i = 0; i < cap && i < *n_out; ++i) out[i] = dims[i];
+    return SUSHI_OK;
+}
+
+int sushi_team_plan(const sushi_arch *arch, const sushi_subnet_cfg *cfg, int batch, int team_wgs, sushi_team_op *out,
+                    int cap, int *n_out) {
+    if (!arch || !cfg || !n_out || cap < 0 || (cap > 0 && !out) || batch < 1 || team_wgs < 1 || team_wgs > 32)
+        return SUSHI_EINVAL;
+    SuperNet sn;
+    std::string err;
+    int rc = build_supernet(*arch, sn, err);
+    if (rc) return rc;
+    Plan plan;
+    rc = plan_subnet(sn, *cfg, batch, plan, err);
+    if (rc) return rc;
+    *n_out = (int)plan.ops.size();
+    for (int i = 0; i < *n_out; ++i) {
+        const Op &o = plan.ops[i];
+        DevOp op{};
+        op.kind = o.kind;
+        op.layer = (o.kind == OP_CONV || o.kind == OP_FC) ? o.layer : -1;
+        if (o.kind == OP_CONV || o.kind == OP_DW || o.kind == OP_FC) {
+            const SuperLayer &S = sn.layers[o.layer];
+            ConvArgs &a = op.conv;
+            a.B = o.B, a.H = o.H, a.W = o.W, a.C = o.C, a.P = o.P, a.Q = o.Q, a.K = o.K;
+            a.R = o.r, a.stride = o.stride, a.pad = o.pad, a.Rmax = S.Rmax;
+            a.Kpad = S.Kpad, a.CG = S.CG;
+            a.act = o.act, a.hsigmoid = o.hsigmoid ? 1 : 0, a.out_f32 = o.out_f32 ? 1 : 0;
+            a.res = o.res_buf >= 0 ? &op : nullptr;  // (only whether there is one matters to the tiling)
+        }
+        if (!tile_team_op(op, team_wgs)) return SUSHI_ESTATE;
+        if (i < cap) {
+            sushi_team_op &t = out[i];
+            t.kind = o.kind, t.layer = op.layer;
+            t.B = o.B, t.H = o.H, t.W = o.W, t.C = o.C, t.P = o.P, t.Q = o.Q, t.K = o.K, t.R = o.r, t.stride = o.stride;
+            t.ft = op.ft, t.pt = op.pt, t.wk = op.wk, t.n_units = op.n_units, t.n_p = op.n_p;
+            t.lds_bytes = (int32_t)dev_op_lds_bytes(op);
+        }
+    }
     return SUSHI_OK;
 }
 

@@ -165,3 +165,89 @@ def test_latency_target_stream_matches_the_oracle():
         served.add(got[0])
     assert len(served) >= 3
     ctx.close()
+
+
+# ---------------------------------------------------------------- team-kernel tilings (host side of exec mode 3)
+
+LDS_SCRATCH = 32 * 1024      # bytes of LDS scratch a unit variant may use
+TILED_SHAPES = {(2, 1), (2, 2), (3, 1), (3, 2), (3, 4), (4, 1), (4, 2), (4, 4), (6, 1), (6, 2)}
+RESIDENT_SHAPES = {(2, 1), (2, 2), (4, 1), (4, 2), (6, 1)}
+SPLIT_SHAPES = {(2, 4), (1, 4), (2, 2), (1, 2), (4, 1), (2, 1), (1, 1)}
+DW_ITEMS = 5
+
+
+def _ceil(a, b):
+    return -(-a // b)
+
+
+def _check_team_op(op, team):
+    """What the kernels assume of a tiling, restated from their unit layouts."""
+    kind, wk, ft, pt = op["kind"], op["wk"], op["ft"], op["pt"]
+    M = op["B"] * op["P"] * op["Q"]
+    ptiles, ftiles = _ceil(M, 16), _ceil(op["K"], 16)
+    nsteps = op["R"] * op["R"] * _ceil(op["C"], 32)
+    assert 0 <= op["lds_bytes"] <= LDS_SCRATCH, op
+    if kind in (0, 4) and op["C"] % 8 == 0:                   # dense conv / FC on the matrix cores
+        assert op["R"] * op["R"] <= 32 and nsteps + 1 <= 256, op
+        if wk == 0:
+            assert (ft, pt) in TILED_SHAPES and ptiles >= 8, op
+            ks = 1 if pt >= 4 else 2
+            pad = _ceil(nsteps, 3 * ks) * 3 * ks
+            assert op["lds_bytes"] == 2 * ks * ft * 1024 + ft * 128 + (pad + 3 * ks) * 16, op
+            assert op["n_p"] == _ceil(ptiles, 8 * pt) and op["n_units"] == _ceil(ftiles, ft) * op["n_p"], op
+        elif wk == -3:
+            assert (ft, pt) in RESIDENT_SHAPES and ptiles >= 8, op
+            assert op["lds_bytes"] == nsteps * ft * 1024 + ft * 128 + _ceil(nsteps, 4) * 4 * 16, op
+            assert op["n_p"] == _ceil(ptiles, 8 * pt) and op["n_units"] == _ceil(ftiles, ft) * op["n_p"], op
+        else:
+            assert wk in (1, 2, 4, 8) and (ft, pt) in SPLIT_SHAPES, op
+            assert ft * pt <= 4 or wk == 8, op
+            assert pt <= ptiles or (pt == 4 and ptiles == 3), op
+            if ptiles <= 4:
+                assert ft <= 2, op                            # only such units can read resident slabs
+            assert op["n_p"] == _ceil(ptiles, pt) and op["n_units"] == _ceil(ftiles, ft) * op["n_p"], op
+    elif kind == 0:                                           # the stem (3 input channels)
+        assert wk == -1 and op["R"] * op["R"] * op["C"] <= 64 and op["K"] <= 64, op
+        rows_in = (pt - 1) * op["stride"] + op["R"]
+        assert op["lds_bytes"] == rows_in * op["W"] * op["C"] * 2, op
+        assert op["n_units"] == op["B"] * _ceil(op["P"], pt), op
+    elif kind == 1:                                           # depthwise
+        assert wk in (-2, -4) and op["R"] in (3, 5, 7) and op["stride"] in (1, 2) and op["K"] % 8 == 0, op
+        if wk == -2:
+            assert ft in (1, 2, 4) and 1 <= pt <= op["P"], op
+            need = (_ceil(op["Q"], DW_ITEMS) * DW_ITEMS - 1) * op["stride"] + op["R"]
+            wp = max(need, op["W"] + op["R"] - 1)
+            rows_in = (pt - 1) * op["stride"] + op["R"]
+            assert op["lds_bytes"] == op["R"] * op["R"] * ft * 32 + rows_in * wp * ft * 16, op
+            assert op["n_units"] == op["B"] * _ceil(op["K"] // 8, ft) * _ceil(op["P"], pt), op
+
+
+@pytest.mark.parametrize("mk", [A.small_resnet_arch, A.small_mbv3_arch, A.resnet_arch, A.mbv3_arch])
+@pytest.mark.parametrize("team", [4, 8, 16, 32])
+def test_team_tilings_fit_the_kernels(mk, team):
+    """Every op of sampled SubNets, at batch 1 and 16, gets a unit variant the kernels implement, unit
+    counts that cover all tiles, and an LDS footprint (restated here from the kernels' layouts)
+    within the 32 KiB scratch."""
+    arch = mk()
+    st = Stream(23)
+    res = max(arch.res_choices)
+    cfgs = [A.min_cfg(arch, min(arch.res_choices)), A.max_cfg(arch, res)] + [streams.uniform_cfg(arch, st) for _ in range(6)]
+    seen = set()
+    for batch in (1, 16):
+        for cfg in cfgs:
+            ops = S.sushi_team_plan(arch, cfg, batch, team)
+            assert len(ops) >= 5
+            for op in ops:
+                _check_team_op(op, team)
+                seen.add((op["kind"], op["wk"]))
+    assert any(k in (0, 4) and w > 0 for k, w in seen)        # few-pixel layers use split units
+    if mk in (A.resnet_arch, A.mbv3_arch):
+        assert (0, 0) in seen                                 # many-pixel layers use tiled units
+
+
+def test_team_plan_rejects_bad_arguments():
+    arch = A.small_resnet_arch()
+    cfg = A.max_cfg(arch, max(arch.res_choices))
+    for batch, team in ((0, 8), (1, 0), (1, 33)):
+        with pytest.raises(S.SushiError):
+            S.sushi_team_plan(arch, cfg, batch, team)
