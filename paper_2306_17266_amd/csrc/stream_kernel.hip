@@ -1307,8 +1307,6 @@ __device__ __forceinline__ void dw_tiled_units(const DevOp &op, float *lds, int 
                     unpack8(make_uint4(xq.x, xq.y, xq.z, xq.w), xv);
 #pragma unroll
                     for (int k = 0; k < IT; ++k) {
-                        constexpr int dummy = 0;
-                        (void)dummy;
                         const int ds = col - k * S;  // (a constant once the loops are unrolled)
                         if (ds >= 0 && ds < R) {
 #pragma unroll
