@@ -93,6 +93,39 @@ __device__ __forceinline__ bool grid_barrier(const StreamArgs &sa, unsigned long
 
 // LD / ST: cache policy of activation loads / stores; sys_out: the output is the caller's buffer and
 // is written through to memory at system scope.
+// Activation layout inside the stream and team kernels: [image][group of 8 channels][pixel][8 channels], one
+// 16-byte cell per (group, pixel).  The 16 pixels x 4 channel groups a matrix-core operand takes are then four
+// runs of 256 contiguous bytes (8 cache lines; 16 half-used lines if the channels of a pixel were contiguous,
+// which costs a compute unit 2.5 times as long per load), and an output tile is written the same way.  With one
+// pixel per image (pooled features, gates, logits) this is the plain [image][channel] order, for any channel
+// count; with more pixels the channel count must be a multiple of 8.  The caller's input (3 channels) keeps its
+// [image][pixel][channel] order and is read by the stem units only.
+__device__ __forceinline__ int in_cell(const ConvArgs &a, int n, int cg, int h, int w) {  // byte offset
+    return (((n * (a.C >> 3) + cg) * a.H + h) * a.W + w) * 16;
+}
+// Byte offset of the output cell (channel group cg, pixel pix of image n); the channel count is a multiple of 8.
+__device__ __forceinline__ int out_cell(const ConvArgs &a, int n, int cg, int pix) {
+    return ((n * (a.K >> 3) + cg) * (a.P * a.Q) + pix) * 16;
+}
+// Element offset of filter f of output pixel m (m counts pixels over the whole batch).
+__device__ __forceinline__ long out_elem(const ConvArgs &a, int m, int f) {
+    const int pq = a.P * a.Q;
+    if (pq == 1) return (long)m * a.K + f;
+    const int n = a.B == 1 ? 0 : m / pq, pix = m - n * pq;
+    return (((long)n * (a.K >> 3) + (f >> 3)) * pq + pix) * 8 + (f & 7);
+}
+// The same in two parts for loops over tiles: out_elem = out_pixel_part(m) + out_filter_part(f).
+__device__ __forceinline__ int out_pixel_part(const ConvArgs &a, int m) {
+    const int pq = a.P * a.Q;
+    if (pq == 1) return m * a.K;
+    const int n = a.B == 1 ? 0 : m / pq, pix = m - n * pq;
+    return (n * (a.K >> 3) * pq + pix) * 8;
+}
+__device__ __forceinline__ int out_filter_part(const ConvArgs &a, int f) {
+    const int pq = a.P * a.Q;
+    return pq == 1 ? f : (f >> 3) * pq * 8 + (f & 7);
+}
+
 // Scale and shift of the lane's four filters (and optionally the residual of one tile), fetched at
 // the start of a unit so that their latency hides behind the reduction.
 struct Epilogue {
@@ -115,7 +148,7 @@ __device__ __forceinline__ Epilogue fetch_epilogue(const ConvArgs &a, __amdgpu_b
         e.sc[0] = sc.x, e.sc[1] = sc.y, e.sc[2] = sc.z, e.sc[3] = sc.w;
         e.sh[0] = sh.x, e.sh[1] = sh.y, e.sh[2] = sh.z, e.sh[3] = sh.w;
         if (want_res && a.res && m < M) {
-            e.res = __builtin_amdgcn_raw_buffer_load_b64(rres, (int)(((long)m * a.K + fbase) * 2), 0, LD);
+            e.res = __builtin_amdgcn_raw_buffer_load_b64(rres, (int)(out_elem(a, m, fbase) * 2), 0, LD);
             e.have_res = true;
         }
     }
@@ -129,7 +162,7 @@ __device__ __forceinline__ void store_tile_coherent(const ConvArgs &a, __amdgpu_
     if (fbase >= a.K || m >= M) return;
     const int nf = min(4, a.K - fbase);
     const bool vec = nf == 4 && (a.K & 3) == 0;
-    const long o = (long)m * a.K + fbase;
+    const long o = out_elem(a, m, fbase);  // (the lane's filters never straddle a group of 8: fbase is a multiple of 4)
     float v[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -197,7 +230,7 @@ __device__ __forceinline__ void store_tile_fast(const ConvArgs &a, __amdgpu_buff
     if (has_res) v[0] += bf2f(res.x & 0xFFFFu), v[1] += bf2f(res.x >> 16), v[2] += bf2f(res.y & 0xFFFFu), v[3] += bf2f(res.y >> 16);
 #pragma unroll
     for (int i = 0; i < 4; ++i) v[i] = act_fast<ACT>(v[i]);
-    const int o = m * a.K + fbase;
+    const int o = (int)out_elem(a, m, fbase);
     if (a.out_f32) {
         const uint4 pk = make_uint4(__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3]));
         if (sys_out)
@@ -279,7 +312,7 @@ __device__ __forceinline__ void build_step_tables(const ConvArgs &a, int cg_res,
             const int tap = st / csteps, c = st - tap * csteps;
             const int dr = tap / a.R, ds = tap - dr * a.R;
             e.x = (unsigned)((tap * a.CG + c * 4) * a.Kpad * 16);
-            e.y = (unsigned)((dr * a.W + ds) * a.C * 2 + c * 64);
+            e.y = (unsigned)(((dr * a.W + ds) + c * 4 * a.H * a.W) * 16);
             e.z = c == csteps - 1 ? 0u : 1u << tap;
             e.w = c == csteps - 1 ? 1u << tap : 0u;
             r.x = (unsigned)((tap * cg_res + c * 4) * 256);
@@ -309,7 +342,7 @@ __device__ __forceinline__ void pixel_cell(const ConvArgs &a, int m, bool valid,
     const int rem = mm - nn * a.P * a.Q;
     const int pp = div_small(rem, a.Q, rcp_q), qq = rem - pp * a.Q;
     const int h0 = pp * a.stride - a.pad, w0 = qq * a.stride - a.pad;
-    *offset = (((nn * a.H + h0) * a.W + w0) * a.C + kg * 8) * 2;
+    *offset = in_cell(a, nn, kg, h0, w0);
     unsigned cols = 0, mk = 0;
     for (int ds = 0; ds < a.R; ++ds)
         if (w0 + ds >= 0 && w0 + ds < a.W) cols |= 1u << ds;
@@ -613,7 +646,7 @@ __device__ __forceinline__ void conv_tile_units(const DevOp &op, u32x4_t *stage,
         u32x4_t e = {0u, 0u, 0u, 0u};
         if (st < nsteps) {
             e.x = (unsigned)((tap * a.CG + c * 4) * a.Kpad * 16);
-            e.y = (unsigned)((dr * a.W + ds) * a.C * 2 + c * 64);
+            e.y = (unsigned)(((dr * a.W + ds) + c * 4 * a.H * a.W) * 16);
             e.z = c == csteps - 1 ? 0u : 1u << tap;
             e.w = c == csteps - 1 ? 1u << tap : 0u;
         }
@@ -653,7 +686,7 @@ __device__ __forceinline__ void conv_tile_units(const DevOp &op, u32x4_t *stage,
             const int rem = mm - nn * a.P * a.Q;
             const int pp = div_small(rem, a.Q, rcp_q), qq = rem - pp * a.Q;
             const int h0 = pp * a.stride - a.pad, w0 = qq * a.stride - a.pad;
-            b_lane[j] = (((nn * a.H + h0) * a.W + w0) * a.C + kg * 8) * 2;
+            b_lane[j] = in_cell(a, nn, kg, h0, w0);
             unsigned cols = 0, mk = 0;
             for (int ds = 0; ds < a.R; ++ds)
                 if (w0 + ds >= 0 && w0 + ds < a.W) cols |= 1u << ds;
@@ -749,7 +782,7 @@ __device__ __forceinline__ void conv_tile_units(const DevOp &op, u32x4_t *stage,
             for (int j = 0; j < BT; ++j) {
                 const int m = m0 + j * 16 + l16;
                 const bool want = a.res && vec_k && fbase + 4 <= a.K && m < M;  // else: past the end, reads zeros
-                resid[i][j] = __builtin_amdgcn_raw_buffer_load_b64(rres, want ? (m * a.K + fbase) * 2 : OOB_STORE, 0, LD);
+                resid[i][j] = __builtin_amdgcn_raw_buffer_load_b64(rres, want ? (out_pixel_part(a, m) + out_filter_part(a, fbase)) * 2 : OOB_STORE, 0, LD);
             }
         }
         if (tid < AT * 16) epi_lds[tid] = e_sc, epi_lds[AT * 16 + tid] = e_sh;
@@ -766,7 +799,7 @@ __device__ __forceinline__ void conv_tile_units(const DevOp &op, u32x4_t *stage,
                     for (int j = 0; j < BT; ++j) {
                         const int m = m0 + j * 16 + l16;
                         const bool ok = fbase + 4 <= a.K && m < M;
-                        store_tile_bf16<ACT, ST>(ry, acc[i][j], sc, sh, resid[i][j], ok ? (m * a.K + fbase) * 2 : OOB_STORE);
+                        store_tile_bf16<ACT, ST>(ry, acc[i][j], sc, sh, resid[i][j], ok ? (out_pixel_part(a, m) + out_filter_part(a, fbase)) * 2 : OOB_STORE);
                     }
                 }
             });
@@ -836,7 +869,7 @@ __device__ __forceinline__ void conv_ares_units(const DevOp &op, u32x4_t *lds, i
         u32x4_t e = {0u, 0u, 0u, 0u};
         if (st < nsteps) {
             e.x = (unsigned)((tap * a.CG + c * 4) * a.Kpad * 16);
-            e.y = (unsigned)((dr * a.W + ds) * a.C * 2 + c * 64);
+            e.y = (unsigned)(((dr * a.W + ds) + c * 4 * a.H * a.W) * 16);
             e.z = c == csteps - 1 ? 0u : 1u << tap;
             e.w = c == csteps - 1 ? 1u << tap : 0u;
         }
@@ -900,7 +933,7 @@ __device__ __forceinline__ void conv_ares_units(const DevOp &op, u32x4_t *lds, i
             for (int j = 0; j < BT; ++j) {
                 const int m = m0 + j * 16 + l16;
                 const bool want = a.res && vec_k && fbase + 4 <= a.K && m < M;
-                resid[i][j] = __builtin_amdgcn_raw_buffer_load_b64(rres, want ? (m * a.K + fbase) * 2 : OOB_STORE, 0, LD);
+                resid[i][j] = __builtin_amdgcn_raw_buffer_load_b64(rres, want ? (out_pixel_part(a, m) + out_filter_part(a, fbase)) * 2 : OOB_STORE, 0, LD);
             }
         }
         u32x4_t rb[D][BT];
@@ -955,7 +988,7 @@ __device__ __forceinline__ void conv_ares_units(const DevOp &op, u32x4_t *lds, i
                     for (int j = 0; j < BT; ++j) {
                         const int m = m0 + j * 16 + l16;
                         const bool ok = fbase + 4 <= a.K && m < M;
-                        store_tile_bf16<ACT, ST>(ry, acc[i][j], sc, sh, resid[i][j], ok ? (m * a.K + fbase) * 2 : OOB_STORE);
+                        store_tile_bf16<ACT, ST>(ry, acc[i][j], sc, sh, resid[i][j], ok ? (out_pixel_part(a, m) + out_filter_part(a, fbase)) * 2 : OOB_STORE);
                     }
                 }
             });
@@ -1012,7 +1045,7 @@ __device__ __forceinline__ void conv_direct_units(const ConvArgs &a, int rank, i
                     }
             }
         }
-        const long obase = m * a.K + fb;
+        const long obase = out_elem(a, (int)m, fb);
         float v4[4];
         const int nf = min(4, a.K - fb);
         for (int i = 0; i < 4; ++i)
@@ -1167,7 +1200,7 @@ __device__ __forceinline__ void stem_units(const DevOp &op, float *lds, int rank
                         const float4 sh = *reinterpret_cast<const float4 *>(a.shift + fbase);
                         float4 sc = make_float4(1.f, 1.f, 1.f, 1.f);
                         if (a.scale) sc = *reinterpret_cast<const float4 *>(a.scale + fbase);
-                        store_tile_bf16<ACT, ST>(ry, acc[ft], sc, sh, u32x2_t{0u, 0u}, (m * a.K + fbase) * 2);
+                        store_tile_bf16<ACT, ST>(ry, acc[ft], sc, sh, u32x2_t{0u, 0u}, (int)(out_elem(a, m, fbase) * 2));
                     }
                 }
             });
@@ -1185,9 +1218,9 @@ __device__ __forceinline__ void dwconv_units(const ConvArgs &a, int rank, int nr
     const __amdgpu_buffer_rsrc_t ry = make_rsrc(a.y, (long)a.B * a.P * a.Q * a.K * 2);
     const int ntaps = a.R * a.R;
     for (long idx = (long)rank * STREAM_THREADS + threadIdx.x; idx < total; idx += (long)nranks * STREAM_THREADS) {
-        const int cg = (int)(idx % cgs);
-        const long m = idx / cgs;
-        const int qq = (int)(m % a.Q), pp = (int)((m / a.Q) % a.P), n = (int)(m / ((long)a.Q * a.P));
+        const int qq = (int)(idx % a.Q), pp = (int)((idx / a.Q) % a.P);
+        const long plane = idx / ((long)a.Q * a.P);
+        const int cg = (int)(plane % cgs), n = (int)(plane / cgs);
         const int c = cg * 8;
         float acc[8];
 #pragma unroll
@@ -1196,7 +1229,7 @@ __device__ __forceinline__ void dwconv_units(const ConvArgs &a, int rank, int nr
             const int h = pp * a.stride + c_dw_dr[t], v = qq * a.stride + c_dw_ds[t];
             if (h < 0 || h >= a.H || v < 0 || v >= a.W) continue;
             float xv[8], wv[8];
-            unpack8(act_ld16<LD>(rx, (((n * a.H + h) * a.W + v) * a.C + c) * 2), xv);
+            unpack8(act_ld16<LD>(rx, in_cell(a, n, cg, h, v)), xv);
             load8(w + (long)t * a.Kpad + c, wv);
 #pragma unroll
             for (int j = 0; j < 8; ++j) acc[j] = fmaf(wv[j], xv[j], acc[j]);
@@ -1206,7 +1239,7 @@ __device__ __forceinline__ void dwconv_units(const ConvArgs &a, int rank, int nr
         load8(a.shift + c, sh);
 #pragma unroll
         for (int j = 0; j < 8; ++j) acc[j] = activate(acc[j] * sc[j] + sh[j], a.act, 0);
-        act_st16<ST>(ry, (int)((m * a.K + c) * 2), pack8(acc));
+        act_st16<ST>(ry, out_cell(a, n, cg, pp * a.Q + qq), pack8(acc));
     }
 }
 
@@ -1264,7 +1297,7 @@ __device__ __forceinline__ void dw_tiled_units(const DevOp &op, float *lds, int 
                 const int r = pix / Wp, col = pix - r * Wp - HALF;
                 const int h = h_first + r;
                 const bool ok = i < cells && h >= 0 && h < a.H && col >= 0 && col < a.W && c < cgs;
-                v[u] = __builtin_amdgcn_raw_buffer_load_b128(rx, ok ? (((n * a.H + h) * a.W + col) * a.C + c * 8) * 2 : (int)OOB_OFFSET, 0, LD);
+                v[u] = __builtin_amdgcn_raw_buffer_load_b128(rx, ok ? in_cell(a, n, c, h, col) : (int)OOB_OFFSET, 0, LD);
             }
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
@@ -1323,8 +1356,7 @@ __device__ __forceinline__ void dw_tiled_units(const DevOp &op, float *lds, int 
                     const int q = qb * IT + k;
 #pragma unroll
                     for (int j = 0; j < 8; ++j) acc[k][j] = activate(acc[k][j] * sc[j] + sh[j], a.act, 0);
-                    const int m = (n * a.P + p0 + pr) * a.Q + q;
-                    act_st16<ST>(ry, q < a.Q ? (m * a.K + c) * 2 : (int)OOB_OFFSET, pack8(acc[k]));
+                    act_st16<ST>(ry, q < a.Q ? out_cell(a, n, cg0 + cb, (p0 + pr) * a.Q + q) : (int)OOB_OFFSET, pack8(acc[k]));
                 }
             }
         }
@@ -1342,63 +1374,65 @@ __device__ __forceinline__ int dw_tap_index(int dr, int ds) {
 }
 
 // Depthwise k x k straight from memory (wk == -4), for layers whose bands in LDS would be too small to
-// keep a workgroup's threads busy (wide maps, stride 2): the same items as in dw_tiled_units (DW_ITEMS
-// neighbouring outputs of one row and channel group per thread, every input cell of a tap row loaded
-// once for all of them), spread over all threads of the team; no LDS, no barriers.  Cells outside the
-// image are requested past the end of the buffer and arrive as zeros.
+// keep a workgroup's threads busy (wide maps, stride 2).  A thread computes DW_ITEMS outputs of one column
+// and channel group, one below the other: for every tap column it loads the column's k weights and the
+// (DW_ITEMS - 1) * stride + k input cells those outputs share, each once.  Neighbouring lanes take
+// neighbouring columns, so every load and store of a wave is one contiguous run of cells; items are spread
+// over all threads of the team; no LDS, no barriers.  Cells outside the image are requested past the end
+// of the buffer and arrive as zeros.
 template <int R, int S, int LD, int ST>
 __device__ __forceinline__ void dw_direct_units(const DevOp &op, int rank, int nranks) {
-    constexpr int HALF = (R - 1) / 2, IT = DW_ITEMS, NCOL = (IT - 1) * S + R;
+    constexpr int HALF = (R - 1) / 2, IT = DW_ITEMS, NROW = (IT - 1) * S + R;
     const ConvArgs &a = op.conv;
-    const int cgs = a.K >> 3, qblocks = (a.Q + IT - 1) / IT;
-    const long items = (long)a.B * a.P * qblocks * cgs;
+    const int cgs = a.K >> 3, pblocks = (a.P + IT - 1) / IT;
+    const long items = (long)a.B * cgs * pblocks * a.Q;
     const __amdgpu_buffer_rsrc_t rx = make_rsrc(a.x, (long)a.B * a.H * a.W * a.C * 2);
     const __amdgpu_buffer_rsrc_t ry = make_rsrc(a.y, (long)a.B * a.P * a.Q * a.K * 2);
     const __amdgpu_buffer_rsrc_t rw = make_rsrc(a.w, (long)a.Rmax * a.Rmax * a.Kpad * 2);
     for (long it = (long)rank * STREAM_THREADS + threadIdx.x; it < items; it += (long)nranks * STREAM_THREADS) {
-        const int cg = (int)(it % cgs);
-        const long blk = it / cgs;
-        const int qb = (int)(blk % qblocks);
-        const long rowi = blk / qblocks;
-        const int pr = (int)(rowi % a.P), n = (int)(rowi / a.P);
+        // items in storage order (image, channel group, block of rows, column)
+        const int q = (int)(it % a.Q);
+        const long rowi = it / a.Q;
+        const int pb = (int)(rowi % pblocks);
+        const long plane = rowi / pblocks;
+        const int cg = (int)(plane % cgs), n = (int)(plane / cgs);
         const int c = cg * 8;
-        const int col0 = qb * IT * S - HALF;
+        const int row0 = pb * IT * S - HALF, col0 = q * S - HALF;
         float acc[IT][8];
 #pragma unroll
         for (int k = 0; k < IT; ++k)
 #pragma unroll
             for (int j = 0; j < 8; ++j) acc[k][j] = 0.f;
-        int col_off[NCOL];  // byte offset of the row's cells from the row start; past the end outside the image
+        int row_off[NROW];  // byte offset of the window's rows at column 0; -1 outside the image
 #pragma unroll
-        for (int cc = 0; cc < NCOL; ++cc) {
-            const int col = col0 + cc;
-            col_off[cc] = col >= 0 && col < a.W ? (col * a.C + c) * 2 : -1;
+        for (int r = 0; r < NROW; ++r) {
+            const int h = row0 + r;
+            row_off[r] = h >= 0 && h < a.H ? in_cell(a, n, cg, h, 0) : -1;
         }
 #pragma unroll 1
-        for (int dr = 0; dr < R; ++dr) {
-            const int h = pr * S - HALF + dr;
-            const bool row_ok = h >= 0 && h < a.H;
-            const int row_base = ((n * a.H + h) * a.W) * a.C * 2;
-            u32x4_t wq[R], xq[NCOL];
+        for (int ds = 0; ds < R; ++ds) {
+            const int col = col0 + ds;
+            const bool col_ok = col >= 0 && col < a.W;
+            u32x4_t wq[R], xq[NROW];
 #pragma unroll
-            for (int ds = 0; ds < R; ++ds)
-                wq[ds] = __builtin_amdgcn_raw_buffer_load_b128(rw, (dw_tap_index(dr - HALF, ds - HALF) * a.Kpad + c) * 2, 0, 0);
+            for (int dr = 0; dr < R; ++dr)
+                wq[dr] = __builtin_amdgcn_raw_buffer_load_b128(rw, (dw_tap_index(dr - HALF, ds - HALF) * a.Kpad + c) * 2, 0, 0);
 #pragma unroll
-            for (int cc = 0; cc < NCOL; ++cc)
-                xq[cc] = __builtin_amdgcn_raw_buffer_load_b128(rx, row_ok && col_off[cc] >= 0 ? row_base + col_off[cc] : (int)OOB_OFFSET, 0, LD);
+            for (int r = 0; r < NROW; ++r)
+                xq[r] = __builtin_amdgcn_raw_buffer_load_b128(rx, col_ok && row_off[r] >= 0 ? row_off[r] + col * 16 : (int)OOB_OFFSET, 0, LD);
             float wv[R][8];
 #pragma unroll
-            for (int ds = 0; ds < R; ++ds) unpack8(make_uint4(wq[ds].x, wq[ds].y, wq[ds].z, wq[ds].w), wv[ds]);
+            for (int dr = 0; dr < R; ++dr) unpack8(make_uint4(wq[dr].x, wq[dr].y, wq[dr].z, wq[dr].w), wv[dr]);
 #pragma unroll
-            for (int cc = 0; cc < NCOL; ++cc) {
+            for (int r = 0; r < NROW; ++r) {
                 float xv[8];
-                unpack8(make_uint4(xq[cc].x, xq[cc].y, xq[cc].z, xq[cc].w), xv);
+                unpack8(make_uint4(xq[r].x, xq[r].y, xq[r].z, xq[r].w), xv);
 #pragma unroll
                 for (int k = 0; k < IT; ++k) {
-                    const int ds = cc - k * S;  // (a constant once the loops are unrolled)
-                    if (ds >= 0 && ds < R) {
+                    const int dr = r - k * S;  // (a constant once the loops are unrolled)
+                    if (dr >= 0 && dr < R) {
 #pragma unroll
-                        for (int j = 0; j < 8; ++j) acc[k][j] = fmaf(wv[ds][j], xv[j], acc[k][j]);
+                        for (int j = 0; j < 8; ++j) acc[k][j] = fmaf(wv[dr][j], xv[j], acc[k][j]);
                     }
                 }
             }
@@ -1408,11 +1442,10 @@ __device__ __forceinline__ void dw_direct_units(const DevOp &op, int rank, int n
         load8(a.shift + c, sh);
 #pragma unroll
         for (int k = 0; k < IT; ++k) {
-            const int q = qb * IT + k;
+            const int pr = pb * IT + k;
 #pragma unroll
             for (int j = 0; j < 8; ++j) acc[k][j] = activate(acc[k][j] * sc[j] + sh[j], a.act, 0);
-            const long m = ((long)n * a.P + pr) * a.Q + q;
-            act_st16<ST>(ry, q < a.Q ? (int)((m * a.K + c) * 2) : (int)OOB_OFFSET, pack8(acc[k]));
+            act_st16<ST>(ry, pr < a.P ? out_cell(a, n, cg, pr * a.Q + q) : (int)OOB_OFFSET, pack8(acc[k]));
         }
     }
 }
@@ -1424,9 +1457,10 @@ __device__ __forceinline__ void maxpool_units(const PoolArgs &a, int rank, int n
     const __amdgpu_buffer_rsrc_t rx = make_rsrc(a.x, (long)a.B * a.H * a.W * a.C * 2);
     const __amdgpu_buffer_rsrc_t ry = make_rsrc(a.y, (long)a.B * a.P * a.Q * a.C * 2);
     for (long idx = (long)rank * STREAM_THREADS + threadIdx.x; idx < total; idx += (long)nranks * STREAM_THREADS) {
-        const int cg = (int)(idx % cgs);
-        const long m = idx / cgs;
-        const int qq = (int)(m % a.Q), pp = (int)((m / a.Q) % a.P), n = (int)(m / ((long)a.Q * a.P));
+        // outputs in storage order (image, channel group, pixel): neighbouring lanes, neighbouring cells
+        const int qq = (int)(idx % a.Q), pp = (int)((idx / a.Q) % a.P);
+        const long plane = idx / ((long)a.Q * a.P);
+        const int cg = (int)(plane % cgs), n = (int)(plane / cgs);
         float best[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) best[j] = -3.4028235e38f;
@@ -1437,12 +1471,12 @@ __device__ __forceinline__ void maxpool_units(const PoolArgs &a, int rank, int n
                 const int v = qq * 2 - 1 + s;
                 if (v < 0 || v >= a.W) continue;
                 float xv[8];
-                unpack8(act_ld16<LD>(rx, (((n * a.H + h) * a.W + v) * a.C + cg * 8) * 2), xv);
+                unpack8(act_ld16<LD>(rx, (((n * cgs + cg) * a.H + h) * a.W + v) * 16), xv);
 #pragma unroll
                 for (int j = 0; j < 8; ++j) best[j] = fmaxf(best[j], xv[j]);
             }
         }
-        act_st16<ST>(ry, (int)((m * a.C + cg * 8) * 2), pack8(best));
+        act_st16<ST>(ry, (((n * cgs + cg) * a.P + pp) * a.Q + qq) * 16, pack8(best));
     }
 }
 
@@ -1467,7 +1501,7 @@ __device__ __forceinline__ void gap_units(const PoolArgs &a, float *lds, int ran
         if (cg < cgs)
             for (int p = pl; p < hw; p += 64) {
                 float xv[8];
-                unpack8(act_ld16<LD>(rx, ((n * hw + p) * a.C + cg * 8) * 2), xv);
+                unpack8(act_ld16<LD>(rx, ((n * cgs + cg) * hw + p) * 16), xv);
 #pragma unroll
                 for (int j = 0; j < 8; ++j) acc[j] += xv[j];
             }
@@ -1500,16 +1534,15 @@ __device__ __forceinline__ void gate_units(const PoolArgs &a, int rank, int nran
     const __amdgpu_buffer_rsrc_t ry = make_rsrc(a.y, bytes);
     const __amdgpu_buffer_rsrc_t rg = make_rsrc(a.gate, (long)a.B * a.C * 4);
     for (long idx = (long)rank * STREAM_THREADS + threadIdx.x; idx < total; idx += (long)nranks * STREAM_THREADS) {
-        const int cg = (int)(idx % cgs);
-        const long m = idx / cgs;
-        const int n = (int)(m / ((long)a.H * a.W));
+        const long plane = idx / ((long)a.H * a.W);  // cells are taken in storage order: image, channel group, pixel
+        const int cg = (int)(plane % cgs), n = (int)(plane / cgs);
         float xv[8];
-        unpack8(act_ld16<LD>(rx, (int)((m * a.C + cg * 8) * 2)), xv);
+        unpack8(act_ld16<LD>(rx, (int)(idx * 16)), xv);
         const uint4 g0 = act_ld16<LD>(rg, (n * a.C + cg * 8) * 4), g1 = act_ld16<LD>(rg, (n * a.C + cg * 8) * 4 + 16);
         xv[0] *= __uint_as_float(g0.x), xv[1] *= __uint_as_float(g0.y), xv[2] *= __uint_as_float(g0.z);
         xv[3] *= __uint_as_float(g0.w), xv[4] *= __uint_as_float(g1.x), xv[5] *= __uint_as_float(g1.y);
         xv[6] *= __uint_as_float(g1.z), xv[7] *= __uint_as_float(g1.w);
-        act_st16<ST>(ry, (int)((m * a.C + cg * 8) * 2), pack8(xv));
+        act_st16<ST>(ry, (int)(idx * 16), pack8(xv));
     }
 }
 
@@ -2143,7 +2176,7 @@ bool tile_dw_op(DevOp &op, int nwg) {
     // straight from memory: every thread of the team takes items in turn; a tap row costs a load round trip
     // (no other wave of the SIMD may be there to hide it) plus its instructions
     {
-        const long items = (long)a.B * a.P * qblocks * cgs;
+        const long items = (long)a.B * cgs * ((a.P + DW_ITEMS - 1) / DW_ITEMS) * a.Q;
         const long per_thread = (items + (long)nwg * STREAM_THREADS - 1) / ((long)nwg * STREAM_THREADS);
         const double row = 2500.0 + (ncol * 10.0 + DW_ITEMS * a.R * 8.0 + a.R * 10.0 + 30.0) * 8.0;
         const double direct = per_thread * (a.R * row + DW_ITEMS * 40.0 * 8.0) + 1000.0;

@@ -462,6 +462,8 @@ int replay_graph(sushi_ctx *c, CachedPlan &cp, const void *input_dev, void *logi
 }
 
 // Exec mode 2: builds (once per plan) the device program and launches the stream kernel.
+static bool planar_layout_fits(const DevOp &op);
+
 int ensure_stream_state(sushi_ctx *c) {
     if (c->d_sync) return SUSHI_OK;
     hipError_t e;
@@ -501,6 +503,8 @@ int run_stream_kernel(sushi_ctx *c, CachedPlan &cp, const void *input_dev, void 
             op.in_patch = L.in_patch, op.out_patch = L.out_patch;
             op.pt = op.wk = op.ft = 1;
             op.layer = -1;
+            if (!planar_layout_fits(op))
+                return fail(c, SUSHI_ESTATE, "a layer's channel count does not fit the stream kernel's activation layout");
             if (L.kind == OP_CONV || L.kind == OP_FC) {
                 if ((L.conv.C & 7) == 0 && !dense_op_fits(L.conv))
                     return fail(c, SUSHI_ESTATE, "a dense layer has too many reduction steps or taps for the stream kernel");
@@ -831,10 +835,24 @@ void publish_post(sushi_ctx *c, int t, TeamPost *slot) {
 
 int synchronize_teams(sushi_ctx *c);
 
+// The stream and team kernels keep activations by groups of 8 channels (one 16-byte cell per group and pixel):
+// every tensor with more than one pixel per image must have a multiple of 8 channels, except the caller's
+// input, which only the stem units read (in its own order) and which therefore must not have one.
+static bool planar_layout_fits(const DevOp &op) {
+    if (op.kind == OP_CONV || op.kind == OP_DW || op.kind == OP_FC) {
+        const ConvArgs &a = op.conv;
+        if (a.P * a.Q > 1 && (a.K & 7) != 0) return false;
+        if (op.in_patch) return (a.C & 7) != 0;
+        return a.H * a.W == 1 || (a.C & 7) == 0;
+    }
+    return (op.pool.C & 7) == 0;
+}
+
 // Tiles one op of a plan for a team of nwg workgroups (dims only; the activation pointers stay as they are).
-// False: a dense layer does not fit the team kernel.
+// False: a layer does not fit the team kernel.
 static bool tile_team_op(DevOp &op, int nwg) {
     op.pt = op.wk = op.ft = 1;
+    if (!planar_layout_fits(op)) return false;
     if (op.kind == OP_CONV || op.kind == OP_FC) {
         if ((op.conv.C & 7) == 0 && !dense_op_fits(op.conv)) return false;
         if ((op.conv.C & 7) == 0)
@@ -873,7 +891,7 @@ int post_team_query(sushi_ctx *c, CachedPlan &cp, const void *input_dev, void *l
             op.pool.gate = static_cast<const float *>(rel(o.gate_buf, true));
             op.layer = (L.kind == OP_CONV || L.kind == OP_FC) ? o.layer : -1;
             if (!tile_team_op(op, c->team_size()))
-                return fail(c, SUSHI_ESTATE, "a dense layer has too many reduction steps or taps for the team kernel");
+                return fail(c, SUSHI_ESTATE, "a layer does not fit the team kernel (reduction steps, taps or channel counts)");
             prog.push_back(op);
         }
         if (prog.size() > (size_t)TEAM_PROG_MAX_OPS) return fail(c, SUSHI_ESTATE, "the SubNet has too many ops for the team kernel");
@@ -1007,6 +1025,8 @@ int sushi_team_plan(const sushi_arch *arch, const sushi_subnet_cfg *cfg, int bat
         DevOp op{};
         op.kind = o.kind;
         op.layer = (o.kind == OP_CONV || o.kind == OP_FC) ? o.layer : -1;
+        op.in_patch = o.in_buf == BUF_INPUT, op.out_patch = o.out_buf == BUF_LOGITS;
+        op.pool.B = o.B, op.pool.H = o.H, op.pool.W = o.W, op.pool.C = o.C, op.pool.P = o.P, op.pool.Q = o.Q;
         if (o.kind == OP_CONV || o.kind == OP_DW || o.kind == OP_FC) {
             const SuperLayer &S = sn.layers[o.layer];
             ConvArgs &a = op.conv;
