@@ -2055,10 +2055,10 @@ void tile_dev_op(DevOp &op, int nwg, bool team) {
     const long M = (long)a.B * a.P * a.Q;
     const long ptiles = (M + 15) / 16, ftiles = (a.K + 15) / 16;
     const int nsteps = a.R * a.R * ((a.C + 31) / 32);
-    // In round trips of about one microsecond, fitted to timings of the layer shapes of a
-    // ResNet50-like SuperNet on one XCD: a group of units (one per slot) has a fixed cost (first loads,
-    // reduction across waves, epilogue) and a cost per reduction step of a wave that grows mostly with
-    // the activation tiles it loads.
+    // In microseconds, a least-squares fit to timings of the layer shapes of a ResNet50-like SuperNet with
+    // every team of the chip busy: a group of units (one per slot) has a fixed cost (first loads, reduction
+    // across waves) plus an epilogue per tile, and a cost per reduction step of a wave that grows mostly
+    // with the activation tiles it loads.
     static const int shapes[7][2] = {{2, 4}, {1, 4}, {2, 2}, {1, 2}, {4, 1}, {2, 1}, {1, 1}};
     auto shape_cost = [&](int ft, int pt, int wk) {
         const long n_f = (ftiles + ft - 1) / ft, n_p = (ptiles + pt - 1) / pt;
@@ -2066,9 +2066,9 @@ void tile_dev_op(DevOp &op, int nwg, bool team) {
         const int slots = STREAM_WAVES / wk;
         const long iters = ((units + slots - 1) / slots + nwg - 1) / nwg;
         const int per_wave = (nsteps + wk - 1) / wk;
-        const double step = 0.08 + 0.16 * pt + 0.04 * ft;
-        const double fixed = 4.5 + (wk > 1 ? 0.5 : 0.0) + (ft * pt > 4 ? 1.0 : 0.0);
-        return iters * (fixed + per_wave * step);
+        const double step = 0.047 + 0.1275 * pt + 0.038 * ft;
+        const double fixed = 2.84 + 0.56 * ft * pt;
+        return 2.87 + iters * (fixed + per_wave * step);
     };
     // team kernel, at most 64 output pixels: units of at most two filter tiles can take their weights
     // from resident slabs
@@ -2077,7 +2077,9 @@ void tile_dev_op(DevOp &op, int nwg, bool team) {
     int bft = 1, bpt = 1, bwk = 1;
     for (const auto &sh : shapes)
         for (int wk = 1; wk <= STREAM_WAVES; wk *= 2) {
-            if (sh[0] * sh[1] > 4 && wk != STREAM_WAVES) continue;  // eight tiles only with all waves on one unit
+            // eight tiles: one wave per unit (nothing to add up) or all waves on one unit (the partial sums of
+            // one filter tile at a time fit the scratch)
+            if (sh[0] * sh[1] > 4 && wk != STREAM_WAVES && wk != 1) continue;
             if (slab_shapes_only && sh[0] > 2) continue;
             if (sh[1] > ptiles && !(sh[1] == 4 && ptiles == 3)) continue;
             const double cost = shape_cost(sh[0], sh[1], wk);
@@ -2101,9 +2103,9 @@ void tile_dev_op(DevOp &op, int nwg, bool team) {
                 // LDS: two weight stages, the epilogue constants, one 16-byte entry per step (the loads
                 // run one round past the last step)
                 if (2 * tile_ks(bt) * at * 1024 + at * 128 + (steps_pad + round) * 16 > RED_BYTES) continue;
-                const double step_cost = 0.0193 + 0.0222 * at + 0.1487 * bt - 0.0112 * at * bt;
-                const double unit_cost = 0.80 + at * bt * (a.res ? 0.48 : 0.384) + steps_pad * step_cost;
-                const double cost = 2.67 + iters * unit_cost;
+                const double step_cost = 0.034 + 0.0234 * at + 0.0847 * bt - 0.0035 * at * bt;
+                const double unit_cost = 1.54 + at * bt * (a.res ? 0.346 : 0.327) + steps_pad * step_cost;
+                const double cost = 2.14 + iters * unit_cost;
                 if (cost < best - 1e-9) best = cost, bft = at, bpt = bt, bwk = 0, tiled = true;
             }
         }
@@ -2121,9 +2123,9 @@ void tile_dev_op(DevOp &op, int nwg, bool team) {
             // filter groups a workgroup meets on its way through units rank, rank + nwg, ...
             const long reloads = std::min<long>(iters, n_p >= nwg ? (iters * nwg + n_p - 1) / n_p + 1 : iters);
             (void)reloads;  // (the fitted unit cost includes the reloads the timed shapes had)
-            const double step_cost = std::max(0.02, 0.0608 - 0.0463 * at + 0.1156 * bt + 0.0115 * at * bt);
-            const double unit_cost = 1.09 + at * bt * (a.res ? 0.494 : 0.307) + steps_pad * step_cost;
-            const double cost = 3.86 + iters * unit_cost;
+            const double step_cost = std::max(0.02, -0.1377 + 0.0582 * at + 0.2535 * bt - 0.0653 * at * bt);
+            const double unit_cost = 1.07 + at * bt * (a.res ? 0.515 : 0.40) + steps_pad * step_cost;
+            const double cost = 3.18 + iters * unit_cost;
             if (cost < best - 1e-9) best = cost, bft = at, bpt = bt, bwk = -3, ares = true;
         }
     }

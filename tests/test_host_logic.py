@@ -201,7 +201,7 @@ def _check_team_op(op, team):
             assert op["n_p"] == _ceil(ptiles, 8 * pt) and op["n_units"] == _ceil(ftiles, ft) * op["n_p"], op
         else:
             assert wk in (1, 2, 4, 8) and (ft, pt) in SPLIT_SHAPES, op
-            assert ft * pt <= 4 or wk == 8, op
+            assert ft * pt <= 4 or wk in (1, 8), op
             assert pt <= ptiles or (pt == 4 and ptiles == 3), op
             if ptiles <= 4:
                 assert ft <= 2, op                            # only such units can read resident slabs
