@@ -731,8 +731,6 @@ __device__ __forceinline__ void conv_tile_units(const DevOp &op, u32x4_t *stage,
             const u32x4_t *cur = stage + par * (KS * AT * 64);
             u32x4_t *nxt = stage + (par ^ 1) * (KS * AT * 64);
 #pragma unroll
-            for (int k = 0; k < KS; ++k) nxt[k * AT * 64 + st_cell] = a_next[k];
-#pragma unroll
             for (int k = 0; k < KS; ++k) {
                 u32x4_t fa[AT];
 #pragma unroll
@@ -749,6 +747,10 @@ __device__ __forceinline__ void conv_tile_units(const DevOp &op, u32x4_t *stage,
                     }
                 }
             }
+            // (the hand-over comes after the products: the wait for the next interval's weight cells then
+            // falls behind this interval's matrix-core work instead of in front of it)
+#pragma unroll
+            for (int k = 0; k < KS; ++k) nxt[k * AT * 64 + st_cell] = a_next[k];
 #pragma unroll
             for (int k = 0; k < KS; ++k) issue(a_free[k], b[k]);
             __syncthreads();
