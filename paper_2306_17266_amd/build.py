@@ -21,5 +21,18 @@ def build(verbose=False):
     return LIB
 
 
+def build_tools():
+    """The stand-alone measurement programs (not part of the library)."""
+    out = os.path.join(HERE, "vmem_patterns")
+    cmd = ["hipcc"] + [f for f in FLAGS if f not in ("-fPIC", "-shared")] + [os.path.join(CSRC, "vmem_patterns.hip"), "-o", out]
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + res.stdout)
+    return out
+
+
 if __name__ == "__main__":
+    import sys
     print(build(verbose=True))
+    if "--tools" in sys.argv:
+        print(build_tools())
