@@ -881,6 +881,39 @@ __device__ __forceinline__ void conv_ares_units(const DevOp &op, u32x4_t *lds, i
     const float rcp_q = 1.0f / (float)a.Q, rcp_pq = 1.0f / (float)(a.P * a.Q);
     const bool vec_k = (a.K & 3) == 0;
 
+    // Lane state of the unit whose activation cells are being requested, the ring of cells in flight and
+    // the step the next request fetches.  The requests run ahead across units: while a unit's last D steps
+    // are multiplied, the first D steps of the workgroup's next unit are requested, so they arrive during
+    // this unit's epilogue (with one to three steps per unit the load round trip would otherwise be paid
+    // once per unit).  A unit past the last one asks for nothing.
+    int b_lane[BT];
+    unsigned mask_full[BT], mask_tail[BT];
+    auto aim_at = [&](int unit) {
+        const bool live = unit < op.n_units;
+        const int pgroup = unit % op.n_p;
+        const int m0 = (pgroup * STREAM_WAVES + wave) * BT * 16;
+#pragma unroll
+        for (int j = 0; j < BT; ++j) {
+            const int m = m0 + j * 16 + l16;
+            pixel_cell(a, m, live && m < M, kg, rcp_q, rcp_pq, &b_lane[j], &mask_full[j]);
+            mask_tail[j] = kg < tail_active ? mask_full[j] : 0u;
+        }
+    };
+    u32x4_t rb[D][BT];
+    int i_step = 0;
+    auto issue = [&](u32x4_t *qb) {
+        const u32x4_t e = table[min(i_step, nsteps_pad - 1)];
+        ++i_step;
+#pragma unroll
+        for (int j = 0; j < BT; ++j) {
+            const bool ok = ((mask_full[j] & e.z) | (mask_tail[j] & e.w)) != 0u;
+            qb[j] = __builtin_amdgcn_raw_buffer_load_b128(rx, ok ? b_lane[j] + (int)e.y : (int)OOB_OFFSET, 0, LD);
+        }
+    };
+    aim_at(rank);
+#pragma unroll
+    for (int d = 0; d < D; ++d) issue(rb[d]);
+
     int loaded_group = -1;
     for (int unit = rank; unit < op.n_units; unit += nranks) {
         const int fgroup = unit / op.n_p, pgroup = unit - fgroup * op.n_p;
@@ -918,14 +951,6 @@ __device__ __forceinline__ void conv_ares_units(const DevOp &op, u32x4_t *lds, i
             }
             __syncthreads();
         }
-        int b_lane[BT];
-        unsigned mask_full[BT], mask_tail[BT];
-#pragma unroll
-        for (int j = 0; j < BT; ++j) {
-            const int m = m0 + j * 16 + l16;
-            pixel_cell(a, m, m < M, kg, rcp_q, rcp_pq, &b_lane[j], &mask_full[j]);
-            mask_tail[j] = kg < tail_active ? mask_full[j] : 0u;
-        }
         // residuals early: their latency hides behind the reduction
         u32x2_t resid[AT][BT];
 #pragma unroll
@@ -938,26 +963,16 @@ __device__ __forceinline__ void conv_ares_units(const DevOp &op, u32x4_t *lds, i
                 resid[i][j] = __builtin_amdgcn_raw_buffer_load_b64(rres, want ? (out_pixel_part(a, m) + out_filter_part(a, fbase)) * 2 : OOB_STORE, 0, LD);
             }
         }
-        u32x4_t rb[D][BT];
-        int i_step = 0;
-        auto issue = [&](u32x4_t *qb) {
-            const u32x4_t e = table[min(i_step, nsteps_pad - 1)];
-            const bool past = i_step >= nsteps_pad;
-            ++i_step;
-#pragma unroll
-            for (int j = 0; j < BT; ++j) {
-                const bool ok = !past && ((mask_full[j] & e.z) | (mask_tail[j] & e.w)) != 0u;
-                qb[j] = __builtin_amdgcn_raw_buffer_load_b128(rx, ok ? b_lane[j] + (int)e.y : (int)OOB_OFFSET, 0, LD);
-            }
-        };
         f32x4_t acc[AT][BT];
 #pragma unroll
         for (int i = 0; i < AT; ++i)
 #pragma unroll
             for (int j = 0; j < BT; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int d = 0; d < D; ++d) issue(rb[d]);
         for (int s0 = 0; s0 < nsteps_pad; s0 += D) {
+            if (s0 + D >= nsteps_pad) {  // the requests of the last D steps go to the next unit
+                aim_at(unit + nranks);
+                i_step = 0;
+            }
 #pragma unroll
             for (int d = 0; d < D; ++d) {
                 const int step = min(s0 + d, nsteps - 1);  // steps past the end multiply zeros with the last weights
@@ -2125,9 +2140,9 @@ void tile_dev_op(DevOp &op, int nwg, bool team) {
             // filter groups a workgroup meets on its way through units rank, rank + nwg, ...
             const long reloads = std::min<long>(iters, n_p >= nwg ? (iters * nwg + n_p - 1) / n_p + 1 : iters);
             (void)reloads;  // (the fitted unit cost includes the reloads the timed shapes had)
-            const double step_cost = std::max(0.02, -0.1377 + 0.0582 * at + 0.2535 * bt - 0.0653 * at * bt);
-            const double unit_cost = 1.07 + at * bt * (a.res ? 0.515 : 0.40) + steps_pad * step_cost;
-            const double cost = 3.18 + iters * unit_cost;
+            const double step_cost = 0.0735 - 0.0053 * at + 0.0522 * bt + 0.0009 * at * bt;
+            const double unit_cost = 0.99 + at * bt * (a.res ? 0.453 : 0.358) + steps_pad * step_cost;
+            const double cost = 3.99 + iters * unit_cost;
             if (cost < best - 1e-9) best = cost, bft = at, bpt = bt, bwk = -3, ares = true;
         }
     }
