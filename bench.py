@@ -87,8 +87,10 @@ def main():
                     help="0 = launch per layer, 1 = HIP graph replay, 2 = stream kernel, 3 = persistent XCD-team kernel")
     ap.add_argument("--teams-per-xcd", type=int, default=4, choices=[1, 2, 4, 8],
                     help="mode 3: teams per XCD (2 = twice as many queries in flight, each on half the workgroups)")
-    ap.add_argument("--sgs", choices=["sched", "off"], default="sched",
-                    help="sched = the scheduler re-chooses the cached SubGraph every Q queries; off = nothing is cached")
+    ap.add_argument("--sgs", choices=["sched", "fixed", "off"], default="sched",
+                    help="sched = the scheduler re-chooses the cached SubGraph every Q queries; fixed = the smallest "
+                         "SubNet of the stream, shrunk to the budget, is cached once and kept (the state-unaware "
+                         "baseline of the paper's scheduler ablation); off = nothing is cached")
     ap.add_argument("--Q", type=int, default=0, help="queries between cache re-choices (default: the workload's)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="run one 256 MiB device-to-device copy first (reference dispatch for byte counters)")
@@ -159,6 +161,9 @@ def main():
     mode = args.exec_mode
     ctx.sushi_set_option(S.OPT_EXEC_MODE, mode)
     ctx.sushi_set_option(S.OPT_TEAMS_PER_XCD, args.teams_per_xcd)
+    if args.sgs == "fixed":
+        smallest = min(box_of.values(), key=lambda b: streams.box_bytes(b, 2))
+        ctx.sushi_set_subgraph_cache(streams.shrink_box(smallest, budget, 2), budget)
     for _ in range(args.warmup):
         step()
     ctx.sushi_synchronize()
