@@ -98,8 +98,8 @@ def main():
     ap.add_argument("--no-roofline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
-        raise SystemExit("bench.py: this build runs on ONE GPU; --gpus %d is not supported "
-                         "(queries would shard by replica, see DESIGN.md)" % args.gpus)
+        raise SystemExit("bench.py: the library runs on ONE GPU; --gpus %d is not supported (with more GPUs each "
+                         "would hold a replica of the SuperNet and serve its own share of the queries)" % args.gpus)
 
     import numpy as np
     import torch
