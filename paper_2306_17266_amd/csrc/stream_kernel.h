@@ -105,7 +105,7 @@ struct TeamPost {  // written by the host
     unsigned long long pad[3];
 };
 
-constexpr int POST_RING = 8;  // posts a team's mailbox holds (post number s sits in slot s % POST_RING)
+constexpr int POST_RING = 32;  // posts a team's mailbox holds (post number s sits in slot s % POST_RING)
 
 struct TeamHostState {  // pinned HOST memory, device-visible
     TeamPost post[MAX_TEAMS][POST_RING];

@@ -1821,23 +1821,78 @@ __device__ __forceinline__ bool fetch_table(const TeamArgs &ta, const ResTable *
     return true;
 }
 
-// Copies the slabs this workgroup owns from the packed weights into its LDS store.
-__device__ void install_slabs(const ResTable *tab, int rank, char *store) {
-    for (int l = 0; l < tab->n_layers; ++l) {
-        const ResLayer &L = tab->layers[l];
-        if (L.n_res == 0) continue;
-        const uint16_t *w = static_cast<const uint16_t *>(L.w);
-        const int chunks = L.taps * L.cg_res * 16;  // 16-byte pieces of one slab
-        for (int f = 0; f < L.n_res; ++f) {
-            const ResEntry e = tab->entries[L.first_entry + f];
-            if (e.owner != rank) continue;
-            for (int i = threadIdx.x; i < chunks; i += STREAM_THREADS) {
-                const int j = i & 15, tc = i >> 4;
-                const int tap = tc / L.cg_res, cg = tc - tap * L.cg_res;
-                const uint4 v = *reinterpret_cast<const uint4 *>(w + (((long)tap * L.CG + cg) * L.Kpad + f * 16 + j) * 8);
-                *reinterpret_cast<uint4 *>(store + e.lds_off + (long)i * 16) = v;
-            }
+// Copies the slabs this workgroup owns from the packed weights into its LDS store.  `work` is LDS
+// that is idle during an install (the partial-sum area).  The table sits in device memory and every
+// dependent read of it costs a round trip, so nothing here walks it entry by entry: the layers come
+// into LDS in one pass, the entries are searched by all threads at once, and the 16-byte pieces of
+// all owned slabs form one index space that the threads share, eight loads each in flight.
+struct InstallItem {
+    int layer_f;      // layer << 16 | filter tile
+    int lds_off;      // byte offset of the slab inside the store
+    int first_piece;  // index of the slab's first piece among all pieces of this workgroup
+    int pad;
+};
+constexpr int INSTALL_MAX_ITEMS = RES_STORE_BYTES / 256;  // a slab is at least one 256-byte cell row
+static_assert(RES_MAX_LAYERS * sizeof(ResLayer) + INSTALL_MAX_ITEMS * sizeof(InstallItem) + 16 <= RED_BYTES,
+              "the install work area must fit the partial-sum area");
+
+__device__ void install_slabs(const ResTable *tab, int rank, char *store, char *work) {
+    ResLayer *lay = reinterpret_cast<ResLayer *>(work);
+    InstallItem *items = reinterpret_cast<InstallItem *>(work + RES_MAX_LAYERS * sizeof(ResLayer));
+    int *cnt = reinterpret_cast<int *>(items + INSTALL_MAX_ITEMS);  // [0] items, [1] pieces
+    const int tid = threadIdx.x;
+    const int nl = min(tab->n_layers, RES_MAX_LAYERS), ne = min(tab->n_entries, RES_MAX_ENTRIES);
+    const ResLayer *layers = tab->layers;
+    const ResEntry *entries = tab->entries;
+    __syncthreads();  // the work area may still be read by the op before
+    if (tid == 0) cnt[0] = 0, cnt[1] = 0;
+    for (int l = tid; l < nl; l += STREAM_THREADS) lay[l] = layers[l];
+    __syncthreads();
+    for (int i = tid; i < ne; i += STREAM_THREADS) {
+        const ResEntry e = entries[i];
+        if (e.owner != rank) continue;
+        int l = 0;
+        while (l < nl && !(lay[l].n_res > 0 && i >= lay[l].first_entry && i < lay[l].first_entry + lay[l].n_res)) ++l;
+        if (l == nl) continue;
+        const int k = atomicAdd(&cnt[0], 1);
+        if (k < INSTALL_MAX_ITEMS) items[k] = InstallItem{(l << 16) | (i - lay[l].first_entry), e.lds_off, 0, 0};
+    }
+    __syncthreads();
+    const int n = min(cnt[0], INSTALL_MAX_ITEMS);
+    if (tid == 0) {
+        int p = 0;
+        for (int k = 0; k < n; ++k) {
+            const ResLayer &L = lay[items[k].layer_f >> 16];
+            items[k].first_piece = p;
+            p += L.taps * L.cg_res * 16;
         }
+        cnt[1] = p;
+    }
+    __syncthreads();
+    const int total = cnt[1];
+    constexpr int BATCH = 8;
+    for (int p0 = tid; p0 < total; p0 += BATCH * STREAM_THREADS) {
+        uint4 v[BATCH];
+        int dst[BATCH];
+#pragma unroll
+        for (int u = 0; u < BATCH; ++u) {
+            const int p = min(p0 + u * STREAM_THREADS, total - 1);
+            int lo = 0, hi = n - 1;  // the last slab that starts at or before piece p
+            while (lo < hi) {
+                const int mid = (lo + hi + 1) >> 1;
+                if (items[mid].first_piece <= p) lo = mid; else hi = mid - 1;
+            }
+            const InstallItem it = items[lo];
+            const ResLayer &L = lay[it.layer_f >> 16];
+            const int f = it.layer_f & 0xFFFF, i = p - it.first_piece;
+            const int j = i & 15, tc = i >> 4;
+            const int tap = tc / L.cg_res, cg = tc - tap * L.cg_res;
+            v[u] = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(L.w) + (((long)tap * L.CG + cg) * L.Kpad + f * 16 + j) * 8);
+            dst[u] = it.lds_off + i * 16;
+        }
+#pragma unroll
+        for (int u = 0; u < BATCH; ++u)
+            if (p0 + u * STREAM_THREADS < total) *reinterpret_cast<uint4 *>(store + dst[u]) = v[u];
     }
     __syncthreads();
 }
@@ -1904,7 +1959,7 @@ __global__ __launch_bounds__(STREAM_THREADS, 2) void sushi_team_kernel(TeamArgs 
     unsigned long long epoch = 0;
     const ResTable *table = nullptr;
     if (!fetch_table(ta, ta.table, team_mem + TEAM_TABLE_OFFSET, team, rank, tsize, epoch, s_hdr, &flag, &table)) return;
-    if (table) install_slabs(table, rank, store);
+    if (table) install_slabs(table, rank, store, dyn_lds);
     unsigned long long *go = &ta.sync[sy_go(team)];
     unsigned long long *slot = &ta.sync[sy_slot(team)];
     const unsigned long long *posted = &ta.host->posted[team * 8];
@@ -1975,7 +2030,7 @@ __global__ __launch_bounds__(STREAM_THREADS, 2) void sushi_team_kernel(TeamArgs 
             if (!fetch_table(ta, reinterpret_cast<const ResTable *>(s_slot[1]), team_mem + TEAM_TABLE_OFFSET, team, rank,
                              tsize, epoch, s_hdr, &flag, &table))
                 return;
-            if (table) install_slabs(table, rank, store);
+            if (table) install_slabs(table, rank, store, dyn_lds);
             epoch += 1;
             if (!team_barrier(ta, team, tsize, epoch, &flag)) return;
             if (rank == 0 && threadIdx.x == 0)

@@ -114,7 +114,7 @@ struct sushi_ctx {
     char *h_prog_pool = nullptr;  // pinned HOST
     size_t prog_pool_used = 0;
     char *d_team_mem = nullptr;   // DEVICE, MAX_TEAMS x TEAM_MEM_BYTES
-    static constexpr int N_RES_GENS = 4;
+    static constexpr int N_RES_GENS = 32;
     ResGen res_gens[N_RES_GENS];  // a generation stays untouched while an install post may still name it
     bool gen_valid[N_RES_GENS] = {};  // slot holds a table (false: nothing cached)
     int gen_cur = 0;
@@ -622,7 +622,10 @@ int build_res_table(sushi_ctx *c) {
 }
 
 // Uploads the table as a new device generation.  The slot it takes over held the generation from
-// three installs ago; every team must have got past that generation's install post first.
+// N_RES_GENS - 1 installs ago; every team must have got past that generation's install post first
+// (with few generations, or shallow mailboxes, this wait and the one for a free mailbox slot tie the
+// host to the slowest team: every team gets every install post, so at one install per eight queries a
+// team finds several of them between two queries of its own).
 int upload_res_table(sushi_ctx *c) {
     const int slot = (c->gen_cur + 1) % sushi_ctx::N_RES_GENS;
     sushi_ctx::ResGen &g = c->res_gens[slot];
