@@ -85,7 +85,7 @@ def main():
     ap.add_argument("--workload", default="resnet_bs1_sticky")
     ap.add_argument("--exec-mode", type=int, default=3,
                     help="0 = launch per layer, 1 = HIP graph replay, 2 = stream kernel, 3 = persistent XCD-team kernel")
-    ap.add_argument("--teams-per-xcd", type=int, default=4, choices=[1, 2, 4, 8],
+    ap.add_argument("--teams-per-xcd", type=int, default=8, choices=[1, 2, 4, 8],
                     help="mode 3: teams per XCD (2 = twice as many queries in flight, each on half the workgroups)")
     ap.add_argument("--sgs", choices=["sched", "fixed", "off"], default="sched",
                     help="sched = the scheduler re-chooses the cached SubGraph every Q queries; fixed = the smallest "

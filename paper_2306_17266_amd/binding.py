@@ -208,6 +208,7 @@ class Sushi:
         self.arch = None
         self.dtype = None
         self._cfg_cache = {}
+        self._box_cache = {}
 
     def close(self):
         if self._h:
@@ -227,14 +228,23 @@ class Sushi:
                self._h)
         self.arch, self.dtype = arch, dtype
         self._cfg_cache = {}
+        self._box_cache = {}
 
     def sushi_set_subgraph_cache(self, box, budget_bytes):
         """box: list of (K, C, r) per layer, or None to empty the cache."""
         if not box:
             _check(lib().sushi_set_subgraph_cache(self._h, None, 0), self._h)
             return
-        arr = (CLayerDims * len(box))(*[CLayerDims(k, c, r) for (k, c, r) in box])
-        g = CSubgraphCfg(len(box), arr)
+        try:
+            key = tuple(box)
+            g = self._box_cache.get(key)
+        except TypeError:  # layers given as lists: marshal every time
+            key, g = None, None
+        if g is None:
+            arr = (CLayerDims * len(box))(*[CLayerDims(k, c, r) for (k, c, r) in box])
+            g = CSubgraphCfg(len(box), arr)
+            if key is not None and len(self._box_cache) < 1024:
+                self._box_cache[key] = g
         _check(lib().sushi_set_subgraph_cache(self._h, C.byref(g), int(budget_bytes)), self._h)
 
     def sushi_infer(self, cfg, x, logits):

@@ -2,6 +2,7 @@
 // per-query plan cache and launch loop, counters.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <chrono>
 #include <cmath>
 #include <cstdio>
@@ -601,9 +602,10 @@ int build_res_table(sushi_ctx *c) {
         R.n_res = (g.K + 15) / 16;
         R.first_entry = (int)c->h_res_entries.size();
         bool any = false;
+        long most_free = RES_STORE_BYTES - *std::min_element(used.begin(), used.end());
         for (int f = 0; f < R.n_res; ++f) {
             ResEntry e{-1, 0};
-            for (int k = 0; k < team_size; ++k) {
+            for (int k = 0; k < team_size && slab <= most_free; ++k) {
                 const int r = (cursor + k) % team_size;
                 if (used[r] + slab <= RES_STORE_BYTES) {
                     e.owner = r, e.lds_off = (int)used[r];
@@ -611,6 +613,7 @@ int build_res_table(sushi_ctx *c) {
                     cursor = (r + 1) % team_size;
                     c->table_bytes += (uint64_t)taps * cg_res * 8 * std::min(16, g.K - 16 * f) * 2;
                     any = true;
+                    most_free = RES_STORE_BYTES - *std::min_element(used.begin(), used.end());
                     break;
                 }
             }
