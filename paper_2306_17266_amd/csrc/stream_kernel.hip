@@ -2093,6 +2093,9 @@ __global__ __launch_bounds__(STREAM_THREADS, 2) void sushi_team_kernel(TeamArgs 
             if (!team_barrier<false>(ta, team, tsize, epoch, &flag)) return;
             if (ta.trace && rank == 0 && threadIdx.x == 0 && i + 1 < TRACE_SLOTS)
                 ta.trace[team * TRACE_SLOTS + i + 1] = wall_clock64();
+            // a team at work keeps all teams alive: were the idle ones to leave during a query that takes
+            // longer than the idle limit, a post to one of them would wait for the whole kernel to leave
+            if (rank == 0 && threadIdx.x == 0) st_agent(&ta.sync[SY_CLOCK], (unsigned long long)wall_clock64());
         }
         // every workgroup's (write-through) logits stores have completed: report
         if (rank == 0 && threadIdx.x == 0)
