@@ -80,7 +80,7 @@ def build_workload(name):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--steps", type=int, default=4000)
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="resnet_bs1_sticky")
     ap.add_argument("--exec-mode", type=int, default=3,
