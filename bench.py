@@ -1,9 +1,12 @@
 """Benchmark of the SubNet-stream hot path on one MI355X.
 
-One step = one query: the scheduler's cache bookkeeping (sushi_sched_record, and
-sushi_set_subgraph_cache when the cached SubGraph changes) plus sushi_infer of the query's SubNet
-on one input batch that already sits in HBM.  The default workload is the ResNet50-shaped
-SuperNet at batch 1 with the sticky 1000-query stream (next SubNet repeats with p = 0.8).
+One step = one block of `queries_per_step` consecutive queries of the workload's stream (200 at
+batch 1, 100 at batch 16), so that `--steps 20 --warmup 5` times 4000 queries of steady state after
+1000 warm-up queries.  A query is: the scheduler's part (sushi_sched_step when the stream gives
+latency targets, else sushi_sched_record of the named SubNet; sushi_set_subgraph_cache when the
+cached SubGraph changes) plus sushi_infer on one input batch that already sits in HBM.  The timed
+region starts with the persistent kernel stopped and ends when it has stopped again, so it holds
+exactly one launch of it.
 
 Prints ONE JSON line: queries/s over the timed steps, plus
   roofline      the kernel with the largest summed time, measured with HIP events on the stream it
@@ -51,51 +54,32 @@ def stored_traffic(workload, mode, teams_per_xcd, sgs, Q):
     return float(kv["fetch_bytes_per_query"]) + float(kv["write_bytes_per_query"])
 
 
-def build_workload(name):
-    from workloads import arch as A
-    from workloads import streams
-    if name == "resnet_bs1_sticky":
-        arch = A.resnet_arch()
-        return dict(arch=arch, batch=1, cfgs=streams.stream_sticky(arch, 1000, 2, 0.8, 224), Q=8,
-                    budget=16 << 20, desc="ResNet50-shaped SuperNet, bf16, batch 1, 224x224, 1000-query stream, "
-                    "next SubNet repeats with p=0.8 else uniform, cache re-chosen every 8 queries, budget 16 MiB")
-    if name == "mbv3_bs1_zipf":
-        arch = A.mbv3_arch()
-        pool = streams.subnet_pool(arch, 32, 3, 224)
-        cfgs = [pool[i] for i, _ in streams.stream_zipf(32, 1000, 3, 1.2)]
-        return dict(arch=arch, batch=1, cfgs=cfgs, Q=10, budget=4 << 20,
-                    desc="MobileNetV3-shaped SuperNet, bf16, batch 1, 224x224, 1000-query stream, Zipf(1.2) over a "
-                    "pool of 32 SubNets, cache re-chosen every 10 queries, budget 4 MiB")
-    if name == "resnet_bs16_levels":
-        arch = A.resnet_arch()
-        pool = streams.subnet_pool(arch, 16, 4, 224)
-        lv = streams.stream_levels(5, 2000, 4)
-        # without a measured latency table the level picks a SubNet of the pool by size rank
-        return dict(arch=arch, batch=16, cfgs=None, pool=pool, levels=lv, Q=8, budget=64 << 20,
-                    desc="ResNet50-shaped SuperNet, bf16, batch 16, 224x224, 2000-query stream, SubNet picked by "
-                    "a latency target drawn from 5 levels (table = weight bytes not cached), budget 64 MiB")
-    raise SystemExit("unknown workload %r" % name)
-
-
 def main():
+    from workloads import configs
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=4000)
-    ap.add_argument("--warmup", type=int, default=50)
-    ap.add_argument("--workload", default="resnet_bs1_sticky")
+    ap.add_argument("--steps", type=int, default=20, help="timed blocks of queries")
+    ap.add_argument("--warmup", type=int, default=5, help="untimed blocks of queries before them")
+    ap.add_argument("--queries-per-step", type=int, default=0, help="default: 200 at batch 1, 100 at batch 16")
+    ap.add_argument("--workload", default="resnet_bs1_sticky", choices=[n for n in configs.NAMES if n != "tiny_uniform"])
+    ap.add_argument("--budget-mib", type=int, default=0, help="SubGraph cache budget (default: the workload's)")
     ap.add_argument("--exec-mode", type=int, default=3,
                     help="0 = launch per layer, 1 = HIP graph replay, 2 = stream kernel, 3 = persistent XCD-team kernel")
-    ap.add_argument("--teams-per-xcd", type=int, default=8, choices=[1, 2, 4, 8],
-                    help="mode 3: teams per XCD (2 = twice as many queries in flight, each on half the workgroups)")
+    ap.add_argument("--teams-per-xcd", type=int, default=0, choices=[0, 1, 2, 4, 8],
+                    help="mode 3: teams per XCD (default 8 at batch 1, 1 at batch 16)")
     ap.add_argument("--sgs", choices=["sched", "fixed", "off"], default="sched",
                     help="sched = the scheduler re-chooses the cached SubGraph every Q queries; fixed = the smallest "
                          "SubNet of the stream, shrunk to the budget, is cached once and kept (the state-unaware "
                          "baseline of the paper's scheduler ablation); off = nothing is cached")
     ap.add_argument("--Q", type=int, default=0, help="queries between cache re-choices (default: the workload's)")
+    ap.add_argument("--cold-sweep", action="store_true",
+                    help="modes 0-2: stream a 512 MiB scratch buffer through the caches before every query (a device "
+                         "whose caches are lost between queries)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="run one 256 MiB device-to-device copy first (reference dispatch for byte counters)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-roofline", action="store_true")
+    ap.add_argument("--no-latency", action="store_true", help="skip the lone-query latency passes")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py: the library runs on ONE GPU; --gpus %d is not supported (with more GPUs each "
@@ -105,52 +89,91 @@ def main():
     import torch
 
     import paper_2306_17266_amd as S
+    from paper_2306_17266_amd import sushiabs
+    from workloads import streams
     from workloads import tensors as T
 
-    wl = build_workload(args.workload)
+    wl = configs.build(args.workload, args.budget_mib or None)
     arch, batch, Q, budget = wl["arch"], wl["batch"], args.Q or wl["Q"], wl["budget"]
+    qps = args.queries_per_step or (200 if batch == 1 else 100)
+    teams = args.teams_per_xcd or (8 if batch == 1 else 1)
     table = S.sushi_describe_supernet(arch)
     tensors = T.make_weights([(s, k) for _, s, k in table], 1, True)
     ctx = S.Sushi(0)
     ctx.sushi_load_supernet(arch, T.flatten(tensors), S.BF16)
+    mode = args.exec_mode
+    ctx.sushi_set_option(S.OPT_EXEC_MODE, mode)
+    ctx.sushi_set_option(S.OPT_TEAMS_PER_XCD, teams)
+    if args.cold_sweep:
+        ctx.sushi_set_option(S.OPT_COLD_SWEEP_MIB, 512)
 
-    # the stream, each SubNet's vector/box (library's encoder) and the candidate SubGraphs
-    from workloads import streams
-    if wl["cfgs"] is None:
-        pool = wl["pool"]
-        boxes = [S.sushi_subnet_layers(arch, c) for c in pool]
-        order = sorted(range(len(pool)), key=lambda i: streams.box_bytes(boxes[i], 2))
-        pick = [order[(lv * (len(pool) - 1)) // 4] for lv in range(5)]
-        cfgs = [pool[pick[lv]] for lv in wl["levels"]]
-    else:
-        cfgs = wl["cfgs"]
+    # the serving SubNets, each one's vector/box (library's encoder) and the candidate SubGraphs
+    by_target = wl["cfgs"] is None
+    serving = wl["pool"] if by_target else wl["cfgs"]
     distinct = {}
-    for c in cfgs:
+    for c in serving:
         distinct.setdefault(c.key(), c)
     box_of = {k: S.sushi_subnet_layers(arch, c) for k, c in distinct.items()}
     vec_of = {k: np.array([v for (kk, cc, r) in b for v in (kk, cc)], dtype=np.int32) for k, b in box_of.items()}
     cands = streams.candidate_subgraphs(list(box_of.values()), budget, 2, 40)
     gvecs = [[v for (k, c, r) in b for v in (k, c)] for b in cands]
     n = len(gvecs[0])
-    ctx.sushi_sched_init([[0] * n], [0.0], gvecs, [[1.0] * (len(gvecs) + 1)], Q, S.STRICT_LATENCY)
 
+    res_list = sorted({c.resolution for c in serving})
     n_inputs, n_outputs = 8, 64
-    res = cfgs[0].resolution
-    xs = [torch.from_numpy(T.make_input(11, t, batch, res, arch.in_channels, True)).cuda().to(torch.bfloat16)
-          for t in range(n_inputs)]
+    xs = {r: [torch.from_numpy(T.make_input(11, t, batch, r, arch.in_channels, True)).cuda().to(torch.bfloat16)
+              for t in range(n_inputs)] for r in res_list}
     outs = [torch.empty(batch, arch.n_classes, device="cuda", dtype=torch.float32) for _ in range(n_outputs)]
     torch.cuda.synchronize()
-    state = {"cache": -1, "t": 0}
 
-    def step():
+    levels = None
+    table_info = None
+    if by_target:
+        # Algorithm 1 in the loop: the latency table L[SubNet][cached SubGraph] measured on this GPU (frozen
+        # to a file when one is shipped for this workload), synthetic accuracies that grow with SubNet size
+        pool = wl["pool"]
+        sizes = [streams.box_bytes(box_of[c.key()], 2) for c in pool]
+        acc = [0.0] * len(pool)
+        for rank, i in enumerate(sorted(range(len(pool)), key=lambda i: sizes[i])):
+            acc[i] = float(np.float32(0.70 + 0.01 * rank))
+        frozen = sushiabs.load_table(sushiabs.table_path(args.workload, budget), len(pool), len(cands))
+        if frozen is not None:
+            lat, table_info = frozen["table"], "frozen: " + os.path.relpath(sushiabs.table_path(args.workload, budget), ROOT)
+        else:
+            lat = sushiabs.measure_table(ctx, pool, cands, budget, xs[res_list[0]][0], outs[0], runs=3)
+            table_info = "measured in this run (3 runs per entry)"
+            out_dir = os.path.join(ROOT, "gpurun_out")
+            if os.path.isdir(out_dir):
+                sushiabs.save_table(os.path.join(out_dir, os.path.basename(sushiabs.table_path(args.workload, budget))),
+                                    lat, args.workload, budget, 3)
+        levels = sushiabs.latency_levels(lat, wl["n_levels"])
+        ctx.sushi_sched_init([vec_of[c.key()] for c in pool], acc, gvecs, lat, Q, S.STRICT_LATENCY)
+    else:
+        ctx.sushi_sched_init([[0] * n], [0.0], gvecs, [[1.0] * (len(gvecs) + 1)], Q, S.STRICT_LATENCY)
+
+    state = {"cache": -1, "t": 0}
+    served = {}
+
+    def one_query():
         t = state["t"]
-        cfg = cfgs[t % len(cfgs)]
-        ctx.sushi_infer(cfg, xs[t % n_inputs], outs[t % n_outputs])
-        j = ctx.sushi_sched_record(vec_of[cfg.key()])
+        if by_target:
+            i, j = ctx.sushi_sched_step(0.0, levels[wl["levels"][t % len(wl["levels"])]])
+            cfg = wl["pool"][i]
+            served[i] = served.get(i, 0) + 1
+        else:
+            cfg = serving[t % len(serving)]
+            j = None
+        ctx.sushi_infer(cfg, xs[cfg.resolution][t % n_inputs], outs[t % n_outputs])
+        if j is None:
+            j = ctx.sushi_sched_record(vec_of[cfg.key()])
         if args.sgs == "sched" and j >= 0 and j != state["cache"]:
             ctx.sushi_set_subgraph_cache(cands[j], budget)
             state["cache"] = j
         state["t"] = t + 1
+
+    def step():
+        for _ in range(qps):
+            one_query()
 
     if args.calibration_copy:
         src = torch.zeros(256 << 20, dtype=torch.uint8, device="cuda")
@@ -158,45 +181,56 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    mode = args.exec_mode
-    ctx.sushi_set_option(S.OPT_EXEC_MODE, mode)
-    ctx.sushi_set_option(S.OPT_TEAMS_PER_XCD, args.teams_per_xcd)
+    ctx.sushi_set_subgraph_cache(None, 0)
     if args.sgs == "fixed":
         smallest = min(box_of.values(), key=lambda b: streams.box_bytes(b, 2))
         ctx.sushi_set_subgraph_cache(streams.shrink_box(smallest, budget, 2), budget)
     for _ in range(args.warmup):
         step()
-    ctx.sushi_synchronize()
+    ctx.sushi_quiesce()          # the timed region gets a kernel launch of its own (mode 3)
     t_start = state["t"]
     # The timed region.  Modes 2 and 3 are timed with their HIP events in place (one pair per query
     # launch / one pair around the persistent kernel); modes 0 and 1 are timed bare and measured per
     # kernel in a second pass below.
     live_events = mode in (2, 3) and not args.no_roofline
-    if mode == 3:
-        ctx.sushi_quiesce()          # the timed region gets a kernel launch of its own
     if live_events:
         ctx.sushi_set_option(S.OPT_KERNEL_TIMING, 1)
+    stats0 = ctx.sushi_get_stats()
+    torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
-    ctx.sushi_synchronize()
+    ctx.sushi_quiesce()          # all queries done and the persistent kernel gone: its launch lies inside [t0, t1]
+    torch.cuda.synchronize()
     t1 = time.perf_counter()
     elapsed = t1 - t0
+    n_queries = args.steps * qps
     stats = ctx.sushi_get_stats()
+    dstat = {k: stats[k] - stats0[k] for k in stats if isinstance(stats[k], int) or k == "sum_hit_ratio"}
     ks = None
     if live_events:
         ks = [k for k in ctx.sushi_get_kernel_stats() if k["launches"]]
         ctx.sushi_set_option(S.OPT_KERNEL_TIMING, 0)
 
-    # p50 latency of a lone query: post, wait, repeat (same steps as the timed region)
-    lat = []
-    state["t"] = t_start
-    for _ in range(min(args.steps, 200)):
-        a = time.perf_counter()
-        step()
-        ctx.sushi_synchronize()
-        lat.append(time.perf_counter() - a)
-    p50_ms = float(np.median(lat) * 1e3)
+    # p50 latency of a lone query: post, wait, repeat (same queries as the timed region); then the same
+    # through one launch per layer (mode 0), the shortest path for a query that has the GPU to itself
+    p50_ms = p50_mode0_ms = None
+    if not args.no_latency:
+        def lone_pass(count):
+            lat = []
+            state["t"] = t_start
+            for _ in range(count):
+                a = time.perf_counter()
+                one_query()
+                ctx.sushi_synchronize()
+                lat.append(time.perf_counter() - a)
+            return float(np.median(lat) * 1e3)
+        p50_ms = lone_pass(200 if batch == 1 else 50)
+        if mode != 0 and not args.cold_sweep:
+            ctx.sushi_set_option(S.OPT_EXEC_MODE, 0)
+            lone_pass(10)
+            p50_mode0_ms = lone_pass(200 if batch == 1 else 50)
+            ctx.sushi_set_option(S.OPT_EXEC_MODE, mode)
 
     roofline = None
     if not args.no_roofline:
@@ -205,7 +239,7 @@ def main():
             ctx.sushi_set_option(S.OPT_EXEC_MODE, 0)
             state["t"] = t_start
             for _ in range(20):
-                step()
+                one_query()
             ctx.sushi_synchronize()
             state["t"] = t_start
             ctx.sushi_set_option(S.OPT_KERNEL_TIMING, 1)
@@ -222,16 +256,19 @@ def main():
             achieved, peak, unit, bound = dom["flops"] / sec / 1e12, MFMA_BF16_PEAK_TFLOPS, "TFLOP/s", "mfma"
         else:
             achieved, peak, unit, bound = dom["bytes"] / sec / 1e9, HBM_PEAK_GBS, "GB/s", "hbm"
-        # measured bytes per launch of the dominant kernel: known only for the team kernel, whose one
-        # launch serves all timed queries
+        # measured bytes per launch of the dominant kernel: a STORED counter reading (two rocprofv3 --pmc runs
+        # of this command), valid only for the configuration and the sources it was taken with
         traffic = None
         if mode == 3 and dom["launches"] == 1:
-            per_query = stored_traffic(args.workload, mode, args.teams_per_xcd, args.sgs, Q)
+            per_query = stored_traffic(args.workload, mode, teams, args.sgs, Q)
             if per_query is not None:
-                traffic = per_query * args.steps
+                traffic = per_query * n_queries
         roofline = {"bound": bound, "achieved": achieved, "peak": peak, "unit": unit, "frac": achieved / peak,
-                    "traffic": traffic, "kernel": dom["name"], "launches": dom["launches"],
+                    "traffic": traffic,
+                    "traffic_source": "stored reading, profiles/team_kernel_traffic.txt" if traffic is not None else None,
+                    "kernel": dom["name"], "launches": dom["launches"],
                     "avg_launch_us": dom["total_ms"] * 1e3 / dom["launches"],
+                    "kernel_ms_per_step": dom["total_ms"] / args.steps,
                     "alg_bytes_per_launch": dom["bytes"] / dom["launches"],
                     "alg_flops_per_launch": dom["flops"] / dom["launches"],
                     "arithmetic_intensity": ai,
@@ -244,30 +281,43 @@ def main():
     if not args.no_cpu_baseline:
         from oracle import subnet_eval as E
         wts = E.name_weights(arch, tensors)
-        n_sample = 16 if batch == 1 else 2
-        sample = [cfgs[(t_start + i * 7) % len(cfgs)] for i in range(n_sample)]
-        x0 = np.ascontiguousarray(T.make_input(11, 0, batch, res, arch.in_channels, True).transpose(0, 3, 1, 2))
-        E.forward(arch, wts, sample[0], x0)
+        n_sample = 64 if batch == 1 else 4
+        sample = [serving[(t_start + i * 7) % len(serving)] for i in range(n_sample)]
+        x_of = {r: np.ascontiguousarray(T.make_input(11, 0, batch, r, arch.in_channels, True).transpose(0, 3, 1, 2))
+                for r in res_list}
+        E.forward(arch, wts, sample[0], x_of[sample[0].resolution])
         c0 = time.perf_counter()
+        done = 0
         for cfg in sample:
-            E.forward(arch, wts, cfg, x0)
+            E.forward(arch, wts, cfg, x_of[cfg.resolution])
+            done += 1
+            if time.perf_counter() - c0 > 25.0:
+                break
         c1 = time.perf_counter()
         cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
-        cpu = {"value": n_sample / (c1 - c0), "unit": "queries/s", "cores": cores, "kind": "oracle",
-               "sample": "%d queries of the same stream (every 7th from the first timed step), batch %d, "
-                         "%.1f s of CPU work" % (n_sample, batch, c1 - c0)}
+        cpu = {"value": done / (c1 - c0), "unit": "queries/s", "cores": cores, "kind": "oracle",
+               "sample": "%d queries of the same stream (every 7th from the first timed query), batch %d, "
+                         "%.1f s of CPU work" % (done, batch, c1 - c0)}
 
-    out = {"metric": "SubNet queries/sec (batch %d)" % batch, "value": args.steps / elapsed, "unit": "queries/s",
+    nq = max(1, dstat["queries"])
+    out = {"metric": "SubNet queries/sec (batch %d)" % batch, "value": n_queries / elapsed, "unit": "queries/s",
            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": elapsed / args.steps * 1e3,
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-           "config": {"workload": args.workload, "description": wl["desc"], "exec_mode": args.exec_mode, "teams_per_xcd": args.teams_per_xcd, "sgs": args.sgs, "Q": Q,
-                      "distinct_subnets": len(distinct), "candidate_subgraphs": len(cands)},
-           "p50_latency_ms": p50_ms,
-           "weight_bytes_per_query": stats["weight_bytes_total"] / max(1, stats["queries"]),
-           "weight_bytes_per_query_in_cached_subgraph": stats["weight_bytes_resident"] / max(1, stats["queries"]),
-           "weight_bytes_per_query_from_lds": stats["weight_bytes_lds"] / max(1, stats["queries"]),
-           "mean_hit_ratio": stats["sum_hit_ratio"] / max(1, stats["queries"]),
-           "cache_installs": stats["cache_installs"],
+           "config": {"workload": args.workload, "description": wl["desc"], "queries_per_step": qps,
+                      "timed_queries": n_queries, "warmup_queries": args.warmup * qps, "exec_mode": mode,
+                      "teams_per_xcd": teams, "sgs": args.sgs, "Q": Q, "budget_bytes": budget,
+                      "cold_sweep": bool(args.cold_sweep),
+                      "distinct_subnets": len(distinct), "candidate_subgraphs": len(cands),
+                      "latency_table": table_info,
+                      "subnets_served": len(served) if by_target else len({c.key() for c in serving})},
+           "p50_latency_ms": p50_ms, "p50_latency_ms_mode0": p50_mode0_ms,
+           "weight_bytes_per_query": dstat["weight_bytes_total"] / nq,
+           "weight_bytes_per_query_inside_cached_subgraph": dstat["weight_bytes_in_subgraph"] / nq,
+           "weight_bytes_per_query_from_lds": dstat["weight_bytes_lds"] / nq,
+           "mean_hit_ratio": dstat["sum_hit_ratio"] / nq,
+           "cache_installs": dstat["cache_installs"],
+           "residency_changes": dstat["residency_changes"],
+           "install_bytes_per_team_lds": dstat["install_bytes_lds"],
            "roofline": roofline, "cpu_baseline": cpu}
     print(json.dumps(out))
     ctx.close()

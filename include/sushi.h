@@ -158,18 +158,28 @@ typedef struct sushi_sched_desc {
 typedef struct sushi_stats {
     uint64_t queries;                /* sushi_infer calls that enqueued work                          */
     uint64_t weight_bytes_total;     /* sum over queries of the SubNet's weight bytes                 */
-    uint64_t weight_bytes_resident;  /* of those, bytes inside the cached SubGraph (not re-fetched)   */
+    uint64_t weight_bytes_in_subgraph; /* of those, bytes that lie inside the cached SubGraph G (the
+                                        closed form bytes(SN ∩ G) the scheduler's table reasons with; a
+                                        nominal figure: what of G really sits on chip is the next but
+                                        one counter)                                                   */
     uint64_t last_weight_bytes;      /* the same two figures for the last query                       */
-    uint64_t last_resident_bytes;
+    uint64_t last_in_subgraph_bytes;
     uint64_t cache_installs;         /* sushi_set_subgraph_cache calls that installed a SubGraph      */
-    uint64_t cache_bytes_installed;  /* bytes moved by them                                           */
-    uint64_t cache_bytes;            /* size of the SubGraph cached now                               */
+    uint64_t cache_bytes_installed;  /* sum of bytes(G) over them (nominal, as above)                 */
+    uint64_t cache_bytes;            /* bytes(G) of the SubGraph cached now                           */
     double last_hit_ratio;           /* ||SN ∩ G||_2 / ||SN||_2 on the [K,C] vectors (Appendix A.4)   */
     double sum_hit_ratio;            /* summed over queries                                           */
     uint64_t plan_cache_hits, plan_cache_misses;
-    uint64_t weight_bytes_lds;       /* team kernel: weight bytes read from resident LDS slabs, summed   */
+    uint64_t weight_bytes_lds;       /* team kernel: weight bytes the queries took from resident LDS slabs
+                                        instead of memory, counted on the host from the residency table
+                                        each query ran under (the only bytes that are never fetched)   */
     uint64_t last_lds_bytes;         /* the same for the last query                                    */
-    uint64_t cache_bytes_lds;        /* bytes of the cached SubGraph that fit the LDS stores (per XCD) */
+    uint64_t cache_bytes_lds;        /* bytes of the cached SubGraph that sit in a team's LDS stores    */
+    uint64_t residency_changes;      /* cache changes that altered what a team's LDS stores hold (a new residency
+                                        table was published; the others changed the SubGraph outside the stores) */
+    uint64_t install_bytes_lds;      /* slab bytes those changes make valid that were not valid under the table
+                                        before: what ONE team copies into its LDS if it serves a query under
+                                        every table (a team that skips tables copies less)               */
 } sushi_stats;
 
 /* ---------------------------------------------------------------- host-only helpers (no GPU needed) */
@@ -292,8 +302,12 @@ typedef enum {
                                    More, smaller teams serve more queries at a time, each more slowly:
                                    more queries per second, longer latency of a lone query.
                                    Only before the first query in mode 3 */
-    SUSHI_OPT_IDLE_US = 3       /* microseconds without a query after which the team kernel leaves
+    SUSHI_OPT_IDLE_US = 3,      /* microseconds without a query after which the team kernel leaves
                                    (default 2000); the next query starts it again */
+    SUSHI_OPT_COLD_SWEEP_MIB = 7 /* modes 0 - 2, measurement aid: before every query a kernel streams a scratch
+                                   buffer of this many MiB (0 = off, at most 4096) through the caches, so the
+                                   query finds none of its weights on chip: a device that loses its caches
+                                   between queries, the premise the paper's SGS starts from (Section 4.3) */
 } sushi_option;
 int sushi_set_option(sushi_ctx *ctx, int option, int64_t value);
 

@@ -18,6 +18,7 @@ OPT_IDLE_US = 3
 OPT_STREAM_WGS = 4
 OPT_TEAM_WGS_PER_CU = 5
 OPT_TEAMS_PER_XCD = 6
+OPT_COLD_SWEEP_MIB = 7
 
 
 class SushiError(RuntimeError):
@@ -72,12 +73,13 @@ class CSchedDesc(C.Structure):
 
 
 class CStats(C.Structure):
-    _fields_ = [("queries", C.c_uint64), ("weight_bytes_total", C.c_uint64), ("weight_bytes_resident", C.c_uint64),
-                ("last_weight_bytes", C.c_uint64), ("last_resident_bytes", C.c_uint64),
+    _fields_ = [("queries", C.c_uint64), ("weight_bytes_total", C.c_uint64), ("weight_bytes_in_subgraph", C.c_uint64),
+                ("last_weight_bytes", C.c_uint64), ("last_in_subgraph_bytes", C.c_uint64),
                 ("cache_installs", C.c_uint64), ("cache_bytes_installed", C.c_uint64), ("cache_bytes", C.c_uint64),
                 ("last_hit_ratio", C.c_double), ("sum_hit_ratio", C.c_double),
                 ("plan_cache_hits", C.c_uint64), ("plan_cache_misses", C.c_uint64),
-                ("weight_bytes_lds", C.c_uint64), ("last_lds_bytes", C.c_uint64), ("cache_bytes_lds", C.c_uint64)]
+                ("weight_bytes_lds", C.c_uint64), ("last_lds_bytes", C.c_uint64), ("cache_bytes_lds", C.c_uint64),
+                ("residency_changes", C.c_uint64), ("install_bytes_lds", C.c_uint64)]
 
 
 class CKernelStats(C.Structure):

@@ -509,6 +509,23 @@ __global__ __launch_bounds__(256) void gate_kernel(PoolArgs a) {
     store8(static_cast<T *>(a.y) + m * a.C + cg * 8, xv);
 }
 
+// ------------------------------------------------------------------ cache sweep
+
+__global__ __launch_bounds__(256) void cold_sweep_kernel(const uint4 *buf, size_t n, uint4 *sink) {
+    uint4 acc = make_uint4(0, 0, 0, 0);
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
+        const uint4 v = buf[i];
+        acc.x ^= v.x, acc.y ^= v.y, acc.z ^= v.z, acc.w ^= v.w;
+    }
+    if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9E3779B9u && threadIdx.x == 0) sink[blockIdx.x] = acc;  // (never, for a zeroed buffer)
+}
+
+hipError_t launch_cold_sweep(const void *buf, size_t bytes, void *sink, hipStream_t s) {
+    hipLaunchKernelGGL(cold_sweep_kernel, dim3(2048), dim3(256), 0, s, static_cast<const uint4 *>(buf), bytes / 16,
+                       static_cast<uint4 *>(sink));
+    return hipGetLastError();
+}
+
 // ------------------------------------------------------------------ launchers
 
 static inline unsigned blocks_for(long total) { return (unsigned)((total + 255) / 256); }

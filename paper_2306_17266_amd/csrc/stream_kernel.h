@@ -55,14 +55,18 @@ struct StreamArgs {
 // team leave, so the kernel always ends by itself.
 constexpr int MAX_XCDS = 8;
 constexpr int MAX_TEAMS = 64;  // up to eight teams per XCD
-enum TeamCmd { TEAM_RUN = 0, TEAM_STOP = 1, TEAM_INSTALL = 2, TEAM_SKIP = 3 };  // TEAM_SKIP: kernel-internal, an install the next post replaces
+enum TeamCmd { TEAM_RUN = 0, TEAM_STOP = 1 };
 
 // SubGraph residency inside the team kernel (the persistent buffer of the paper, Section 4.2.2, kept
 // in LDS): every workgroup of a team owns RES_STORE_BYTES of LDS that survive from query to query.
-// The cached SubGraph is cut into slabs, one per 16-filter tile of a layer:
-// [tap][channel group < cg_res][16 filters][8 channels] bf16, i.e. 256 bytes per (tap, group).  Slab f
+// The store is cut into slabs, one per 16-filter tile of a layer:
+// [tap][channel group < cg_stride][16 filters][8 channels] bf16, i.e. 256 bytes per (tap, group).  Slab f
 // of a layer lives in the LDS of workgroup `owner` at byte offset `lds_off`; that workgroup computes
 // filter tile f of the layer for every query and reads those weights from LDS instead of memory.
+// Which slab sits where (the geometry) is fixed for as long as the cached SubGraphs fit it: a layer's
+// slabs are as wide (cg_stride) and as many as the largest SubGraph cached so far asked for.  A new
+// SubGraph then only changes how much of every slab is valid (tiles below n_res, channel groups below
+// cg_res), and an install copies just the cells that were not valid before.
 // Every team holds the same slabs.  Only layers that run as a single pixel group (at most 64 output
 // pixels per query: the late stages, squeeze-excite and classifier layers, which hold most of the
 // weights) use their slabs.
@@ -70,23 +74,25 @@ constexpr int RES_STORE_BYTES = 120 * 1024;
 constexpr int RED_BYTES = STREAM_WAVES * 4 * 256 * 4;  // partial-sum scratch in front of the store
 
 struct ResEntry {
-    int owner;    // rank inside the team, -1 = not resident
+    int owner;    // rank inside the team, -1 = the geometry has no slab for this tile
     int lds_off;  // byte offset inside the owner's store
 };
 
 struct ResLayer {
     const void *w;  // packed weights of the layer (DEVICE)
     int Kpad, CG, taps;
-    int cg_res;      // resident channel groups of every resident tile
-    int n_res;       // filter tiles 0 .. n_res-1 may be resident (see entries)
+    int cg_res;      // valid channel groups of every valid tile (cached SubGraph's channels, at most cg_stride)
+    int n_res;       // filter tiles 0 .. n_res-1 are valid where the geometry has a slab for them (see entries)
     int first_entry; // index of tile 0's entry in ResTable::entries
+    int cg_stride;   // channel groups a slab of this layer has room for
+    int pad;
 };
 
 // The host writes a table into pinned HOST memory; a team copies it into device memory of its own
 // before it uses it (see TeamArgs::team_mem), with `layers` and `entries` pointing into that copy.
 struct ResTable {
     int n_layers, team_size;  // team size the owners were assigned for
-    int n_entries, pad;
+    int n_entries, geometry;  // tables with the same geometry number place every slab alike
     const ResLayer *layers;   // one per SuperNet layer
     const ResEntry *entries;
 };
@@ -99,11 +105,18 @@ constexpr int TEAM_PROG_MAX_OPS = 512;
 struct TeamPost {  // written by the host
     unsigned long long seq;  // the post's number (1, 2, ...)
     int cmd, n_ops;
-    const DevOp *prog;  // pinned HOST; activation pointers are arena offsets + 1 (TEAM_INSTALL: a ResTable, pinned HOST)
+    const DevOp *prog;  // pinned HOST; activation pointers are arena offsets + 1
     const void *input;  // DEVICE
     void *logits;       // DEVICE
-    unsigned long long pad[3];
+    // The residency table the query runs under (pinned HOST, null: nothing cached) and its number.  A team
+    // that holds another number brings its LDS stores up to this table before it runs the query, so a team
+    // pays for a change of the cached SubGraph once per query at most, however many changes went by
+    // since its last query.
+    const ResTable *table;
+    unsigned long long table_seq;  // > 0
+    unsigned long long pad;
 };
+static_assert(sizeof(TeamPost) == 64, "a post is eight 8-byte words");
 
 constexpr int POST_RING = 32;  // posts a team's mailbox holds (post number s sits in slot s % POST_RING)
 
@@ -126,13 +139,14 @@ struct TeamArgs {
     long idle_ticks;           // 100 MHz ticks a leader waits for a post before its team leaves
     int teams_per_xcd;         // 1: the workgroups of an XCD form one team; 2, 4, 8: that many teams, each a share of them
     int spin_limit;
-    const ResTable *table;     // pinned HOST or null: SubGraph to install when the kernel starts
-    char *team_mem;            // DEVICE, MAX_TEAMS areas of TEAM_MEM_BYTES: [program][residency table]
+    char *team_mem;            // DEVICE, MAX_TEAMS areas of TEAM_MEM_BYTES: [program][two residency tables]
     unsigned long long *trace;  // DEVICE or null: [MAX_TEAMS][TRACE_SLOTS] 100 MHz timestamps, one after each op
 };
 constexpr int TRACE_SLOTS = 256;
+// [program][residency table][residency table]: the table in use and the one before it (an install reads both)
 constexpr long TEAM_TABLE_OFFSET = (long)TEAM_PROG_MAX_OPS * sizeof(DevOp);
-constexpr long TEAM_MEM_BYTES = TEAM_TABLE_OFFSET + 64 + (long)RES_MAX_LAYERS * sizeof(ResLayer) + (long)RES_MAX_ENTRIES * sizeof(ResEntry);
+constexpr long TEAM_TABLE_BYTES = 64 + (long)RES_MAX_LAYERS * sizeof(ResLayer) + (long)RES_MAX_ENTRIES * sizeof(ResEntry);
+constexpr long TEAM_MEM_BYTES = TEAM_TABLE_OFFSET + 2 * TEAM_TABLE_BYTES;
 static_assert(sizeof(DevOp) % 8 == 0, "programs are copied in 8-byte words");
 
 hipError_t launch_team_kernel(const TeamArgs &a, int nwg, hipStream_t s);

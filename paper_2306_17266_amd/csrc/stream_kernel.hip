@@ -302,7 +302,7 @@ struct StepTables {
 };
 constexpr unsigned OOB_OFFSET = 0x7FFFFFF0u;  // past the end of any buffer: a buffer load there returns zeros
 
-__device__ __forceinline__ void build_step_tables(const ConvArgs &a, int cg_res, StepTables tb) {
+__device__ __forceinline__ void build_step_tables(const ConvArgs &a, int cg_stride, StepTables tb) {
     const int csteps = (a.C + 31) >> 5;
     const int nsteps = a.R * a.R * csteps;
     for (int st = threadIdx.x; st <= nsteps; st += STREAM_THREADS) {
@@ -315,7 +315,7 @@ __device__ __forceinline__ void build_step_tables(const ConvArgs &a, int cg_res,
             e.y = (unsigned)(((dr * a.W + ds) + c * 4 * a.H * a.W) * 16);
             e.z = c == csteps - 1 ? 0u : 1u << tap;
             e.w = c == csteps - 1 ? 1u << tap : 0u;
-            r.x = (unsigned)((tap * cg_res + c * 4) * 256);
+            r.x = (unsigned)((tap * cg_stride + c * 4) * 256);
             r.y = (unsigned)(c * 4);
         }
         tb.steps[st] = e;
@@ -387,7 +387,7 @@ __device__ __forceinline__ void conv_units(const DevOp &op, float *red, int rank
     const int ftiles = (a.K + 15) >> 4;
     const bool listed = CAN_LIST && rv.layer != nullptr && M <= 64;
     const int cg_res_op = listed ? __builtin_amdgcn_readfirstlane(rv.layer->cg_res) : 0;
-    build_step_tables(a, cg_res_op, tb);
+    build_step_tables(a, listed ? __builtin_amdgcn_readfirstlane(rv.layer->cg_stride) : 0, tb);
     int n_listed = 0;
     if (listed) {
         if (wave == 0) {
@@ -1760,6 +1760,9 @@ __device__ __forceinline__ void invalidate_vector_l1() {
 template <bool INV = true>
 __device__ __forceinline__ bool team_barrier(const TeamArgs &ta, int team, unsigned tsize, unsigned long long e,
                                              int *lds_flag) {
+    // Every store of this wave has been acknowledged by the XCD's L2 (the vector L1 writes through) before the
+    // wave reaches the workgroup barrier, hence before thread 0 counts the workgroup in at that same L2.
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     if (threadIdx.x == 0) {
         unsigned long long *ctr = &ta.sync[sy_barrier(team)];
@@ -1801,7 +1804,7 @@ __device__ __forceinline__ bool fetch_table(const TeamArgs &ta, const ResTable *
     if (threadIdx.x < 4) hdr[threadIdx.x] = ld_sys(reinterpret_cast<const unsigned long long *>(src) + threadIdx.x);
     __syncthreads();
     const int n_layers = min((int)(hdr[0] & 0xFFFFFFFFull), RES_MAX_LAYERS), team_size = (int)(hdr[0] >> 32);
-    const int n_entries = min((int)(hdr[1] & 0xFFFFFFFFull), RES_MAX_ENTRIES);
+    const int n_entries = min((int)(hdr[1] & 0xFFFFFFFFull), RES_MAX_ENTRIES), geometry = (int)(hdr[1] >> 32);
     const unsigned long long *layers = reinterpret_cast<const unsigned long long *>(hdr[2]);
     const unsigned long long *entries = reinterpret_cast<const unsigned long long *>(hdr[3]);
     __syncthreads();  // hdr may be written again
@@ -1810,7 +1813,7 @@ __device__ __forceinline__ bool fetch_table(const TeamArgs &ta, const ResTable *
     ResLayer *dst_layers = reinterpret_cast<ResLayer *>(mem + 64);
     ResEntry *dst_entries = reinterpret_cast<ResEntry *>(mem + 64 + (long)RES_MAX_LAYERS * sizeof(ResLayer));
     if (rank == 0 && threadIdx.x == 0) {
-        dst->n_layers = n_layers, dst->team_size = team_size, dst->n_entries = n_entries, dst->pad = 0;
+        dst->n_layers = n_layers, dst->team_size = team_size, dst->n_entries = n_entries, dst->geometry = geometry;
         dst->layers = dst_layers, dst->entries = dst_entries;
     }
     team_fetch(reinterpret_cast<unsigned long long *>(dst_layers), layers, n_layers * (int)(sizeof(ResLayer) / 8), rank, tsize);
@@ -1821,32 +1824,41 @@ __device__ __forceinline__ bool fetch_table(const TeamArgs &ta, const ResTable *
     return true;
 }
 
-// Copies the slabs this workgroup owns from the packed weights into its LDS store.  `work` is LDS
-// that is idle during an install (the partial-sum area).  The table sits in device memory and every
-// dependent read of it costs a round trip, so nothing here walks it entry by entry: the layers come
-// into LDS in one pass, the entries are searched by all threads at once, and the 16-byte pieces of
-// all owned slabs form one index space that the threads share, eight loads each in flight.
+// Copies slab cells this workgroup owns from the packed weights into its LDS store: all valid cells of
+// `tab`, or, when `prev` (the table installed before, null if none) has the same geometry, only those that
+// `prev` did not make valid already: tiles from prev's n_res on in full, and in the tiles before that the
+// channel groups from prev's cg_res on.  `work` is LDS that is idle during an install (the partial-sum
+// area).  The tables sit in device memory and every dependent read costs a round trip, so nothing here
+// walks them entry by entry: the layers come into LDS in one pass, the entries are searched by all
+// threads at once, and the 16-byte pieces of all cells to copy form one index space that the threads
+// share, eight loads each in flight.
 struct InstallItem {
     int layer_f;      // layer << 16 | filter tile
     int lds_off;      // byte offset of the slab inside the store
-    int first_piece;  // index of the slab's first piece among all pieces of this workgroup
-    int pad;
+    int first_piece;  // index of the item's first piece among all pieces of this workgroup
+    int cg_from;      // first channel group to copy
 };
 constexpr int INSTALL_MAX_ITEMS = RES_STORE_BYTES / 256;  // a slab is at least one 256-byte cell row
-static_assert(RES_MAX_LAYERS * sizeof(ResLayer) + INSTALL_MAX_ITEMS * sizeof(InstallItem) + 16 <= RED_BYTES,
+static_assert(RES_MAX_LAYERS * (sizeof(ResLayer) + 8) + INSTALL_MAX_ITEMS * sizeof(InstallItem) + 16 <= RED_BYTES,
               "the install work area must fit the partial-sum area");
 
-__device__ void install_slabs(const ResTable *tab, int rank, char *store, char *work) {
+__device__ void install_slabs(const ResTable *tab, const ResTable *prev, int rank, char *store, char *work) {
     ResLayer *lay = reinterpret_cast<ResLayer *>(work);
-    InstallItem *items = reinterpret_cast<InstallItem *>(work + RES_MAX_LAYERS * sizeof(ResLayer));
+    int2 *was = reinterpret_cast<int2 *>(work + RES_MAX_LAYERS * sizeof(ResLayer));  // per layer: {n_res, cg_res} valid before
+    InstallItem *items = reinterpret_cast<InstallItem *>(work + RES_MAX_LAYERS * (sizeof(ResLayer) + 8));
     int *cnt = reinterpret_cast<int *>(items + INSTALL_MAX_ITEMS);  // [0] items, [1] pieces
     const int tid = threadIdx.x;
     const int nl = min(tab->n_layers, RES_MAX_LAYERS), ne = min(tab->n_entries, RES_MAX_ENTRIES);
     const ResLayer *layers = tab->layers;
     const ResEntry *entries = tab->entries;
+    const bool keep = prev != nullptr && prev->geometry == tab->geometry && prev->n_layers == tab->n_layers &&
+                      prev->team_size == tab->team_size;
     __syncthreads();  // the work area may still be read by the op before
     if (tid == 0) cnt[0] = 0, cnt[1] = 0;
-    for (int l = tid; l < nl; l += STREAM_THREADS) lay[l] = layers[l];
+    for (int l = tid; l < nl; l += STREAM_THREADS) {
+        lay[l] = layers[l];
+        was[l] = keep ? make_int2(prev->layers[l].n_res, prev->layers[l].cg_res) : make_int2(0, 0);
+    }
     __syncthreads();
     for (int i = tid; i < ne; i += STREAM_THREADS) {
         const ResEntry e = entries[i];
@@ -1854,8 +1866,11 @@ __device__ void install_slabs(const ResTable *tab, int rank, char *store, char *
         int l = 0;
         while (l < nl && !(lay[l].n_res > 0 && i >= lay[l].first_entry && i < lay[l].first_entry + lay[l].n_res)) ++l;
         if (l == nl) continue;
+        const int f = i - lay[l].first_entry;
+        const int cg_from = f < was[l].x ? was[l].y : 0;
+        if (cg_from >= lay[l].cg_res) continue;  // everything this SubGraph wants of the tile is there already
         const int k = atomicAdd(&cnt[0], 1);
-        if (k < INSTALL_MAX_ITEMS) items[k] = InstallItem{(l << 16) | (i - lay[l].first_entry), e.lds_off, 0, 0};
+        if (k < INSTALL_MAX_ITEMS) items[k] = InstallItem{(l << 16) | f, e.lds_off, 0, cg_from};
     }
     __syncthreads();
     const int n = min(cnt[0], INSTALL_MAX_ITEMS);
@@ -1864,7 +1879,7 @@ __device__ void install_slabs(const ResTable *tab, int rank, char *store, char *
         for (int k = 0; k < n; ++k) {
             const ResLayer &L = lay[items[k].layer_f >> 16];
             items[k].first_piece = p;
-            p += L.taps * L.cg_res * 16;
+            p += L.taps * (L.cg_res - items[k].cg_from) * 16;
         }
         cnt[1] = p;
     }
@@ -1877,7 +1892,7 @@ __device__ void install_slabs(const ResTable *tab, int rank, char *store, char *
 #pragma unroll
         for (int u = 0; u < BATCH; ++u) {
             const int p = min(p0 + u * STREAM_THREADS, total - 1);
-            int lo = 0, hi = n - 1;  // the last slab that starts at or before piece p
+            int lo = 0, hi = n - 1;  // the last item that starts at or before piece p
             while (lo < hi) {
                 const int mid = (lo + hi + 1) >> 1;
                 if (items[mid].first_piece <= p) lo = mid; else hi = mid - 1;
@@ -1886,9 +1901,10 @@ __device__ void install_slabs(const ResTable *tab, int rank, char *store, char *
             const ResLayer &L = lay[it.layer_f >> 16];
             const int f = it.layer_f & 0xFFFF, i = p - it.first_piece;
             const int j = i & 15, tc = i >> 4;
-            const int tap = tc / L.cg_res, cg = tc - tap * L.cg_res;
+            const int ncg = L.cg_res - it.cg_from;
+            const int tap = tc / ncg, cg = it.cg_from + (tc - tap * ncg);
             v[u] = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(L.w) + (((long)tap * L.CG + cg) * L.Kpad + f * 16 + j) * 8);
-            dst[u] = it.lds_off + i * 16;
+            dst[u] = it.lds_off + ((tap * L.cg_stride + cg) * 16 + j) * 16;
         }
 #pragma unroll
         for (int u = 0; u < BATCH; ++u)
@@ -1910,7 +1926,7 @@ __global__ __launch_bounds__(STREAM_THREADS, 2) void sushi_team_kernel(TeamArgs 
     const StepTables tb{step_entries, slab_entries};
     __shared__ int flag;
     __shared__ int s_team, s_rank, s_size;
-    __shared__ unsigned long long s_slot[5];
+    __shared__ unsigned long long s_slot[7];
     __shared__ unsigned long long s_hdr[4];
 
     // ---- team formation: which XCD am I on, how many of us are there
@@ -1957,9 +1973,11 @@ __global__ __launch_bounds__(STREAM_THREADS, 2) void sushi_team_kernel(TeamArgs 
     DevOp *prog = reinterpret_cast<DevOp *>(team_mem);
     unsigned long long my_seq = ta.last_seq[team];
     unsigned long long epoch = 0;
+    // the residency table in use and which half of the team's table memory holds it: a new table goes to
+    // the other half, so that an install can compare it with the one before
     const ResTable *table = nullptr;
-    if (!fetch_table(ta, ta.table, team_mem + TEAM_TABLE_OFFSET, team, rank, tsize, epoch, s_hdr, &flag, &table)) return;
-    if (table) install_slabs(table, rank, store, dyn_lds);
+    int table_half = 0;
+    unsigned long long table_seq = 0;  // number of the table the LDS stores hold (0: a fresh launch finds nothing there)
     unsigned long long *go = &ta.sync[sy_go(team)];
     unsigned long long *slot = &ta.sync[sy_slot(team)];
     const unsigned long long *posted = &ta.host->posted[team * 8];
@@ -1974,17 +1992,21 @@ __global__ __launch_bounds__(STREAM_THREADS, 2) void sushi_team_kernel(TeamArgs 
                 const TeamPost *post = &ta.host->post[team][0];
                 for (;;) {
                     if (ld_sys(posted) > my_seq) {
+                        // The host wrote the post (and, before that, the program and the table it names) ahead of
+                        // the counter, with a release fence between; this thread has the counter's value in hand
+                        // before it asks for the post, and every load of the post goes to host memory itself.
+                        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "");
                         st_agent(&ta.sync[SY_CLOCK], (unsigned long long)wall_clock64());  // any team's post keeps all teams alive
                         seq = my_seq + 1;
                         post = &ta.host->post[team][seq % POST_RING];
                         cmd = (unsigned long long)__hip_atomic_load(&post->cmd, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
                         n_ops = (unsigned long long)__hip_atomic_load(&post->n_ops, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-                        // an install directly followed by another install is void: the team refills its LDS
-                        // once, for the newest SubGraph, when installs have piled up behind a query
-                        if (cmd == TEAM_INSTALL && ld_sys(posted) > seq &&
-                            __hip_atomic_load(&ta.host->post[team][(seq + 1) % POST_RING].cmd, __ATOMIC_RELAXED,
-                                              __HIP_MEMORY_SCOPE_SYSTEM) == TEAM_INSTALL)
-                            cmd = TEAM_SKIP;
+                        // (a slot is rewritten only after `done` has passed the post that sat in it, so the words
+                        // belong to post `seq`; its first word says so)
+                        if (ld_sys(&post->seq) != seq) {
+                            raise_abort(ta);
+                            cmd = TEAM_STOP;
+                        }
                         break;
                     }
                     const long long last = std::max(t0, (long long)ld_agent(&ta.sync[SY_CLOCK]));
@@ -1998,7 +2020,9 @@ __global__ __launch_bounds__(STREAM_THREADS, 2) void sushi_team_kernel(TeamArgs 
                 st_agent(&slot[2], ld_sys(reinterpret_cast<const unsigned long long *>(&post->input)));
                 st_agent(&slot[3], ld_sys(reinterpret_cast<const unsigned long long *>(&post->logits)));
                 st_agent(&slot[4], seq);
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // the slot is written before go moves
+                st_agent(&slot[5], ld_sys(reinterpret_cast<const unsigned long long *>(&post->table)));
+                st_agent(&slot[6], ld_sys(&post->table_seq));
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the slot is in the L2 before go moves
                 st_agent(go, iter);
             } else {
                 const long long t0 = wall_clock64();
@@ -2012,33 +2036,24 @@ __global__ __launch_bounds__(STREAM_THREADS, 2) void sushi_team_kernel(TeamArgs 
                 }
             }
             if (good)
-                for (int k = 0; k < 5; ++k) s_slot[k] = ld_agent(&slot[k]);
+                for (int k = 0; k < 7; ++k) s_slot[k] = ld_agent(&slot[k]);
             invalidate_vector_l1();
             flag = good;
         }
         __syncthreads();
         if (!flag) return;
         const int cmd = (int)(s_slot[0] & 0xFFFFFFFFull), n_ops = min((int)(s_slot[0] >> 32), TEAM_PROG_MAX_OPS);
-        if (cmd == TEAM_SKIP) {
-            if (rank == 0 && threadIdx.x == 0)
-                __hip_atomic_store(&ta.host->done[team * 8], s_slot[4], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-            my_seq = s_slot[4];
-            continue;
-        }
-        if (cmd == TEAM_INSTALL) {
-            // a new cached SubGraph: refill the LDS store (a table made for another team size is ignored)
-            if (!fetch_table(ta, reinterpret_cast<const ResTable *>(s_slot[1]), team_mem + TEAM_TABLE_OFFSET, team, rank,
-                             tsize, epoch, s_hdr, &flag, &table))
-                return;
-            if (table) install_slabs(table, rank, store, dyn_lds);
-            epoch += 1;
-            if (!team_barrier(ta, team, tsize, epoch, &flag)) return;
-            if (rank == 0 && threadIdx.x == 0)
-                __hip_atomic_store(&ta.host->done[team * 8], s_slot[4], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-            my_seq = s_slot[4];
-            continue;
-        }
         if (cmd != TEAM_RUN) return;
+        // ---- the cached SubGraph this query runs under: bring the LDS stores up to its table if they hold another
+        if (s_slot[6] != table_seq) {
+            const ResTable *before = table;
+            if (before) table_half ^= 1;
+            if (!fetch_table(ta, reinterpret_cast<const ResTable *>(s_slot[5]), team_mem + TEAM_TABLE_OFFSET + table_half * TEAM_TABLE_BYTES,
+                             team, rank, tsize, epoch, s_hdr, &flag, &table))
+                return;
+            if (table) install_slabs(table, before, rank, store, dyn_lds);
+            table_seq = s_slot[6];
+        }
         const void *input = reinterpret_cast<const void *>(s_slot[2]);
         void *logits = reinterpret_cast<void *>(s_slot[3]);
         const unsigned long long seq = s_slot[4];

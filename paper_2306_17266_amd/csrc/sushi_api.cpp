@@ -90,6 +90,8 @@ struct sushi_ctx {
     int teams_per_xcd = 1;  // teams each XCD's workgroups are dealt to (1, 2, 4 or 8)
     int team_size() const { return team_wgs / (MAX_XCDS * teams_per_xcd); }  // workgroups of a team, if they spread evenly
     int spin_limit = 400000;
+    void *d_sweep = nullptr;  // SUSHI_OPT_COLD_SWEEP_MIB: scratch streamed through the caches before every query
+    size_t sweep_bytes = 0;
     // exec mode 3 (team kernel): mailboxes in pinned host memory, per-team arenas, private stream
     TeamHostState *th = nullptr;
     unsigned long long *d_tsync = nullptr;
@@ -106,7 +108,7 @@ struct sushi_ctx {
         ResTable *table = nullptr;  // pinned HOST: header, then RES_MAX_LAYERS layers, then RES_MAX_ENTRIES entries
         ResLayer *layers = nullptr;
         ResEntry *entries = nullptr;
-        unsigned long long install_seq[MAX_TEAMS] = {};  // post that installs this generation on team t
+        unsigned long long last_ref[MAX_TEAMS] = {};  // last post to team t that names this generation
     };
     // While the team kernel runs it fills every compute unit, and hipMalloc / hipFree / hipMemcpy may
     // wait for it to leave.  What the host hands to a running kernel (programs, residency tables)
@@ -119,9 +121,15 @@ struct sushi_ctx {
     ResGen res_gens[N_RES_GENS];  // a generation stays untouched while an install post may still name it
     bool gen_valid[N_RES_GENS] = {};  // slot holds a table (false: nothing cached)
     int gen_cur = 0;
-    std::vector<ResLayer> h_res_layers;
-    std::vector<ResEntry> h_res_entries;
+    std::vector<ResLayer> h_res_layers;   // the table in force: geometry + valid part per layer
+    std::vector<ResEntry> h_res_entries;  // (empty: nothing resident)
+    // slab geometry: per layer the tiles and channel groups slabs have room for (grow only), and the placement
+    std::vector<int> geo_n, geo_cg;
+    std::vector<ResLayer> geo_layers;
+    std::vector<ResEntry> geo_entries;
+    int geometry = 0, geometry_team_size = 0;
     uint64_t table_version = 0;
+    unsigned long long table_seq = 1;  // number of the table in force, carried by every query post (see TeamPost)
     uint64_t table_bytes = 0;  // bytes of the cached SubGraph that sit in LDS (per team)
     unsigned long long *d_trace = nullptr;
     // per-kernel timing (SUSHI_OPT_KERNEL_TIMING): event pairs around every launch
@@ -574,36 +582,35 @@ int make_team_pools(sushi_ctx *c) {
     return SUSHI_OK;
 }
 
-// Cuts the cached SubGraph into slabs and assigns them to the workgroups of a team: layers from
-// the last to the first (the late, few-pixel layers hold most weights and are the ones that use
-// their slabs), tiles round-robin over the ranks, first rank with room wins.
-int build_res_table(sushi_ctx *c) {
+// Slab geometry of the LDS stores: which 16-filter tile of which layer has a slab, how wide it is, which
+// workgroup of a team holds it and where.  Layers from the last to the first (the late, few-pixel layers
+// hold most weights and are the ones that use their slabs), tiles round-robin over the ranks, first rank
+// with room wins.  A layer's slabs are as many (n_alloc) and as wide (cg_alloc) as the largest SubGraph
+// cached since the SuperNet was loaded asked for, so the geometry changes only when a SubGraph outgrows
+// it; between such changes a new SubGraph just moves the valid part of every slab, and the teams copy
+// only the cells that were not valid before.
+void rebuild_geometry(sushi_ctx *c) {
     const int team_size = c->team_size();
     const size_t n_layers = c->sn.layers.size();
-    c->h_res_layers.assign(n_layers, ResLayer{});
-    c->h_res_entries.clear();
-    c->table_bytes = 0;
-    ++c->table_version;
-    if (c->G.empty() || team_size < 1) return SUSHI_OK;
+    c->geo_layers.assign(n_layers, ResLayer{});
+    c->geo_entries.clear();
+    ++c->geometry;
+    if (team_size < 1) return;
     std::vector<long> used(team_size, 0);
     int cursor = 0;
     for (int l = (int)n_layers - 1; l >= 0; --l) {
         const SuperLayer &L = c->sn.layers[l];
-        const sushi_layer_dims &g = c->G[l];
-        if (L.type == L_DW || g.K == 0) continue;
+        if (L.type == L_DW || c->geo_n[l] == 0 || c->geo_cg[l] == 0) continue;
         const int taps = L.Rmax * L.Rmax;
-        const int cg_res = std::min(g.C / 8, RES_STORE_BYTES / (taps * 256));
-        if (cg_res < 1) continue;
-        const long slab = (long)taps * cg_res * 256;
-        if (c->h_res_entries.size() + (size_t)(g.K + 15) / 16 > (size_t)RES_MAX_ENTRIES) break;
-        ResLayer &R = c->h_res_layers[l];
+        const long slab = (long)taps * c->geo_cg[l] * 256;
+        if (c->geo_entries.size() + (size_t)c->geo_n[l] > (size_t)RES_MAX_ENTRIES) break;
+        ResLayer &R = c->geo_layers[l];
         R.w = static_cast<const char *>(c->d_weights) + L.pk_w * 2;
-        R.Kpad = L.Kpad, R.CG = L.CG, R.taps = taps, R.cg_res = cg_res;
-        R.n_res = (g.K + 15) / 16;
-        R.first_entry = (int)c->h_res_entries.size();
+        R.Kpad = L.Kpad, R.CG = L.CG, R.taps = taps, R.cg_stride = c->geo_cg[l];
+        R.first_entry = (int)c->geo_entries.size();
         bool any = false;
         long most_free = RES_STORE_BYTES - *std::min_element(used.begin(), used.end());
-        for (int f = 0; f < R.n_res; ++f) {
+        for (int f = 0; f < c->geo_n[l]; ++f) {
             ResEntry e{-1, 0};
             for (int k = 0; k < team_size && slab <= most_free; ++k) {
                 const int r = (cursor + k) % team_size;
@@ -611,24 +618,81 @@ int build_res_table(sushi_ctx *c) {
                     e.owner = r, e.lds_off = (int)used[r];
                     used[r] += slab;
                     cursor = (r + 1) % team_size;
-                    c->table_bytes += (uint64_t)taps * cg_res * 8 * std::min(16, g.K - 16 * f) * 2;
                     any = true;
                     most_free = RES_STORE_BYTES - *std::min_element(used.begin(), used.end());
                     break;
                 }
             }
-            c->h_res_entries.push_back(e);
+            c->geo_entries.push_back(e);
         }
-        if (!any) R.n_res = 0;
+        R.n_res = any ? c->geo_n[l] : 0;  // (here: tiles the geometry lists; the table sets the valid count)
+        if (!any) {  // no room for any slab of this layer: it takes no entries (the teams fetch the whole list)
+            c->geo_entries.resize(R.first_entry);
+            R = ResLayer{};
+        }
     }
-    return SUSHI_OK;
 }
 
-// Uploads the table as a new device generation.  The slot it takes over held the generation from
-// N_RES_GENS - 1 installs ago; every team must have got past that generation's install post first
-// (with few generations, or shallow mailboxes, this wait and the one for a free mailbox slot tie the
-// host to the slowest team: every team gets every install post, so at one install per eight queries a
-// team finds several of them between two queries of its own).
+// The residency table of the cached SubGraph: the geometry with every layer's valid part set to what
+// the SubGraph covers.  Returns true if it differs from the table in force (a team would then hold
+// other cells than now).  Also counts the slab bytes that become valid (per team).
+bool build_res_table(sushi_ctx *c, uint64_t *new_bytes) {
+    const size_t n_layers = c->sn.layers.size();
+    *new_bytes = 0;
+    if (c->geo_n.size() != n_layers) c->geo_n.assign(n_layers, 0), c->geo_cg.assign(n_layers, 0), c->geometry_team_size = 0;
+    bool grow = c->geometry_team_size != c->team_size();
+    if (!c->G.empty())
+        for (size_t l = 0; l < n_layers; ++l) {
+            const SuperLayer &L = c->sn.layers[l];
+            const sushi_layer_dims &g = c->G[l];
+            if (L.type == L_DW || g.K == 0) continue;
+            const int want_cg = std::min(g.C / 8, RES_STORE_BYTES / (L.Rmax * L.Rmax * 256)), want_n = (g.K + 15) / 16;
+            if (want_cg > c->geo_cg[l]) c->geo_cg[l] = want_cg, grow = true;
+            if (want_n > c->geo_n[l]) c->geo_n[l] = want_n, grow = true;
+        }
+    if (grow) {
+        rebuild_geometry(c);
+        c->geometry_team_size = c->team_size();
+    }
+    std::vector<ResLayer> layers = c->geo_layers;
+    uint64_t bytes = 0;
+    bool any = false;
+    for (size_t l = 0; l < layers.size(); ++l) {
+        ResLayer &R = layers[l];
+        const int listed = R.n_res;
+        R.n_res = 0, R.cg_res = 0;
+        if (c->G.empty() || listed == 0 || c->G[l].K == 0) continue;
+        R.n_res = std::min(listed, (c->G[l].K + 15) / 16);
+        R.cg_res = std::min(c->G[l].C / 8, R.cg_stride);
+        if (R.cg_res < 1) R.n_res = 0;
+        for (int f = 0; f < R.n_res; ++f)
+            if (c->geo_entries[R.first_entry + f].owner >= 0) {
+                const uint64_t cells = (uint64_t)R.taps * 8 * std::min(16, c->G[l].K - 16 * f) * 2;
+                bytes += cells * R.cg_res;
+                any = true;
+                // cells valid before (same geometry): tiles below the old n_res up to the old cg_res
+                const bool had = !grow && l < c->h_res_layers.size() && f < c->h_res_layers[l].n_res;
+                const int from = had ? std::min(c->h_res_layers[l].cg_res, R.cg_res) : 0;
+                *new_bytes += cells * (R.cg_res - from);
+            }
+    }
+    bool changed = grow || layers.size() != c->h_res_layers.size() || any != !c->h_res_entries.empty();
+    for (size_t l = 0; !changed && l < layers.size(); ++l)
+        changed = layers[l].n_res != c->h_res_layers[l].n_res || layers[l].cg_res != c->h_res_layers[l].cg_res;
+    if (!changed) {
+        *new_bytes = 0;
+        return false;
+    }
+    c->h_res_layers = std::move(layers);
+    if (any) c->h_res_entries = c->geo_entries; else c->h_res_entries.clear();
+    c->table_bytes = bytes;
+    ++c->table_version;
+    return true;
+}
+
+// Writes the table into the next of the pinned generations and makes it the one later posts name.  The slot
+// it takes over held the table from N_RES_GENS - 1 changes ago; every post that still names that one must
+// have been served first (with 32 generations and at most 32 posts per mailbox that wait never lasts).
 int upload_res_table(sushi_ctx *c) {
     const int slot = (c->gen_cur + 1) % sushi_ctx::N_RES_GENS;
     sushi_ctx::ResGen &g = c->res_gens[slot];
@@ -636,16 +700,17 @@ int upload_res_table(sushi_ctx *c) {
         for (int t = 0; t < MAX_TEAMS; ++t) {
             const auto t0 = std::chrono::steady_clock::now();
             unsigned spins = 0;
-            while (*(volatile unsigned long long *)&c->th->done[t * 8] < g.install_seq[t]) {
+            while (*(volatile unsigned long long *)&c->th->done[t * 8] < g.last_ref[t]) {
                 if ((++spins & 0x3FF) != 0) continue;
                 if (!team_kernel_running(c)) {  // the post is still in the mailbox: let a new launch serve it
                     int rc = launch_teams(c);
                     if (rc) return rc;
                 }
                 if (std::chrono::steady_clock::now() - t0 > std::chrono::seconds(20))
-                    return fail(c, SUSHI_EDEVICE, "timed out waiting for an install");
+                    return fail(c, SUSHI_EDEVICE, "timed out waiting for a team");
             }
         }
+    ++c->table_seq;
     c->gen_cur = slot;
     c->gen_valid[slot] = false;
     if (c->h_res_entries.empty()) return SUSHI_OK;
@@ -655,6 +720,7 @@ int upload_res_table(sushi_ctx *c) {
     std::memcpy(g.entries, c->h_res_entries.data(), c->h_res_entries.size() * sizeof(ResEntry));
     ResTable t{};
     t.n_layers = (int)c->h_res_layers.size(), t.team_size = c->team_size(), t.n_entries = (int)c->h_res_entries.size();
+    t.geometry = c->geometry;
     t.layers = g.layers, t.entries = g.entries;
     *g.table = t;
     c->gen_valid[slot] = true;
@@ -723,7 +789,6 @@ int launch_teams(sushi_ctx *c) {
     for (int t = 0; t < MAX_TEAMS; ++t) ta.last_seq[t] = c->th->done[t * 8];
     ta.idle_ticks = c->idle_ticks, ta.spin_limit = c->spin_limit;
     ta.trace = c->d_trace;
-    ta.table = c->gen_valid[c->gen_cur] ? c->res_gens[c->gen_cur].table : nullptr;
     ta.team_mem = c->d_team_mem;
     close_team_timing(c);
     if (c->timing) {
@@ -770,9 +835,9 @@ int ensure_team_state(sushi_ctx *c, int batch) {
             return hip_fail(c, e, "hipStreamCreateWithFlags");
         int rc = make_team_pools(c);
         if (rc) return rc;
-        rc = build_res_table(c);  // a SubGraph may have been cached before the first query
-        if (rc == SUSHI_OK) rc = upload_res_table(c);
-        if (rc) return rc;
+        uint64_t fresh = 0;
+        if (build_res_table(c, &fresh) && (rc = upload_res_table(c)) != SUSHI_OK) return rc;  // a SubGraph may have been cached before the first query
+        c->stats.cache_bytes_lds = c->table_bytes;
     }
     if (batch > c->tarena_batch) {
         int rc = stop_team_kernel(c);
@@ -898,6 +963,17 @@ int post_team_query(sushi_ctx *c, CachedPlan &cp, const void *input_dev, void *l
             op.layer = (L.kind == OP_CONV || L.kind == OP_FC) ? o.layer : -1;
             if (!tile_team_op(op, c->team_size()))
                 return fail(c, SUSHI_ESTATE, "a layer does not fit the team kernel (reduction steps, taps or channel counts)");
+            // every activation tensor of the op must lie inside the buffer of the team arena it names
+            {
+                const bool conv = L.kind == OP_CONV || L.kind == OP_DW || L.kind == OP_FC;
+                const long in_bytes = (long)o.B * o.H * o.W * o.C * 2;
+                const long out_elems = (long)o.B * o.P * o.Q * (conv ? o.K : o.C);
+                const long out_bytes = out_elems * (o.out_f32 ? 4 : 2);
+                auto fits = [&](int id, bool small, long bytes) { return id < 0 || bytes <= (small ? c->tsmall_bytes : c->tbig_bytes); };
+                if (!fits(o.in_buf, o.in_small, in_bytes) || !fits(o.out_buf, o.out_small, out_bytes) ||
+                    !fits(o.res_buf, false, out_elems * 2) || !fits(o.gate_buf, true, (long)o.B * o.C * 4))
+                    return fail(c, SUSHI_ESTATE, "internal: an activation tensor does not fit its team arena buffer");
+            }
             prog.push_back(op);
         }
         if (prog.size() > (size_t)TEAM_PROG_MAX_OPS) return fail(c, SUSHI_ESTATE, "the SubNet has too many ops for the team kernel");
@@ -942,28 +1018,24 @@ int post_team_query(sushi_ctx *c, CachedPlan &cp, const void *input_dev, void *l
     c->stats.last_lds_bytes = cp.lds_bytes;
     TeamPost &p = *slot;
     p.cmd = TEAM_RUN, p.n_ops = cp.n_dev_ops, p.prog = cp.h_team_prog, p.input = input_dev, p.logits = logits_dev;
+    p.table = c->gen_valid[c->gen_cur] ? c->res_gens[c->gen_cur].table : nullptr;
+    p.table_seq = c->table_seq;
+    c->res_gens[c->gen_cur].last_ref[t] = c->posted[t] + 1;
     publish_post(c, t, slot);
     return SUSHI_OK;
 }
 
-// Makes the teams of a running kernel refill their LDS stores from the current table (in mailbox
-// order, so queries posted earlier still see the old slabs); a stopped kernel installs at its start.
+// Rebuilds the residency table for the cached SubGraph.  If the teams would hold other cells than now, the
+// table becomes a new generation; queries posted from here on name it, and a team brings its LDS stores up
+// to it before the first such query it serves (queries posted earlier still run under the table they name).
 int install_on_teams(sushi_ctx *c) {
     if (!c->th) return SUSHI_OK;  // the team kernel has never run: the table is built at its first start
-    int rc = build_res_table(c);
-    if (rc == SUSHI_OK) rc = upload_res_table(c);
+    uint64_t fresh = 0;
+    if (!build_res_table(c, &fresh)) return SUSHI_OK;  // the teams would hold exactly what they hold now
+    int rc = upload_res_table(c);
     if (rc) return rc;
-    if (!team_kernel_running(c)) return SUSHI_OK;
-    for (int t = 0; t < MAX_TEAMS; ++t) {
-        if (c->th->team_size[t] == 0) continue;
-        TeamPost *slot = nullptr;
-        if ((rc = reserve_post(c, t, &slot)) != SUSHI_OK) return rc;
-        TeamPost &p = *slot;
-        p.cmd = TEAM_INSTALL, p.n_ops = 0, p.prog = reinterpret_cast<const DevOp *>(c->gen_valid[c->gen_cur] ? c->res_gens[c->gen_cur].table : nullptr);
-        p.input = nullptr, p.logits = nullptr;
-        publish_post(c, t, slot);
-        c->res_gens[c->gen_cur].install_seq[t] = c->posted[t];
-    }
+    c->stats.residency_changes += 1;
+    c->stats.install_bytes_lds += fresh;
     return SUSHI_OK;
 }
 
@@ -1106,6 +1178,7 @@ void sushi_destroy(sushi_ctx *c) {
         if (c->d_tarena) (void)hipFree(c->d_tarena);
         (void)hipHostFree(c->th);
     }
+    if (c->d_sweep) (void)hipFree(c->d_sweep);
     if (c->d_sync) (void)hipFree(c->d_sync);
     if (c->h_abort) (void)hipHostFree(c->h_abort);
     free_arena(c);
@@ -1135,6 +1208,10 @@ int sushi_load_supernet(sushi_ctx *c, const sushi_arch *arch, const void *weight
     if (c->th) {
         (void)synchronize_teams(c);
         (void)stop_team_kernel(c);
+        // the team arenas were sized by the previous SuperNet's largest SubNet
+        if (c->d_tarena) (void)hipFree(c->d_tarena);
+        c->d_tarena = nullptr;
+        c->tarena_batch = 0, c->tarena_bytes = 0, c->tbig_bytes = 0, c->tsmall_bytes = 0;
     }
     free_arena(c);
     c->plans.clear();
@@ -1145,6 +1222,10 @@ int sushi_load_supernet(sushi_ctx *c, const sushi_arch *arch, const void *weight
     ++c->g_version;
     for (bool &v : c->gen_valid) v = false;
     c->h_res_layers.clear(), c->h_res_entries.clear();
+    c->geo_n.clear(), c->geo_cg.clear(), c->geo_layers.clear(), c->geo_entries.clear();
+    ++c->geometry;
+    ++c->table_seq;  // (teams drop the table they hold)
+    c->geometry_team_size = 0;
     c->prog_pool_used = 0;
     ++c->table_version;
     c->stats = sushi_stats{};
@@ -1251,6 +1332,10 @@ int sushi_infer(sushi_ctx *c, const sushi_subnet_cfg *cfg, const void *input_dev
         }
 
     if (c->exec_mode != 3) c->stream_dirty = true;
+    if (c->exec_mode != 3 && c->sweep_bytes) {
+        if ((e = launch_cold_sweep(c->d_sweep, c->sweep_bytes, c->d_sweep, c->stream)) != hipSuccess)
+            return hip_fail(c, e, "cache sweep");
+    }
     if (c->exec_mode == 3) {
         int rc = post_team_query(c, *cp, input_dev, logits_dev, batch);
         if (rc) return rc;
@@ -1267,9 +1352,9 @@ int sushi_infer(sushi_ctx *c, const sushi_subnet_cfg *cfg, const void *input_dev
     sushi_stats &s = c->stats;
     s.queries++;
     s.weight_bytes_total += cp->weight_bytes;
-    s.weight_bytes_resident += cp->resident_bytes;
+    s.weight_bytes_in_subgraph += cp->resident_bytes;
     s.last_weight_bytes = cp->weight_bytes;
-    s.last_resident_bytes = cp->resident_bytes;
+    s.last_in_subgraph_bytes = cp->resident_bytes;
     s.last_hit_ratio = cp->hit_ratio;
     s.sum_hit_ratio += cp->hit_ratio;
     return SUSHI_OK;
@@ -1404,6 +1489,24 @@ int sushi_set_option(sushi_ctx *c, int option, int64_t value) {
     if (option == SUSHI_OPT_TEAMS_PER_XCD && (value == 1 || value == 2 || value == 4 || value == 8) && value <= MAX_TEAMS / MAX_XCDS) {
         if (c->th) return fail(c, SUSHI_ESTATE, "set the number of teams before the first query");
         c->teams_per_xcd = (int)value;
+        return SUSHI_OK;
+    }
+    if (option == SUSHI_OPT_COLD_SWEEP_MIB && value >= 0 && value <= 4096) {
+        if (c->device < 0) return fail(c, SUSHI_ESTATE, "set_option: host-only context");
+        hipError_t e = hipStreamSynchronize(c->stream);
+        if (e != hipSuccess) return hip_fail(c, e, "hipStreamSynchronize");
+        if (c->d_sweep) (void)hipFree(c->d_sweep);
+        c->d_sweep = nullptr, c->sweep_bytes = 0;
+        if (value == 0) return SUSHI_OK;
+        if (c->th) {  // an allocation may wait for the persistent kernel to leave
+            int rc = synchronize_teams(c);
+            if (rc == SUSHI_OK) rc = stop_team_kernel(c);
+            if (rc) return rc;
+        }
+        const size_t bytes = (size_t)value << 20;
+        if (hipMalloc(&c->d_sweep, bytes) != hipSuccess) return fail(c, SUSHI_ENOMEM, "hipMalloc(cache sweep buffer)");
+        if ((e = hipMemset(c->d_sweep, 0, bytes)) != hipSuccess) return hip_fail(c, e, "hipMemset");
+        c->sweep_bytes = bytes;
         return SUSHI_OK;
     }
     if (option == SUSHI_OPT_IDLE_US && value >= 10 && value <= 10000000) {

@@ -25,3 +25,10 @@ def rel_l2(got, want):
 
 def oracle_logits(arch, wts, cfg, x_nhwc):
     return E.forward(arch, wts, cfg, np.ascontiguousarray(x_nhwc.transpose(0, 3, 1, 2)))
+
+
+def oracle_logits_bf16_stores(arch, wts, cfg, x_nhwc):
+    """The oracle's diagnostic variant: every stored feature map rounded to bf16 (nearest even), all
+    arithmetic as in the acceptance oracle.  Not the acceptance reference: it shows how much of a
+    query's error budget the bf16 activation format alone uses up."""
+    return E.forward(arch, wts, cfg, np.ascontiguousarray(x_nhwc.transpose(0, 3, 1, 2)), act_round=T.round_to_bf16)

@@ -70,7 +70,7 @@ def test_config1_tiny_stream_fp32():
         st = ctx.sushi_get_stats()
         sn = E.subnet_box(arch, cfg)
         assert st["last_weight_bytes"] == 4 * E.weight_count(sn)
-        assert st["last_resident_bytes"] == 4 * E.weight_count(E.intersect(sn, box))
+        assert st["last_in_subgraph_bytes"] == 4 * E.weight_count(E.intersect(sn, box))
         assert abs(st["last_hit_ratio"] - E.hit_ratio(E.encode_vector(arch, cfg),
                                                       [v for (k, c, r) in box for v in (k, c)])) < 1e-12
     assert ctx.sushi_get_stats()["queries"] == 8
