@@ -249,6 +249,21 @@ int sushi_set_subgraph_cache(sushi_ctx *ctx, const sushi_subgraph_cfg *g, size_t
  * cached.  SUSHI_EINVAL (nothing enqueued) if cfg is not a SubNet of the loaded SuperNet. */
 int sushi_infer(sushi_ctx *ctx, const sushi_subnet_cfg *cfg, const void *input_dev, int batch, void *logits_dev);
 
+/* For callers that must not allocate device memory while they run (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): sushi_infer as exec mode 0 does it (one launch per layer on
+ * the context's stream, float32 or bf16), with the activation buffers of the query in a static device array
+ * of the library instead of the context's arena.  Calls no hipMalloc / hipFree and no allocating library
+ * routine; same arguments, results and error behaviour as sushi_infer.
+ *   - The array holds SUSHI_STATIC_SCRATCH_BYTES per GPU for as long as the library is loaded.  A query whose
+ *     SubNet needs more at its batch size and resolution (six feature-map buffers of its largest layer output
+ *     plus four vector buffers) is refused with SUSHI_ENOMEM and nothing is enqueued.
+ *   - Every call on a GPU, from any context, uses the same array: calls whose work overlaps in time on one
+ *     GPU (two contexts, two streams) race.  Nothing in it has to start at zero; a call leaves its
+ *     activations behind.
+ *   - The SubGraph cache has no effect on this path (as in exec mode 0); the counters are kept. */
+#define SUSHI_STATIC_SCRATCH_BYTES (16u << 20)
+int sushi_infer_static(sushi_ctx *ctx, const sushi_subnet_cfg *cfg, const void *input_dev, int batch, void *logits_dev);
+
 /* Waits until every query enqueued or posted through ctx has finished and its logits are visible
  * to the host and to later work on any stream. */
 int sushi_synchronize(sushi_ctx *ctx);

@@ -111,6 +111,7 @@ def lib():
     L.sushi_load_supernet.argtypes = [vp, C.POINTER(CArch), vp, C.c_size_t, C.c_int]
     L.sushi_set_subgraph_cache.argtypes = [vp, C.POINTER(CSubgraphCfg), C.c_size_t]
     L.sushi_infer.argtypes = [vp, C.POINTER(CSubnetCfg), vp, C.c_int, vp]
+    L.sushi_infer_static.argtypes = [vp, C.POINTER(CSubnetCfg), vp, C.c_int, vp]
     L.sushi_sched_init.argtypes = [vp, C.POINTER(CSchedDesc)]
     L.sushi_sched_step.argtypes = [vp, C.c_float, C.c_float, ip, ip]
     L.sushi_sched_record.argtypes = [vp, C.POINTER(C.c_int32), ip]
@@ -257,6 +258,15 @@ class Sushi:
             s = self._cfg_cache[key] = c_cfg(cfg)
         _check(lib().sushi_infer(self._h, C.byref(s), C.c_void_p(x.data_ptr()), x.shape[0],
                                  C.c_void_p(logits.data_ptr())), self._h)
+
+    def sushi_infer_static(self, cfg, x, logits):
+        """sushi_infer through the entry point that allocates nothing (activations in the library's static array)."""
+        key = cfg.key()
+        s = self._cfg_cache.get(key)
+        if s is None:
+            s = self._cfg_cache[key] = c_cfg(cfg)
+        _check(lib().sushi_infer_static(self._h, C.byref(s), C.c_void_p(x.data_ptr()), x.shape[0],
+                                        C.c_void_p(logits.data_ptr())), self._h)
 
     def sushi_synchronize(self):
         _check(lib().sushi_synchronize(self._h), self._h)

@@ -69,6 +69,12 @@ hipError_t launch_gate(const PoolArgs &a, bool bf16, hipStream_t s);      // y =
 // depends on all of them, so the reads cannot be dropped).  A measurement aid: see SUSHI_OPT_COLD_SWEEP_MIB.
 hipError_t launch_cold_sweep(const void *buf, size_t bytes, void *sink, hipStream_t s);
 
+// The library's static scratch buffer on the current device: STATIC_SCRATCH_BYTES of device memory that
+// belong to the loaded code object (no allocation), for sushi_infer_static.  The address is looked up once
+// per device, with that device current.
+constexpr size_t STATIC_SCRATCH_BYTES = 16u << 20;
+hipError_t static_scratch(int device, void **ptr);
+
 // Ring order of depthwise taps: tap t of a 7x7 kernel sits at row/col offset (dr, ds) from the centre.
 void dw_tap_offsets(int t, int *dr, int *ds);
 hipError_t upload_tap_table();

@@ -526,6 +526,26 @@ hipError_t launch_cold_sweep(const void *buf, size_t bytes, void *sink, hipStrea
     return hipGetLastError();
 }
 
+// ------------------------------------------------------------------ static scratch
+
+// Activation buffers of sushi_infer_static.  In host code the array's name only stands for the symbol; the
+// device address (one per GPU that loaded this code object) comes from hipGetSymbolAddress.
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
+hipError_t static_scratch(int device, void **ptr) {
+    constexpr int MAX_DEVICES = 64;
+    static void *ptrs[MAX_DEVICES] = {};
+    if (device < 0 || device >= MAX_DEVICES) return hipErrorInvalidDevice;
+    if (!ptrs[device]) {
+        void *p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        ptrs[device] = p;
+    }
+    *ptr = ptrs[device];
+    return hipSuccess;
+}
+
 // ------------------------------------------------------------------ launchers
 
 static inline unsigned blocks_for(long total) { return (unsigned)((total + 255) / 256); }

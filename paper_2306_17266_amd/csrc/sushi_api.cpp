@@ -90,6 +90,7 @@ struct sushi_ctx {
     int teams_per_xcd = 1;  // teams each XCD's workgroups are dealt to (1, 2, 4 or 8)
     int team_size() const { return team_wgs / (MAX_XCDS * teams_per_xcd); }  // workgroups of a team, if they spread evenly
     int spin_limit = 400000;
+    void *static_buf = nullptr;  // this device's copy of the library's static scratch array (sushi_infer_static)
     void *d_sweep = nullptr;  // SUSHI_OPT_COLD_SWEEP_MIB: scratch streamed through the caches before every query
     size_t sweep_bytes = 0;
     // exec mode 3 (team kernel): mailboxes in pinned host memory, per-team arenas, private stream
@@ -278,13 +279,20 @@ int ensure_arena(sushi_ctx *c, int batch) {
     return SUSHI_OK;
 }
 
-void *buf_ptr(sushi_ctx *c, int id, bool small) {
+// Where a plan's activation buffers live: the context's arena, or one block cut into equal parts.
+struct BufBase {
+    char *block = nullptr;  // null: the context's arena
+    size_t big_bytes = 0, small_bytes = 0;
+};
+
+void *buf_ptr(sushi_ctx *c, const BufBase &bb, int id, bool small) {
     if (id < 0) return nullptr;
-    return small ? c->small_[id] : c->big[id];
+    if (!bb.block) return small ? c->small_[id] : c->big[id];
+    return small ? bb.block + N_BIG_BUFS * bb.big_bytes + id * bb.small_bytes : bb.block + id * bb.big_bytes;
 }
 
 // Turns a plan into launch records with device pointers bound.
-void bind_plan(sushi_ctx *c, CachedPlan &cp) {
+void bind_plan(sushi_ctx *c, CachedPlan &cp, const BufBase &bb = BufBase()) {
     const size_t es = elem_size(c);
     for (const Op &op : cp.plan.ops) {
         Launch L;
@@ -292,9 +300,9 @@ void bind_plan(sushi_ctx *c, CachedPlan &cp) {
         if (op.kind == OP_CONV || op.kind == OP_DW || op.kind == OP_FC) {
             const SuperLayer &S = c->sn.layers[op.layer];
             ConvArgs &a = L.conv;
-            a.x = buf_ptr(c, op.in_buf, op.in_small);
-            a.y = buf_ptr(c, op.out_buf, op.out_small);
-            a.res = buf_ptr(c, op.res_buf, false);
+            a.x = buf_ptr(c, bb, op.in_buf, op.in_small);
+            a.y = buf_ptr(c, bb, op.out_buf, op.out_small);
+            a.res = buf_ptr(c, bb, op.res_buf, false);
             a.w = static_cast<const char *>(c->d_weights) + S.pk_w * es;
             a.scale = S.has_scale ? c->d_params + S.pk_scale : nullptr;
             a.shift = c->d_params + S.pk_shift;
@@ -306,9 +314,9 @@ void bind_plan(sushi_ctx *c, CachedPlan &cp) {
             L.out_patch = op.out_buf == BUF_LOGITS;
         } else {
             PoolArgs &a = L.pool;
-            a.x = buf_ptr(c, op.in_buf, op.in_small);
-            a.y = buf_ptr(c, op.out_buf, op.out_small);
-            a.gate = static_cast<const float *>(buf_ptr(c, op.gate_buf, true));
+            a.x = buf_ptr(c, bb, op.in_buf, op.in_small);
+            a.y = buf_ptr(c, bb, op.out_buf, op.out_small);
+            a.gate = static_cast<const float *>(buf_ptr(c, bb, op.gate_buf, true));
             a.B = op.B, a.H = op.H, a.W = op.W, a.C = op.C, a.P = op.P, a.Q = op.Q;
         }
         cp.launches.push_back(L);
@@ -1151,6 +1159,12 @@ int sushi_create(sushi_ctx **out, int device_id, void *hip_stream) {
     if (!c) return SUSHI_ENOMEM;
     c->device = device_id;
     c->stream = static_cast<hipStream_t>(hip_stream);
+    // address of the static scratch array on this device (device_id is current), for sushi_infer_static
+    if ((e = static_scratch(device_id, &c->static_buf)) != hipSuccess) {
+        g_create_error = std::string("hipGetSymbolAddress(static scratch): ") + hipGetErrorString(e);
+        delete c;
+        return SUSHI_EDEVICE;
+    }
     *out = c;
     return SUSHI_OK;
 }
@@ -1349,6 +1363,60 @@ int sushi_infer(sushi_ctx *c, const sushi_subnet_cfg *cfg, const void *input_dev
         e = issue_launches(c, *cp, input_dev, logits_dev, c->stream);
         if (e != hipSuccess) return hip_fail(c, e, "kernel launch");
     }
+    sushi_stats &s = c->stats;
+    s.queries++;
+    s.weight_bytes_total += cp->weight_bytes;
+    s.weight_bytes_in_subgraph += cp->resident_bytes;
+    s.last_weight_bytes = cp->weight_bytes;
+    s.last_in_subgraph_bytes = cp->resident_bytes;
+    s.last_hit_ratio = cp->hit_ratio;
+    s.sum_hit_ratio += cp->hit_ratio;
+    return SUSHI_OK;
+}
+
+int sushi_infer_static(sushi_ctx *c, const sushi_subnet_cfg *cfg, const void *input_dev, int batch, void *logits_dev) {
+    if (!c) return SUSHI_EINVAL;
+    if (!c->loaded) return fail(c, SUSHI_ESTATE, "infer before load_supernet");
+    if (!cfg || !input_dev || !logits_dev || batch < 1) return fail(c, SUSHI_EINVAL, "infer: bad argument");
+    hipError_t e;
+    if ((e = hipSetDevice(c->device)) != hipSuccess) return hip_fail(c, e, "hipSetDevice");
+    if (!c->static_buf) return fail(c, SUSHI_ESTATE, "the static scratch buffer was not found on this device");
+    CachedPlan *cp = nullptr;
+    std::string key = plan_key(*cfg, batch);
+    key.push_back('S');  // (plans bound to the static buffer are kept apart from those bound to the arena)
+    auto it = c->plans.find(key);
+    if (it != c->plans.end()) {
+        cp = it->second.get();
+        c->stats.plan_cache_hits++;
+    } else {
+        std::unique_ptr<CachedPlan> np(new (std::nothrow) CachedPlan());
+        if (!np) return fail(c, SUSHI_ENOMEM, "infer: plan allocation failed");
+        std::string err;
+        int rc = plan_subnet(c->sn, *cfg, batch, np->plan, err);
+        if (rc) return fail(c, rc, err);
+        // the activation buffers of THIS SubNet at this batch size and resolution, cut out of the static array
+        BufBase bb;
+        bb.block = static_cast<char *>(c->static_buf);
+        bb.big_bytes = round_up(np->plan.max_big_elems * elem_size(c), 256);
+        bb.small_bytes = round_up(std::max<size_t>(np->plan.max_small_elems, 8) * 4, 256);
+        const size_t need = N_BIG_BUFS * bb.big_bytes + N_SMALL_BUFS * bb.small_bytes;
+        if (need > STATIC_SCRATCH_BYTES)
+            return fail(c, SUSHI_ENOMEM, "infer_static: this SubNet needs " + std::to_string(need) +
+                                             " bytes of activation scratch at this batch size and resolution, the "
+                                             "static buffer holds " + std::to_string(STATIC_SCRATCH_BYTES));
+        bind_plan(c, *np, bb);
+        cp = np.get();
+        c->plans[key] = std::move(np);
+        c->stats.plan_cache_misses++;
+    }
+    refresh_residency(c, *cp);
+    c->stream_dirty = true;
+    // one launch per op on the context's stream; no events, no allocation
+    const bool timing = c->timing;
+    c->timing = false;
+    e = issue_launches(c, *cp, input_dev, logits_dev, c->stream);
+    c->timing = timing;
+    if (e != hipSuccess) return hip_fail(c, e, "kernel launch");
     sushi_stats &s = c->stats;
     s.queries++;
     s.weight_bytes_total += cp->weight_bytes;
