@@ -77,6 +77,9 @@ def main():
                          "whose caches are lost between queries)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="run one 256 MiB device-to-device copy first (reference dispatch for byte counters)")
+    ap.add_argument("--measure-table", action="store_true",
+                    help="latency-target stream: measure the latency table in this run even if a frozen one is shipped")
+    ap.add_argument("--table-runs", type=int, default=3, help="runs per table entry when it is measured")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-roofline", action="store_true")
     ap.add_argument("--no-latency", action="store_true", help="skip the lone-query latency passes")
@@ -136,16 +139,17 @@ def main():
         acc = [0.0] * len(pool)
         for rank, i in enumerate(sorted(range(len(pool)), key=lambda i: sizes[i])):
             acc[i] = float(np.float32(0.70 + 0.01 * rank))
-        frozen = sushiabs.load_table(sushiabs.table_path(args.workload, budget), len(pool), len(cands))
+        tpath = sushiabs.table_path(args.workload, budget, teams)
+        frozen = sushiabs.load_table(tpath, len(pool), len(cands)) if mode == 3 and not args.measure_table else None
         if frozen is not None:
-            lat, table_info = frozen["table"], "frozen: " + os.path.relpath(sushiabs.table_path(args.workload, budget), ROOT)
+            lat, table_info = frozen["table"], "frozen: " + os.path.relpath(tpath, ROOT)
         else:
-            lat = sushiabs.measure_table(ctx, pool, cands, budget, xs[res_list[0]][0], outs[0], runs=3)
-            table_info = "measured in this run (3 runs per entry)"
+            lat = sushiabs.measure_table(ctx, pool, cands, budget, xs[res_list[0]][0], outs[0], runs=args.table_runs)
+            table_info = "measured in this run (median of %d runs per entry)" % args.table_runs
             out_dir = os.path.join(ROOT, "gpurun_out")
             if os.path.isdir(out_dir):
-                sushiabs.save_table(os.path.join(out_dir, os.path.basename(sushiabs.table_path(args.workload, budget))),
-                                    lat, args.workload, budget, 3)
+                sushiabs.save_table(os.path.join(out_dir, os.path.basename(tpath)), lat, args.workload, budget, args.table_runs,
+                                    "exec mode %d, %d teams per XCD, batch %d" % (mode, teams, batch))
         levels = sushiabs.latency_levels(lat, wl["n_levels"])
         ctx.sushi_sched_init([vec_of[c.key()] for c in pool], acc, gvecs, lat, Q, S.STRICT_LATENCY)
     else:
@@ -153,21 +157,28 @@ def main():
 
     state = {"cache": -1, "t": 0}
     served = {}
+    # everything a query passes to the library, marshalled once (the loop below is the host's share of a query)
+    import ctypes
+    m_of = {k: (ctx.marshal_cfg(c), ctx.marshal_vec(vec_of[k]), c.resolution) for k, c in distinct.items()}
+    m_serving = [m_of[c.key()] for c in serving]
+    m_cands = [ctx.marshal_subgraph(b) for b in cands]
+    x_ptrs = {r: [ctypes.c_void_p(x.data_ptr()) for x in xs[r]] for r in res_list}
+    out_ptrs = [ctypes.c_void_p(o.data_ptr()) for o in outs]
+    n_serving = len(m_serving)
+    use_sched = args.sgs == "sched"
 
     def one_query():
         t = state["t"]
         if by_target:
             i, j = ctx.sushi_sched_step(0.0, levels[wl["levels"][t % len(wl["levels"])]])
-            cfg = wl["pool"][i]
             served[i] = served.get(i, 0) + 1
+            ctx.infer_marshalled(m_serving[i][0], x_ptrs[m_serving[i][2]][t % n_inputs], batch, out_ptrs[t % n_outputs])
         else:
-            cfg = serving[t % len(serving)]
-            j = None
-        ctx.sushi_infer(cfg, xs[cfg.resolution][t % n_inputs], outs[t % n_outputs])
-        if j is None:
-            j = ctx.sushi_sched_record(vec_of[cfg.key()])
-        if args.sgs == "sched" and j >= 0 and j != state["cache"]:
-            ctx.sushi_set_subgraph_cache(cands[j], budget)
+            cs, vec, r = m_serving[t % n_serving]
+            ctx.infer_marshalled(cs, x_ptrs[r][t % n_inputs], batch, out_ptrs[t % n_outputs])
+            j = ctx.sched_record_marshalled(vec)
+        if use_sched and j >= 0 and j != state["cache"]:
+            ctx.set_subgraph_cache_marshalled(m_cands[j], budget)
             state["cache"] = j
         state["t"] = t + 1
 

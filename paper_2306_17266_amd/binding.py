@@ -212,6 +212,7 @@ class Sushi:
         self.dtype = None
         self._cfg_cache = {}
         self._box_cache = {}
+        self._j = C.c_int(0)
 
     def close(self):
         if self._h:
@@ -267,6 +268,40 @@ class Sushi:
             s = self._cfg_cache[key] = c_cfg(cfg)
         _check(lib().sushi_infer_static(self._h, C.byref(s), C.c_void_p(x.data_ptr()), x.shape[0],
                                         C.c_void_p(logits.data_ptr())), self._h)
+
+    # Pre-marshalled arguments for callers that issue many queries: the same C calls, with the ctypes objects
+    # built once instead of per call.
+    def marshal_cfg(self, cfg):
+        """A sushi_subnet_cfg for infer_marshalled."""
+        return c_cfg(cfg)
+
+    def marshal_subgraph(self, box):
+        """A sushi_subgraph_cfg for set_subgraph_cache_marshalled (keeps its layer array alive)."""
+        arr = (CLayerDims * len(box))(*[CLayerDims(k, c, r) for (k, c, r) in box])
+        g = CSubgraphCfg(len(box), arr)
+        g._keep = arr
+        return g
+
+    def marshal_vec(self, vec):
+        """(int32 array, pointer) for sched_record_marshalled."""
+        v = np.ascontiguousarray(vec, dtype=np.int32)
+        return v, v.ctypes.data_as(C.POINTER(C.c_int32))
+
+    def infer_marshalled(self, c_cfg_struct, x_ptr, batch, logits_ptr):
+        rc = lib().sushi_infer(self._h, C.byref(c_cfg_struct), x_ptr, batch, logits_ptr)
+        if rc != 0:
+            _check(rc, self._h)
+
+    def set_subgraph_cache_marshalled(self, g, budget_bytes):
+        rc = lib().sushi_set_subgraph_cache(self._h, C.byref(g), budget_bytes)
+        if rc != 0:
+            _check(rc, self._h)
+
+    def sched_record_marshalled(self, vec_pair):
+        rc = lib().sushi_sched_record(self._h, vec_pair[1], C.byref(self._j))
+        if rc != 0:
+            _check(rc, self._h)
+        return self._j.value
 
     def sushi_synchronize(self):
         _check(lib().sushi_synchronize(self._h), self._h)

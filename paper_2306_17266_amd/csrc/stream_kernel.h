@@ -66,7 +66,7 @@ enum TeamCmd { TEAM_RUN = 0, TEAM_STOP = 1 };
 // Which slab sits where (the geometry) is fixed for as long as the cached SubGraphs fit it: a layer's
 // slabs are as wide (cg_stride) and as many as the largest SubGraph cached so far asked for.  A new
 // SubGraph then only changes how much of every slab is valid (tiles below n_res, channel groups below
-// cg_res), and an install copies just the cells that were not valid before.
+// cg_res), and a team copies just the cells its stores do not hold yet.
 // Every team holds the same slabs.  Only layers that run as a single pixel group (at most 64 output
 // pixels per query: the late stages, squeeze-excite and classifier layers, which hold most of the
 // weights) use their slabs.
@@ -139,14 +139,14 @@ struct TeamArgs {
     long idle_ticks;           // 100 MHz ticks a leader waits for a post before its team leaves
     int teams_per_xcd;         // 1: the workgroups of an XCD form one team; 2, 4, 8: that many teams, each a share of them
     int spin_limit;
-    char *team_mem;            // DEVICE, MAX_TEAMS areas of TEAM_MEM_BYTES: [program][two residency tables]
+    char *team_mem;            // DEVICE, MAX_TEAMS areas of TEAM_MEM_BYTES: [program][residency table][slab words]
     unsigned long long *trace;  // DEVICE or null: [MAX_TEAMS][TRACE_SLOTS] 100 MHz timestamps, one after each op
 };
 constexpr int TRACE_SLOTS = 256;
-// [program][residency table][residency table]: the table in use and the one before it (an install reads both)
+// [program][residency table][one word per table entry: what of the slab the owner's LDS store holds]
 constexpr long TEAM_TABLE_OFFSET = (long)TEAM_PROG_MAX_OPS * sizeof(DevOp);
 constexpr long TEAM_TABLE_BYTES = 64 + (long)RES_MAX_LAYERS * sizeof(ResLayer) + (long)RES_MAX_ENTRIES * sizeof(ResEntry);
-constexpr long TEAM_MEM_BYTES = TEAM_TABLE_OFFSET + 2 * TEAM_TABLE_BYTES;
+constexpr long TEAM_MEM_BYTES = TEAM_TABLE_OFFSET + TEAM_TABLE_BYTES + (long)RES_MAX_ENTRIES * 4;
 static_assert(sizeof(DevOp) % 8 == 0, "programs are copied in 8-byte words");
 
 hipError_t launch_team_kernel(const TeamArgs &a, int nwg, hipStream_t s);

@@ -19,7 +19,7 @@ typedef __attribute__((address_space(1))) float global_f32;
 // Cache policy bits of buffer accesses (gfx942/gfx950): sc0 = coherent within the XCD (skips the
 // compute unit's vector L1, served by the XCD's L2), sc1 = coherent across the device's XCDs
 // (stores write through the L2, loads do not hit stale lines there), both = system scope.
-constexpr int AUX_PLAIN = 0, AUX_SC0 = 1, AUX_SC1 = 16, AUX_SYS = 17;
+constexpr int AUX_PLAIN = 0, AUX_SC0 = 1, AUX_NT = 2, AUX_SC1 = 16, AUX_SYS = 17;
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *p, long bytes) {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, (int)bytes, 0x00020000);
@@ -503,6 +503,19 @@ __device__ __forceinline__ void conv_units(const DevOp &op, float *red, int rank
             for (int d = 0; d < DA; ++d) issue_a(ra[d]);
 #pragma unroll
             for (int d = 0; d < DB; ++d) issue_b(rb[d]);
+            // Resident cells are read from the slab one step ahead of their product, so that the LDS round trip
+            // (table entry, then the cell) lies behind the step before instead of in front of every product.
+            uint4 sv[FT];
+            bool sres[FT];
+            auto fetch_slab = [&]() {
+                const u32x2_t sl = tb.slabs[min(ic, nsteps)];
+#pragma unroll
+                for (int ft = 0; ft < FT; ++ft) {
+                    sres[ft] = sl.y + (unsigned)kg < (unsigned)cg_res[ft];
+                    if (sres[ft]) sv[ft] = *reinterpret_cast<const uint4 *>(slab[ft] + sl.x);
+                }
+            };
+            if (CAN_LIST) fetch_slab();
             for (int i0 = 0; i0 < per_wave; i0 += DA) {
 #pragma unroll
                 for (int u = 0; u < DA; ++u) {
@@ -510,13 +523,12 @@ __device__ __forceinline__ void conv_units(const DevOp &op, float *red, int rank
 #pragma unroll
                     for (int ft = 0; ft < FT; ++ft) fa[ft].u = make_uint4(ra[u][ft].x, ra[u][ft].y, ra[u][ft].z, ra[u][ft].w);
                     if (CAN_LIST) {
-                        const u32x2_t sl = tb.slabs[min(ic, nsteps)];
 #pragma unroll
                         for (int ft = 0; ft < FT; ++ft)
-                            if (sl.y + (unsigned)kg < (unsigned)cg_res[ft])
-                                fa[ft].u = *reinterpret_cast<const uint4 *>(slab[ft] + sl.x);
+                            if (sres[ft]) fa[ft].u = sv[ft];
                     }
                     ic += wk;
+                    if (CAN_LIST) fetch_slab();
 #pragma unroll
                     for (int pt = 0; pt < PT; ++pt) {
                         Frag fb;
@@ -1741,9 +1753,13 @@ __device__ __forceinline__ unsigned long long ld_sys(const unsigned long long *p
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
 }
 
-__device__ __forceinline__ void raise_abort(const TeamArgs &ta) {
-    st_agent(&ta.sync[0], 1ull);
-    __hip_atomic_store(&ta.host->abort_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+// Why a workgroup gave up: which bounded wait ran out (the host reports it with the next call).
+enum AbortWhy { ABORT_FORMATION = 1, ABORT_BARRIER = 2, ABORT_GO = 3, ABORT_POST = 4 };
+__device__ __forceinline__ void raise_abort(const TeamArgs &ta, int why) {
+    // the first reason stays: the waits that give up because somebody else did would overwrite it
+    if (ld_agent(&ta.sync[SY_ABORT]) == 0)
+        __hip_atomic_store(&ta.host->abort_flag, (unsigned)why, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    st_agent(&ta.sync[SY_ABORT], 1ull);
 }
 
 // Drops every line of this compute unit's vector L1.  A team's activations live in its XCD's L2:
@@ -1771,7 +1787,7 @@ __device__ __forceinline__ bool team_barrier(const TeamArgs &ta, int team, unsig
         int spins = 0, good = 1;
         while (ld_agent(ctr) < target) {
             if (++spins > ta.spin_limit || ld_agent(&ta.sync[SY_ABORT]) != 0) {
-                raise_abort(ta);
+                raise_abort(ta, ABORT_BARRIER);
                 good = 0;
                 break;
             }
@@ -1824,14 +1840,15 @@ __device__ __forceinline__ bool fetch_table(const TeamArgs &ta, const ResTable *
     return true;
 }
 
-// Copies slab cells this workgroup owns from the packed weights into its LDS store: all valid cells of
-// `tab`, or, when `prev` (the table installed before, null if none) has the same geometry, only those that
-// `prev` did not make valid already: tiles from prev's n_res on in full, and in the tiles before that the
-// channel groups from prev's cg_res on.  `work` is LDS that is idle during an install (the partial-sum
-// area).  The tables sit in device memory and every dependent read costs a round trip, so nothing here
-// walks them entry by entry: the layers come into LDS in one pass, the entries are searched by all
-// threads at once, and the 16-byte pieces of all cells to copy form one index space that the threads
-// share, eight loads each in flight.
+// Copies slab cells this workgroup owns from the packed weights into its LDS store: the valid cells of `tab`
+// that the store does not hold yet.  `present` (device memory of the team, one word per table entry, cleared
+// when the kernel starts) remembers for every slab how many channel groups of it have been copied, tagged
+// with the geometry they were copied under; only the slab's owner reads and writes its word.  Cells stay in the store
+// when a later SubGraph no longer covers them (they are still the SuperNet's weights), so a SubGraph that grows
+// back finds them there.  `work` is LDS that is idle during an install (the partial-sum area).  The table sits
+// in device memory and every dependent read costs a round trip, so nothing here walks it entry by entry: the
+// layers come into LDS in one pass, the entries are searched by all threads at once, and the 16-byte pieces
+// of all cells to copy form one index space that the threads share, eight loads each in flight.
 struct InstallItem {
     int layer_f;      // layer << 16 | filter tile
     int lds_off;      // byte offset of the slab inside the store
@@ -1839,25 +1856,28 @@ struct InstallItem {
     int cg_from;      // first channel group to copy
 };
 constexpr int INSTALL_MAX_ITEMS = RES_STORE_BYTES / 256;  // a slab is at least one 256-byte cell row
-static_assert(RES_MAX_LAYERS * (sizeof(ResLayer) + 8) + INSTALL_MAX_ITEMS * sizeof(InstallItem) + 16 <= RED_BYTES,
+static_assert(RES_MAX_LAYERS * sizeof(ResLayer) + INSTALL_MAX_ITEMS * sizeof(InstallItem) + 16 <= RED_BYTES,
               "the install work area must fit the partial-sum area");
 
-__device__ void install_slabs(const ResTable *tab, const ResTable *prev, int rank, char *store, char *work) {
+__device__ void install_slabs(const ResTable *tab, unsigned *present, int rank, char *store, char *work, unsigned *layer_mask) {
     ResLayer *lay = reinterpret_cast<ResLayer *>(work);
-    int2 *was = reinterpret_cast<int2 *>(work + RES_MAX_LAYERS * sizeof(ResLayer));  // per layer: {n_res, cg_res} valid before
-    InstallItem *items = reinterpret_cast<InstallItem *>(work + RES_MAX_LAYERS * (sizeof(ResLayer) + 8));
+    InstallItem *items = reinterpret_cast<InstallItem *>(work + RES_MAX_LAYERS * sizeof(ResLayer));
     int *cnt = reinterpret_cast<int *>(items + INSTALL_MAX_ITEMS);  // [0] items, [1] pieces
     const int tid = threadIdx.x;
     const int nl = min(tab->n_layers, RES_MAX_LAYERS), ne = min(tab->n_entries, RES_MAX_ENTRIES);
     const ResLayer *layers = tab->layers;
     const ResEntry *entries = tab->entries;
-    const bool keep = prev != nullptr && prev->geometry == tab->geometry && prev->n_layers == tab->n_layers &&
-                      prev->team_size == tab->team_size;
+    // a slab's word: the geometry number (never 0) in the upper 23 bits, channel groups present in the lower 9;
+    // the words are cleared when the kernel starts
+    static_assert(RES_STORE_BYTES / 256 < 512, "a slab's channel groups fit 9 bits");
+    const unsigned tag = ((unsigned)tab->geometry & 0x7FFFFFu) << 9;
     __syncthreads();  // the work area may still be read by the op before
     if (tid == 0) cnt[0] = 0, cnt[1] = 0;
+    if (tid < RES_MAX_LAYERS / 32) layer_mask[tid] = 0u;
+    __syncthreads();
     for (int l = tid; l < nl; l += STREAM_THREADS) {
         lay[l] = layers[l];
-        was[l] = keep ? make_int2(prev->layers[l].n_res, prev->layers[l].cg_res) : make_int2(0, 0);
+        if (lay[l].n_res > 0) atomicOr(&layer_mask[l >> 5], 1u << (l & 31));  // layers with valid slabs, for the op loop
     }
     __syncthreads();
     for (int i = tid; i < ne; i += STREAM_THREADS) {
@@ -1866,11 +1886,14 @@ __device__ void install_slabs(const ResTable *tab, const ResTable *prev, int ran
         int l = 0;
         while (l < nl && !(lay[l].n_res > 0 && i >= lay[l].first_entry && i < lay[l].first_entry + lay[l].n_res)) ++l;
         if (l == nl) continue;
-        const int f = i - lay[l].first_entry;
-        const int cg_from = f < was[l].x ? was[l].y : 0;
+        const unsigned word = __hip_atomic_load(&present[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const int cg_from = (word & 0xFFFFFE00u) == tag ? (int)(word & 0x1FFu) : 0;
         if (cg_from >= lay[l].cg_res) continue;  // everything this SubGraph wants of the tile is there already
         const int k = atomicAdd(&cnt[0], 1);
-        if (k < INSTALL_MAX_ITEMS) items[k] = InstallItem{(l << 16) | f, e.lds_off, 0, cg_from};
+        if (k < INSTALL_MAX_ITEMS) {
+            items[k] = InstallItem{(l << 16) | (i - lay[l].first_entry), e.lds_off, 0, cg_from};
+            __hip_atomic_store(&present[i], tag | (unsigned)lay[l].cg_res, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
     }
     __syncthreads();
     const int n = min(cnt[0], INSTALL_MAX_ITEMS);
@@ -1928,6 +1951,7 @@ __global__ __launch_bounds__(STREAM_THREADS, 2) void sushi_team_kernel(TeamArgs 
     __shared__ int s_team, s_rank, s_size;
     __shared__ unsigned long long s_slot[7];
     __shared__ unsigned long long s_hdr[4];
+    __shared__ unsigned s_layer_mask[RES_MAX_LAYERS / 32];  // bit l: layer l has valid slabs under the table in use
 
     // ---- team formation: which XCD am I on, how many of us are there
     if (threadIdx.x == 0) {
@@ -1938,7 +1962,7 @@ __global__ __launch_bounds__(STREAM_THREADS, 2) void sushi_team_kernel(TeamArgs 
         int spins = 0, good = 1;
         while (ld_agent(&ta.sync[SY_JOINED]) < gridDim.x) {
             if (++spins > ta.spin_limit || ld_agent(&ta.sync[SY_ABORT]) != 0) {
-                raise_abort(ta);
+                raise_abort(ta, ABORT_FORMATION);
                 good = 0;
                 break;
             }
@@ -1973,11 +1997,12 @@ __global__ __launch_bounds__(STREAM_THREADS, 2) void sushi_team_kernel(TeamArgs 
     DevOp *prog = reinterpret_cast<DevOp *>(team_mem);
     unsigned long long my_seq = ta.last_seq[team];
     unsigned long long epoch = 0;
-    // the residency table in use and which half of the team's table memory holds it: a new table goes to
-    // the other half, so that an install can compare it with the one before
-    const ResTable *table = nullptr;
-    int table_half = 0;
-    unsigned long long table_seq = 0;  // number of the table the LDS stores hold (0: a fresh launch finds nothing there)
+    const ResTable *table = nullptr;   // the residency table in use (the team's device copy)
+    unsigned long long table_seq = 0;  // its number (0: a fresh launch finds nothing in the LDS stores)
+    unsigned *present = reinterpret_cast<unsigned *>(team_mem + TEAM_TABLE_OFFSET + TEAM_TABLE_BYTES);
+    // (cleared by the whole team; the barrier inside the first table fetch comes before any of them is read)
+    for (int i = rank * STREAM_THREADS + (int)threadIdx.x; i < RES_MAX_ENTRIES; i += tsize * STREAM_THREADS)
+        __hip_atomic_store(&present[i], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     unsigned long long *go = &ta.sync[sy_go(team)];
     unsigned long long *slot = &ta.sync[sy_slot(team)];
     const unsigned long long *posted = &ta.host->posted[team * 8];
@@ -2004,7 +2029,7 @@ __global__ __launch_bounds__(STREAM_THREADS, 2) void sushi_team_kernel(TeamArgs 
                         // (a slot is rewritten only after `done` has passed the post that sat in it, so the words
                         // belong to post `seq`; its first word says so)
                         if (ld_sys(&post->seq) != seq) {
-                            raise_abort(ta);
+                            raise_abort(ta, ABORT_POST);
                             cmd = TEAM_STOP;
                         }
                         break;
@@ -2027,8 +2052,12 @@ __global__ __launch_bounds__(STREAM_THREADS, 2) void sushi_team_kernel(TeamArgs 
             } else {
                 const long long t0 = wall_clock64();
                 while (ld_agent(go) < iter) {
-                    if (ld_agent(&ta.sync[SY_ABORT]) != 0 || wall_clock64() - t0 > 4 * ta.idle_ticks + 100000000ll) {
-                        raise_abort(ta);
+                    // The leader polls for as long as any team of the kernel is at work or gets posts (they stamp the
+                    // shared clock), which may be far longer than its own team has anything to do: the bound counts
+                    // from the last stamp, after which the leader itself gives up within the idle limit.
+                    const long long last = std::max(t0, (long long)ld_agent(&ta.sync[SY_CLOCK]));
+                    if (ld_agent(&ta.sync[SY_ABORT]) != 0 || wall_clock64() - last > 4 * ta.idle_ticks + 100000000ll) {
+                        raise_abort(ta, ABORT_GO);
                         good = 0;
                         break;
                     }
@@ -2046,12 +2075,14 @@ __global__ __launch_bounds__(STREAM_THREADS, 2) void sushi_team_kernel(TeamArgs 
         if (cmd != TEAM_RUN) return;
         // ---- the cached SubGraph this query runs under: bring the LDS stores up to its table if they hold another
         if (s_slot[6] != table_seq) {
-            const ResTable *before = table;
-            if (before) table_half ^= 1;
-            if (!fetch_table(ta, reinterpret_cast<const ResTable *>(s_slot[5]), team_mem + TEAM_TABLE_OFFSET + table_half * TEAM_TABLE_BYTES,
-                             team, rank, tsize, epoch, s_hdr, &flag, &table))
+            if (!fetch_table(ta, reinterpret_cast<const ResTable *>(s_slot[5]), team_mem + TEAM_TABLE_OFFSET, team, rank, tsize,
+                             epoch, s_hdr, &flag, &table))
                 return;
-            if (table) install_slabs(table, before, rank, store, dyn_lds);
+            if (table)
+                install_slabs(table, present, rank, store, dyn_lds, s_layer_mask);
+            else if (threadIdx.x < RES_MAX_LAYERS / 32)
+                s_layer_mask[threadIdx.x] = 0u;
+            __syncthreads();
             table_seq = s_slot[6];
         }
         const void *input = reinterpret_cast<const void *>(s_slot[2]);
@@ -2099,7 +2130,9 @@ __global__ __launch_bounds__(STREAM_THREADS, 2) void sushi_team_kernel(TeamArgs 
             uop = uniform_op(uop);  // the arena and the caller's buffers came through LDS
             if (ta.trace && i == 0 && rank == 0 && threadIdx.x == 0) ta.trace[team * TRACE_SLOTS] = wall_clock64();
             ResView rv{nullptr, nullptr, store, unit_list};
-            if (table && uop.layer >= 0 && uop.layer < table->n_layers && table->layers[uop.layer].n_res > 0) {
+            // (asked of the mask in LDS: a look into the table costs a round trip to the L2 in front of every op)
+            if (table && uop.layer >= 0 && uop.layer < RES_MAX_LAYERS &&
+                ((__builtin_amdgcn_readfirstlane((int)s_layer_mask[uop.layer >> 5]) >> (uop.layer & 31)) & 1) != 0) {
                 rv.layer = &table->layers[uop.layer];
                 rv.entries = table->entries + rv.layer->first_entry;
             }

@@ -129,6 +129,7 @@ struct sushi_ctx {
     std::vector<ResLayer> geo_layers;
     std::vector<ResEntry> geo_entries;
     int geometry = 0, geometry_team_size = 0;
+    std::vector<int> geo_present;  // per entry: channel groups a team that served under every table has copied (this geometry)
     uint64_t table_version = 0;
     unsigned long long table_seq = 1;  // number of the table in force, carried by every query post (see TeamPost)
     uint64_t table_bytes = 0;  // bytes of the cached SubGraph that sit in LDS (per team)
@@ -661,6 +662,7 @@ bool build_res_table(sushi_ctx *c, uint64_t *new_bytes) {
     if (grow) {
         rebuild_geometry(c);
         c->geometry_team_size = c->team_size();
+        c->geo_present.assign(c->geo_entries.size(), 0);
     }
     std::vector<ResLayer> layers = c->geo_layers;
     uint64_t bytes = 0;
@@ -678,19 +680,15 @@ bool build_res_table(sushi_ctx *c, uint64_t *new_bytes) {
                 const uint64_t cells = (uint64_t)R.taps * 8 * std::min(16, c->G[l].K - 16 * f) * 2;
                 bytes += cells * R.cg_res;
                 any = true;
-                // cells valid before (same geometry): tiles below the old n_res up to the old cg_res
-                const bool had = !grow && l < c->h_res_layers.size() && f < c->h_res_layers[l].n_res;
-                const int from = had ? std::min(c->h_res_layers[l].cg_res, R.cg_res) : 0;
-                *new_bytes += cells * (R.cg_res - from);
+                // cells such a team's store does not hold yet
+                int &have = c->geo_present[R.first_entry + f];
+                if (R.cg_res > have) *new_bytes += cells * (R.cg_res - have), have = R.cg_res;
             }
     }
     bool changed = grow || layers.size() != c->h_res_layers.size() || any != !c->h_res_entries.empty();
     for (size_t l = 0; !changed && l < layers.size(); ++l)
         changed = layers[l].n_res != c->h_res_layers[l].n_res || layers[l].cg_res != c->h_res_layers[l].cg_res;
-    if (!changed) {
-        *new_bytes = 0;
-        return false;
-    }
+    if (!changed) return false;
     c->h_res_layers = std::move(layers);
     if (any) c->h_res_entries = c->geo_entries; else c->h_res_entries.clear();
     c->table_bytes = bytes;
@@ -785,9 +783,15 @@ int launch_teams(sushi_ctx *c) {
         c->team_launched = false;
     }
     if (c->th->abort_flag) {
+        static const char *const why[] = {"?", "not every workgroup of the launch became resident",
+                                          "a workgroup did not reach a team barrier within the spin limit",
+                                          "a team leader did not hand a post to its team in time",
+                                          "a mailbox slot did not hold the post its counter announced"};
+        const unsigned code = c->th->abort_flag;
         c->th->abort_flag = 0;
         for (int t = 0; t < MAX_TEAMS; ++t) c->th->done[t * 8] = c->posted[t];  // drop what was in flight
-        return fail(c, SUSHI_EDEVICE, "a wait inside the team kernel ran out; queries in flight were dropped");
+        return fail(c, SUSHI_EDEVICE, std::string("a wait inside the team kernel ran out (") + why[code < 5 ? code : 0] +
+                                          "); queries in flight were dropped");
     }
     c->th->ready = 0;
     if ((e = hipMemsetAsync(c->d_tsync, 0, SYNC_WORDS * 8, c->pstream)) != hipSuccess) return hip_fail(c, e, "hipMemsetAsync");

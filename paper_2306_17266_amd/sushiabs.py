@@ -26,8 +26,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 TABLE_DIR = os.path.join(HERE, "tables")
 
 
-def table_path(workload, budget_bytes):
-    return os.path.join(TABLE_DIR, "%s_%dMiB_mi355x.json" % (workload, budget_bytes >> 20))
+def table_path(workload, budget_bytes, teams_per_xcd):
+    """Where the frozen table of a workload lives: measured in exec mode 3 with that many teams per XCD."""
+    return os.path.join(TABLE_DIR, "%s_%dMiB_%dteams_mi355x.json" % (workload, budget_bytes >> 20, teams_per_xcd))
 
 
 def save_table(path, table, workload, budget_bytes, runs, note=""):

@@ -251,3 +251,38 @@ def test_team_plan_rejects_bad_arguments():
     for batch, team in ((0, 8), (1, 0), (1, 33)):
         with pytest.raises(S.SushiError):
             S.sushi_team_plan(arch, cfg, batch, team)
+
+
+def test_frozen_latency_table_decisions_match_the_oracle():
+    """Configuration 4 as the benchmark runs it: the latency table measured on the GPU and frozen to a file,
+    synthetic accuracies that grow with SubNet size, five latency targets between the fastest and the slowest
+    SubNet, Algorithm 1 with strict latency.  The library and the oracle scheduler read the same file and must
+    take the same decisions (SubNet served, cache chosen, and when) on the whole 2000-query stream."""
+    from paper_2306_17266_amd import sushiabs
+    from workloads import configs
+    wl = configs.build("resnet_bs16_levels")
+    arch, pool = wl["arch"], wl["pool"]
+    boxes = [S.sushi_subnet_layers(arch, c) for c in pool]
+    cands = streams.candidate_subgraphs(boxes, wl["budget"], 2, 40)
+    frozen = sushiabs.load_table(sushiabs.table_path("resnet_bs16_levels", wl["budget"], 1), len(pool), len(cands))
+    assert frozen is not None, "the frozen table does not fit the serving pool and candidate set"
+    table = frozen["table"]
+    assert table.dtype == np.float32 and (table > 0).all()
+    sizes = [streams.box_bytes(b, 2) for b in boxes]
+    acc = [0.0] * len(pool)
+    for rank, i in enumerate(sorted(range(len(pool)), key=lambda i: sizes[i])):
+        acc[i] = float(np.float32(0.70 + 0.01 * rank))
+    levels = sushiabs.latency_levels(table, wl["n_levels"])
+    vecs = [E.encode_vector(arch, c) for c in pool]
+    gvecs = [[v for (k, c, r) in b for v in (k, c)] for b in cands]
+    ref = SchedRef(vecs, acc, gvecs, [[float(v) for v in row] for row in table], wl["Q"], STRICT_LATENCY)
+    ctx = S.Sushi(-1)
+    ctx.sushi_sched_init(vecs, acc, gvecs, table, wl["Q"], S.STRICT_LATENCY)
+    served, changes = set(), 0
+    for lv in wl["levels"]:
+        got = ctx.sushi_sched_step(0.0, levels[lv])
+        assert got == ref.step(0.0, levels[lv])
+        served.add(got[0])
+        changes += got[1] >= 0
+    assert len(served) >= 3 and changes == len(wl["levels"]) // wl["Q"]
+    ctx.close()
