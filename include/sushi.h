@@ -206,6 +206,7 @@ typedef struct sushi_team_op {
     int32_t B, H, W, C, P, Q, K, R, stride;
     int32_t ft, pt, wk, n_units, n_p;
     int32_t lds_bytes;
+    int32_t res, out_f32; /* the op adds a residual of the output's shape / stores float32 (gates, logits) */
 } sushi_team_op;
 
 /* The ops of SubNet cfg at the given batch size as a team of team_wgs workgroups (4 .. 32) would run them, in order.
@@ -339,6 +340,18 @@ typedef struct sushi_kernel_stats {
     double flops;
 } sushi_kernel_stats;
 int sushi_get_kernel_stats(sushi_ctx *ctx, sushi_kernel_stats *out, int cap, int *n_out);
+
+/* One timed launch of exec mode 0 (SUSHI_OPT_KERNEL_TIMING = 1): which op of the query's plan it ran (the order
+ * sushi_team_plan lists them in), the kernel family (index into sushi_get_kernel_stats), its duration by HIP
+ * events and its algorithmic bytes and flops.  The library keeps the records of the launches since timing was
+ * switched on, at most 65536.  Waits for outstanding timed launches.  Writes min(n, cap) entries. */
+typedef struct sushi_launch_record {
+    int32_t op_index, kernel_class;
+    float ms;
+    float pad;
+    double bytes, flops;
+} sushi_launch_record;
+int sushi_get_launch_records(sushi_ctx *ctx, sushi_launch_record *out, int cap, int *n_out);
 
 #ifdef __cplusplus
 }

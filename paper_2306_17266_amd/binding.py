@@ -58,7 +58,7 @@ class CLayerDims(C.Structure):
 
 class CTeamOp(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("kind", "layer", "B", "H", "W", "C", "P", "Q", "K", "R", "stride",
-                                          "ft", "pt", "wk", "n_units", "n_p", "lds_bytes")]
+                                          "ft", "pt", "wk", "n_units", "n_p", "lds_bytes", "res", "out_f32")]
 
 
 class CSubgraphCfg(C.Structure):
@@ -84,6 +84,11 @@ class CStats(C.Structure):
 
 class CKernelStats(C.Structure):
     _fields_ = [("name", C.c_char * 32), ("launches", C.c_uint64), ("total_ms", C.c_double),
+                ("bytes", C.c_double), ("flops", C.c_double)]
+
+
+class CLaunchRecord(C.Structure):
+    _fields_ = [("op_index", C.c_int32), ("kernel_class", C.c_int32), ("ms", C.c_float), ("pad", C.c_float),
                 ("bytes", C.c_double), ("flops", C.c_double)]
 
 
@@ -121,6 +126,7 @@ def lib():
     L.sushi_team_trace.argtypes = [vp, C.c_int, C.POINTER(C.c_uint64), C.c_int]
     L.sushi_set_option.argtypes = [vp, C.c_int, C.c_int64]
     L.sushi_get_kernel_stats.argtypes = [vp, C.POINTER(CKernelStats), C.c_int, ip]
+    L.sushi_get_launch_records.argtypes = [vp, C.POINTER(CLaunchRecord), C.c_int, ip]
     _lib = L
     return L
 
@@ -344,6 +350,13 @@ class Sushi:
 
     def sushi_set_option(self, option, value):
         _check(lib().sushi_set_option(self._h, option, value), self._h)
+
+    def sushi_get_launch_records(self):
+        n = C.c_int(0)
+        _check(lib().sushi_get_launch_records(self._h, None, 0, C.byref(n)), self._h)
+        buf = (CLaunchRecord * max(1, n.value))()
+        _check(lib().sushi_get_launch_records(self._h, buf, n.value, C.byref(n)), self._h)
+        return [(buf[i].op_index, buf[i].kernel_class, buf[i].ms, buf[i].bytes, buf[i].flops) for i in range(n.value)]
 
     def sushi_get_kernel_stats(self):
         buf, n = (CKernelStats * 16)(), C.c_int(0)

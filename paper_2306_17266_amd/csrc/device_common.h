@@ -22,6 +22,17 @@ typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 static __constant__ signed char c_dw_dr[49] = {DW_DR_LIST};
 static __constant__ signed char c_dw_ds[49] = {DW_DS_LIST};
 
+// Position of the tap at offset (dr, ds) from the centre in the ring order of the stored taps.
+__host__ __device__ constexpr int dw_tap_index(int dr, int ds) {
+    const int ar = dr < 0 ? -dr : dr, as = ds < 0 ? -ds : ds;
+    const int r = ar > as ? ar : as;
+    if (r <= 1) return (dr + 1) * 3 + ds + 1;
+    const int base = (2 * r - 1) * (2 * r - 1);
+    if (dr == -r) return base + ds + r;
+    if (dr == r) return base + (2 * r + 1) + 2 * (2 * r - 1) + ds + r;
+    return base + (2 * r + 1) + (dr + r - 1) * 2 + (ds == r ? 1 : 0);
+}
+
 union Frag {
     uint4 u;
     bf16x8_t v;
@@ -31,11 +42,17 @@ union Frag {
 
 __device__ __forceinline__ float bf2f(uint32_t b) { return __uint_as_float(b << 16); }
 
-__device__ __forceinline__ uint32_t f2bf(float f) {  // round to nearest even
-    uint32_t u = __float_as_uint(f);
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return u >> 16;
+typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+
+// Two float32 values to one word of two bf16 (lo in bits 15:0), round to nearest even: the hardware's packed
+// conversion (v_cvt_pk_bf16_f32), one instruction instead of about ten.
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    const f32x2_t v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
+
+__device__ __forceinline__ uint32_t f2bf(float f) { return pack_bf16x2(f, 0.0f) & 0xFFFFu; }  // round to nearest even
 
 __device__ __forceinline__ void load8(const float *p, float v[8]) {
     const float4 a = *reinterpret_cast<const float4 *>(p);
@@ -56,8 +73,8 @@ __device__ __forceinline__ void store8(float *p, const float v[8]) {
 
 __device__ __forceinline__ void store8(uint16_t *p, const float v[8]) {
     uint4 a;
-    a.x = f2bf(v[0]) | (f2bf(v[1]) << 16), a.y = f2bf(v[2]) | (f2bf(v[3]) << 16);
-    a.z = f2bf(v[4]) | (f2bf(v[5]) << 16), a.w = f2bf(v[6]) | (f2bf(v[7]) << 16);
+    a.x = pack_bf16x2(v[0], v[1]), a.y = pack_bf16x2(v[2], v[3]);
+    a.z = pack_bf16x2(v[4], v[5]), a.w = pack_bf16x2(v[6], v[7]);
     *reinterpret_cast<uint4 *>(p) = a;
 }
 

@@ -65,6 +65,10 @@ hipError_t launch_maxpool(const PoolArgs &a, bool bf16, hipStream_t s);   // 3x3
 hipError_t launch_gap(const PoolArgs &a, bool bf16, hipStream_t s);       // [B][H][W][C] -> [B][C]
 hipError_t launch_gate(const PoolArgs &a, bool bf16, hipStream_t s);      // y = x * gate[b][c]
 
+// Depthwise k x k, k in {3, 5, 7}, stride 1 or 2, bf16, tensors below 2 GiB: the row-strip kernel (dwconv.hip).
+// Returns hipErrorNotSupported (nothing launched) for any other case.
+hipError_t launch_dwconv_rows(const ConvArgs &a, hipStream_t s);
+
 // Streams `bytes` of `buf` through the caches (reads every 16-byte word once; `sink` receives one word that
 // depends on all of them, so the reads cannot be dropped).  A measurement aid: see SUSHI_OPT_COLD_SWEEP_MIB.
 hipError_t launch_cold_sweep(const void *buf, size_t bytes, void *sink, hipStream_t s);

@@ -122,7 +122,7 @@ __device__ __forceinline__ void store_tile(const ConvArgs &a, const f32x4_t acc,
         uint16_t *yp = static_cast<uint16_t *>(a.y) + o;
         if (vec) {
             uint2 r;
-            r.x = f2bf(v[0]) | (f2bf(v[1]) << 16), r.y = f2bf(v[2]) | (f2bf(v[3]) << 16);
+            r.x = pack_bf16x2(v[0], v[1]), r.y = pack_bf16x2(v[2], v[3]);
             *reinterpret_cast<uint2 *>(yp) = r;
         } else {
             for (int i = 0; i < nf; ++i) yp[i] = (uint16_t)f2bf(v[i]);
@@ -572,7 +572,7 @@ static hipError_t launch_splitk(const ConvArgs &a, int wk, hipStream_t s) {
 
 const char *kernel_class_name(int kc) {
     static const char *names[KC_COUNT] = {"conv_direct_kernel", "conv_mfma_kernel", "conv_mfma_splitk_kernel",
-                                          "dwconv_kernel",      "maxpool_kernel",   "gap_kernel",
+                                          "dwconv_rows_kernel", "maxpool_kernel",   "gap_kernel",
                                           "gate_kernel",        "sushi_stream_kernel", "sushi_team_kernel"};
     return kc >= 0 && kc < KC_COUNT ? names[kc] : "?";
 }
@@ -610,6 +610,10 @@ hipError_t launch_conv(const ConvArgs &a, bool bf16, hipStream_t s, int *kc) {
 
 hipError_t launch_dwconv(const ConvArgs &a, bool bf16, hipStream_t s) {
     const long total = (long)a.B * a.P * a.Q * (a.K >> 3);
+    if (bf16) {
+        const hipError_t e = launch_dwconv_rows(a, s);
+        if (e != hipErrorNotSupported) return e;
+    }
     if (bf16)
         hipLaunchKernelGGL(dwconv_kernel<uint16_t>, dim3(blocks_for(total)), dim3(256), 0, s, a);
     else

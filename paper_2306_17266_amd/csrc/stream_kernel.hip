@@ -50,8 +50,8 @@ __device__ __forceinline__ void unpack8(const uint4 a, float v[8]) {
 
 __device__ __forceinline__ uint4 pack8(const float v[8]) {
     uint4 a;
-    a.x = f2bf(v[0]) | (f2bf(v[1]) << 16), a.y = f2bf(v[2]) | (f2bf(v[3]) << 16);
-    a.z = f2bf(v[4]) | (f2bf(v[5]) << 16), a.w = f2bf(v[6]) | (f2bf(v[7]) << 16);
+    a.x = pack_bf16x2(v[0], v[1]), a.y = pack_bf16x2(v[2], v[3]);
+    a.z = pack_bf16x2(v[4], v[5]), a.w = pack_bf16x2(v[6], v[7]);
     return a;
 }
 
@@ -197,7 +197,7 @@ __device__ __forceinline__ void store_tile_coherent(const ConvArgs &a, __amdgpu_
         }
     } else {
         if (vec) {
-            const uint2 pk = make_uint2(f2bf(v[0]) | (f2bf(v[1]) << 16), f2bf(v[2]) | (f2bf(v[3]) << 16));
+            const uint2 pk = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
             if (sys_out)
                 act_st8<AUX_SYS>(ry, (int)(o * 2), pk);
             else
@@ -238,7 +238,7 @@ __device__ __forceinline__ void store_tile_fast(const ConvArgs &a, __amdgpu_buff
         else
             act_st16<ST>(ry, o * 4, pk);
     } else {
-        const uint2 pk = make_uint2(f2bf(v[0]) | (f2bf(v[1]) << 16), f2bf(v[2]) | (f2bf(v[3]) << 16));
+        const uint2 pk = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
         if (sys_out)
             act_st8<AUX_SYS>(ry, o * 2, pk);
         else
@@ -257,7 +257,7 @@ __device__ __forceinline__ void store_tile_bf16(__amdgpu_buffer_rsrc_t ry, const
     v[0] += bf2f(res.x & 0xFFFFu), v[1] += bf2f(res.x >> 16), v[2] += bf2f(res.y & 0xFFFFu), v[3] += bf2f(res.y >> 16);
 #pragma unroll
     for (int i = 0; i < 4; ++i) v[i] = act_fast<ACT>(v[i]);
-    act_st8<ST>(ry, offset, make_uint2(f2bf(v[0]) | (f2bf(v[1]) << 16), f2bf(v[2]) | (f2bf(v[3]) << 16)));
+    act_st8<ST>(ry, offset, make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])));
 }
 
 // Calls f(std::integral_constant<int, ACT>) for the activation of the op.
@@ -1083,7 +1083,7 @@ __device__ __forceinline__ void conv_direct_units(const ConvArgs &a, int rank, i
         uint16_t *yp = static_cast<uint16_t *>(a.y) + obase;
         if (nf == 4 && (a.K & 3) == 0) {
             act_st8<ST>(ry, (int)(obase * 2),
-                        make_uint2(f2bf(v4[0]) | (f2bf(v4[1]) << 16), f2bf(v4[2]) | (f2bf(v4[3]) << 16)));
+                        make_uint2(pack_bf16x2(v4[0], v4[1]), pack_bf16x2(v4[2], v4[3])));
         } else {
             for (int i = 0; i < nf; ++i)
                 __hip_atomic_store(yp + i, (uint16_t)f2bf(v4[i]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -1390,16 +1390,6 @@ __device__ __forceinline__ void dw_tiled_units(const DevOp &op, float *lds, int 
             }
         }
     }
-}
-
-// Position of the tap at offset (dr, ds) from the centre in the ring order of the stored taps.
-__device__ __forceinline__ int dw_tap_index(int dr, int ds) {
-    const int r = max(abs(dr), abs(ds));
-    if (r <= 1) return (dr + 1) * 3 + ds + 1;
-    const int base = (2 * r - 1) * (2 * r - 1);
-    if (dr == -r) return base + ds + r;
-    if (dr == r) return base + (2 * r + 1) + 2 * (2 * r - 1) + ds + r;
-    return base + (2 * r + 1) + (dr + r - 1) * 2 + (ds == r ? 1 : 0);
 }
 
 // Depthwise k x k straight from memory (wk == -4), for layers whose bands in LDS would be too small to

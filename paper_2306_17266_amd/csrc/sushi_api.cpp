@@ -140,7 +140,9 @@ struct sushi_ctx {
         hipEvent_t a, b;
         int kc;
         double bytes, flops;
+        int op_index = -1;
     };
+    std::vector<sushi_launch_record> records;  // per-launch durations of mode 0 since timing was switched on
     std::vector<Pending> pending;
     std::vector<hipEvent_t> free_events;
     sushi_kernel_stats kstats[KC_COUNT] = {};
@@ -388,6 +390,8 @@ hipError_t drain_timing(sushi_ctx *c) {
         if (e == hipSuccess) {
             sushi_kernel_stats &k = c->kstats[p.kc];
             k.launches += 1, k.total_ms += ms, k.bytes += p.bytes, k.flops += p.flops;
+            if (p.op_index >= 0 && c->records.size() < 65536)
+                c->records.push_back(sushi_launch_record{p.op_index, p.kc, ms, 0.f, p.bytes, p.flops});
         }
         c->free_events.push_back(p.a);
         c->free_events.push_back(p.b);
@@ -399,8 +403,10 @@ hipError_t drain_timing(sushi_ctx *c) {
 hipError_t issue_launches(sushi_ctx *c, CachedPlan &cp, const void *input_dev, void *logits_dev, hipStream_t st) {
     const bool timed = c->timing && st == c->stream;
     hipError_t e = hipSuccess;
+    int op_index = -1;
     for (Launch &L : cp.launches) {
         sushi_ctx::Pending pend{};
+        pend.op_index = ++op_index;
         if (timed) {
             if ((e = get_event(c, &pend.a)) != hipSuccess || (e = get_event(c, &pend.b)) != hipSuccess) return e;
             if ((e = hipEventRecord(pend.a, st)) != hipSuccess) return e;
@@ -1133,6 +1139,7 @@ int sushi_team_plan(const sushi_arch *arch, const sushi_subnet_cfg *cfg, int bat
             t.B = o.B, t.H = o.H, t.W = o.W, t.C = o.C, t.P = o.P, t.Q = o.Q, t.K = o.K, t.R = o.r, t.stride = o.stride;
             t.ft = op.ft, t.pt = op.pt, t.wk = op.wk, t.n_units = op.n_units, t.n_p = op.n_p;
             t.lds_bytes = (int32_t)dev_op_lds_bytes(op);
+            t.res = o.res_buf >= 0 ? 1 : 0, t.out_f32 = o.out_f32 ? 1 : 0;
         }
     }
     return SUSHI_OK;
@@ -1526,12 +1533,25 @@ int sushi_get_kernel_stats(sushi_ctx *c, sushi_kernel_stats *out, int cap, int *
     return SUSHI_OK;
 }
 
+int sushi_get_launch_records(sushi_ctx *c, sushi_launch_record *out, int cap, int *n_out) {
+    if (!c || !n_out || cap < 0 || (cap > 0 && !out)) return SUSHI_EINVAL;
+    if (c->device >= 0) {
+        hipError_t e = drain_timing(c);
+        if (e != hipSuccess) return hip_fail(c, e, "kernel timing");
+    }
+    *n_out = (int)c->records.size();
+    for (int i = 0; i < cap && i < *n_out; ++i) out[i] = c->records[i];
+    return SUSHI_OK;
+}
+
 int sushi_set_option(sushi_ctx *c, int option, int64_t value) {
     if (!c) return SUSHI_EINVAL;
     if (option == SUSHI_OPT_KERNEL_TIMING && (value == 0 || value == 1)) {
         if (c->device >= 0) (void)drain_timing(c);
-        if (value == 1)
+        if (value == 1) {
             for (auto &k : c->kstats) k = sushi_kernel_stats{};
+            c->records.clear();
+        }
         c->timing = value == 1;
         return SUSHI_OK;
     }
