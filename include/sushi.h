@@ -195,6 +195,13 @@ int sushi_describe_supernet(const sushi_arch *arch, sushi_tensor_desc *out, int 
 int sushi_subnet_layers(const sushi_arch *arch, const sushi_subnet_cfg *cfg, sushi_layer_dims *out, int cap,
                         int *n_out);
 
+/* What a SubNet has in common with a cached SubGraph (both as per-layer boxes of n layers, K = 0: layer unused):
+ * the SubNet's weight bytes, the bytes inside the intersection (per layer the elementwise minimum of the
+ * boxes), and the hit ratio of Appendix A.4, ||min(v_SN, v_G)||_2 / ||v_SN||_2 on the [K_1, C_1, ..., K_n, C_n]
+ * vectors.  Host only.  Any output pointer may be NULL. */
+int sushi_subgraph_overlap(const sushi_layer_dims *subnet, const sushi_layer_dims *subgraph, int n, int bytes_per_weight,
+                           uint64_t *subnet_bytes, uint64_t *common_bytes, double *hit_ratio);
+
 /* How exec mode 3 cuts one op of a SubNet's per-query plan (Section 3.1: a query activates one SubNet; Section 4.2:
  * its layers run one after the other) into units for a team of workgroups.  kind: 0 dense conv, 1 depthwise conv,
  * 2 max-pool, 3 global average pool, 4 fully connected, 5 channel gate.  layer: SuperNet layer (order of

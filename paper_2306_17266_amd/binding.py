@@ -108,6 +108,8 @@ def lib():
     L.sushi_describe_supernet.argtypes = [C.POINTER(CArch), C.POINTER(CTensorDesc), C.c_int, ip]
     L.sushi_subnet_layers.argtypes = [C.POINTER(CArch), C.POINTER(CSubnetCfg), C.POINTER(CLayerDims), C.c_int, ip]
     L.sushi_team_plan.argtypes = [C.POINTER(CArch), C.POINTER(CSubnetCfg), C.c_int, C.c_int, C.POINTER(CTeamOp), C.c_int, ip]
+    L.sushi_subgraph_overlap.argtypes = [C.POINTER(CLayerDims), C.POINTER(CLayerDims), C.c_int, C.c_int,
+                                         C.POINTER(C.c_uint64), C.POINTER(C.c_uint64), C.POINTER(C.c_double)]
     L.sushi_create.argtypes = [C.POINTER(vp), C.c_int, vp]
     L.sushi_destroy.argtypes = [vp]
     L.sushi_destroy.restype = None
@@ -199,6 +201,21 @@ def sushi_team_plan(arch, cfg, batch, team_wgs):
     buf = (CTeamOp * 512)()
     _check(lib().sushi_team_plan(C.byref(a), C.byref(s), int(batch), int(team_wgs), buf, 512, C.byref(n)))
     return [{f: getattr(buf[i], f) for f, _ in CTeamOp._fields_} for i in range(n.value)]
+
+
+def marshal_box(box):
+    """(K, C, r) triples -> sushi_layer_dims array."""
+    return (CLayerDims * len(box))(*[CLayerDims(k, c, r) for (k, c, r) in box])
+
+
+def sushi_subgraph_overlap(subnet_box, subgraph_box, bytes_per_weight=2):
+    """(SubNet weight bytes, bytes inside the cached SubGraph, hit ratio of Appendix A.4).  The boxes may be
+    lists of (K, C, r) or arrays from marshal_box."""
+    a = subnet_box if isinstance(subnet_box, C.Array) else marshal_box(subnet_box)
+    b = subgraph_box if isinstance(subgraph_box, C.Array) else marshal_box(subgraph_box)
+    total, common, hit = C.c_uint64(0), C.c_uint64(0), C.c_double(0.0)
+    _check(lib().sushi_subgraph_overlap(a, b, len(a), bytes_per_weight, C.byref(total), C.byref(common), C.byref(hit)))
+    return total.value, common.value, hit.value
 
 
 class Sushi:

@@ -1104,6 +1104,27 @@ int sushi_subnet_layers(const sushi_arch *arch, const sushi_subnet_cfg *cfg, sus
     return SUSHI_OK;
 }
 
+int sushi_subgraph_overlap(const sushi_layer_dims *sn, const sushi_layer_dims *g, int n, int bytes_per_weight,
+                           uint64_t *subnet_bytes, uint64_t *common_bytes, double *hit_ratio) {
+    if (!sn || !g || n < 1 || bytes_per_weight < 1) return SUSHI_EINVAL;
+    uint64_t total = 0, common = 0;
+    double norm2 = 0.0, inter2 = 0.0;
+    for (int i = 0; i < n; ++i) {
+        const sushi_layer_dims &d = sn[i], &c = g[i];
+        if (d.K <= 0) continue;
+        total += (uint64_t)d.K * d.C * d.r * d.r * bytes_per_weight;
+        norm2 += (double)d.K * d.K + (double)d.C * d.C;
+        if (c.K <= 0) continue;
+        const uint64_t k = std::min(d.K, c.K), ch = std::min(d.C, c.C), r = std::min(d.r, c.r);
+        common += k * ch * r * r * bytes_per_weight;
+        inter2 += (double)k * k + (double)ch * ch;
+    }
+    if (subnet_bytes) *subnet_bytes = total;
+    if (common_bytes) *common_bytes = common;
+    if (hit_ratio) *hit_ratio = norm2 > 0 ? std::sqrt(inter2) / std::sqrt(norm2) : 0.0;
+    return SUSHI_OK;
+}
+
 int sushi_team_plan(const sushi_arch *arch, const sushi_subnet_cfg *cfg, int batch, int team_wgs, sushi_team_op *out,
                     int cap, int *n_out) {
     if (!arch || !cfg || !n_out || cap < 0 || (cap > 0 && !out) || batch < 1 || team_wgs < 1 || team_wgs > 32)

@@ -286,3 +286,23 @@ def test_frozen_latency_table_decisions_match_the_oracle():
         changes += got[1] >= 0
     assert len(served) >= 3 and changes == len(wl["levels"]) // wl["Q"]
     ctx.close()
+
+
+@pytest.mark.parametrize("mk", [A.small_resnet_arch, A.mbv3_arch, A.resnet_arch])
+def test_subgraph_overlap_matches_the_oracle(mk):
+    """Bytes inside SN ∩ G and the hit ratio of Appendix A.4 from the library's host-only helper against the
+    oracle's intersect / weight_count / hit_ratio, for SubNets against shrunken SubGraphs and the empty one."""
+    arch = mk()
+    st = Stream(29)
+    res = max(arch.res_choices)
+    cfgs = [A.min_cfg(arch, res), A.max_cfg(arch, res)] + [streams.uniform_cfg(arch, st, res) for _ in range(6)]
+    boxes = [E.subnet_box(arch, c) for c in cfgs]
+    graphs = [streams.shrink_box(b, 1 << 20, 2) for b in boxes[:4]] + [boxes[1], [(0, 0, 0)] * len(boxes[0])]
+    for cfg, sn in zip(cfgs, boxes):
+        for g in graphs:
+            total, common, hit = S.sushi_subgraph_overlap(sn, g, 2)
+            assert total == 2 * E.weight_count(sn)
+            assert common == 2 * E.weight_count(E.intersect(sn, g))
+            want = E.hit_ratio(E.encode_vector(arch, cfg), [v for (k, c, r) in g for v in (k if k else 0, c if k else 0)])
+            assert abs(hit - want) < 1e-12
+    assert S.sushi_subgraph_overlap(boxes[0], boxes[1], 2)[2] == 1.0      # G ⊇ SN
