@@ -54,6 +54,21 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 
 __device__ __forceinline__ uint32_t f2bf(float f) { return pack_bf16x2(f, 0.0f) & 0xFFFFu; }  // round to nearest even
 
+// Eight float32 values (two 16-byte words) as two bf16 operands of eight: x = hi + lo, hi = bf16(x) rounded to
+// nearest even, lo = bf16(x - hi); together they carry about 16 bits of x's mantissa.
+__device__ __forceinline__ void split_f32x8(const uint4 a, const uint4 b, uint4 *hi, uint4 *lo) {
+    const float x[8] = {__uint_as_float(a.x), __uint_as_float(a.y), __uint_as_float(a.z), __uint_as_float(a.w),
+                        __uint_as_float(b.x), __uint_as_float(b.y), __uint_as_float(b.z), __uint_as_float(b.w)};
+    unsigned h[4], l[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        h[i] = pack_bf16x2(x[2 * i], x[2 * i + 1]);
+        l[i] = pack_bf16x2(x[2 * i] - bf2f(h[i] & 0xFFFFu), x[2 * i + 1] - bf2f(h[i] >> 16));
+    }
+    *hi = make_uint4(h[0], h[1], h[2], h[3]);
+    *lo = make_uint4(l[0], l[1], l[2], l[3]);
+}
+
 __device__ __forceinline__ void load8(const float *p, float v[8]) {
     const float4 a = *reinterpret_cast<const float4 *>(p);
     const float4 b = *reinterpret_cast<const float4 *>(p + 4);

@@ -33,6 +33,8 @@ struct ConvArgs {
     int act;             // sushi_act; applied after the residual add
     int hsigmoid;        // replace act by min(max(v+3,0),6)/6
     int out_f32;         // store float32 regardless of the activation type
+    int in_f32;          // bf16 mode: the input is a float32 vector per image (pooled features, squeeze-excite and
+                         // head vectors); the kernels split it into two bf16 terms (value = hi + lo) on the fly
 };
 
 struct PoolArgs {
@@ -40,6 +42,7 @@ struct PoolArgs {
     void *y;
     const float *gate;  // OP_GATE: [B][C] multipliers
     int B, H, W, C, P, Q;
+    int out_f32;        // OP_GAP in bf16 mode: store the averages as float32
 };
 
 // Kernel families, for per-kernel accounting.

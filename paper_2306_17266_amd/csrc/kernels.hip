@@ -277,7 +277,10 @@ __global__ __launch_bounds__(256) void conv_mfma_kernel(ConvArgs a, int tiles_f,
 // before the first MFMA, and the partial sums are added in a fixed order through LDS.  One
 // workgroup computes FT x PT tiles.  Loads are unconditional (addresses clamped into the tensor);
 // masked activations are zeroed afterwards, which also covers the spatial zero padding.
-template <int FT, int PT, int U, int MAXT>
+// IN32: the input is a float32 vector per image (H = W = 1): every value is split into two bf16 terms,
+// x = hi + lo with hi = bf16(x) and lo = bf16(x - hi), and both are multiplied with the same weight fragment, so
+// the product carries about 16 bits of the input's mantissa instead of 8.
+template <int FT, int PT, int U, int MAXT, bool IN32 = false>
 __global__ __launch_bounds__(MAXT) void conv_mfma_splitk_kernel(ConvArgs a) {
     extern __shared__ float red[];  // [WK][FT*PT][4][64]
     const int WK = blockDim.x >> 6;
@@ -318,6 +321,7 @@ __global__ __launch_bounds__(MAXT) void conv_mfma_splitk_kernel(ConvArgs a) {
     const int nsteps = a.R * a.R * csteps;
     for (int base = wk; base < nsteps; base += WK * U) {
         Frag fa[U][FT], fb[U][PT];
+        Frag fb2[IN32 ? U : 1][IN32 ? PT : 1];  // IN32: the second four floats of the lane's eight
         bool ok[U][PT];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -337,20 +341,43 @@ __global__ __launch_bounds__(MAXT) void conv_mfma_splitk_kernel(ConvArgs a) {
                 const int h = ph[pt] + dr, v = pw[pt] + ds;
                 ok[u][pt] = cv && pv[pt] && h >= 0 && h < a.H && v >= 0 && v < a.W;
                 const int hh = ok[u][pt] ? h : 0, vv = ok[u][pt] ? v : 0;
-                fb[u][pt].u = *reinterpret_cast<const uint4 *>(x + (((long)pn[pt] * a.H + hh) * a.W + vv) * a.C + cc);
+                const long e0 = (((long)pn[pt] * a.H + hh) * a.W + vv) * a.C + cc;
+                if (IN32) {
+                    const float *xf = static_cast<const float *>(a.x) + e0;
+                    fb[u][pt].u = *reinterpret_cast<const uint4 *>(xf);
+                    fb2[IN32 ? u : 0][IN32 ? pt : 0].u = *reinterpret_cast<const uint4 *>(xf + 4);
+                } else {
+                    fb[u][pt].u = *reinterpret_cast<const uint4 *>(x + e0);
+                }
             }
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
 #pragma unroll
             for (int pt = 0; pt < PT; ++pt)
-                if (!ok[u][pt]) fb[u][pt].u = make_uint4(0, 0, 0, 0);
+                if (!ok[u][pt]) {
+                    fb[u][pt].u = make_uint4(0, 0, 0, 0);
+                    if (IN32) fb2[IN32 ? u : 0][IN32 ? pt : 0].u = make_uint4(0, 0, 0, 0);
+                }
+            if (IN32) {
 #pragma unroll
-            for (int ft = 0; ft < FT; ++ft)
+                for (int pt = 0; pt < PT; ++pt) {
+                    Frag hi, lo;
+                    split_f32x8(fb[u][pt].u, fb2[IN32 ? u : 0][IN32 ? pt : 0].u, &hi.u, &lo.u);
 #pragma unroll
-                for (int pt = 0; pt < PT; ++pt)
-                    acc[ft][pt] =
-                        __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[u][ft].v, fb[u][pt].v, acc[ft][pt], 0, 0, 0);
+                    for (int ft = 0; ft < FT; ++ft) {
+                        acc[ft][pt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[u][ft].v, hi.v, acc[ft][pt], 0, 0, 0);
+                        acc[ft][pt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[u][ft].v, lo.v, acc[ft][pt], 0, 0, 0);
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int ft = 0; ft < FT; ++ft)
+#pragma unroll
+                    for (int pt = 0; pt < PT; ++pt)
+                        acc[ft][pt] =
+                            __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[u][ft].v, fb[u][pt].v, acc[ft][pt], 0, 0, 0);
+            }
         }
     }
 
@@ -488,7 +515,10 @@ __global__ __launch_bounds__(256) void gap_kernel(PoolArgs a) {
         const float inv = 1.0f / (float)hw;
 #pragma unroll
         for (int j = 0; j < 8; ++j) o[j] = part[0][cgi][j] * inv;
-        store8(static_cast<T *>(a.y) + (long)n * a.C + cg * 8, o);
+        if (a.out_f32)
+            store8(static_cast<float *>(a.y) + (long)n * a.C + cg * 8, o);
+        else
+            store8(static_cast<T *>(a.y) + (long)n * a.C + cg * 8, o);
     }
 }
 
@@ -559,14 +589,14 @@ static hipError_t launch_mfma(const ConvArgs &a, hipStream_t s) {
     return hipGetLastError();
 }
 
-template <int FT, int PT, int U, int MAXT>
+template <int FT, int PT, int U, int MAXT, bool IN32 = false>
 static hipError_t launch_splitk(const ConvArgs &a, int wk, hipStream_t s) {
     const int M = a.B * a.P * a.Q;
     const int n_pgroups = (M + 16 * PT - 1) / (16 * PT);
     const int n_ftiles = (a.K + 16 * FT - 1) / (16 * FT);
     wk = std::max(1, std::min(wk, MAXT / 64));
     const size_t lds = wk > 1 ? (size_t)wk * FT * PT * 256 * sizeof(float) : 0;
-    hipLaunchKernelGGL((conv_mfma_splitk_kernel<FT, PT, U, MAXT>), dim3(n_pgroups * n_ftiles), dim3(64 * wk), lds, s, a);
+    hipLaunchKernelGGL((conv_mfma_splitk_kernel<FT, PT, U, MAXT, IN32>), dim3(n_pgroups * n_ftiles), dim3(64 * wk), lds, s, a);
     return hipGetLastError();
 }
 
@@ -591,7 +621,11 @@ hipError_t launch_conv(const ConvArgs &a, bool bf16, hipStream_t s, int *kc) {
         return hipGetLastError();
     }
     const long ptiles = (M + 15) / 16, ftiles = (a.K + 15) / 16;
-    const long tiles16 = ptiles * ftiles;
+    if (a.in_f32) {  // a float32 vector per image (fully connected layers): always the latency-oriented kernel
+        if (a.H * a.W != 1) return hipErrorInvalidValue;
+        *kc = KC_CONV_SPLITK;
+        return launch_splitk<1, 1, 4, 1024, true>(a, (a.R * a.R * ((a.C + 31) / 32) + 3) / 4, s);
+    }
     // Many tiles: LDS-tiled workgroups; the largest tile that still yields two workgroups per compute unit.
     *kc = KC_CONV_MFMA;
     if (a.K > 64 && ((M + 127) / 128) * ((a.K + 127) / 128) >= 512) return launch_mfma<128, 128>(a, s);

@@ -278,7 +278,7 @@ struct Walker {
         Op op;
         op.kind = OP_GAP;
         op.B = B, op.H = H, op.W = W, op.C = C, op.K = C, op.P = op.Q = 1;
-        op.in_buf = in_buf, op.out_buf = out_small, op.out_small = true;
+        op.in_buf = in_buf, op.out_buf = out_small, op.out_small = true, op.out_f32 = true;
         plan.ops.push_back(op);
         note_small((size_t)B * C);
     }
@@ -290,7 +290,7 @@ struct Walker {
         op.B = B, op.H = op.W = op.P = op.Q = 1, op.C = C, op.K = K;
         op.act = act, op.hsigmoid = hsig;
         op.in_buf = in_small, op.in_small = true;
-        op.out_buf = out_buf, op.out_small = out_is_small, op.out_f32 = f32;
+        op.out_buf = out_buf, op.out_small = out_is_small, op.out_f32 = f32 || out_is_small;  // per-image vectors stay float32
         plan.ops.push_back(op);
         plan.dims[li++] = sushi_layer_dims{K, C, 1};
         if (out_is_small) note_small((size_t)B * K);

@@ -54,7 +54,8 @@ struct Op {
     int act = SUSHI_ACT_NONE;
     int in_buf = BUF_NONE, out_buf = BUF_NONE, res_buf = BUF_NONE, gate_buf = BUF_NONE;
     bool in_small = false, out_small = false;  // which buffer family the ids refer to
-    bool out_f32 = false;              // float32 output even in bf16 mode (gates, logits)
+    bool out_f32 = false;              // float32 output even in bf16 mode (per-image vectors: pooled features,
+                                       // squeeze-excite and head vectors, gates; logits)
     bool hsigmoid = false;             // FC epilogue: min(max(x+3,0),6)/6 instead of act
 };
 

@@ -354,10 +354,14 @@ __device__ __forceinline__ void pixel_cell(const ConvArgs &a, int m, bool valid,
 // The waves of a slot take the reduction steps ks, ks + wk, ...  Weight cells are requested DA steps
 // ahead (they come from memory and take longest), activation cells DB steps ahead, both into
 // register rings; the loop body is the same on every path, so the waits are exact.
-template <int FT, int PT, int LD, int ST, bool RES>
+// IN32: the input is a float32 vector per image (fully connected layers fed by pooled features, squeeze-excite
+// or head vectors): a lane's eight channels are two 16-byte words, split on the fly into two bf16 operands
+// (x = hi + lo) that are both multiplied with the step's weight fragment.
+template <int FT, int PT, int LD, int ST, bool RES, bool IN32 = false>
 __device__ __forceinline__ void conv_units(const DevOp &op, float *red, int rank, int nranks, const ResView rv,
                                            const StepTables tb) {
     constexpr int NT = FT * PT;   // 16 x 16 tiles of one unit (at most 4)
+    constexpr int BW = IN32 ? 2 : 1;  // 16-byte words of one activation cell
     constexpr int DA = 8 / FT;    // weight steps in flight per wave
     constexpr int DB = 2;         // activation steps in flight per wave
     const ConvArgs &a = op.conv;
@@ -368,7 +372,7 @@ __device__ __forceinline__ void conv_units(const DevOp &op, float *red, int rank
     const int l16 = lane & 15, kg = lane >> 4;
     const int M = a.B * a.P * a.Q;
     const int taps = a.R * a.R;
-    const __amdgpu_buffer_rsrc_t rx = make_rsrc(a.x, (long)a.B * a.H * a.W * a.C * 2);
+    const __amdgpu_buffer_rsrc_t rx = make_rsrc(a.x, (long)a.B * a.H * a.W * a.C * (IN32 ? 4 : 2));
     const __amdgpu_buffer_rsrc_t rw = make_rsrc(a.w, (long)taps * a.CG * a.Kpad * 16);
     const long out_bytes = (long)M * a.K * (a.out_f32 ? 4 : 2);
     const __amdgpu_buffer_rsrc_t ry = make_rsrc(a.y, out_bytes);
@@ -473,7 +477,7 @@ __device__ __forceinline__ void conv_units(const DevOp &op, float *red, int rank
 
         if (active) {
             const int per_wave = (nsteps - ks + wk - 1) / wk;  // steps ks, ks + wk, ... below nsteps
-            u32x4_t ra[DA][FT], rb[DB][PT];
+            u32x4_t ra[DA][FT], rb[DB][PT * BW];
             int ia = ks, ib = ks, ic = ks;  // step of the next weight request, activation request, product
             auto issue_a = [&](u32x4_t *q) {
                 const int idx = min(ia, nsteps);
@@ -496,7 +500,9 @@ __device__ __forceinline__ void conv_units(const DevOp &op, float *red, int rank
 #pragma unroll
                 for (int pt = 0; pt < PT; ++pt) {
                     const bool ok = ((mask_full[pt] & e.z) | (mask_tail[pt] & e.w)) != 0u;
-                    q[pt] = __builtin_amdgcn_raw_buffer_load_b128(rx, ok ? b_lane[pt] + (int)e.y : (int)OOB_OFFSET, 0, LD);
+                    const int off = ok ? (b_lane[pt] + (int)e.y) * BW : (int)OOB_OFFSET;
+                    q[pt * BW] = __builtin_amdgcn_raw_buffer_load_b128(rx, off, 0, LD);
+                    if (IN32) q[pt * BW + BW - 1] = __builtin_amdgcn_raw_buffer_load_b128(rx, ok ? off + 16 : (int)OOB_OFFSET, 0, LD);
                 }
             };
 #pragma unroll
@@ -532,8 +538,16 @@ __device__ __forceinline__ void conv_units(const DevOp &op, float *red, int rank
 #pragma unroll
                     for (int pt = 0; pt < PT; ++pt) {
                         Frag fb;
-                        const u32x4_t b = rb[u % DB][pt];
+                        const u32x4_t b = rb[u % DB][pt * BW];
                         fb.u = make_uint4(b.x, b.y, b.z, b.w);
+                        if (IN32) {
+                            const u32x4_t b2 = rb[u % DB][pt * BW + BW - 1];
+                            Frag lo;
+                            split_f32x8(fb.u, make_uint4(b2.x, b2.y, b2.z, b2.w), &fb.u, &lo.u);
+#pragma unroll
+                            for (int ft = 0; ft < FT; ++ft)
+                                acc[ft][pt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[ft].v, lo.v, acc[ft][pt], 0, 0, 0);
+                        }
 #pragma unroll
                         for (int ft = 0; ft < FT; ++ft)
                             acc[ft][pt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[ft].v, fb.v, acc[ft][pt], 0, 0, 0);
@@ -1510,7 +1524,7 @@ __device__ __forceinline__ void gap_units(const PoolArgs &a, float *lds, int ran
     const int cgi = threadIdx.x & 7, pl = threadIdx.x >> 3;
     const int hw = a.H * a.W;
     const __amdgpu_buffer_rsrc_t rx = make_rsrc(a.x, (long)a.B * hw * a.C * 2);
-    const __amdgpu_buffer_rsrc_t ry = make_rsrc(a.y, (long)a.B * a.C * 2);
+    const __amdgpu_buffer_rsrc_t ry = make_rsrc(a.y, (long)a.B * a.C * (a.out_f32 ? 4 : 2));
     for (int b = rank; b < n_blocks; b += nranks) {
         const int n = b / blocks_per_image;
         const int cg = (b - n * blocks_per_image) * 8 + cgi;
@@ -1538,7 +1552,12 @@ __device__ __forceinline__ void gap_units(const PoolArgs &a, float *lds, int ran
             const float inv = 1.0f / (float)hw;
 #pragma unroll
             for (int j = 0; j < 8; ++j) o[j] = part[0][cgi][j] * inv;
-            act_st16<ST>(ry, (n * a.C + cg * 8) * 2, pack8(o));
+            if (a.out_f32) {  // (per-image vectors stay float32: the layers they feed split them into two bf16 terms)
+                act_st16<ST>(ry, (n * a.C + cg * 8) * 4, make_uint4(__float_as_uint(o[0]), __float_as_uint(o[1]), __float_as_uint(o[2]), __float_as_uint(o[3])));
+                act_st16<ST>(ry, (n * a.C + cg * 8) * 4 + 16, make_uint4(__float_as_uint(o[4]), __float_as_uint(o[5]), __float_as_uint(o[6]), __float_as_uint(o[7])));
+            } else {
+                act_st16<ST>(ry, (n * a.C + cg * 8) * 2, pack8(o));
+            }
         }
         __syncthreads();
     }
@@ -1630,6 +1649,12 @@ __device__ __forceinline__ void run_op(const DevOp &op, float *lds, int rank, in
                 run_tiled<LD, ST>(op, reinterpret_cast<u32x4_t *>(lds), rank, nranks);
             else if (op.wk == -3)
                 run_ares<LD, ST>(op, reinterpret_cast<u32x4_t *>(lds), rank, nranks);
+            else if (op.conv.in_f32 && op.ft == 4)
+                conv_units<4, 1, LD, ST, RES, true>(op, lds, rank, nranks, rv, tb);
+            else if (op.conv.in_f32 && op.ft == 2)
+                conv_units<2, 1, LD, ST, RES, true>(op, lds, rank, nranks, rv, tb);
+            else if (op.conv.in_f32)
+                conv_units<1, 1, LD, ST, RES, true>(op, lds, rank, nranks, rv, tb);
             else if (op.ft == 2 && op.pt == 4)
                 conv_units<2, 4, LD, ST, RES>(op, lds, rank, nranks, rv, tb);
             else if (op.ft == 1 && op.pt == 4)
@@ -2194,13 +2219,14 @@ void tile_dev_op(DevOp &op, int nwg, bool team) {
             // one filter tile at a time fit the scratch)
             if (sh[0] * sh[1] > 4 && wk != STREAM_WAVES && wk != 1) continue;
             if (slab_shapes_only && sh[0] > 2) continue;
+            if (a.in_f32 && sh[1] != 1) continue;  // float32 vector input: units of one pixel tile
             if (sh[1] > ptiles && !(sh[1] == 4 && ptiles == 3)) continue;
             const double cost = shape_cost(sh[0], sh[1], wk);
             if (cost < best - 1e-9) best = cost, bft = sh[0], bpt = sh[1], bwk = wk;
         }
     // tiled units (wk = 0): at filter tiles x 8 waves x bt pixel tiles, the weight tile shared in LDS
     bool tiled = false;
-    if ((a.C & 7) == 0 && ptiles >= STREAM_WAVES) {
+    if ((a.C & 7) == 0 && ptiles >= STREAM_WAVES && !a.in_f32) {
         static const int tile_shapes[10][2] = {{2, 1}, {2, 2}, {3, 1}, {3, 2}, {3, 4}, {4, 1}, {4, 2}, {4, 4}, {6, 1}, {6, 2}};
         for (const auto &tsh : tile_shapes) {
             const int at = tsh[0], bt = tsh[1];
@@ -2225,7 +2251,7 @@ void tile_dev_op(DevOp &op, int nwg, bool team) {
     }
     // the same units with the filter group's weights held in LDS (wk = -3): short reductions only
     bool ares = false;
-    if ((a.C & 7) == 0 && ptiles >= STREAM_WAVES) {
+    if ((a.C & 7) == 0 && ptiles >= STREAM_WAVES && !a.in_f32) {
         static const int shapes_r[5][2] = {{2, 1}, {2, 2}, {4, 1}, {4, 2}, {6, 1}};
         const int steps_pad = (nsteps + ARES_D - 1) / ARES_D * ARES_D;
         for (const auto &sh : shapes_r) {

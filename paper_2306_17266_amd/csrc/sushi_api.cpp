@@ -313,6 +313,7 @@ void bind_plan(sushi_ctx *c, CachedPlan &cp, const BufBase &bb = BufBase()) {
             a.R = op.r, a.stride = op.stride, a.pad = op.pad, a.Rmax = S.Rmax;
             a.Kpad = S.Kpad, a.CG = S.CG;
             a.act = op.act, a.hsigmoid = op.hsigmoid ? 1 : 0, a.out_f32 = op.out_f32 ? 1 : 0;
+            a.in_f32 = (op.in_small && c->bf16) ? 1 : 0;
             L.in_patch = op.in_buf == BUF_INPUT;
             L.out_patch = op.out_buf == BUF_LOGITS;
         } else {
@@ -321,6 +322,7 @@ void bind_plan(sushi_ctx *c, CachedPlan &cp, const BufBase &bb = BufBase()) {
             a.y = buf_ptr(c, bb, op.out_buf, op.out_small);
             a.gate = static_cast<const float *>(buf_ptr(c, bb, op.gate_buf, true));
             a.B = op.B, a.H = op.H, a.W = op.W, a.C = op.C, a.P = op.P, a.Q = op.Q;
+            a.out_f32 = (op.out_f32 && c->bf16) ? 1 : 0;
         }
         cp.launches.push_back(L);
     }
@@ -360,13 +362,13 @@ void launch_cost(const sushi_ctx *c, const Launch &L, double *bytes, double *flo
         const double in = (double)a.B * a.H * a.W * a.C, out = (double)a.B * a.P * a.Q * a.K;
         const double taps = (double)a.R * a.R;
         const double wts = L.kind == OP_DW ? a.K * taps : (double)a.K * a.C * taps;
-        *bytes = (in + wts + (a.res ? out : 0.0)) * es + out * (a.out_f32 ? 4.0 : es) + 8.0 * a.K;
+        *bytes = in * (a.in_f32 ? 4.0 : es) + (wts + (a.res ? out : 0.0)) * es + out * (a.out_f32 ? 4.0 : es) + 8.0 * a.K;
         *flops = 2.0 * out * (L.kind == OP_DW ? taps : a.C * taps);
     } else {
         const PoolArgs &a = L.pool;
         const double in = (double)a.B * a.H * a.W * a.C;
         const double out = L.kind == OP_GATE ? in : (double)a.B * a.P * a.Q * a.C;
-        *bytes = (in + out) * es + (L.kind == OP_GATE ? 4.0 * a.B * a.C : 0.0);
+        *bytes = in * es + out * (a.out_f32 ? 4.0 : es) + (L.kind == OP_GATE ? 4.0 * a.B * a.C : 0.0);
         *flops = L.kind == OP_MAXPOOL ? 9.0 * out : in;
     }
 }
@@ -984,7 +986,7 @@ int post_team_query(sushi_ctx *c, CachedPlan &cp, const void *input_dev, void *l
             // every activation tensor of the op must lie inside the buffer of the team arena it names
             {
                 const bool conv = L.kind == OP_CONV || L.kind == OP_DW || L.kind == OP_FC;
-                const long in_bytes = (long)o.B * o.H * o.W * o.C * 2;
+                const long in_bytes = (long)o.B * o.H * o.W * o.C * (o.in_small ? 4 : 2);
                 const long out_elems = (long)o.B * o.P * o.Q * (conv ? o.K : o.C);
                 const long out_bytes = out_elems * (o.out_f32 ? 4 : 2);
                 auto fits = [&](int id, bool small, long bytes) { return id < 0 || bytes <= (small ? c->tsmall_bytes : c->tbig_bytes); };
@@ -1151,6 +1153,7 @@ int sushi_team_plan(const sushi_arch *arch, const sushi_subnet_cfg *cfg, int bat
             a.R = o.r, a.stride = o.stride, a.pad = o.pad, a.Rmax = S.Rmax;
             a.Kpad = S.Kpad, a.CG = S.CG;
             a.act = o.act, a.hsigmoid = o.hsigmoid ? 1 : 0, a.out_f32 = o.out_f32 ? 1 : 0;
+            a.in_f32 = o.in_small ? 1 : 0;
             a.res = o.res_buf >= 0 ? &op : nullptr;  // (only whether there is one matters to the tiling)
         }
         if (!tile_team_op(op, team_wgs)) return SUSHI_ESTATE;

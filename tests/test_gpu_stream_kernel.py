@@ -234,7 +234,7 @@ def test_team_kernel_logits_do_not_depend_on_resident_slabs(fam, teams):
             emu = oracle_logits_bf16_stores(arch, wts, cfg, xs_np[t])
             floor, to_emu = rel_l2(emu, want), rel_l2(base[t], emu)
             print("query", t, "err", err, "bf16-store floor", floor, "vs emulation", to_emu, flush=True)
-            assert floor > 0.9e-2 and err <= 1.5e-2, (t, err, floor, to_emu)
+            assert floor > 0.9e-2 and to_emu <= 6e-3 and err <= 1.25e-2, (t, err, floor, to_emu)
     ctx.sushi_set_subgraph_cache(E.subnet_box(arch, A.max_cfg(arch, res)), 1 << 30)    # the whole SuperNet
     got, lds1 = run_all()
     for t in range(len(cfgs)):
