@@ -35,6 +35,8 @@ def kernel_sources_digest():
     import hashlib
     h = hashlib.sha256()
     for path in sorted(glob.glob(os.path.join(ROOT, "paper_2306_17266_amd", "csrc", "*"))):
+        if not os.path.isfile(path):
+            continue
         h.update(os.path.basename(path).encode())
         h.update(open(path, "rb").read())
     return h.hexdigest()
