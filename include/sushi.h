@@ -327,10 +327,15 @@ typedef enum {
                                    Only before the first query in mode 3 */
     SUSHI_OPT_IDLE_US = 3,      /* microseconds without a query after which the team kernel leaves
                                    (default 2000); the next query starts it again */
-    SUSHI_OPT_COLD_SWEEP_MIB = 7 /* modes 0 - 2, measurement aid: before every query a kernel streams a scratch
+    SUSHI_OPT_COLD_SWEEP_MIB = 7, /* modes 0 - 2, measurement aid: before every query a kernel streams a scratch
                                    buffer of this many MiB (0 = off, at most 4096) through the caches, so the
                                    query finds none of its weights on chip: a device that loses its caches
                                    between queries, the premise the paper's SGS starts from (Section 4.3) */
+    SUSHI_OPT_PATCH_CONV_MIN_PIXELS = 8 /* modes 0 - 1, bf16: dense 1x1 / 3x3 layers with at least this many output
+                                   pixels (batch x rows x columns) run in the kernel that stages a tile's input
+                                   patch in LDS (large batches); below four times this many only if the layer's
+                                   reduction (input channels x taps) is at least 1024 long.  0 = never.
+                                   Default 3136.  In mode 1 it applies to SubNets recorded afterwards */
 } sushi_option;
 int sushi_set_option(sushi_ctx *ctx, int option, int64_t value);
 

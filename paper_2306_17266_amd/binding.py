@@ -19,6 +19,7 @@ OPT_STREAM_WGS = 4
 OPT_TEAM_WGS_PER_CU = 5
 OPT_TEAMS_PER_XCD = 6
 OPT_COLD_SWEEP_MIB = 7
+OPT_PATCH_CONV_MIN_PIXELS = 8
 
 
 class SushiError(RuntimeError):

@@ -56,13 +56,20 @@ enum KernelClass {
     KC_GATE = 6,
     KC_STREAM = 7,  // sushi_stream_kernel (one launch per query)
     KC_TEAM = 8,    // sushi_team_kernel (persistent; one launch serves many queries)
-    KC_COUNT = 9
+    KC_CONV_PATCH = 9,  // conv_patch_kernel (large pixel counts; the input patch of a tile staged in LDS)
+    KC_COUNT = 10
 };
 const char *kernel_class_name(int kc);
 
 // Every launcher returns hipSuccess or the launch error.  bf16 = activations and weights are bf16.
 // launch_conv reports the kernel family it picked in *kc (may be null).
-hipError_t launch_conv(const ConvArgs &a, bool bf16, hipStream_t s, int *kc);  // dense conv and FC
+// patch_min_pixels: dense 1x1 / 3x3 layers with at least that many output pixels (B * P * Q) go to the patch
+// kernel (conv_patch.hip) where it covers the shape; 0 = never.
+hipError_t launch_conv(const ConvArgs &a, bool bf16, hipStream_t s, int *kc, long patch_min_pixels);  // dense conv and FC
+
+// Dense 1x1 (stride 1) and 3x3 (stride 1 or 2) convolution, bf16, C and K multiples of 8, tensors below 2 GiB: the
+// patch kernel (conv_patch.hip).  Returns hipErrorNotSupported (nothing launched) for any other case.
+hipError_t launch_conv_patch(const ConvArgs &a, hipStream_t s);
 hipError_t launch_dwconv(const ConvArgs &a, bool bf16, hipStream_t s);
 hipError_t launch_maxpool(const PoolArgs &a, bool bf16, hipStream_t s);   // 3x3 stride 2 pad 1
 hipError_t launch_gap(const PoolArgs &a, bool bf16, hipStream_t s);       // [B][H][W][C] -> [B][C]

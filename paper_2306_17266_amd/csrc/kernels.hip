@@ -603,11 +603,12 @@ static hipError_t launch_splitk(const ConvArgs &a, int wk, hipStream_t s) {
 const char *kernel_class_name(int kc) {
     static const char *names[KC_COUNT] = {"conv_direct_kernel", "conv_mfma_kernel", "conv_mfma_splitk_kernel",
                                           "dwconv_rows_kernel", "maxpool_kernel",   "gap_kernel",
-                                          "gate_kernel",        "sushi_stream_kernel", "sushi_team_kernel"};
+                                          "gate_kernel",        "sushi_stream_kernel", "sushi_team_kernel",
+                                          "conv_patch_kernel"};
     return kc >= 0 && kc < KC_COUNT ? names[kc] : "?";
 }
 
-hipError_t launch_conv(const ConvArgs &a, bool bf16, hipStream_t s, int *kc) {
+hipError_t launch_conv(const ConvArgs &a, bool bf16, hipStream_t s, int *kc, long patch_min_pixels) {
     const long M = (long)a.B * a.P * a.Q;
     int dummy;
     if (!kc) kc = &dummy;
@@ -625,6 +626,14 @@ hipError_t launch_conv(const ConvArgs &a, bool bf16, hipStream_t s, int *kc) {
         if (a.H * a.W != 1) return hipErrorInvalidValue;
         *kc = KC_CONV_SPLITK;
         return launch_splitk<1, 1, 4, 1024, true>(a, (a.R * a.R * ((a.C + 31) / 32) + 3) / 4, s);
+    }
+    // (at the threshold itself only long reductions: short ones are quicker in the kernels below)
+    if (patch_min_pixels > 0 && M >= patch_min_pixels && (M >= 4 * patch_min_pixels || (long)a.C * a.R * a.R >= 1024)) {
+        const hipError_t e = launch_conv_patch(a, s);
+        if (e != hipErrorNotSupported) {
+            *kc = KC_CONV_PATCH;
+            return e;
+        }
     }
     // Many tiles: LDS-tiled workgroups; the largest tile that still yields two workgroups per compute unit.
     *kc = KC_CONV_MFMA;

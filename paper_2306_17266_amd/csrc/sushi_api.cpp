@@ -91,6 +91,7 @@ struct sushi_ctx {
     int team_size() const { return team_wgs / (MAX_XCDS * teams_per_xcd); }  // workgroups of a team, if they spread evenly
     int spin_limit = 400000;
     void *static_buf = nullptr;  // this device's copy of the library's static scratch array (sushi_infer_static)
+    long patch_min_pixels = 3136;  // SUSHI_OPT_PATCH_CONV_MIN_PIXELS
     void *d_sweep = nullptr;  // SUSHI_OPT_COLD_SWEEP_MIB: scratch streamed through the caches before every query
     size_t sweep_bytes = 0;
     // exec mode 3 (team kernel): mailboxes in pinned host memory, per-team arenas, private stream
@@ -420,7 +421,7 @@ hipError_t issue_launches(sushi_ctx *c, CachedPlan &cp, const void *input_dev, v
                 ConvArgs a = L.conv;
                 if (L.in_patch) a.x = input_dev;
                 if (L.out_patch) a.y = logits_dev;
-                e = launch_conv(a, c->bf16, st, &kc);
+                e = launch_conv(a, c->bf16, st, &kc, c->patch_min_pixels);
                 break;
             }
             case OP_DW:
@@ -1623,6 +1624,10 @@ int sushi_set_option(sushi_ctx *c, int option, int64_t value) {
         if (hipMalloc(&c->d_sweep, bytes) != hipSuccess) return fail(c, SUSHI_ENOMEM, "hipMalloc(cache sweep buffer)");
         if ((e = hipMemset(c->d_sweep, 0, bytes)) != hipSuccess) return hip_fail(c, e, "hipMemset");
         c->sweep_bytes = bytes;
+        return SUSHI_OK;
+    }
+    if (option == SUSHI_OPT_PATCH_CONV_MIN_PIXELS && value >= 0 && value <= (1l << 40)) {
+        c->patch_min_pixels = (long)value;
         return SUSHI_OK;
     }
     if (option == SUSHI_OPT_IDLE_US && value >= 10 && value <= 10000000) {

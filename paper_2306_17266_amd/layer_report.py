@@ -42,6 +42,8 @@ def main():
     ap.add_argument("--batch", type=int, default=0)
     ap.add_argument("--resolution", type=int, default=224)
     ap.add_argument("--reps", type=int, default=20)
+    ap.add_argument("--patch-min-pixels", type=int, default=-1,
+                    help="SUSHI_OPT_PATCH_CONV_MIN_PIXELS (0 = never use the patch conv kernel; default: the library's)")
     ap.add_argument("--plain", action="store_true", help="run the queries without events and print nothing (profiler run)")
     ap.add_argument("--from-trace", default="", help="kernel-trace CSV of a --plain run under rocprofv3")
     args = ap.parse_args()
@@ -58,6 +60,8 @@ def main():
     table = S.sushi_describe_supernet(arch)
     ctx = S.Sushi(0)
     ctx.sushi_load_supernet(arch, T.flatten(T.make_weights([(s, k) for _, s, k in table], 1, True)), S.BF16)
+    if args.patch_min_pixels >= 0:
+        ctx.sushi_set_option(S.OPT_PATCH_CONV_MIN_PIXELS, args.patch_min_pixels)
     x = torch.from_numpy(T.make_input(11, 0, batch, cfg.resolution, arch.in_channels, True)).cuda().to(torch.bfloat16)
     y = torch.empty(batch, arch.n_classes, device="cuda", dtype=torch.float32)
     for _ in range(5):
@@ -105,7 +109,7 @@ def report_from_trace(args, arch, cfg, batch):
 
     import paper_2306_17266_amd as S
     ops = S.sushi_team_plan(arch, cfg, batch, 32)
-    mine = ("conv_direct_kernel", "conv_mfma_kernel", "conv_mfma_splitk_kernel", "conv_gemm_kernel", "dwconv_kernel",
+    mine = ("conv_direct_kernel", "conv_mfma_kernel", "conv_mfma_splitk_kernel", "conv_patch_kernel", "dwconv_kernel",
             "dwconv_rows_kernel", "maxpool_kernel", "gap_kernel", "gate_kernel")
     rows = []
     for r in csv.DictReader(open(args.from_trace)):

@@ -125,6 +125,36 @@ def test_resnet_full_size_batch16_sampled():
     _check_stream(arch, cfgs, True, 47, 16)
 
 
+@pytest.mark.parametrize("fam", ["tiny", "resnet", "mbv3"])
+def test_patch_conv_kernel_on_every_layer_it_covers(fam):
+    """The large-batch dense conv kernel (input patch in LDS) forced onto every 1x1 / 3x3 layer it supports,
+    whatever the pixel count: ragged tiles (pixel counts that are no multiple of 128, tiles that cross rows and
+    images), filter counts that are no multiple of 32, both strides, residuals, with and without activation.
+    Checked against the oracle, and the same queries with the kernel switched off stay within tolerance too."""
+    import paper_2306_17266_amd as S
+    arch = {"tiny": A.tiny_arch, "resnet": A.small_resnet_arch, "mbv3": A.small_mbv3_arch}[fam]()
+    ctx, wts = _ctx(arch, 67, True)
+    st = Stream(71)
+    for res, batch in ((64, 1), (64, 5), (96, 3)) if fam != "tiny" else ((32, 1), (32, 7)):
+        cfgs = [A.min_cfg(arch, res), A.max_cfg(arch, res)] + [streams.uniform_cfg(arch, st, res) for _ in range(3)]
+        for t, cfg in enumerate(cfgs):
+            x = T.make_input(67, t, batch, cfg.resolution, arch.in_channels, True)
+            want = oracle_logits(arch, wts, cfg, x)
+            for min_pixels in (1, 0):
+                ctx.sushi_set_option(S.OPT_PATCH_CONV_MIN_PIXELS, min_pixels)
+                print(fam, "res", res, "batch", batch, "query", t, "patch kernel from", min_pixels, "pixels", flush=True)
+                got = _run(ctx, cfg, x, True, arch.n_classes)
+                assert np.isfinite(got).all()
+                assert rel_l2(got, want) <= 1e-2, (fam, res, batch, t, min_pixels, rel_l2(got, want))
+    ctx.sushi_set_option(S.OPT_KERNEL_TIMING, 1)
+    ctx.sushi_set_option(S.OPT_PATCH_CONV_MIN_PIXELS, 1)
+    r0 = arch.res_choices[0]
+    _run(ctx, A.max_cfg(arch, r0), T.make_input(67, 0, 2, r0, arch.in_channels, True), True, arch.n_classes)
+    used = {k["name"]: k["launches"] for k in ctx.sushi_get_kernel_stats()}
+    assert used["conv_patch_kernel"] > 0, used
+    ctx.close()
+
+
 def test_logits_do_not_depend_on_the_cache_state():
     """SGS is exact: identical logits with nothing cached, with a SubGraph cached, and across a
     cache change in mid-stream."""
