@@ -73,11 +73,12 @@ __device__ __forceinline__ int cp_base(const ConvArgs &a, const PatchGeom &g, in
     return (n * g.hp + p * a.stride) * g.wp + q * a.stride;
 }
 
-template <int TF, int TM, int CK, int R, int MAXP, int MINB>
-__global__ __launch_bounds__(256, MINB) void conv_patch_kernel(ConvArgs a, PatchGeom g) {
-    constexpr int BN = 32 * TF, BM = 128 * TM, NKG = CK / 8, WPS = BN + 4;
-    constexpr int PPW = 256 / NKG;  // positions one pass of the workgroup's threads covers
-    constexpr int WCELLS = R * NKG * BN, WPT = (WCELLS + 255) / 256;
+template <int TF, int TM, int CK, int R, int MAXP, int MINB, int NW>
+__global__ __launch_bounds__(64 * NW, MINB) void conv_patch_kernel(ConvArgs a, PatchGeom g) {
+    constexpr int NT = 64 * NW;  // threads
+    constexpr int BN = 32 * TF, BM = 32 * NW * TM, NKG = CK / 8, WPS = BN + 4;
+    constexpr int PPW = NT / NKG;  // positions one pass of the workgroup's threads covers
+    constexpr int WCELLS = R * NKG * BN, WPT = (WCELLS + NT - 1) / NT;
     constexpr int KSUB = CK / 16;
     constexpr int ROWC = BN / 8 + 1;  // epilogue: cells per pixel row (one spare)
     extern __shared__ uint4 cp_lds[];
@@ -117,7 +118,7 @@ __global__ __launch_bounds__(256, MINB) void conv_patch_kernel(ConvArgs a, Patch
     int woff[WPT], wkg[WPT], wlds[WPT];
 #pragma unroll
     for (int j = 0; j < WPT; ++j) {
-        const int i = tid + 256 * j;
+        const int i = tid + NT * j;
         const int t = i / (NKG * BN), r = i - t * (NKG * BN);
         const int kg = r / BN, f = r - kg * BN;
         const bool ok = i < WCELLS && f0 + f < a.Kpad;
@@ -160,7 +161,7 @@ __global__ __launch_bounds__(256, MINB) void conv_patch_kernel(ConvArgs a, Patch
         uint4 *dst = wts + buf * R * NKG * WPS;
 #pragma unroll
         for (int j = 0; j < WPT; ++j)
-            if (tid + 256 * j < WCELLS) dst[wlds[j]] = __builtin_bit_cast(uint4, q[j]);
+            if (tid + NT * j < WCELLS) dst[wlds[j]] = __builtin_bit_cast(uint4, q[j]);
     };
 
     // prologue: the loads of the first D stages; stage 0 into LDS.  The tile's scale and shift values go to LDS
@@ -375,11 +376,11 @@ int patch_positions(const ConvArgs &a, int BM) {
     return (int)best;
 }
 
-template <int TF, int TM, int CK, int R, int MAXP, int MINB>
+template <int TF, int TM, int CK, int R, int MAXP, int MINB, int NW>
 hipError_t launch_patch(const ConvArgs &a, hipStream_t s) {
-    constexpr int BN = 32 * TF, BM = 128 * TM, NKG = CK / 8, WPS = BN + 4, ROWC = BN / 8 + 1;
+    constexpr int NT = 64 * NW, BN = 32 * TF, BM = 32 * NW * TM, NKG = CK / 8, WPS = BN + 4, ROWC = BN / 8 + 1;
     const int npos = patch_positions(a, BM);
-    if ((long)npos * NKG > (long)MAXP * 256) return hipErrorNotSupported;
+    if ((long)npos * NKG > (long)MAXP * NT) return hipErrorNotSupported;
     // plane stride: congruent to 16 / NKG modulo 16 cells, so the NKG cells of a position fall into different banks
     int ps = npos;
     while (ps % 16 != 16 / NKG) ++ps;
@@ -395,23 +396,23 @@ hipError_t launch_patch(const ConvArgs &a, hipStream_t s) {
     const size_t lds = (cells + BN / 2) * 16;
     if (lds > 160 * 1024) return hipErrorNotSupported;
     static bool attr_set = false;
-    auto kern = conv_patch_kernel<TF, TM, CK, R, MAXP, MINB>;
+    auto kern = conv_patch_kernel<TF, TM, CK, R, MAXP, MINB, NW>;
     if (!attr_set) {
         const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     const int per_xcd = (g.tiles_m * g.tiles_f + 7) / 8;
-    hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(256), lds, s, a, g);
+    hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(NT), lds, s, a, g);
     return hipGetLastError();
 }
 
-template <int TM, int CK, int R, int MAXP, int MINB>
+template <int TM, int CK, int R, int MAXP, int MINB, int NW>
 hipError_t launch_patch_tf(const ConvArgs &a, int tf, hipStream_t s) {
     switch (tf) {
-        case 2: return launch_patch<2, TM, CK, R, MAXP, MINB>(a, s);
-        case 3: return launch_patch<3, TM, CK, R, MAXP, MINB>(a, s);
-        default: return launch_patch<4, TM, CK, R, MAXP, MINB>(a, s);
+        case 2: return launch_patch<2, TM, CK, R, MAXP, MINB, NW>(a, s);
+        case 3: return launch_patch<3, TM, CK, R, MAXP, MINB, NW>(a, s);
+        default: return launch_patch<4, TM, CK, R, MAXP, MINB, NW>(a, s);
     }
 }
 
@@ -435,13 +436,14 @@ hipError_t launch_conv_patch(const ConvArgs &a, hipStream_t s) {
         if (waste < 0 || w < waste) tf = t, waste = w;
     }
     if (a.R == 3) {
-        if (a.stride == 2) return launch_patch_tf<1, 32, 3, 16, 1>(a, tf, s);
-        // 256-pixel tiles while they still give every compute unit a workgroup, else 128-pixel tiles
+        if (a.stride == 2) return launch_patch_tf<1, 32, 3, 16, 1, 4>(a, tf, s);
+        // 256-pixel tiles (eight waves of 32 pixels: two waves per SIMD get their LDS reads served at twice the
+        // rate of one) while they still give most compute units a workgroup, else 128-pixel tiles of four waves
         const long tiles256 = ((M + 255) / 256) * ((a.K + 32 * tf - 1) / (32 * tf));
-        if (tiles256 >= 160) return launch_patch_tf<2, 32, 3, 12, 1>(a, tf, s);
-        return launch_patch_tf<1, 32, 3, 12, 1>(a, tf, s);
+        if (tiles256 >= 160) return launch_patch_tf<1, 32, 3, 6, 1, 8>(a, tf, s);
+        return launch_patch_tf<1, 32, 3, 12, 1, 4>(a, tf, s);
     }
-    return launch_patch_tf<1, 64, 1, 4, 2>(a, tf, s);
+    return launch_patch_tf<1, 64, 1, 4, 2, 4>(a, tf, s);
 }
 
 }  // namespace sushi
