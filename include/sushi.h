@@ -243,6 +243,29 @@ const char *sushi_last_error(const sushi_ctx *ctx);
 int sushi_load_supernet(sushi_ctx *ctx, const sushi_arch *arch, const void *weights, size_t nbytes,
                         int compute_dtype);
 
+/* The paper's own precision (Section 5.1, footnote on number formats: int8 weights, input activations and zero
+ * points, int32 scale; Section 4.2.2, the zero-point / scale buffer).  Families SUSHI_FAMILY_TINY and
+ * SUSHI_FAMILY_RESNET; exec mode 0 (sushi_infer with another mode set returns SUSHI_ESTATE); SubGraph caching is
+ * accounted at one byte per weight.
+ *   weights  HOST int8: the weight tensors of sushi_describe_supernet (conv [K][C][R][R], fc [K][C]) in that
+ *            order, nothing else; n_weights = their exact total element count
+ *   qparams  HOST int32: for every weight tensor, in the same order: mult[K], rshift[K], bias[K], then eight
+ *            scalars [z_x, z_y, m_res, sh_res, z_res, 0, 0, 0]; n_qparams = sum of 3 K + 8
+ * Arithmetic of a conv layer, all integers (x_q, w_q int8; acc int32; products int64):
+ *   acc[k]   = sum over taps inside the image and active channels of w_q * (x_q - z_x)
+ *   t        = rr((acc[k] + bias[k]) * mult[k], rshift[k]),  rr(v, s) = (v + 2^(s-1)) >> s (arithmetic shift)
+ *   t       += rr((res_q - z_res) * m_res, sh_res)           where the layer adds a residual
+ *   y_q      = clamp(z_y + t, lo, 127),  lo = z_y after a ReLU, else -128
+ * 3x3/2 max-pool: maximum of the codes.  Global pooling: exact int32 sums of (x_q - z_x), z_x = first scalar of the
+ * classifier.  Classifier: acc64[k] = sum_c w_q[k][c] * sum[c] + HW * bias[k];
+ * logit[k] = (float)((double)acc64[k] * ((double)base[k] / (double)HW)), base[k] = the float32 whose bit pattern
+ * is mult[k], HW = pixels pooled over.  rshift must lie in 1 .. 62 for conv layers.
+ * sushi_infer then takes int8 input [batch][resolution][resolution][in_channels] (zero point z_x of the first
+ * layer) and returns float32 logits.  Synchronous.  SUSHI_EINVAL for a family without an int8 path, wrong sizes
+ * or a shift out of range. */
+int sushi_load_supernet_int8(sushi_ctx *ctx, const sushi_arch *arch, const int8_t *weights, size_t n_weights,
+                             const int32_t *qparams, size_t n_qparams);
+
 /* Makes SubGraph g the cached one ("enacts the caching decision", Section 3.1).  g = NULL or
  * g->n_layers = 0 empties the cache (SGS off).  g->n_layers must equal the SuperNet's layer
  * count, every box must lie inside its layer, and the SubGraph's bytes must not exceed
@@ -250,8 +273,8 @@ int sushi_load_supernet(sushi_ctx *ctx, const sushi_arch *arch, const void *weig
 int sushi_set_subgraph_cache(sushi_ctx *ctx, const sushi_subgraph_cfg *g, size_t budget_bytes);
 
 /* Runs SubNet cfg on one batch.
- *   input_dev   DEVICE, [batch][resolution][resolution][in_channels], float32 (SUSHI_FP32) or
- *               bf16 (SUSHI_BF16)
+ *   input_dev   DEVICE, [batch][resolution][resolution][in_channels], float32 (SUSHI_FP32),
+ *               bf16 (SUSHI_BF16) or int8 (after sushi_load_supernet_int8)
  *   logits_dev  DEVICE, float32 [batch][n_classes]
  * Enqueues on the context's stream and returns; results are bit-identical whatever SubGraph is
  * cached.  SUSHI_EINVAL (nothing enqueued) if cfg is not a SubNet of the loaded SuperNet. */

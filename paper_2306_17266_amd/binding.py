@@ -117,6 +117,7 @@ def lib():
     L.sushi_last_error.argtypes = [vp]
     L.sushi_last_error.restype = C.c_char_p
     L.sushi_load_supernet.argtypes = [vp, C.POINTER(CArch), vp, C.c_size_t, C.c_int]
+    L.sushi_load_supernet_int8.argtypes = [vp, C.POINTER(CArch), vp, C.c_size_t, vp, C.c_size_t]
     L.sushi_set_subgraph_cache.argtypes = [vp, C.POINTER(CSubgraphCfg), C.c_size_t]
     L.sushi_infer.argtypes = [vp, C.POINTER(CSubnetCfg), vp, C.c_int, vp]
     L.sushi_infer_static.argtypes = [vp, C.POINTER(CSubnetCfg), vp, C.c_int, vp]
@@ -255,6 +256,18 @@ class Sushi:
         _check(lib().sushi_load_supernet(self._h, C.byref(a), blob.ctypes.data_as(C.c_void_p), blob.nbytes, dtype),
                self._h)
         self.arch, self.dtype = arch, dtype
+        self._cfg_cache = {}
+        self._box_cache = {}
+
+    def sushi_load_supernet_int8(self, arch, weights, qparams):
+        """weights: int8 array (all weight tensors in blob order); qparams: int32 array (per weight tensor
+        mult[K], rshift[K], bias[K] and eight scalars)."""
+        w = np.ascontiguousarray(weights, dtype=np.int8)
+        q = np.ascontiguousarray(qparams, dtype=np.int32)
+        a = c_arch(arch)
+        _check(lib().sushi_load_supernet_int8(self._h, C.byref(a), w.ctypes.data_as(C.c_void_p), w.size,
+                                              q.ctypes.data_as(C.c_void_p), q.size), self._h)
+        self.arch, self.dtype = arch, "int8"
         self._cfg_cache = {}
         self._box_cache = {}
 

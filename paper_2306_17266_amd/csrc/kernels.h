@@ -37,6 +37,18 @@ struct ConvArgs {
                          // head vectors); the kernels split it into two bf16 terms (value = hi + lo) on the fly
 };
 
+// What an int8 layer needs beyond ConvArgs / PoolArgs (int8.hip).  Weights are then
+// [tap][channel group of 16][filter (padded to 16)][16] and ConvArgs::CG counts the stored groups of 16.
+struct QuantArgs {
+    const int32_t *qmult;   // per filter: requantisation multiplier (classifier: bit pattern of a float32 factor)
+    const int32_t *qshift;  // per filter: rounding right shift
+    const int32_t *qbias;   // per filter: added to the accumulator
+    const int32_t *wsum;    // per filter: sum of the active slice's weights over taps and channels (zero-point term)
+    int zx, zy;             // zero points of the input and the output tensor (pooling: zx of the pooled map)
+    int m_res, sh_res, z_res;  // residual: multiplier, shift, zero point
+    int pool_hw;            // classifier: pixels the pooling before it summed over
+};
+
 struct PoolArgs {
     const void *x;
     void *y;
@@ -57,7 +69,9 @@ enum KernelClass {
     KC_STREAM = 7,  // sushi_stream_kernel (one launch per query)
     KC_TEAM = 8,    // sushi_team_kernel (persistent; one launch serves many queries)
     KC_CONV_PATCH = 9,  // conv_patch_kernel (large pixel counts; the input patch of a tile staged in LDS)
-    KC_COUNT = 10
+    KC_CONV_I8 = 10,    // conv_i8_kernel / conv_i8_direct_kernel (int8 mode)
+    KC_I8_OTHER = 11,   // int8 mode: max-pool, pooled sums, classifier
+    KC_COUNT = 12
 };
 const char *kernel_class_name(int kc);
 
@@ -78,6 +92,13 @@ hipError_t launch_gate(const PoolArgs &a, bool bf16, hipStream_t s);      // y =
 // Depthwise k x k, k in {3, 5, 7}, stride 1 or 2, bf16, tensors below 2 GiB: the row-strip kernel (dwconv.hip).
 // Returns hipErrorNotSupported (nothing launched) for any other case.
 hipError_t launch_dwconv_rows(const ConvArgs &a, hipStream_t s);
+
+// int8 mode (int8.hip): dense conv 1x1 / 3x3 on the int8 matrix cores (3 input channels: vector ALUs) with integer
+// requantisation, 3x3/2 max-pool on codes, exact int32 pooled sums, int64 classifier with float32 logits.
+hipError_t launch_conv_i8(const ConvArgs &a, const QuantArgs &q, hipStream_t s);
+hipError_t launch_fc_i8(const ConvArgs &a, const QuantArgs &q, hipStream_t s);
+hipError_t launch_maxpool_i8(const PoolArgs &a, hipStream_t s);
+hipError_t launch_gap_i8(const PoolArgs &a, const QuantArgs &q, hipStream_t s);
 
 // Streams `bytes` of `buf` through the caches (reads every 16-byte word once; `sink` receives one word that
 // depends on all of them, so the reads cannot be dropped).  A measurement aid: see SUSHI_OPT_COLD_SWEEP_MIB.

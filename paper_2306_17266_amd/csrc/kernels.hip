@@ -604,7 +604,7 @@ const char *kernel_class_name(int kc) {
     static const char *names[KC_COUNT] = {"conv_direct_kernel", "conv_mfma_kernel", "conv_mfma_splitk_kernel",
                                           "dwconv_rows_kernel", "maxpool_kernel",   "gap_kernel",
                                           "gate_kernel",        "sushi_stream_kernel", "sushi_team_kernel",
-                                          "conv_patch_kernel"};
+                                          "conv_patch_kernel",  "conv_i8_kernel",      "int8_pool_fc_kernels"};
     return kc >= 0 && kc < KC_COUNT ? names[kc] : "?";
 }
 

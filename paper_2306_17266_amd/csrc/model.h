@@ -28,6 +28,11 @@ struct SuperLayer {
     size_t pk_w = 0;              // element offset of the packed weights
     size_t pk_scale = 0, pk_shift = 0;  // float offsets in the parameter buffer
     bool has_scale = true;
+    // int8 mode: channel groups of 16 in the packed weights, offsets of the layer's parameter words
+    // (mult[Kpad], rshift[Kpad], bias[Kpad]) and of its weight prefix sums ([Cmax/8][Kpad]), its eight scalars
+    int CG16 = 0;
+    size_t pk_q = 0, pk_wsum = 0;
+    int32_t qscalars[8] = {};
 };
 
 struct SuperNet {

@@ -27,6 +27,7 @@ struct Launch {
     int kind;
     ConvArgs conv{};
     PoolArgs pool{};
+    QuantArgs quant{};  // int8 mode
     int in_patch = 0, out_patch = 0;  // 1 = pointer is the caller's input / logits buffer
 };
 
@@ -66,6 +67,9 @@ struct sushi_ctx {
     hipStream_t stream = nullptr;
     std::string err;
     bool loaded = false, bf16 = false;
+    bool int8 = false;               // int8 weights and activations (sushi_load_supernet_int8): exec mode 0 only
+    int32_t *d_qparams = nullptr;    // int8 mode: per layer mult[Kpad], rshift[Kpad], bias[Kpad]
+    int32_t *d_wsum = nullptr;       // int8 mode: per conv layer [channel group of 8][Kpad] prefix sums of the weights
     SuperNet sn;
     void *d_weights = nullptr;
     float *d_params = nullptr;
@@ -172,7 +176,7 @@ inline uint16_t to_bf16(float f) {
 
 size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-size_t elem_size(const sushi_ctx *c) { return c->bf16 ? 2 : 4; }
+size_t elem_size(const sushi_ctx *c) { return c->int8 ? 1 : c->bf16 ? 2 : 4; }
 
 // Lays the SuperNet out for the device.  Dense/FC layer: [tap][channel group][filter, padded to 16][8];
 // depthwise: [tap in ring order][channel, padded to 16].  Scale/shift/bias: float32 runs, each
@@ -315,6 +319,20 @@ void bind_plan(sushi_ctx *c, CachedPlan &cp, const BufBase &bb = BufBase()) {
             a.Kpad = S.Kpad, a.CG = S.CG;
             a.act = op.act, a.hsigmoid = op.hsigmoid ? 1 : 0, a.out_f32 = op.out_f32 ? 1 : 0;
             a.in_f32 = (op.in_small && c->bf16) ? 1 : 0;
+            if (c->int8) {
+                a.scale = nullptr, a.shift = nullptr;
+                QuantArgs &q = L.quant;
+                q.qmult = c->d_qparams + S.pk_q, q.qshift = q.qmult + S.Kpad, q.qbias = q.qshift + S.Kpad;
+                q.wsum = c->d_wsum + S.pk_wsum + (size_t)(std::max(op.C / 8, 1) - 1) * S.Kpad;
+                a.CG = S.CG16;
+                q.zx = S.qscalars[0], q.zy = S.qscalars[1];
+                q.m_res = S.qscalars[2], q.sh_res = std::max(S.qscalars[3], 1), q.z_res = S.qscalars[4];
+                q.pool_hw = 1;
+                if (op.kind == OP_FC && !cp.launches.empty()) {  // the classifier works on the sums of the pooling before it
+                    const PoolArgs &g = cp.launches.back().pool;
+                    q.pool_hw = g.H * g.W;
+                }
+            }
             L.in_patch = op.in_buf == BUF_INPUT;
             L.out_patch = op.out_buf == BUF_LOGITS;
         } else {
@@ -324,6 +342,11 @@ void bind_plan(sushi_ctx *c, CachedPlan &cp, const BufBase &bb = BufBase()) {
             a.gate = static_cast<const float *>(buf_ptr(c, bb, op.gate_buf, true));
             a.B = op.B, a.H = op.H, a.W = op.W, a.C = op.C, a.P = op.P, a.Q = op.Q;
             a.out_f32 = (op.out_f32 && c->bf16) ? 1 : 0;
+            if (c->int8 && op.kind == OP_GAP) {  // the zero point of the pooled map: first scalar of the classifier after it
+                const size_t next = cp.launches.size() + 1;
+                if (next < cp.plan.ops.size() && cp.plan.ops[next].layer >= 0)
+                    L.quant.zx = c->sn.layers[cp.plan.ops[next].layer].qscalars[0];
+            }
         }
         cp.launches.push_back(L);
     }
@@ -357,7 +380,7 @@ void refresh_residency(sushi_ctx *c, CachedPlan &cp) {
 // Algorithmic traffic and arithmetic of one launch: every input, output, residual, weight and
 // scale/shift element of the active slice counted once.
 void launch_cost(const sushi_ctx *c, const Launch &L, double *bytes, double *flops) {
-    const double es = c->bf16 ? 2.0 : 4.0;
+    const double es = c->int8 ? 1.0 : c->bf16 ? 2.0 : 4.0;
     if (L.kind == OP_CONV || L.kind == OP_FC || L.kind == OP_DW) {
         const ConvArgs &a = L.conv;
         const double in = (double)a.B * a.H * a.W * a.C, out = (double)a.B * a.P * a.Q * a.K;
@@ -415,6 +438,32 @@ hipError_t issue_launches(sushi_ctx *c, CachedPlan &cp, const void *input_dev, v
             if ((e = hipEventRecord(pend.a, st)) != hipSuccess) return e;
         }
         int kc = KC_COUNT;
+        if (c->int8) {
+            ConvArgs a = L.conv;
+            PoolArgs pa = L.pool;
+            switch (L.kind) {
+                case OP_CONV:
+                    if (L.in_patch) a.x = input_dev;
+                    kc = KC_CONV_I8;
+                    e = launch_conv_i8(a, L.quant, st);
+                    break;
+                case OP_FC:
+                    if (L.out_patch) a.y = logits_dev;
+                    kc = KC_I8_OTHER;
+                    e = launch_fc_i8(a, L.quant, st);
+                    break;
+                case OP_MAXPOOL:
+                    kc = KC_I8_OTHER;
+                    e = launch_maxpool_i8(pa, st);
+                    break;
+                case OP_GAP:
+                    kc = KC_I8_OTHER;
+                    e = launch_gap_i8(pa, L.quant, st);
+                    break;
+                default:
+                    e = hipErrorNotSupported;
+            }
+        } else
         switch (L.kind) {
             case OP_CONV:
             case OP_FC: {
@@ -1077,6 +1126,42 @@ std::string plan_key(const sushi_subnet_cfg &cfg, int batch) {
 
 }  // namespace
 
+// Makes the context forget the SuperNet it holds (device weights, arenas, plans, cached SubGraph, residency state).
+static int drop_loaded(sushi_ctx *c) {
+    hipError_t e;
+    if ((e = hipSetDevice(c->device)) != hipSuccess) return hip_fail(c, e, "hipSetDevice");
+    if ((e = hipStreamSynchronize(c->stream)) != hipSuccess) return hip_fail(c, e, "hipStreamSynchronize");
+    if (c->th) {
+        (void)synchronize_teams(c);
+        (void)stop_team_kernel(c);
+        // the team arenas were sized by the previous SuperNet's largest SubNet
+        if (c->d_tarena) (void)hipFree(c->d_tarena);
+        c->d_tarena = nullptr;
+        c->tarena_batch = 0, c->tarena_bytes = 0, c->tbig_bytes = 0, c->tsmall_bytes = 0;
+    }
+    free_arena(c);
+    c->plans.clear();
+    if (c->d_weights) (void)hipFree(c->d_weights);
+    if (c->d_params) (void)hipFree(c->d_params);
+    c->d_weights = nullptr, c->d_params = nullptr, c->loaded = false;
+    c->G.clear();
+    ++c->g_version;
+    for (bool &v : c->gen_valid) v = false;
+    c->h_res_layers.clear(), c->h_res_entries.clear();
+    c->geo_n.clear(), c->geo_cg.clear(), c->geo_layers.clear(), c->geo_entries.clear();
+    ++c->geometry;
+    ++c->table_seq;  // (teams drop the table they hold)
+    c->geometry_team_size = 0;
+    c->prog_pool_used = 0;
+    ++c->table_version;
+    c->stats = sushi_stats{};
+
+    if (c->d_qparams) (void)hipFree(c->d_qparams);
+    if (c->d_wsum) (void)hipFree(c->d_wsum);
+    c->d_qparams = nullptr, c->d_wsum = nullptr, c->int8 = false;
+    return SUSHI_OK;
+}
+
 extern "C" {
 
 int sushi_synchronize(sushi_ctx *c);
@@ -1234,6 +1319,8 @@ void sushi_destroy(sushi_ctx *c) {
     free_arena(c);
     if (c->d_weights) (void)hipFree(c->d_weights);
     if (c->d_params) (void)hipFree(c->d_params);
+    if (c->d_qparams) (void)hipFree(c->d_qparams);
+    if (c->d_wsum) (void)hipFree(c->d_wsum);
     delete c;
 }
 
@@ -1252,33 +1339,7 @@ int sushi_load_supernet(sushi_ctx *c, const sushi_arch *arch, const void *weight
         return fail(c, SUSHI_EINVAL, "load: blob holds " + std::to_string(nbytes) + " bytes, the SuperNet needs " +
                                          std::to_string(sn.blob_floats * sizeof(float)));
     hipError_t e;
-    if ((e = hipSetDevice(c->device)) != hipSuccess) return hip_fail(c, e, "hipSetDevice");
-    if ((e = hipStreamSynchronize(c->stream)) != hipSuccess) return hip_fail(c, e, "hipStreamSynchronize");
-    // drop whatever was loaded before
-    if (c->th) {
-        (void)synchronize_teams(c);
-        (void)stop_team_kernel(c);
-        // the team arenas were sized by the previous SuperNet's largest SubNet
-        if (c->d_tarena) (void)hipFree(c->d_tarena);
-        c->d_tarena = nullptr;
-        c->tarena_batch = 0, c->tarena_bytes = 0, c->tbig_bytes = 0, c->tsmall_bytes = 0;
-    }
-    free_arena(c);
-    c->plans.clear();
-    if (c->d_weights) (void)hipFree(c->d_weights);
-    if (c->d_params) (void)hipFree(c->d_params);
-    c->d_weights = nullptr, c->d_params = nullptr, c->loaded = false;
-    c->G.clear();
-    ++c->g_version;
-    for (bool &v : c->gen_valid) v = false;
-    c->h_res_layers.clear(), c->h_res_entries.clear();
-    c->geo_n.clear(), c->geo_cg.clear(), c->geo_layers.clear(), c->geo_entries.clear();
-    ++c->geometry;
-    ++c->table_seq;  // (teams drop the table they hold)
-    c->geometry_team_size = 0;
-    c->prog_pool_used = 0;
-    ++c->table_version;
-    c->stats = sushi_stats{};
+    if ((rc = drop_loaded(c)) != SUSHI_OK) return rc;
 
     const float *blob = static_cast<const float *>(weights);
     std::vector<float> params;
@@ -1309,6 +1370,100 @@ int sushi_load_supernet(sushi_ctx *c, const sushi_arch *arch, const void *weight
     c->sn = std::move(sn);
     c->bf16 = dtype == SUSHI_BF16;
     c->weight_elems = wbytes / (c->bf16 ? 2 : 4);
+    c->loaded = true;
+    return SUSHI_OK;
+}
+
+int sushi_load_supernet_int8(sushi_ctx *c, const sushi_arch *arch, const int8_t *weights, size_t n_weights,
+                             const int32_t *qparams, size_t n_qparams) {
+    if (!c) return SUSHI_EINVAL;
+    if (c->device < 0) return fail(c, SUSHI_ESTATE, "load: host-only context");
+    if (!arch || !weights || !qparams) return fail(c, SUSHI_EINVAL, "load: null argument");
+    if (arch->family != SUSHI_FAMILY_TINY && arch->family != SUSHI_FAMILY_RESNET)
+        return fail(c, SUSHI_EINVAL, "load: the int8 path covers the TINY and RESNET families");
+    SuperNet sn;
+    std::string err;
+    int rc = build_supernet(*arch, sn, err);
+    if (rc) return fail(c, rc, err);
+    size_t need_w = 0, need_q = 0;
+    for (const SuperLayer &L : sn.layers) {
+        if (L.type == L_DW) return fail(c, SUSHI_EINVAL, "load: no int8 depthwise layers");
+        need_w += (size_t)L.Kmax * L.Cmax * L.Rmax * L.Rmax;
+        need_q += 3 * (size_t)L.Kmax + 8;
+    }
+    if (n_weights != need_w || n_qparams != need_q)
+        return fail(c, SUSHI_EINVAL, "load: the SuperNet needs " + std::to_string(need_w) + " int8 weights and " +
+                                         std::to_string(need_q) + " int32 parameter words");
+    if ((rc = drop_loaded(c)) != SUSHI_OK) return rc;
+
+    // Packed layout: [tap][channel group of 16][filter, padded to 16][16 channels], channels beyond Cmax zero; a
+    // matrix-core operand of 16 filters x 64 channels is four runs of 256 bytes.  Parameter words per layer:
+    // mult[Kpad], rshift[Kpad], bias[Kpad].  Prefix sums per conv layer: wsum[g][k] = sum of w_q[k][c][tap] over
+    // all taps and the channels c < 8 (g + 1): the zero-point term of a SubNet that keeps 8 (g + 1) channels.
+    std::vector<int8_t> w8;
+    std::vector<int32_t> q, wsum;
+    try {
+        size_t welems = 0, qwords = 0, swords = 0;
+        for (SuperLayer &L : sn.layers) {
+            L.Kpad = (int)round_up(L.Kmax, 16);
+            L.CG16 = (L.Cmax + 15) / 16;
+            L.CG = (L.Cmax + 7) / 8;
+            L.pk_w = welems;
+            welems = round_up(welems + (size_t)L.Rmax * L.Rmax * L.CG16 * L.Kpad * 16, 256);
+            L.pk_q = qwords;
+            qwords += 3 * (size_t)L.Kpad;
+            L.pk_wsum = swords;
+            if (L.type == L_CONV && L.Cmax >= 8) swords += (size_t)L.CG * L.Kpad;
+        }
+        w8.assign(welems, 0);
+        q.assign(std::max<size_t>(qwords, 64), 0);
+        wsum.assign(std::max<size_t>(swords, 64), 0);
+        const int8_t *src = weights;
+        const int32_t *qs = qparams;
+        for (SuperLayer &L : sn.layers) {
+            const int R2 = L.Rmax * L.Rmax;
+            int8_t *dst = w8.data() + L.pk_w;
+            for (int k = 0; k < L.Kmax; ++k)
+                for (int ch = 0; ch < L.Cmax; ++ch)
+                    for (int t = 0; t < R2; ++t)
+                        dst[(((size_t)t * L.CG16 + ch / 16) * L.Kpad + k) * 16 + (ch & 15)] = src[((size_t)k * L.Cmax + ch) * R2 + t];
+            if (L.type == L_CONV && L.Cmax >= 8) {
+                int32_t *ws = wsum.data() + L.pk_wsum;
+                for (int k = 0; k < L.Kmax; ++k) {
+                    int32_t run = 0;
+                    for (int ch = 0; ch < L.Cmax; ++ch) {
+                        for (int t = 0; t < R2; ++t) run += src[((size_t)k * L.Cmax + ch) * R2 + t];
+                        if ((ch & 7) == 7 || ch == L.Cmax - 1) ws[(size_t)(ch / 8) * L.Kpad + k] = run;
+                    }
+                }
+            }
+            src += (size_t)L.Kmax * L.Cmax * R2;
+            int32_t *qd = q.data() + L.pk_q;
+            for (int k = 0; k < L.Kmax; ++k) {
+                qd[k] = qs[k], qd[L.Kpad + k] = qs[L.Kmax + k], qd[2 * L.Kpad + k] = qs[2 * L.Kmax + k];
+                if (L.type == L_CONV && (qd[L.Kpad + k] < 1 || qd[L.Kpad + k] > 62))
+                    return fail(c, SUSHI_EINVAL, "load: shift of layer " + L.name + " outside 1 .. 62");
+            }
+            for (int k = L.Kmax; k < L.Kpad; ++k) qd[L.Kpad + k] = 1;
+            for (int i = 0; i < 8; ++i) L.qscalars[i] = qs[3 * (size_t)L.Kmax + i];
+            if (L.qscalars[0] < -128 || L.qscalars[0] > 127 || L.qscalars[1] < -128 || L.qscalars[1] > 127 ||
+                L.qscalars[4] < -128 || L.qscalars[4] > 127 || L.qscalars[3] < 0 || L.qscalars[3] > 62 || L.qscalars[2] < 0)
+                return fail(c, SUSHI_EINVAL, "load: scalars of layer " + L.name + " out of range");
+            qs += 3 * (size_t)L.Kmax + 8;
+        }
+    } catch (const std::bad_alloc &) {
+        return fail(c, SUSHI_ENOMEM, "load: host staging allocation failed");
+    }
+    hipError_t e;
+    if (hipMalloc(&c->d_weights, std::max<size_t>(w8.size(), 256)) != hipSuccess) return fail(c, SUSHI_ENOMEM, "load: hipMalloc(weights)");
+    if (hipMalloc(reinterpret_cast<void **>(&c->d_qparams), q.size() * 4) != hipSuccess) return fail(c, SUSHI_ENOMEM, "load: hipMalloc(parameter words)");
+    if (hipMalloc(reinterpret_cast<void **>(&c->d_wsum), wsum.size() * 4) != hipSuccess) return fail(c, SUSHI_ENOMEM, "load: hipMalloc(weight sums)");
+    if ((e = hipMemcpy(c->d_weights, w8.data(), w8.size(), hipMemcpyHostToDevice)) != hipSuccess) return hip_fail(c, e, "hipMemcpy(weights)");
+    if ((e = hipMemcpy(c->d_qparams, q.data(), q.size() * 4, hipMemcpyHostToDevice)) != hipSuccess) return hip_fail(c, e, "hipMemcpy(parameter words)");
+    if ((e = hipMemcpy(c->d_wsum, wsum.data(), wsum.size() * 4, hipMemcpyHostToDevice)) != hipSuccess) return hip_fail(c, e, "hipMemcpy(weight sums)");
+    c->sn = std::move(sn);
+    c->bf16 = false, c->int8 = true;
+    c->weight_elems = w8.size();
     c->loaded = true;
     return SUSHI_OK;
 }
@@ -1353,6 +1508,7 @@ int sushi_infer(sushi_ctx *c, const sushi_subnet_cfg *cfg, const void *input_dev
     if (!c) return SUSHI_EINVAL;
     if (!c->loaded) return fail(c, SUSHI_ESTATE, "infer before load_supernet");
     if (!cfg || !input_dev || !logits_dev || batch < 1) return fail(c, SUSHI_EINVAL, "infer: bad argument");
+    if (c->int8 && c->exec_mode != 0) return fail(c, SUSHI_ESTATE, "infer: the int8 path runs in exec mode 0 only");
     hipError_t e;
     if ((e = hipSetDevice(c->device)) != hipSuccess) return hip_fail(c, e, "hipSetDevice");
     CachedPlan *cp = nullptr;

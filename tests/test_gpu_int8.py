@@ -1,0 +1,95 @@
+"""GPU parity of the int8 path: the library's int8 kernels (through the C ABI) against oracle/int8_eval.py on the
+same seeded int8 model and inputs.  Every step of the path is integer arithmetic with one right answer, the final
+logit two stated float64 roundings, so the comparison is BIT-EXACT."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import int8_eval as Q
+from oracle import subnet_eval as E
+from workloads import arch as A
+from workloads import quant, streams, tensors as T
+from workloads.rng import Stream
+
+pytestmark = pytest.mark.gpu
+
+
+def _problem(arch, seed):
+    import paper_2306_17266_amd as S
+    lib_table = S.sushi_describe_supernet(arch)
+    ora_table = E.supernet_tensors(arch)
+    assert lib_table == [(n, tuple(s), k) for n, s, k in ora_table]
+    tens = T.make_weights([(s, k) for _, s, k in lib_table], seed, False)
+    model = quant.make_int8_model(ora_table, tens, quant.layer_roles(arch))
+    wq, qp = quant.flatten_int8(model)
+    ctx = S.Sushi(0)
+    ctx.sushi_load_supernet_int8(arch, wq, qp)
+    return ctx, Q.name_model(model)
+
+
+def _run(ctx, cfg, xq, n_classes):
+    x = torch.from_numpy(xq).cuda()
+    logits = torch.full((xq.shape[0], n_classes), float("nan"), device="cuda", dtype=torch.float32)
+    ctx.sushi_infer(cfg, x.contiguous(), logits)
+    torch.cuda.synchronize()
+    return logits.cpu().numpy()
+
+
+def _check(arch, cfgs, seed, batch):
+    ctx, qm = _problem(arch, seed)
+    for t, cfg in enumerate(cfgs):
+        xq = quant.quantize_input(T.make_input(seed, t, batch, cfg.resolution, arch.in_channels, False))
+        print("int8 query", t, "batch", batch, "cfg", cfg.key(), flush=True)
+        got = _run(ctx, cfg, xq, arch.n_classes)
+        want = Q.forward_int8(arch, qm, cfg, np.ascontiguousarray(xq.transpose(0, 3, 1, 2)))
+        assert np.isfinite(got).all()
+        np.testing.assert_array_equal(got, want)
+    ctx.close()
+
+
+def test_tiny_int8_all_depths_bit_exact():
+    arch = A.tiny_arch()
+    st = Stream(3)
+    cfgs = [A.min_cfg(arch), A.max_cfg(arch)] + [streams.uniform_cfg(arch, st) for _ in range(6)]
+    for batch in (1, 5):
+        _check(arch, cfgs, 11, batch)
+
+
+def test_small_bottleneck_supernet_int8_bit_exact():
+    """Shrunken bottleneck SuperNet: ragged pixel and filter counts (channel counts that are no multiple of 16,
+    pixel counts that are no multiple of 16), both strides, residuals from the block input and from the projection."""
+    arch = A.small_resnet_arch()
+    st = Stream(17)
+    for res, batch in ((64, 1), (96, 3)):
+        cfgs = [A.min_cfg(arch, res), A.max_cfg(arch, res)] + [streams.uniform_cfg(arch, st, res) for _ in range(4)]
+        _check(arch, cfgs, 23, batch)
+
+
+def test_full_size_bottleneck_supernet_int8_bit_exact():
+    """The benchmarked shape: ResNet50-shaped SuperNet, batch 1 (smallest, largest, one random SubNet) and the
+    smallest SubNet at batch 16."""
+    arch = A.resnet_arch()
+    st = Stream(29)
+    _check(arch, [A.min_cfg(arch, 224), A.max_cfg(arch, 224), streams.uniform_cfg(arch, st, 224)], 31, 1)
+    _check(arch, [A.min_cfg(arch, 224)], 31, 16)
+
+
+def test_int8_rejects_what_it_does_not_cover():
+    import paper_2306_17266_amd as S
+    ctx = S.Sushi(0)
+    with pytest.raises(S.SushiError) as e:
+        ctx.sushi_load_supernet_int8(A.small_mbv3_arch(), np.zeros(8, np.int8), np.zeros(8, np.int32))
+    assert e.value.code == -1
+    arch = A.tiny_arch()
+    with pytest.raises(S.SushiError) as e:
+        ctx.sushi_load_supernet_int8(arch, np.zeros(8, np.int8), np.zeros(8, np.int32))      # wrong sizes
+    assert e.value.code == -1
+    ctx.close()
+    ctx, _ = _problem(arch, 1)
+    ctx.sushi_set_option(S.OPT_EXEC_MODE, 3)
+    x = torch.zeros(1, 32, 32, 3, device="cuda", dtype=torch.int8)
+    y = torch.zeros(1, 10, device="cuda")
+    with pytest.raises(S.SushiError) as e:
+        ctx.sushi_infer(A.max_cfg(arch), x, y)
+    assert e.value.code == -3
+    ctx.close()
