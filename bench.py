@@ -26,6 +26,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
+MFMA_INT8_PEAK_TOPS = 5000.0
 
 
 def kernel_sources_digest():
@@ -65,8 +66,11 @@ def main():
     ap.add_argument("--queries-per-step", type=int, default=0, help="default: 200 at batch 1, 100 at batch 16")
     ap.add_argument("--workload", default="resnet_bs1_sticky", choices=[n for n in configs.NAMES if n != "tiny_uniform"])
     ap.add_argument("--budget-mib", type=int, default=0, help="SubGraph cache budget (default: the workload's)")
-    ap.add_argument("--exec-mode", type=int, default=3,
-                    help="0 = launch per layer, 1 = HIP graph replay, 2 = stream kernel, 3 = persistent XCD-team kernel")
+    ap.add_argument("--dtype", choices=["bf16", "int8"], default="bf16",
+                    help="int8: the paper's own precision (ResNet50-shaped workloads, exec mode 0 only)")
+    ap.add_argument("--exec-mode", type=int, default=-1,
+                    help="0 = launch per layer, 1 = HIP graph replay, 2 = stream kernel, 3 = persistent XCD-team kernel "
+                         "(default: 3 for bf16, 0 for int8)")
     ap.add_argument("--teams-per-xcd", type=int, default=0, choices=[0, 1, 2, 4, 8],
                     help="mode 3: teams per XCD (default 8 at batch 1, 1 at batch 16)")
     ap.add_argument("--sgs", choices=["sched", "fixed", "off"], default="sched",
@@ -103,9 +107,21 @@ def main():
     qps = args.queries_per_step or (200 if batch == 1 else 100)
     teams = args.teams_per_xcd or (8 if batch == 1 else 1)
     table = S.sushi_describe_supernet(arch)
-    tensors = T.make_weights([(s, k) for _, s, k in table], 1, True)
+    int8 = args.dtype == "int8"
+    es = 1 if int8 else 2                       # bytes per weight
+    if args.exec_mode < 0:
+        args.exec_mode = 0 if int8 else 3
+    if int8 and args.exec_mode != 0:
+        raise SystemExit("bench.py: the int8 path runs in exec mode 0 only")
+    tensors = T.make_weights([(s, k) for _, s, k in table], 1, not int8)
     ctx = S.Sushi(0)
-    ctx.sushi_load_supernet(arch, T.flatten(tensors), S.BF16)
+    qmodel = None
+    if int8:
+        from workloads import quant
+        qmodel = quant.make_int8_model(table, tensors, quant.layer_roles(arch))
+        ctx.sushi_load_supernet_int8(arch, *quant.flatten_int8(qmodel))
+    else:
+        ctx.sushi_load_supernet(arch, T.flatten(tensors), S.BF16)
     mode = args.exec_mode
     ctx.sushi_set_option(S.OPT_EXEC_MODE, mode)
     ctx.sushi_set_option(S.OPT_TEAMS_PER_XCD, teams)
@@ -120,14 +136,18 @@ def main():
         distinct.setdefault(c.key(), c)
     box_of = {k: S.sushi_subnet_layers(arch, c) for k, c in distinct.items()}
     vec_of = {k: np.array([v for (kk, cc, r) in b for v in (kk, cc)], dtype=np.int32) for k, b in box_of.items()}
-    cands = streams.candidate_subgraphs(list(box_of.values()), budget, 2, 40)
+    cands = streams.candidate_subgraphs(list(box_of.values()), budget, es, 40)
     gvecs = [[v for (k, c, r) in b for v in (k, c)] for b in cands]
     n = len(gvecs[0])
 
     res_list = sorted({c.resolution for c in serving})
     n_inputs, n_outputs = 8, 64
-    xs = {r: [torch.from_numpy(T.make_input(11, t, batch, r, arch.in_channels, True)).cuda().to(torch.bfloat16)
-              for t in range(n_inputs)] for r in res_list}
+    if int8:
+        xs = {r: [torch.from_numpy(quant.quantize_input(T.make_input(11, t, batch, r, arch.in_channels, False))).cuda()
+                  for t in range(n_inputs)] for r in res_list}
+    else:
+        xs = {r: [torch.from_numpy(T.make_input(11, t, batch, r, arch.in_channels, True)).cuda().to(torch.bfloat16)
+                  for t in range(n_inputs)] for r in res_list}
     outs = [torch.empty(batch, arch.n_classes, device="cuda", dtype=torch.float32) for _ in range(n_outputs)]
     torch.cuda.synchronize()
 
@@ -137,7 +157,7 @@ def main():
         # Algorithm 1 in the loop: the latency table L[SubNet][cached SubGraph] measured on this GPU (frozen
         # to a file when one is shipped for this workload), synthetic accuracies that grow with SubNet size
         pool = wl["pool"]
-        sizes = [streams.box_bytes(box_of[c.key()], 2) for c in pool]
+        sizes = [streams.box_bytes(box_of[c.key()], es) for c in pool]
         acc = [0.0] * len(pool)
         for rank, i in enumerate(sorted(range(len(pool)), key=lambda i: sizes[i])):
             acc[i] = float(np.float32(0.70 + 0.01 * rank))
@@ -196,8 +216,8 @@ def main():
         del src, dst
     ctx.sushi_set_subgraph_cache(None, 0)
     if args.sgs == "fixed":
-        smallest = min(box_of.values(), key=lambda b: streams.box_bytes(b, 2))
-        ctx.sushi_set_subgraph_cache(streams.shrink_box(smallest, budget, 2), budget)
+        smallest = min(box_of.values(), key=lambda b: streams.box_bytes(b, es))
+        ctx.sushi_set_subgraph_cache(streams.shrink_box(smallest, budget, es), budget)
     for _ in range(args.warmup):
         step()
     ctx.sushi_quiesce()          # the timed region gets a kernel launch of its own (mode 3)
@@ -265,8 +285,9 @@ def main():
         dom = max(ks, key=lambda k: k["total_ms"])
         sec = dom["total_ms"] * 1e-3
         ai = dom["flops"] / dom["bytes"]
-        if ai >= MFMA_BF16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9):
-            achieved, peak, unit, bound = dom["flops"] / sec / 1e12, MFMA_BF16_PEAK_TFLOPS, "TFLOP/s", "mfma"
+        mfma_peak = MFMA_INT8_PEAK_TOPS if int8 else MFMA_BF16_PEAK_TFLOPS
+        if ai >= mfma_peak * 1e12 / (HBM_PEAK_GBS * 1e9):
+            achieved, peak, unit, bound = dom["flops"] / sec / 1e12, mfma_peak, "TOP/s" if int8 else "TFLOP/s", "mfma"
         else:
             achieved, peak, unit, bound = dom["bytes"] / sec / 1e9, HBM_PEAK_GBS, "GB/s", "hbm"
         # measured bytes per launch of the dominant kernel: a STORED counter reading (two rocprofv3 --pmc runs
@@ -293,16 +314,28 @@ def main():
     cpu = None
     if not args.no_cpu_baseline:
         from oracle import subnet_eval as E
-        wts = E.name_weights(arch, tensors)
         n_sample = 64 if batch == 1 else 4
         sample = [serving[(t_start + i * 7) % len(serving)] for i in range(n_sample)]
-        x_of = {r: np.ascontiguousarray(T.make_input(11, 0, batch, r, arch.in_channels, True).transpose(0, 3, 1, 2))
-                for r in res_list}
-        E.forward(arch, wts, sample[0], x_of[sample[0].resolution])
+        if int8:
+            from oracle import int8_eval as QE
+            qm = QE.name_model(qmodel)
+            x_of = {r: np.ascontiguousarray(quant.quantize_input(T.make_input(11, 0, batch, r, arch.in_channels, False)).transpose(0, 3, 1, 2))
+                    for r in res_list}
+
+            def ref_forward(cfg):
+                return QE.forward_int8(arch, qm, cfg, x_of[cfg.resolution])
+        else:
+            wts = E.name_weights(arch, tensors)
+            x_of = {r: np.ascontiguousarray(T.make_input(11, 0, batch, r, arch.in_channels, True).transpose(0, 3, 1, 2))
+                    for r in res_list}
+
+            def ref_forward(cfg):
+                return E.forward(arch, wts, cfg, x_of[cfg.resolution])
+        ref_forward(sample[0])
         c0 = time.perf_counter()
         done = 0
         for cfg in sample:
-            E.forward(arch, wts, cfg, x_of[cfg.resolution])
+            ref_forward(cfg)
             done += 1
             if time.perf_counter() - c0 > 25.0:
                 break
@@ -315,7 +348,7 @@ def main():
     nq = max(1, dstat["queries"])
     out = {"metric": "SubNet queries/sec (batch %d)" % batch, "value": n_queries / elapsed, "unit": "queries/s",
            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": elapsed / args.steps * 1e3,
-           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "i8" if int8 else "bf16", "data": "synthetic",
            "config": {"workload": args.workload, "description": wl["desc"], "queries_per_step": qps,
                       "timed_queries": n_queries, "warmup_queries": args.warmup * qps, "exec_mode": mode,
                       "teams_per_xcd": teams, "sgs": args.sgs, "Q": Q, "budget_bytes": budget,

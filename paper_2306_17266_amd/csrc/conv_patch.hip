@@ -32,6 +32,8 @@
 namespace sushi {
 
 typedef __attribute__((ext_vector_type(16))) float cp_f32x16;
+typedef __attribute__((ext_vector_type(16))) int cp_i32x16;
+typedef __attribute__((ext_vector_type(4))) int cp_i32x4;
 typedef __attribute__((ext_vector_type(4))) unsigned cp_u32x4;
 constexpr int CP_OOB = 0x7FFFFFF0;
 
@@ -73,14 +75,17 @@ __device__ __forceinline__ int cp_base(const ConvArgs &a, const PatchGeom &g, in
     return (n * g.hp + p * a.stride) * g.wp + q * a.stride;
 }
 
-template <int TF, int TM, int CK, int R, int MAXP, int MINB, int NW>
-__global__ __launch_bounds__(64 * NW, MINB) void conv_patch_kernel(ConvArgs a, PatchGeom g) {
+// I8: the int8 path (int8 codes, v_mfma_i32_32x32x32_i8, integer requantisation: see int8.hip for the arithmetic).
+// A 16-byte cell then holds 16 channels instead of 8; everything that is counted in cells stays as it is.
+template <int TF, int TM, int CK, int R, int MAXP, int MINB, int NW, bool I8>
+__global__ __launch_bounds__(64 * NW, MINB) void conv_patch_kernel(ConvArgs a, PatchGeom g, QuantArgs q) {
     constexpr int NT = 64 * NW;  // threads
-    constexpr int BN = 32 * TF, BM = 32 * NW * TM, NKG = CK / 8, WPS = BN + 4;
+    constexpr int ES = I8 ? 1 : 2, CPC = 16 / ES;  // bytes per element, channels per cell
+    constexpr int BN = 32 * TF, BM = 32 * NW * TM, NKG = CK / CPC, WPS = BN + 4;
     constexpr int PPW = NT / NKG;  // positions one pass of the workgroup's threads covers
     constexpr int WCELLS = R * NKG * BN, WPT = (WCELLS + NT - 1) / NT;
-    constexpr int KSUB = CK / 16;
-    constexpr int ROWC = BN / 8 + 1;  // epilogue: cells per pixel row (one spare)
+    constexpr int KSUB = NKG / 2;     // a matrix instruction takes two cells per lane pair
+    constexpr int ROWC = BN / 8 + 1;  // epilogue: pieces per pixel row (one spare); a piece = 8 filters (16 bytes, int8: 8)
     extern __shared__ uint4 cp_lds[];
     uint4 *const patch = cp_lds;                         // [2][NKG * ps]
     uint4 *const wts = cp_lds + 2 * NKG * g.ps;          // [2][R * NKG * WPS]
@@ -98,7 +103,7 @@ __global__ __launch_bounds__(64 * NW, MINB) void conv_patch_kernel(ConvArgs a, P
     const int npos = cp_base(a, g, mlast) + (R - 1) * (g.wp + 1) - u0 + 1;
 
     const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<void *>(a.x), 0, (int)((long)a.B * a.H * a.W * a.C * 2), 0x00020000);
+        const_cast<void *>(a.x), 0, (int)((long)a.B * a.H * a.W * a.C * ES), 0x00020000);
     const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<void *>(a.w), 0, (int)((long)R * R * a.CG * a.Kpad * 16), 0x00020000);
 
@@ -112,7 +117,7 @@ __global__ __launch_bounds__(64 * NW, MINB) void conv_patch_kernel(ConvArgs a, P
         const int t = fdiv(u, g.dwp), n = fdiv(t, g.dhp);
         const int h = t - n * g.hp - a.pad, w = u - t * g.wp - a.pad;
         const bool ok = pos < npos && n < a.B && (unsigned)h < (unsigned)a.H && (unsigned)w < (unsigned)a.W;
-        poff[j] = ok ? (((n * a.H + h) * a.W + w) * a.C + kgp * 8) * 2 : -1;
+        poff[j] = ok ? (((n * a.H + h) * a.W + w) * a.C + kgp * CPC) * ES : -1;
     }
     // ... and of a stage's weights: cells (tap column t, group kg, filter f)
     int woff[WPT], wkg[WPT], wlds[WPT];
@@ -135,33 +140,45 @@ __global__ __launch_bounds__(64 * NW, MINB) void conv_patch_kernel(ConvArgs a, P
     constexpr int D = 3;
     constexpr int NPS = R == 3 ? 1 : D;
     cp_u32x4 pr[NPS][MAXP], wr[D][WPT];
-    auto load_patch = [&](int chunk, cp_u32x4 *q) {
+    auto load_patch = [&](int chunk, cp_u32x4 *regs) {
         const int c0 = chunk * CK;
-        const bool cv = c0 + kgp * 8 < a.C;
+        const bool cv = c0 + kgp * CPC < a.C;
 #pragma unroll
         for (int j = 0; j < MAXP; ++j)
             if (j * PPW < npos)
-                q[j] = __builtin_amdgcn_raw_buffer_load_b128(rx, cv && poff[j] >= 0 ? poff[j] + c0 * 2 : CP_OOB, 0, 0);
+                regs[j] = __builtin_amdgcn_raw_buffer_load_b128(rx, cv && poff[j] >= 0 ? poff[j] + c0 * ES : CP_OOB, 0, 0);
     };
-    auto store_patch = [&](int buf, const cp_u32x4 *q) {
+    // int8: a cell of the frame holds the code of the real value 0 (the input's zero point) in its active channels,
+    // and the upper half of a cell that straddles the SubNet's channel count holds zeros (the load brought the next
+    // pixel's bytes there).  `chunk` is the chunk the registers were loaded for.
+    const unsigned zfill = (unsigned)(q.zx & 0xFF) * 0x01010101u;
+    auto store_patch = [&](int buf, const cp_u32x4 *regs, int chunk) {
         uint4 *dst = patch + buf * NKG * g.ps + kgp * g.ps + pk;
+        const int cc = chunk * CK + kgp * CPC;  // first channel of this thread's cells
 #pragma unroll
         for (int j = 0; j < MAXP; ++j)
-            if (pk + j * PPW < npos) dst[j * PPW] = __builtin_bit_cast(uint4, q[j]);
+            if (pk + j * PPW < npos) {
+                cp_u32x4 v = regs[j];
+                if (I8) {
+                    if (poff[j] < 0 && cc < a.C) v = cp_u32x4{zfill, zfill, zfill, zfill};
+                    if (cc + 8 >= a.C) v[2] = 0u, v[3] = 0u;
+                }
+                dst[j * PPW] = __builtin_bit_cast(uint4, v);
+            }
     };
-    auto load_w = [&](int stage, cp_u32x4 *q) {
+    auto load_w = [&](int stage, cp_u32x4 *regs) {
         const int chunk = stage / R, dr = stage - chunk * R;
         const int cg0 = chunk * NKG;
         const int add = (dr * R * a.CG + cg0) * a.Kpad * 16;
 #pragma unroll
         for (int j = 0; j < WPT; ++j)
-            q[j] = __builtin_amdgcn_raw_buffer_load_b128(rw, woff[j] >= 0 && cg0 + wkg[j] < a.CG ? woff[j] + add : CP_OOB, 0, 0);
+            regs[j] = __builtin_amdgcn_raw_buffer_load_b128(rw, woff[j] >= 0 && cg0 + wkg[j] < a.CG ? woff[j] + add : CP_OOB, 0, 0);
     };
-    auto store_w = [&](int buf, const cp_u32x4 *q) {
+    auto store_w = [&](int buf, const cp_u32x4 *regs) {
         uint4 *dst = wts + buf * R * NKG * WPS;
 #pragma unroll
         for (int j = 0; j < WPT; ++j)
-            if (tid + NT * j < WCELLS) dst[wlds[j]] = __builtin_bit_cast(uint4, q[j]);
+            if (tid + NT * j < WCELLS) dst[wlds[j]] = __builtin_bit_cast(uint4, regs[j]);
     };
 
     // prologue: the loads of the first D stages; stage 0 into LDS.  The tile's scale and shift values go to LDS
@@ -182,22 +199,36 @@ __global__ __launch_bounds__(64 * NW, MINB) void conv_patch_kernel(ConvArgs a, P
         boff[j] = m < M ? cp_base(a, g, m) - u0 : 0;
     }
 
-    cp_f32x16 acc[TF][TM];
+    typename std::conditional<I8, cp_i32x16, cp_f32x16>::type acc[TF][TM];
 #pragma unroll
     for (int i = 0; i < TF; ++i)
 #pragma unroll
         for (int j = 0; j < TM; ++j)
 #pragma unroll
-            for (int k = 0; k < 16; ++k) acc[i][j][k] = 0.f;
+            for (int k = 0; k < 16; ++k) acc[i][j][k] = 0;
 
-    if (tid < BN / 2) {
+    if (I8) {
+        // int8: multiplier, shift, and the bias with the zero-point term folded in (bias - z_x * sum of the active weights)
+        if (tid < 3 * BN / 4) {
+            const int which = tid / (BN / 4), f = f0 + (tid - which * (BN / 4)) * 4;
+            int4 v = which == 1 ? make_int4(1, 1, 1, 1) : make_int4(0, 0, 0, 0);
+            if (f < a.K) {
+                v = *reinterpret_cast<const int4 *>((which == 0 ? q.qmult : which == 1 ? q.qshift : q.qbias) + f);
+                if (which == 2) {
+                    const int4 ws = *reinterpret_cast<const int4 *>(q.wsum + f);
+                    v.x -= q.zx * ws.x, v.y -= q.zx * ws.y, v.z -= q.zx * ws.z, v.w -= q.zx * ws.w;
+                }
+            }
+            reinterpret_cast<int4 *>(cp_lds + g.ss)[tid] = v;
+        }
+    } else if (tid < BN / 2) {
         const bool is_shift = tid >= BN / 4;
         const int f = f0 + (is_shift ? tid - BN / 4 : tid) * 4;
         float4 v = is_shift ? make_float4(0.f, 0.f, 0.f, 0.f) : make_float4(1.f, 1.f, 1.f, 1.f);
         if (f < a.K && (is_shift || a.scale)) v = *reinterpret_cast<const float4 *>((is_shift ? a.shift : a.scale) + f);
         reinterpret_cast<float4 *>(cp_lds + g.ss)[tid] = v;
     }
-    store_patch(0, pr[0]);
+    store_patch(0, pr[0], 0);
     store_w(0, wr[0]);
     __syncthreads();
     for (int grp = 0; grp * D < nstages; ++grp) {
@@ -239,14 +270,18 @@ __global__ __launch_bounds__(64 * NW, MINB) void conv_patch_kernel(ConvArgs a, P
                 // the LDS buffers that stage st - 1 used, so the stores run under those instructions
                 if (s == NSUB - 1 && st + 1 < nstages) {
                     store_w((st + 1) & 1, wr[dn]);
-                    if (chunk_ends) store_patch((chunk + 1) & 1, pr[dn % NPS]);
+                    if (chunk_ends) store_patch((chunk + 1) & 1, pr[dn % NPS], chunk + 1);
                 }
                 __builtin_amdgcn_sched_barrier(0);  // (the scheduler would otherwise sink the reads to their first use)
 #pragma unroll
                 for (int i = 0; i < TF; ++i)
 #pragma unroll
                     for (int j = 0; j < TM; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[s % NFS][i].v, fb[s % NFS][j].v, acc[i][j], 0, 0, 0);
+                        if constexpr (I8)
+                            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(__builtin_bit_cast(cp_i32x4, fa[s % NFS][i].u),
+                                                                                __builtin_bit_cast(cp_i32x4, fb[s % NFS][j].u), acc[i][j], 0, 0, 0);
+                        else
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[s % NFS][i].v, fb[s % NFS][j].v, acc[i][j], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
             }
             __syncthreads();
@@ -254,6 +289,68 @@ __global__ __launch_bounds__(64 * NW, MINB) void conv_patch_kernel(ConvArgs a, P
     }
 
     // ---- epilogue through this wave's own LDS region (the barrier above has released the buffers)
+    if constexpr (I8) {
+        // int8: pieces of 8 filters are 8 bytes; a lane's four filters are one 4-byte word
+        typedef __attribute__((ext_vector_type(2))) unsigned cp_u32x2;
+        const __amdgpu_buffer_rsrc_t rr8 = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<void *>(a.res ? a.res : a.y), 0, (int)((long)M * a.K), 0x00020000);
+        uint2 *const ew2 = reinterpret_cast<uint2 *>(cp_lds) + wave * (TM * 32) * ROWC;
+        const int mw0 = m0 + wave * TM * 32;
+        constexpr int EPT = TM * 32 * (BN / 8) / 64;
+        if (a.res) {
+#pragma unroll
+            for (int it = 0; it < EPT; ++it) {
+                const int idx = lane + 64 * it;
+                const int pix = idx / (BN / 8), cc = idx - pix * (BN / 8);
+                const int m = mw0 + pix, f = f0 + cc * 8;
+                const cp_u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rr8, m < M && f < a.K ? m * a.K + f : CP_OOB, 0, 0);
+                ew2[pix * ROWC + cc] = make_uint2(v[0], v[1]);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        }
+        const int4 *const ss = reinterpret_cast<const int4 *>(cp_lds + g.ss);
+        const int lo = a.act == 1 ? q.zy : -128;
+        const bool with_res = a.res != nullptr;
+#pragma unroll
+        for (int i = 0; i < TF; ++i)
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) {
+                const int fl = i * 32 + 8 * jj + 4 * kh;  // first of this lane's four filters, within the tile
+                const int4 mu = ss[fl >> 2], sh = ss[BN / 4 + (fl >> 2)], bi = ss[BN / 2 + (fl >> 2)];
+                const int mu4[4] = {mu.x, mu.y, mu.z, mu.w}, sh4[4] = {sh.x, sh.y, sh.z, sh.w}, bi4[4] = {bi.x, bi.y, bi.z, bi.w};
+#pragma unroll
+                for (int j = 0; j < TM; ++j) {
+                    unsigned *cell = reinterpret_cast<unsigned *>(ew2 + (j * 32 + l32) * ROWC) + (fl >> 2);
+                    const unsigned r = with_res ? *cell : 0u;
+                    unsigned packed = 0;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        long long t = rr64((long long)(acc[i][j][4 * jj + e] + bi4[e]) * (long long)mu4[e], sh4[e]);
+                        if (with_res) t += rr64((long long)((int)(int8_t)(r >> (8 * e)) - q.z_res) * (long long)q.m_res, q.sh_res);
+                        t += q.zy;
+                        const int v = (int)(t < lo ? lo : t > 127 ? 127 : t);
+                        packed |= (unsigned)(v & 0xFF) << (8 * e);
+                    }
+                    *cell = packed;
+                }
+            }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        const __amdgpu_buffer_rsrc_t ry8 = __builtin_amdgcn_make_buffer_rsrc(a.y, 0, (int)((long)M * a.K), 0x00020000);
+#pragma unroll
+        for (int it = 0; it < EPT; ++it) {
+            const int idx = lane + 64 * it;
+            const int pix = idx / (BN / 8), cc = idx - pix * (BN / 8);
+            const int m = mw0 + pix, f = f0 + cc * 8;
+            const uint2 v = ew2[pix * ROWC + cc];
+            __builtin_amdgcn_raw_buffer_store_b64(cp_u32x2{v.x, v.y}, ry8, m < M && f < a.K ? m * a.K + f : CP_OOB, 0, 0);
+        }
+        return;
+    }
+    if constexpr (!I8) {
     const __amdgpu_buffer_rsrc_t rr = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<void *>(a.res ? a.res : a.y), 0, (int)((long)M * a.K * 2), 0x00020000);
     uint4 *const ew = cp_lds + wave * (TM * 32) * ROWC;
@@ -334,6 +431,7 @@ __global__ __launch_bounds__(64 * NW, MINB) void conv_patch_kernel(ConvArgs a, P
         // (a store past the end of the buffer is dropped)
         __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(cp_u32x4, v), ry, m < M && f < a.K ? (m * a.K + f) * 2 : CP_OOB, 0, 0);
     }
+    }
 }
 
 // ------------------------------------------------------------------ host side
@@ -376,9 +474,9 @@ int patch_positions(const ConvArgs &a, int BM) {
     return (int)best;
 }
 
-template <int TF, int TM, int CK, int R, int MAXP, int MINB, int NW>
-hipError_t launch_patch(const ConvArgs &a, hipStream_t s) {
-    constexpr int NT = 64 * NW, BN = 32 * TF, BM = 32 * NW * TM, NKG = CK / 8, WPS = BN + 4, ROWC = BN / 8 + 1;
+template <int TF, int TM, int CK, int R, int MAXP, int MINB, int NW, bool I8 = false>
+hipError_t launch_patch(const ConvArgs &a, hipStream_t s, const QuantArgs &q = QuantArgs{}) {
+    constexpr int NT = 64 * NW, BN = 32 * TF, BM = 32 * NW * TM, NKG = CK / (I8 ? 16 : 8), WPS = BN + 4, ROWC = BN / 8 + 1;
     const int npos = patch_positions(a, BM);
     if ((long)npos * NKG > (long)MAXP * NT) return hipErrorNotSupported;
     // plane stride: congruent to 16 / NKG modulo 16 cells, so the NKG cells of a position fall into different banks
@@ -393,26 +491,26 @@ hipError_t launch_patch(const ConvArgs &a, hipStream_t s) {
     const size_t cells = std::max<size_t>(2 * (size_t)NKG * ps + 2 * (size_t)R * NKG * WPS, (size_t)BM * ROWC);
     g.ss = (int)cells;
     g.dq = make_fastdiv(a.Q), g.dp = make_fastdiv(a.P), g.dwp = make_fastdiv(g.wp), g.dhp = make_fastdiv(g.hp);
-    const size_t lds = (cells + BN / 2) * 16;
+    const size_t lds = (cells + 3 * BN / 4) * 16;
     if (lds > 160 * 1024) return hipErrorNotSupported;
     static bool attr_set = false;
-    auto kern = conv_patch_kernel<TF, TM, CK, R, MAXP, MINB, NW>;
+    auto kern = conv_patch_kernel<TF, TM, CK, R, MAXP, MINB, NW, I8>;
     if (!attr_set) {
         const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     const int per_xcd = (g.tiles_m * g.tiles_f + 7) / 8;
-    hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(NT), lds, s, a, g);
+    hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(NT), lds, s, a, g, q);
     return hipGetLastError();
 }
 
-template <int TM, int CK, int R, int MAXP, int MINB, int NW>
-hipError_t launch_patch_tf(const ConvArgs &a, int tf, hipStream_t s) {
+template <int TM, int CK, int R, int MAXP, int MINB, int NW, bool I8 = false>
+hipError_t launch_patch_tf(const ConvArgs &a, int tf, hipStream_t s, const QuantArgs &q = QuantArgs{}) {
     switch (tf) {
-        case 2: return launch_patch<2, TM, CK, R, MAXP, MINB, NW>(a, s);
-        case 3: return launch_patch<3, TM, CK, R, MAXP, MINB, NW>(a, s);
-        default: return launch_patch<4, TM, CK, R, MAXP, MINB, NW>(a, s);
+        case 2: return launch_patch<2, TM, CK, R, MAXP, MINB, NW, I8>(a, s, q);
+        case 3: return launch_patch<3, TM, CK, R, MAXP, MINB, NW, I8>(a, s, q);
+        default: return launch_patch<4, TM, CK, R, MAXP, MINB, NW, I8>(a, s, q);
     }
 }
 
@@ -444,6 +542,32 @@ hipError_t launch_conv_patch(const ConvArgs &a, hipStream_t s) {
         return launch_patch_tf<1, 32, 3, 12, 1, 4>(a, tf, s);
     }
     return launch_patch_tf<1, 64, 1, 4, 2, 4>(a, tf, s);
+}
+
+// The same for int8 codes (cells of 16 channels: chunks of 64 and 128 channels).  Returns hipErrorNotSupported
+// (nothing launched) for shapes the patch kernel does not cover.
+hipError_t launch_conv_patch_i8(const ConvArgs &a, const QuantArgs &q, hipStream_t s) {
+    if ((a.C & 7) || a.C < 8 || (a.K & 7) || a.K < 8) return hipErrorNotSupported;
+    if (!(a.R == 1 || a.R == 3) || a.pad != (a.R - 1) / 2 || a.stride < 1 || a.stride > 2) return hipErrorNotSupported;
+    if ((a.R == 1 && a.stride != 1) || a.Rmax != a.R) return hipErrorNotSupported;
+    const long M = (long)a.B * a.P * a.Q;
+    const long lim = (1l << 31) - 4096;
+    if (M * a.K >= lim || (long)a.B * a.H * a.W * a.C >= lim) return hipErrorNotSupported;
+    if ((long)a.B * (a.H + 2 * a.pad) * (a.W + 2 * a.pad) >= lim) return hipErrorNotSupported;
+    if ((long)a.R * a.R * a.CG * a.Kpad * 16 >= lim) return hipErrorNotSupported;
+    int tf = 4;
+    long waste = -1;
+    for (int t = 4; t >= 2; --t) {
+        const long w = (long)((a.K + 32 * t - 1) / (32 * t)) * 32 * t - a.K;
+        if (waste < 0 || w < waste) tf = t, waste = w;
+    }
+    if (a.R == 3) {
+        if (a.stride == 2) return launch_patch_tf<1, 64, 3, 16, 1, 4, true>(a, tf, s, q);
+        const long tiles256 = ((M + 255) / 256) * ((a.K + 32 * tf - 1) / (32 * tf));
+        if (tiles256 >= 160) return launch_patch_tf<1, 64, 3, 6, 1, 8, true>(a, tf, s, q);
+        return launch_patch_tf<1, 64, 3, 12, 1, 4, true>(a, tf, s, q);
+    }
+    return launch_patch_tf<1, 128, 1, 4, 2, 4, true>(a, tf, s, q);
 }
 
 }  // namespace sushi

@@ -98,6 +98,9 @@ __device__ __forceinline__ float ld1(const uint16_t *p) { return bf2f(*p); }
 __device__ __forceinline__ void st1(float *p, float v) { *p = v; }
 __device__ __forceinline__ void st1(uint16_t *p, float v) { *p = (uint16_t)f2bf(v); }
 
+// (v + 2^(s-1)) >> s on 64-bit integers, arithmetic shift, 1 <= s <= 62: the rounding shift of the int8 path
+__device__ __forceinline__ long long rr64(long long v, int s) { return (v + (1ll << (s - 1))) >> s; }
+
 __device__ __forceinline__ float activate(float v, int act, int hsig) {
     if (hsig) return fminf(fmaxf(v + 3.0f, 0.0f), 6.0f) / 6.0f;
     if (act == 1) return fmaxf(v, 0.0f);

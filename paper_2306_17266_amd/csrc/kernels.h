@@ -95,7 +95,8 @@ hipError_t launch_dwconv_rows(const ConvArgs &a, hipStream_t s);
 
 // int8 mode (int8.hip): dense conv 1x1 / 3x3 on the int8 matrix cores (3 input channels: vector ALUs) with integer
 // requantisation, 3x3/2 max-pool on codes, exact int32 pooled sums, int64 classifier with float32 logits.
-hipError_t launch_conv_i8(const ConvArgs &a, const QuantArgs &q, hipStream_t s);
+hipError_t launch_conv_i8(const ConvArgs &a, const QuantArgs &q, hipStream_t s, long patch_min_pixels);
+hipError_t launch_conv_patch_i8(const ConvArgs &a, const QuantArgs &q, hipStream_t s);  // conv_patch.hip
 hipError_t launch_fc_i8(const ConvArgs &a, const QuantArgs &q, hipStream_t s);
 hipError_t launch_maxpool_i8(const PoolArgs &a, hipStream_t s);
 hipError_t launch_gap_i8(const PoolArgs &a, const QuantArgs &q, hipStream_t s);

@@ -445,7 +445,7 @@ hipError_t issue_launches(sushi_ctx *c, CachedPlan &cp, const void *input_dev, v
                 case OP_CONV:
                     if (L.in_patch) a.x = input_dev;
                     kc = KC_CONV_I8;
-                    e = launch_conv_i8(a, L.quant, st);
+                    e = launch_conv_i8(a, L.quant, st, c->patch_min_pixels);
                     break;
                 case OP_FC:
                     if (L.out_patch) a.y = logits_dev;

@@ -44,6 +44,7 @@ def main():
     ap.add_argument("--reps", type=int, default=20)
     ap.add_argument("--patch-min-pixels", type=int, default=-1,
                     help="SUSHI_OPT_PATCH_CONV_MIN_PIXELS (0 = never use the patch conv kernel; default: the library's)")
+    ap.add_argument("--int8", action="store_true", help="the int8 path (ResNet50-shaped and Tiny SuperNets)")
     ap.add_argument("--plain", action="store_true", help="run the queries without events and print nothing (profiler run)")
     ap.add_argument("--from-trace", default="", help="kernel-trace CSV of a --plain run under rocprofv3")
     args = ap.parse_args()
@@ -59,10 +60,18 @@ def main():
         return report_from_trace(args, arch, cfg, batch)
     table = S.sushi_describe_supernet(arch)
     ctx = S.Sushi(0)
-    ctx.sushi_load_supernet(arch, T.flatten(T.make_weights([(s, k) for _, s, k in table], 1, True)), S.BF16)
+    if args.int8:
+        from workloads import quant
+        tens = T.make_weights([(s, k) for _, s, k in table], 1, False)
+        ctx.sushi_load_supernet_int8(arch, *quant.flatten_int8(quant.make_int8_model(table, tens, quant.layer_roles(arch))))
+    else:
+        ctx.sushi_load_supernet(arch, T.flatten(T.make_weights([(s, k) for _, s, k in table], 1, True)), S.BF16)
     if args.patch_min_pixels >= 0:
         ctx.sushi_set_option(S.OPT_PATCH_CONV_MIN_PIXELS, args.patch_min_pixels)
-    x = torch.from_numpy(T.make_input(11, 0, batch, cfg.resolution, arch.in_channels, True)).cuda().to(torch.bfloat16)
+    if args.int8:
+        x = torch.from_numpy(quant.quantize_input(T.make_input(11, 0, batch, cfg.resolution, arch.in_channels, False))).cuda()
+    else:
+        x = torch.from_numpy(T.make_input(11, 0, batch, cfg.resolution, arch.in_channels, True)).cuda().to(torch.bfloat16)
     y = torch.empty(batch, arch.n_classes, device="cuda", dtype=torch.float32)
     for _ in range(5):
         ctx.sushi_infer(cfg, x, y)
@@ -109,7 +118,8 @@ def report_from_trace(args, arch, cfg, batch):
 
     import paper_2306_17266_amd as S
     ops = S.sushi_team_plan(arch, cfg, batch, 32)
-    mine = ("conv_direct_kernel", "conv_mfma_kernel", "conv_mfma_splitk_kernel", "conv_patch_kernel", "dwconv_kernel",
+    mine = ("conv_i8_kernel", "conv_i8_direct_kernel", "maxpool_i8_kernel", "gap_i8_kernel", "fc_i8_kernel",
+            "conv_direct_kernel", "conv_mfma_kernel", "conv_mfma_splitk_kernel", "conv_patch_kernel", "dwconv_kernel",
             "dwconv_rows_kernel", "maxpool_kernel", "gap_kernel", "gate_kernel")
     rows = []
     for r in csv.DictReader(open(args.from_trace)):
@@ -125,7 +135,7 @@ def report_from_trace(args, arch, cfg, batch):
     per_op = {}
     for k, (_, ms, short) in enumerate(rows):
         i = k % n_ops
-        byts, flops = op_cost(ops[i])
+        byts, flops = op_cost(ops[i], 1.0 if args.int8 else 2.0)
         per_op.setdefault(i, []).append((ms, short, byts, flops))
     print_report(args, cfg, batch, ops, per_op, "rocprofv3 kernel trace")
 
@@ -134,7 +144,9 @@ def print_report(args, cfg, batch, ops, per_op, clock):
     names = None
     print("# %s, SubNet %s, batch %d, resolution %d, exec mode 0, median of %d launches per op; durations: %s" %
           (args.workload, args.subnet, batch, cfg.resolution, args.reps, clock))
-    print("# peaks: HBM %.0f GB/s, dense bf16 MFMA %.0f TFLOP/s; bound = max(flops / peak, bytes / peak)" % (HBM_GBS, MFMA_TFLOPS))
+    mfma_peak = 5000.0 if getattr(args, "int8", False) else MFMA_TFLOPS
+    print("# peaks: HBM %.0f GB/s, dense %s MFMA %.0f T%sOP/s; bound = max(flops / peak, bytes / peak)" %
+          (HBM_GBS, "int8" if mfma_peak > MFMA_TFLOPS else "bf16", mfma_peak, "" if mfma_peak > MFMA_TFLOPS else "FL"))
     print("%3s %-7s %-26s %-24s %9s %9s %9s %9s %8s %5s %6s" %
           ("op", "kind", "shape BxHxWxC->PxQxK rxr/s", "kernel", "us", "MB", "GFLOP", "GB/s", "TFLOP/s", "bound", "frac"))
     tot_us = tot_bound = 0.0
@@ -144,7 +156,7 @@ def print_report(args, cfg, batch, ops, per_op, clock):
         _, kname, byts, flops = per_op[i][0]
         op = ops[i]
         us = ms * 1e3
-        t_mem, t_mma = byts / (HBM_GBS * 1e3), flops / (MFMA_TFLOPS * 1e6)      # microseconds
+        t_mem, t_mma = byts / (HBM_GBS * 1e3), flops / (mfma_peak * 1e6)      # microseconds
         bound_us = max(t_mem, t_mma)
         which = "mfma" if t_mma > t_mem else "hbm"
         shape = "%dx%dx%dx%d->%dx%dx%d %dx%d/%d" % (op["B"], op["H"], op["W"], op["C"], op["P"], op["Q"], op["K"],
