@@ -93,3 +93,29 @@ def test_int8_rejects_what_it_does_not_cover():
         ctx.sushi_infer(A.max_cfg(arch), x, y)
     assert e.value.code == -3
     ctx.close()
+
+
+def test_int8_static_entry_point_and_subgraph_accounting():
+    """sushi_infer_static runs the int8 path too (same launches, activations in the static array), and the SubGraph
+    accounting counts one byte per weight."""
+    arch = A.small_resnet_arch()
+    ctx, qm = _problem(arch, 41)
+    st = Stream(43)
+    cfgs = [streams.uniform_cfg(arch, st, 64) for _ in range(3)]
+    box = E.subnet_box(arch, A.min_cfg(arch, 64))
+    ctx.sushi_set_subgraph_cache(box, 1 << 30)
+    for t, cfg in enumerate(cfgs):
+        xq = quant.quantize_input(T.make_input(41, t, 2, 64, 3, False))
+        x = torch.from_numpy(xq).cuda()
+        a = torch.empty(2, arch.n_classes, device="cuda", dtype=torch.float32)
+        b = torch.empty_like(a)
+        ctx.sushi_infer(cfg, x, a)
+        stats = ctx.sushi_get_stats()
+        sn = E.subnet_box(arch, cfg)
+        assert stats["last_weight_bytes"] == E.weight_count(sn)
+        assert stats["last_in_subgraph_bytes"] == E.weight_count(E.intersect(sn, box))
+        ctx.sushi_infer_static(cfg, x, b)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(a.cpu().numpy(), b.cpu().numpy())
+        np.testing.assert_array_equal(a.cpu().numpy(), Q.forward_int8(arch, qm, cfg, np.ascontiguousarray(xq.transpose(0, 3, 1, 2))))
+    ctx.close()
