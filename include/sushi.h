@@ -204,7 +204,10 @@ int sushi_subgraph_overlap(const sushi_layer_dims *subnet, const sushi_layer_dim
 
 /* How exec mode 3 cuts one op of a SubNet's per-query plan (Section 3.1: a query activates one SubNet; Section 4.2:
  * its layers run one after the other) into units for a team of workgroups.  kind: 0 dense conv, 1 depthwise conv,
- * 2 max-pool, 3 global average pool, 4 fully connected, 5 channel gate.  layer: SuperNet layer (order of
+ * 2 max-pool, 3 global average pool, 4 fully connected, 5 channel gate; 6 a whole squeeze-excite block (pooling, two
+ * fully connected layers, gating: the team kernel runs the four ops as one, without barriers between them; H, W, C
+ * describe the gated map, K the width between the two FC layers), 7 the slot of an op that the kind-6 op before it
+ * has done (skipped; the list keeps one entry per op of the plan).  layer: SuperNet layer (order of
  * sushi_subnet_layers) or -1.  wk selects the unit variant (> 0: split units, that many waves per unit; 0: tiled units;
  * -1: stem units; -2 depthwise through LDS; -3 tiled units with resident weights; -4 depthwise from memory), ft / pt its
  * tile shape, n_units / n_p the unit counts, lds_bytes what the variant takes of the 32 KiB LDS scratch. */

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(CSRC, "_build")
 LIB = os.path.join(HERE, "libsushi.so")
-SOURCES = ["kernels.hip", "dwconv.hip", "conv_patch.hip", "int8.hip", "stream_kernel.hip", "model.cpp", "sched.cpp", "sushi_api.cpp"]
+SOURCES = ["kernels.hip", "dwconv.hip", "conv_patch.hip", "int8.hip", "stream_kernel.hip", "team_kernel_mobile.hip", "model.cpp", "sched.cpp", "sushi_api.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 

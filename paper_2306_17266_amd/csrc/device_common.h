@@ -102,9 +102,9 @@ __device__ __forceinline__ void st1(uint16_t *p, float v) { *p = (uint16_t)f2bf(
 __device__ __forceinline__ long long rr64(long long v, int s) { return (v + (1ll << (s - 1))) >> s; }
 
 __device__ __forceinline__ float activate(float v, int act, int hsig) {
-    if (hsig) return fminf(fmaxf(v + 3.0f, 0.0f), 6.0f) / 6.0f;
+    if (hsig) return fminf(fmaxf(v + 3.0f, 0.0f), 6.0f) * (1.0f / 6.0f);
     if (act == 1) return fmaxf(v, 0.0f);
-    if (act == 2) return v * fminf(fmaxf(v + 3.0f, 0.0f), 6.0f) / 6.0f;
+    if (act == 2) return v * fminf(fmaxf(v + 3.0f, 0.0f), 6.0f) * (1.0f / 6.0f);
     return v;
 }
 

@@ -113,7 +113,7 @@ __global__ __launch_bounds__(256) void dwconv_rows_kernel(ConvArgs a) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             const float t = acc[k][e] * sc[e] + sh[e];
-            acc[k][e] = ACT == 1 ? fmaxf(t, 0.0f) : ACT == 2 ? t * fminf(fmaxf(t + 3.0f, 0.0f), 6.0f) / 6.0f : t;
+            acc[k][e] = ACT == 1 ? fmaxf(t, 0.0f) : ACT == 2 ? t * fminf(fmaxf(t + 3.0f, 0.0f), 6.0f) * (1.0f / 6.0f) : t;
         }
         const int p = VERT ? u : v, q = VERT ? v : u;
         store8(y + (((long)n * a.P + p) * a.Q + q) * a.K + c, acc[k]);

@@ -412,11 +412,16 @@ int plan_subnet(const SuperNet &sn, const sushi_subnet_cfg &c, int B, Plan &plan
                     w.gap(d, dH, dW, cmid, 0);
                     w.fc(0, cmid, red, SUSHI_ACT_RELU, 1, true, false);
                     w.fc(1, red, cmid, SUSHI_ACT_NONE, 2, true, true, true);
+                    // The gated map goes to a buffer of its own (the expanded map's, free again): workgroups that
+                    // still average d never see gated values, so pooling, both FC layers and the gating can run as
+                    // one op without a barrier between them.
                     Op g;
                     g.kind = OP_GATE;
                     g.B = B, g.H = dH, g.W = dW, g.C = cmid, g.K = cmid, g.P = dH, g.Q = dW;
-                    g.in_buf = d, g.out_buf = d, g.gate_buf = 2;
+                    g.in_buf = d, g.out_buf = w.bufs.get(), g.gate_buf = 2;
                     plan.ops.push_back(g);
+                    w.bufs.put(d);
+                    d = g.out_buf;
                 }
                 const bool skip = stride == 1 && C == cout;
                 int oH = dH, oW = dW;
@@ -432,7 +437,7 @@ int plan_subnet(const SuperNet &sn, const sushi_subnet_cfg &c, int B, Plan &plan
         w.fc(1, a.head_feat, a.n_classes, SUSHI_ACT_NONE, BUF_LOGITS, false, true);
     }
     for (const Op &op : plan.ops)
-        if ((op.kind == OP_CONV || op.kind == OP_DW || op.kind == OP_MAXPOOL) && op.out_buf < 0) {
+        if ((op.kind == OP_CONV || op.kind == OP_DW || op.kind == OP_MAXPOOL || op.kind == OP_GATE) && op.out_buf < 0) {
             err = "internal: out of activation buffers";
             return SUSHI_EINVAL;
         }

@@ -11,7 +11,11 @@
 
 #include <hip/hip_runtime.h>
 
+#include <cstddef>
+#include <vector>
+
 #include "kernels.h"
+#include "model.h"
 
 namespace sushi {
 
@@ -20,8 +24,30 @@ constexpr int STREAM_WAVES = STREAM_THREADS / 64;
 constexpr int BARRIER_GROUP = 16;    // workgroups per first-level barrier group
 constexpr int SYNC_WORDS = 256 * 16;  // 64-bit words in the barrier area (128-byte spacing)
 
+// A whole squeeze-excite block as one op of a team program (DEV_SE): average over the pixels, the two FC layers
+// (activation `act1` after the first, hard sigmoid after the second), and the map times the resulting gate.
+// Every vector between the steps stays in LDS as float32.
+struct SeArgs {
+    const void *x;            // [B][C / 8][HW][8] bf16, the map to gate (read only)
+    void *y;                  // gated map, same shape, another buffer
+    const void *reserved;     // null (x, y and this word lie where ConvArgs has x, y, res: the team kernel turns
+                              // those three from arena offsets into addresses for every kind of op)
+    const void *w1, *w2;      // packed weights of the FC layers: [channel group of 8][filter < Kpad][8]
+    const float *sc1, *sh1;   // per filter of FC 1 (sc1 may be null = 1)
+    const float *sc2, *sh2;   // per filter of FC 2 (sc2 may be null = 1)
+    int B, HW, C, mid;        // images, pixels per image, channels of the map, filters of FC 1
+    int Kpad1, Kpad2;         // padded filter counts of the two weight tensors
+    int act1;                 // sushi_act after FC 1
+    int pad;
+};
+constexpr int SE_MAX_C = 1024, SE_MAX_MID = 256;  // what the op's LDS layout has room for
+
+// Kinds of a team program beyond OpKind (model.h): a fused squeeze-excite block, and the slots of the ops it
+// replaced (skipped without a barrier, so a program keeps one slot per op of the plan).
+constexpr int DEV_SE = 6, DEV_NONE = 7;
+
 struct DevOp {
-    int kind;      // OpKind (model.h)
+    int kind;      // OpKind (model.h), DEV_SE or DEV_NONE
     int pt, wk;    // dense conv: pixel tiles per unit (1, 2, 4) and waves sharing one unit (1, 2, 4, 8);
                    // wk = 0: tiled units (ft x pt tiles per wave); wk = -1: stem units (pt output rows per band); wk = -2: depthwise through LDS; wk = -3: tiled units with the weights held in LDS; wk = -4: depthwise straight from memory, neighbouring outputs per thread
     int n_units;   // dense conv: filter groups x pixel groups
@@ -31,9 +57,15 @@ struct DevOp {
     int relative;  // activation pointers hold (offset into the team's arena) + 1
     int layer;     // SuperNet layer of a conv / FC op, -1 otherwise
     int ft;        // dense conv: filter tiles per unit (1, 2, 4); ft * pt <= 4
-    ConvArgs conv;
+    union {
+        ConvArgs conv;
+        SeArgs se;  // kind == DEV_SE
+    };
     PoolArgs pool;
 };
+static_assert(sizeof(SeArgs) <= sizeof(ConvArgs) && offsetof(SeArgs, x) == offsetof(ConvArgs, x) &&
+                  offsetof(SeArgs, y) == offsetof(ConvArgs, y) && offsetof(SeArgs, reserved) == offsetof(ConvArgs, res),
+              "the squeeze-excite arguments share the conv arguments' words, activation pointers in the same places");
 
 struct StreamArgs {
     const DevOp *prog;  // DEVICE
@@ -149,11 +181,17 @@ constexpr long TEAM_TABLE_BYTES = 64 + (long)RES_MAX_LAYERS * sizeof(ResLayer) +
 constexpr long TEAM_MEM_BYTES = TEAM_TABLE_OFFSET + TEAM_TABLE_BYTES + (long)RES_MAX_ENTRIES * 4;
 static_assert(sizeof(DevOp) % 8 == 0, "programs are copied in 8-byte words");
 
+// Two team kernels: one for networks without depthwise layers (dense convs, max-pool, pooling, FC) and one for the
+// inverted-residual families (depthwise, gating and squeeze-excite ops instead of the max-pool).  A kernel has one
+// register allocation for all the units in it, so each holds only the units its networks use.
 hipError_t launch_team_kernel(const TeamArgs &a, int nwg, hipStream_t s);
+hipError_t launch_team_kernel_mobile(const TeamArgs &a, int nwg, hipStream_t s);
 // Sets the kernel's dynamic LDS limit; call once per device before the first launch.
 hipError_t prepare_team_kernel();
+hipError_t prepare_team_kernel_mobile();
 // Workgroups of the team kernel that fit on one compute unit at the same time.
 hipError_t team_kernel_blocks_per_cu(int *n);
+hipError_t team_kernel_mobile_blocks_per_cu(int *n);
 
 // The matrix-core paths of both kernels keep one table entry per reduction step (tap x 32 channels)
 // of the running op in LDS and one bit per tap in a 32-bit mask.
@@ -173,6 +211,11 @@ bool tile_stem_op(DevOp &op, int nwg);
 // A depthwise conv: sets wk = -2, the channel groups per unit in ft and the band height in pt if the layer fits
 // the LDS-staged path, else leaves the op alone and returns false.
 bool tile_dw_op(DevOp &op, int nwg);
+
+// Team programs: turns every squeeze-excite block of the plan whose dimensions fit (pooling, FC, FC, gating in
+// four consecutive slots, the gated map in a buffer of its own) into one DEV_SE op in the first slot and DEV_NONE
+// in the other three.  `prog` has one op per op of `plan`.  Returns the number of blocks fused.
+int fuse_se_blocks(std::vector<DevOp> &prog, const Plan &plan);
 
 // Number of grid barriers the kernel executes for a program of n_ops ops.
 inline int stream_barriers(int n_ops) { return n_ops > 0 ? n_ops - 1 : 0; }

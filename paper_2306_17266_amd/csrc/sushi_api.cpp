@@ -869,7 +869,9 @@ int launch_teams(sushi_ctx *c) {
             return hip_fail(c, e, "kernel timing");
         tp.kc = KC_TEAM;
     }
-    if ((e = launch_team_kernel(ta, c->team_wgs, c->pstream)) != hipSuccess) return hip_fail(c, e, "team kernel launch");
+    const bool mobile = c->sn.arch.family == SUSHI_FAMILY_MBV3;  // (a load of another SuperNet stops the kernel first)
+    e = mobile ? launch_team_kernel_mobile(ta, c->team_wgs, c->pstream) : launch_team_kernel(ta, c->team_wgs, c->pstream);
+    if (e != hipSuccess) return hip_fail(c, e, "team kernel launch");
     if (c->timing) {
         if ((e = hipEventRecord(c->team_pending.b, c->pstream)) != hipSuccess) return hip_fail(c, e, "kernel timing");
         c->team_timed = true;
@@ -890,10 +892,13 @@ int ensure_team_state(sushi_ctx *c, int batch) {
     if (!c->th) {
         hipDeviceProp_t prop;
         if ((e = hipGetDeviceProperties(&prop, c->device)) != hipSuccess) return hip_fail(c, e, "hipGetDeviceProperties");
-        if ((e = prepare_team_kernel()) != hipSuccess) return hip_fail(c, e, "hipFuncSetAttribute");
+        if ((e = prepare_team_kernel()) != hipSuccess || (e = prepare_team_kernel_mobile()) != hipSuccess)
+            return hip_fail(c, e, "hipFuncSetAttribute");
         // every workgroup must be resident at once (they wait for each other)
-        int fit = 0;
-        if ((e = team_kernel_blocks_per_cu(&fit)) != hipSuccess) return hip_fail(c, e, "occupancy query");
+        int fit = 0, fit_mobile = 0;
+        if ((e = team_kernel_blocks_per_cu(&fit)) != hipSuccess || (e = team_kernel_mobile_blocks_per_cu(&fit_mobile)) != hipSuccess)
+            return hip_fail(c, e, "occupancy query");
+        fit = std::min(fit, fit_mobile);
         const int per_cu = std::max(1, std::min(c->team_wgs_per_cu, fit));
         c->team_wgs = per_cu * std::max(BARRIER_GROUP, prop.multiProcessorCount / BARRIER_GROUP * BARRIER_GROUP);
         if ((e = hipHostMalloc(reinterpret_cast<void **>(&c->th), sizeof(TeamHostState), hipHostMallocDefault)) != hipSuccess)
@@ -1047,6 +1052,7 @@ int post_team_query(sushi_ctx *c, CachedPlan &cp, const void *input_dev, void *l
             prog.push_back(op);
         }
         if (prog.size() > (size_t)TEAM_PROG_MAX_OPS) return fail(c, SUSHI_ESTATE, "the SubNet has too many ops for the team kernel");
+        fuse_se_blocks(prog, cp.plan);
         cp.team_prog = prog;
         cp.table_version = ~0ull;
         const size_t bytes = round_up(prog.size() * sizeof(DevOp), 256);
@@ -1225,6 +1231,7 @@ int sushi_team_plan(const sushi_arch *arch, const sushi_subnet_cfg *cfg, int bat
     rc = plan_subnet(sn, *cfg, batch, plan, err);
     if (rc) return rc;
     *n_out = (int)plan.ops.size();
+    std::vector<DevOp> prog;
     for (int i = 0; i < *n_out; ++i) {
         const Op &o = plan.ops[i];
         DevOp op{};
@@ -1243,14 +1250,20 @@ int sushi_team_plan(const sushi_arch *arch, const sushi_subnet_cfg *cfg, int bat
             a.res = o.res_buf >= 0 ? &op : nullptr;  // (only whether there is one matters to the tiling)
         }
         if (!tile_team_op(op, team_wgs)) return SUSHI_ESTATE;
-        if (i < cap) {
-            sushi_team_op &t = out[i];
-            t.kind = o.kind, t.layer = op.layer;
-            t.B = o.B, t.H = o.H, t.W = o.W, t.C = o.C, t.P = o.P, t.Q = o.Q, t.K = o.K, t.R = o.r, t.stride = o.stride;
-            t.ft = op.ft, t.pt = op.pt, t.wk = op.wk, t.n_units = op.n_units, t.n_p = op.n_p;
-            t.lds_bytes = (int32_t)dev_op_lds_bytes(op);
-            t.res = o.res_buf >= 0 ? 1 : 0, t.out_f32 = o.out_f32 ? 1 : 0;
-        }
+        op.conv.res = nullptr;
+        prog.push_back(op);
+    }
+    fuse_se_blocks(prog, plan);
+    for (int i = 0; i < *n_out && i < cap; ++i) {
+        const Op &o = plan.ops[i];
+        const DevOp &op = prog[i];
+        sushi_team_op &t = out[i];
+        t.kind = op.kind, t.layer = op.layer;
+        t.B = o.B, t.H = o.H, t.W = o.W, t.C = o.C, t.P = o.P, t.Q = o.Q, t.K = o.K, t.R = o.r, t.stride = o.stride;
+        t.ft = op.ft, t.pt = op.pt, t.wk = op.wk, t.n_units = op.n_units, t.n_p = op.n_p;
+        t.lds_bytes = (int32_t)dev_op_lds_bytes(op);
+        t.res = o.res_buf >= 0 ? 1 : 0, t.out_f32 = o.out_f32 ? 1 : 0;
+        if (op.kind == DEV_SE) t.P = o.H, t.Q = o.W, t.K = op.se.mid, t.out_f32 = 0;  // (o is the block's pooling op)
     }
     return SUSHI_OK;
 }

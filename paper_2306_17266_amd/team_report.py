@@ -18,7 +18,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_GBS, MFMA_TFLOPS = 8000.0, 2500.0
-KIND = {0: "conv", 1: "dwconv", 2: "maxpool", 3: "gap", 4: "fc", 5: "gate"}
+KIND = {0: "conv", 1: "dwconv", 2: "maxpool", 3: "gap", 4: "fc", 5: "gate", 6: "se", 7: "(fused)"}
 
 
 def main():
@@ -79,7 +79,13 @@ def main():
     by_kind = {}
     for i in range(n_ops):
         op = ops[i]
-        byts, flops = op_cost(op)
+        if op["kind"] == 7:      # done by the squeeze-excite op before it
+            continue
+        if op["kind"] == 6:      # map in and out, both FC layers' weights; flops of the FC layers
+            cells, w = op["B"] * op["H"] * op["W"] * op["C"], 2 * op["C"] * op["K"]
+            byts, flops = 2.0 * (2 * cells + w), 2.0 * op["B"] * w
+        else:
+            byts, flops = op_cost(op)
         t_mem, t_mma = byts / (HBM_GBS * 1e3 / n_teams), flops / (MFMA_TFLOPS * 1e6 / n_teams)
         bound = max(t_mem, t_mma)
         tot_bound += bound

@@ -187,6 +187,14 @@ def _check_team_op(op, team):
     ptiles, ftiles = _ceil(M, 16), _ceil(op["K"], 16)
     nsteps = op["R"] * op["R"] * _ceil(op["C"], 32)
     assert 0 <= op["lds_bytes"] <= LDS_SCRATCH, op
+    if kind == 6:                                             # a squeeze-excite block as one op
+        # pooling partials [64 channel groups][8 pixel lanes * 8 + 8] floats, then the averages, the hidden vector, the gate
+        assert op["C"] % 8 == 0 and op["C"] <= 1024 and op["K"] % 8 == 0 and op["K"] <= 256, op
+        assert op["lds_bytes"] == (64 * 72 + 1024 + 256 + 1024) * 4, op
+        return
+    if kind == 7:
+        assert op["lds_bytes"] == 0, op
+        return
     if kind in (0, 4) and op["C"] % 8 == 0:                   # dense conv / FC on the matrix cores
         assert op["R"] * op["R"] <= 32 and nsteps + 1 <= 256, op
         if wk == 0:
@@ -241,6 +249,13 @@ def test_team_tilings_fit_the_kernels(mk, team):
                 _check_team_op(op, team)
                 seen.add((op["kind"], op["wk"]))
     assert any(k in (0, 4) and w > 0 for k, w in seen)        # few-pixel layers use split units
+    if mk in (A.small_mbv3_arch, A.mbv3_arch):                # every squeeze-excite block is one op plus three skipped slots
+        kinds = [op["kind"] for op in S.sushi_team_plan(arch, cfgs[1], 1, team)]
+        assert 6 in kinds and 5 not in kinds
+        for i, k in enumerate(kinds):
+            if k == 6:
+                assert kinds[i + 1:i + 4] == [7, 7, 7]
+        assert kinds.count(7) == 3 * kinds.count(6)
     if mk in (A.resnet_arch, A.mbv3_arch):
         assert (0, 0) in seen                                 # many-pixel layers use tiled units
 
