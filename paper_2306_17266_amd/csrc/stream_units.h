@@ -2041,30 +2041,35 @@ __device__ void install_slabs(const ResTable *tab, unsigned *present, int rank, 
     }
     __syncthreads();
     const int total = cnt[1];
-    constexpr int BATCH = 8;
-    for (int p0 = tid; p0 < total; p0 += BATCH * STREAM_THREADS) {
-        uint4 v[BATCH];
-        int dst[BATCH];
-#pragma unroll
-        for (int u = 0; u < BATCH; ++u) {
-            const int p = min(p0 + u * STREAM_THREADS, total - 1);
-            int lo = 0, hi = n - 1;  // the last item that starts at or before piece p
-            while (lo < hi) {
-                const int mid = (lo + hi + 1) >> 1;
-                if (items[mid].first_piece <= p) lo = mid; else hi = mid - 1;
-            }
-            const InstallItem it = items[lo];
-            const ResLayer &L = lay[it.layer_f >> 16];
-            const int f = it.layer_f & 0xFFFF, i = p - it.first_piece;
-            const int j = i & 15, tc = i >> 4;
-            const int ncg = L.cg_res - it.cg_from;
-            const int tap = tc / ncg, cg = it.cg_from + (tc - tap * ncg);
-            v[u] = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(L.w) + (((long)tap * L.CG + cg) * L.Kpad + f * 16 + j) * 8);
-            dst[u] = it.lds_off + ((tap * L.cg_stride + cg) * 16 + j) * 16;
+    // (eight pieces in flight per thread, in named registers: arrays indexed inside the search loop would live in
+    // scratch memory)
+    auto fetch = [&](int p, uint4 &v, int &dst) {
+        int lo = 0, hi = n - 1;  // the last item that starts at or before piece p
+        while (lo < hi) {
+            const int mid = (lo + hi + 1) >> 1;
+            if (items[mid].first_piece <= p) lo = mid; else hi = mid - 1;
         }
-#pragma unroll
-        for (int u = 0; u < BATCH; ++u)
-            if (p0 + u * STREAM_THREADS < total) *reinterpret_cast<uint4 *>(store + dst[u]) = v[u];
+        const InstallItem it = items[lo];
+        const ResLayer &L = lay[it.layer_f >> 16];
+        const int f = it.layer_f & 0xFFFF, i = p - it.first_piece;
+        const int j = i & 15, tc = i >> 4;
+        const int ncg = L.cg_res - it.cg_from;
+        const int tap = tc / ncg, cg = it.cg_from + (tc - tap * ncg);
+        v = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(L.w) + (((long)tap * L.CG + cg) * L.Kpad + f * 16 + j) * 8);
+        dst = it.lds_off + ((tap * L.cg_stride + cg) * 16 + j) * 16;
+    };
+    for (int p0 = tid; p0 < total; p0 += 8 * STREAM_THREADS) {
+        uint4 v0, v1, v2, v3, v4, v5, v6, v7;
+        int d0, d1, d2, d3, d4, d5, d6, d7;
+        const int last = total - 1, T = STREAM_THREADS;
+        fetch(min(p0, last), v0, d0), fetch(min(p0 + T, last), v1, d1), fetch(min(p0 + 2 * T, last), v2, d2);
+        fetch(min(p0 + 3 * T, last), v3, d3), fetch(min(p0 + 4 * T, last), v4, d4), fetch(min(p0 + 5 * T, last), v5, d5);
+        fetch(min(p0 + 6 * T, last), v6, d6), fetch(min(p0 + 7 * T, last), v7, d7);
+        auto put = [&](int p, const uint4 &v, int dst) {
+            if (p < total) *reinterpret_cast<uint4 *>(store + dst) = v;
+        };
+        put(p0, v0, d0), put(p0 + T, v1, d1), put(p0 + 2 * T, v2, d2), put(p0 + 3 * T, v3, d3);
+        put(p0 + 4 * T, v4, d4), put(p0 + 5 * T, v5, d5), put(p0 + 6 * T, v6, d6), put(p0 + 7 * T, v7, d7);
     }
     __syncthreads();
 }
