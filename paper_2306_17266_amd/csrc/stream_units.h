@@ -1641,8 +1641,9 @@ constexpr int SE_PART = 4608;  // floats: pooling partials [<= 64 channel groups
 static_assert((SE_PART + 2 * SE_MAX_C + SE_MAX_MID) * 4 <= RED_BYTES && SE_PART >= 64 * 72 && SE_PART >= 32 * 136 &&
                   SE_PART >= 16 * 264 && SE_PART >= 8 * 520 && SE_PART >= STREAM_THREADS,
               "the squeeze-excite op's vectors fit the scratch part of LDS");
-// (a function of its own, not inlined: inside the kernel's body its registers would count against those of the
-// convolution units)
+// (a function of its own, not inlined: inside the kernel's body its registers count against those of the other
+// units, which then run slower; and with 16 or more cells in flight per thread the function needs so many registers
+// that the whole kernel slows down by almost half, measured, so SE_BATCH stays at 8)
 template <int LD, int ST>
 __device__ __attribute__((noinline)) void se_units(const SeArgs a, float *lds, int rank, int nranks) {
     const int t = threadIdx.x;

@@ -119,6 +119,33 @@ def test_team_kernel_small_supernets(fam, teams):
     ctx.close()
 
 
+@pytest.mark.parametrize("teams,batch", [(8, 5), (8, 16), (2, 2), (1, 16)])
+def test_team_kernel_squeeze_excite_blocks_at_every_batch_to_team_ratio(teams, batch):
+    """A squeeze-excite block runs as one op in which the images are dealt to groups of a team's workgroups: more images
+    than workgroups (each workgroup takes several images on its own), fewer (several workgroups share an image's
+    gating), and uneven groups.  Logits against the oracle, query by query, and reproducible bit for bit."""
+    arch = A.small_mbv3_arch()
+    ctx, wts = _team_ctx(arch, 7, teams)
+    st = Stream(83)
+    res = min(arch.res_choices)
+    cfgs = [A.max_cfg(arch, res), A.min_cfg(arch, res)] + [streams.uniform_cfg(arch, st, res) for _ in range(4)]
+    xs_np = [T.make_input(7, t, batch, res, 3, True) for t in range(len(cfgs))]
+    xs = [torch.from_numpy(x).cuda().to(torch.bfloat16).contiguous() for x in xs_np]
+    torch.cuda.synchronize()
+    results = []
+    for rep in range(2):
+        outs = [torch.full((batch, arch.n_classes), float("nan"), device="cuda") for _ in cfgs]
+        print("teams", teams, "batch", batch, "pass", rep, flush=True)
+        for cfg, x, o in zip(cfgs, xs, outs):
+            ctx.sushi_infer(cfg, x, o)
+        ctx.sushi_synchronize()
+        results.append([o.cpu().numpy() for o in outs])
+    for t, cfg in enumerate(cfgs):
+        np.testing.assert_array_equal(results[0][t], results[1][t])
+        assert rel_l2(results[0][t], oracle_logits(arch, wts, cfg, xs_np[t])) <= 1e-2, (t, cfg)
+    ctx.close()
+
+
 @pytest.mark.parametrize("fam,teams", [("resnet", 1), ("mbv3", 1), ("resnet", 4), ("mbv3", 2), ("resnet", 8), ("mbv3", 8)])
 def test_team_kernel_full_size_batch1(fam, teams):
     arch = A.resnet_arch() if fam == "resnet" else A.mbv3_arch()
