@@ -71,8 +71,8 @@ def main():
     ap.add_argument("--exec-mode", type=int, default=-1,
                     help="0 = launch per layer, 1 = HIP graph replay, 2 = stream kernel, 3 = persistent XCD-team kernel "
                          "(default: 3 for bf16, 0 for int8)")
-    ap.add_argument("--teams-per-xcd", type=int, default=0, choices=[0, 1, 2, 4, 8],
-                    help="mode 3: teams per XCD (default 8 at batch 1, 1 at batch 16)")
+    ap.add_argument("--teams-per-xcd", type=int, default=0, choices=[0, 1, 2, 4, 8, 16],
+                    help="mode 3: teams per XCD (default 16 at batch 1, 1 at batch 16)")
     ap.add_argument("--sgs", choices=["sched", "fixed", "off"], default="sched",
                     help="sched = the scheduler re-chooses the cached SubGraph every Q queries; fixed = the smallest "
                          "SubNet of the stream, shrunk to the budget, is cached once and kept (the state-unaware "
@@ -105,7 +105,7 @@ def main():
     wl = configs.build(args.workload, args.budget_mib or None)
     arch, batch, Q, budget = wl["arch"], wl["batch"], args.Q or wl["Q"], wl["budget"]
     qps = args.queries_per_step or (200 if batch == 1 else 100)
-    teams = args.teams_per_xcd or (8 if batch == 1 else 1)
+    teams = args.teams_per_xcd or (16 if batch == 1 else 1)
     table = S.sushi_describe_supernet(arch)
     int8 = args.dtype == "int8"
     es = 1 if int8 else 2                       # bytes per weight

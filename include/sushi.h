@@ -347,7 +347,7 @@ typedef enum {
                                    compute unit); only before the first query in mode 2 */
     SUSHI_OPT_TEAM_WGS_PER_CU = 5, /* workgroups of the team kernel per compute unit, 1 or 2 (default 2);
                                    only before the first query in mode 3 */
-    SUSHI_OPT_TEAMS_PER_XCD = 6, /* mode 3: teams the workgroups of one XCD are dealt to: 1 (default), 2, 4 or 8.
+    SUSHI_OPT_TEAMS_PER_XCD = 6, /* mode 3: teams the workgroups of one XCD are dealt to: 1 (default), 2, 4, 8 or 16.
                                    More, smaller teams serve more queries at a time, each more slowly:
                                    more queries per second, longer latency of a lone query.
                                    Only before the first query in mode 3 */

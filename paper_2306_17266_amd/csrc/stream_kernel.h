@@ -22,7 +22,7 @@ namespace sushi {
 constexpr int STREAM_THREADS = 512;  // 8 waves per workgroup
 constexpr int STREAM_WAVES = STREAM_THREADS / 64;
 constexpr int BARRIER_GROUP = 16;    // workgroups per first-level barrier group
-constexpr int SYNC_WORDS = 256 * 16;  // 64-bit words in the barrier area (128-byte spacing)
+constexpr int SYNC_WORDS = 512 * 16;  // 64-bit words in the barrier area (128-byte spacing)
 
 // A whole squeeze-excite block as one op of a team program (DEV_SE): average over the pixels, the two FC layers
 // (activation `act1` after the first, hard sigmoid after the second), and the map times the resulting gate.
@@ -86,7 +86,7 @@ struct StreamArgs {
 // pinned host memory; a team leader that finds no post for `idle_ticks` (or sees `stop`) makes its
 // team leave, so the kernel always ends by itself.
 constexpr int MAX_XCDS = 8;
-constexpr int MAX_TEAMS = 64;  // up to eight teams per XCD
+constexpr int MAX_TEAMS = 128;  // up to sixteen teams per XCD (two workgroups each; with one each the stream runs a third slower)
 enum TeamCmd { TEAM_RUN = 0, TEAM_STOP = 1 };
 
 // SubGraph residency inside the team kernel (the persistent buffer of the paper, Section 4.2.2, kept
@@ -169,7 +169,7 @@ struct TeamArgs {
     long arena_bytes;          // bytes per team arena
     unsigned long long last_seq[MAX_TEAMS];  // posts each team has already finished
     long idle_ticks;           // 100 MHz ticks a leader waits for a post before its team leaves
-    int teams_per_xcd;         // 1: the workgroups of an XCD form one team; 2, 4, 8: that many teams, each a share of them
+    int teams_per_xcd;         // 1: the workgroups of an XCD form one team; 2, 4, 8, 16: that many teams, each a share of them
     int spin_limit;
     char *team_mem;            // DEVICE, MAX_TEAMS areas of TEAM_MEM_BYTES: [program][residency table][slab words]
     unsigned long long *trace;  // DEVICE or null: [MAX_TEAMS][TRACE_SLOTS] 100 MHz timestamps, one after each op

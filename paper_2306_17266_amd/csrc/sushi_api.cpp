@@ -91,7 +91,7 @@ struct sushi_ctx {
     unsigned long long epoch_base = 0;
     int stream_wgs = 0, stream_wgs_override = 0;
     int team_wgs = 0, team_wgs_per_cu = 2;
-    int teams_per_xcd = 1;  // teams each XCD's workgroups are dealt to (1, 2, 4 or 8)
+    int teams_per_xcd = 1;  // teams each XCD's workgroups are dealt to (1, 2, 4, 8 or 16)
     int team_size() const { return team_wgs / (MAX_XCDS * teams_per_xcd); }  // workgroups of a team, if they spread evenly
     int spin_limit = 400000;
     void *static_buf = nullptr;  // this device's copy of the library's static scratch array (sushi_infer_static)
@@ -926,7 +926,8 @@ int ensure_team_state(sushi_ctx *c, int batch) {
         c->tbig_bytes = (long)round_up(p.max_big_elems * 2, 256);
         c->tsmall_bytes = (long)round_up(std::max<size_t>(p.max_small_elems, 8) * 4, 256);
         c->tarena_bytes = N_BIG_BUFS * c->tbig_bytes + N_SMALL_BUFS * c->tsmall_bytes;
-        if ((e = hipMalloc(reinterpret_cast<void **>(&c->d_tarena), (size_t)c->tarena_bytes * MAX_TEAMS)) != hipSuccess)
+        // (one arena per team that can exist: the number of teams per XCD is fixed before the first query)
+        if ((e = hipMalloc(reinterpret_cast<void **>(&c->d_tarena), (size_t)c->tarena_bytes * MAX_XCDS * c->teams_per_xcd)) != hipSuccess)
             return fail(c, SUSHI_ENOMEM, "hipMalloc(team arenas)");
         c->tarena_batch = batch;
         for (auto &kv : c->plans)
@@ -1772,7 +1773,7 @@ int sushi_set_option(sushi_ctx *c, int option, int64_t value) {
         c->team_wgs_per_cu = (int)value;
         return SUSHI_OK;
     }
-    if (option == SUSHI_OPT_TEAMS_PER_XCD && (value == 1 || value == 2 || value == 4 || value == 8) && value <= MAX_TEAMS / MAX_XCDS) {
+    if (option == SUSHI_OPT_TEAMS_PER_XCD && (value == 1 || value == 2 || value == 4 || value == 8 || value == 16) && value <= MAX_TEAMS / MAX_XCDS) {
         if (c->th) return fail(c, SUSHI_ESTATE, "set the number of teams before the first query");
         c->teams_per_xcd = (int)value;
         return SUSHI_OK;

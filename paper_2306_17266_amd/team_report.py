@@ -31,7 +31,7 @@ def main():
     from workloads import tensors as T
     ap = argparse.ArgumentParser()
     ap.add_argument("--workload", default="resnet_bs1_sticky")
-    ap.add_argument("--teams-per-xcd", type=int, default=8, choices=[1, 2, 4, 8])
+    ap.add_argument("--teams-per-xcd", type=int, default=8, choices=[1, 2, 4, 8, 16])
     ap.add_argument("--subnet", default="0", help="min, max, or an index into the workload's stream / pool")
     ap.add_argument("--rounds", type=int, default=6, help="queries per team")
     args = ap.parse_args()

@@ -63,7 +63,8 @@ def _drive(ctx, arch, cfgs, xs, n_classes, Q, budget, sgs):
     return [o.cpu().numpy() for o in outs], installs
 
 
-@pytest.mark.parametrize("workload,teams", [("resnet_bs1_sticky", 8), ("mbv3_bs1_zipf", 8),
+@pytest.mark.parametrize("workload,teams", [("resnet_bs1_sticky", 16), ("mbv3_bs1_zipf", 16),
+                                            ("resnet_bs1_sticky", 8), ("mbv3_bs1_zipf", 8),
                                             ("resnet_bs1_sticky", 1), ("mbv3_bs1_zipf", 1)])
 def test_full_size_stream_with_scheduler_driven_installs(workload, teams):
     wl = configs.build(workload)
@@ -123,12 +124,12 @@ def test_full_size_batch16_in_the_team_kernel(teams):
 
 def test_resolution_stream_with_cache_changes():
     """A sample of configuration 5: per-query resolutions 160 / 192 / 224, the cache re-chosen every 10
-    queries under the 4 MiB budget, eight teams per XCD."""
+    queries under the 4 MiB budget, sixteen teams per XCD (the benchmark's default at batch 1)."""
     wl = configs.build("mbv3_bs1_regimes")
     arch, seed, n_q = wl["arch"], 41, 60
     cfgs = wl["cfgs"][:n_q]
     assert {c.resolution for c in cfgs} == {160, 192, 224}
-    ctx, wts = _team_ctx(arch, seed, 8)
+    ctx, wts = _team_ctx(arch, seed, 16)
     xs_np = [T.make_input(seed, t, 1, c.resolution, 3, True) for t, c in enumerate(cfgs)]
     xs = [torch.from_numpy(x).cuda().to(torch.bfloat16).contiguous() for x in xs_np]
     torch.cuda.synchronize()

@@ -93,7 +93,7 @@ def _team_ctx(arch, seed, teams_per_xcd=1):
     return ctx, wts
 
 
-@pytest.mark.parametrize("fam,teams", [("tiny", 1), ("resnet", 1), ("mbv3", 1), ("resnet", 2), ("mbv3", 4), ("resnet", 8)])
+@pytest.mark.parametrize("fam,teams", [("tiny", 1), ("resnet", 1), ("mbv3", 1), ("resnet", 2), ("mbv3", 4), ("resnet", 8), ("resnet", 16), ("mbv3", 16)])
 def test_team_kernel_small_supernets(fam, teams):
     """Queries are posted without waiting (one in flight per team; 1, 2, 4 or 8 teams per XCD), then all
     logits are checked against the oracle; a second pass must reproduce them bit for bit."""
@@ -146,7 +146,7 @@ def test_team_kernel_squeeze_excite_blocks_at_every_batch_to_team_ratio(teams, b
     ctx.close()
 
 
-@pytest.mark.parametrize("fam,teams", [("resnet", 1), ("mbv3", 1), ("resnet", 4), ("mbv3", 2), ("resnet", 8), ("mbv3", 8)])
+@pytest.mark.parametrize("fam,teams", [("resnet", 1), ("mbv3", 1), ("resnet", 4), ("mbv3", 2), ("resnet", 8), ("mbv3", 8), ("resnet", 16)])
 def test_team_kernel_full_size_batch1(fam, teams):
     arch = A.resnet_arch() if fam == "resnet" else A.mbv3_arch()
     ctx, wts = _team_ctx(arch, 31, teams)
