@@ -231,7 +231,7 @@ def _check_team_op(op, team):
 
 
 @pytest.mark.parametrize("mk", [A.small_resnet_arch, A.small_mbv3_arch, A.resnet_arch, A.mbv3_arch])
-@pytest.mark.parametrize("team", [4, 8, 16, 32])
+@pytest.mark.parametrize("team", [2, 4, 8, 16, 32])
 def test_team_tilings_fit_the_kernels(mk, team):
     """Every op of sampled SubNets, at batch 1 and 16, gets a unit variant the kernels implement, unit
     counts that cover all tiles, and an LDS footprint (restated here from the kernels' layouts)
