@@ -219,7 +219,7 @@ typedef struct sushi_team_op {
     int32_t res, out_f32; /* the op adds a residual of the output's shape / stores float32 (gates, logits) */
 } sushi_team_op;
 
-/* The ops of SubNet cfg at the given batch size as a team of team_wgs workgroups (4 .. 32) would run them, in order.
+/* The ops of SubNet cfg at the given batch size as a team of team_wgs workgroups (2 .. 32) would run them, in order.
  * Host only: needs no device and no weights.  Writes min(n, cap) entries to out (HOST, may be NULL when cap = 0) and
  * the full count to *n_out.  SUSHI_EINVAL for an inconsistent arch or cfg, batch < 1 or team_wgs outside 1 .. 32;
  * SUSHI_ESTATE if a layer does not fit the team kernel. */

@@ -1497,20 +1497,26 @@ __device__ __forceinline__ void maxpool_units(const PoolArgs &a, int rank, int n
         const int qq = (int)(idx % a.Q), pp = (int)((idx / a.Q) % a.P);
         const long plane = idx / ((long)a.Q * a.P);
         const int cg = (int)(plane % cgs), n = (int)(plane / cgs);
-        float best[8];
+        // All nine cells are requested at once.  A row or column outside the image is replaced by the nearest one
+        // inside, which belongs to the same window (the window's centre lies inside): the maximum does not change.
+        uint4 cell[9];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) best[j] = -3.4028235e38f;
         for (int r = 0; r < 3; ++r) {
-            const int h = pp * 2 - 1 + r;
-            if (h < 0 || h >= a.H) continue;
-            for (int s = 0; s < 3; ++s) {
-                const int v = qq * 2 - 1 + s;
-                if (v < 0 || v >= a.W) continue;
-                float xv[8];
-                unpack8(act_ld16<LD>(rx, (((n * cgs + cg) * a.H + h) * a.W + v) * 16), xv);
+            const int h = min(max(pp * 2 - 1 + r, 0), a.H - 1);
 #pragma unroll
-                for (int j = 0; j < 8; ++j) best[j] = fmaxf(best[j], xv[j]);
+            for (int s = 0; s < 3; ++s) {
+                const int v = min(max(qq * 2 - 1 + s, 0), a.W - 1);
+                cell[r * 3 + s] = act_ld16<LD>(rx, (((n * cgs + cg) * a.H + h) * a.W + v) * 16);
             }
+        }
+        float best[8];
+        unpack8(cell[0], best);
+#pragma unroll
+        for (int t = 1; t < 9; ++t) {
+            float xv[8];
+            unpack8(cell[t], xv);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) best[j] = fmaxf(best[j], xv[j]);
         }
         act_st16<ST>(ry, (((n * cgs + cg) * a.P + pp) * a.Q + qq) * 16, pack8(best));
     }
