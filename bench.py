@@ -83,6 +83,7 @@ def main():
                          "whose caches are lost between queries)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="run one 256 MiB device-to-device copy first (reference dispatch for byte counters)")
+    ap.add_argument("--table-out", default="", help="directory that receives a latency table measured in this run (to freeze it)")
     ap.add_argument("--measure-table", action="store_true",
                     help="latency-target stream: measure the latency table in this run even if a frozen one is shipped")
     ap.add_argument("--table-runs", type=int, default=3, help="runs per table entry when it is measured")
@@ -168,9 +169,8 @@ def main():
         else:
             lat = sushiabs.measure_table(ctx, pool, cands, budget, xs[res_list[0]][0], outs[0], runs=args.table_runs)
             table_info = "measured in this run (median of %d runs per entry)" % args.table_runs
-            out_dir = os.path.join(ROOT, "gpurun_out")
-            if os.path.isdir(out_dir):
-                sushiabs.save_table(os.path.join(out_dir, os.path.basename(tpath)), lat, args.workload, budget, args.table_runs,
+            if args.table_out and os.path.isdir(args.table_out):
+                sushiabs.save_table(os.path.join(args.table_out, os.path.basename(tpath)), lat, args.workload, budget, args.table_runs,
                                     "exec mode %d, %d teams per XCD, batch %d" % (mode, teams, batch))
         levels = sushiabs.latency_levels(lat, wl["n_levels"])
         ctx.sushi_sched_init([vec_of[c.key()] for c in pool], acc, gvecs, lat, Q, S.STRICT_LATENCY)
