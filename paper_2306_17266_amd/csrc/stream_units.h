@@ -1522,50 +1522,59 @@ __device__ __forceinline__ void maxpool_units(const PoolArgs &a, int rank, int n
     }
 }
 
-// Global average: a workgroup takes (image, block of 8 channel groups); 64 pixel lanes x 8 channel
-// groups accumulate and a fixed binary tree in LDS combines them.
+// Global average: a workgroup takes (image, block of channel groups).  The threads are pixel lanes x channel groups
+// (8 lanes per group when the groups fill the threads, up to 64 for few groups); a lane requests eight of its
+// pixels at a time, the lanes' sums meet in LDS and one thread per channel group adds them up in a fixed order.
 template <int LD, int ST>
 __device__ __forceinline__ void gap_units(const PoolArgs &a, float *lds, int rank, int nranks) {
-    float(*part)[8][9] = reinterpret_cast<float(*)[8][9]>(lds);  // [64][8][9]
-    const int cgs = a.C >> 3;
-    const int blocks_per_image = (cgs + 7) >> 3;
-    const int n_blocks = a.B * blocks_per_image;
-    const int cgi = threadIdx.x & 7, pl = threadIdx.x >> 3;
-    const int hw = a.H * a.W;
+    const int t = threadIdx.x;
+    const int cgs = a.C >> 3, hw = a.H * a.W;
+    const int PLN = cgs > 32 ? 8 : cgs > 16 ? 16 : cgs > 8 ? 32 : 64, CGP = STREAM_THREADS / PLN, cstride = PLN * 8 + 8;
+    const int passes = (cgs + CGP - 1) / CGP, n_blocks = a.B * passes;
+    const int pl = t % PLN, cgl = t / PLN;
     const __amdgpu_buffer_rsrc_t rx = make_rsrc(a.x, (long)a.B * hw * a.C * 2);
     const __amdgpu_buffer_rsrc_t ry = make_rsrc(a.y, (long)a.B * a.C * (a.out_f32 ? 4 : 2));
+    const float inv = 1.0f / (float)hw;
     for (int b = rank; b < n_blocks; b += nranks) {
-        const int n = b / blocks_per_image;
-        const int cg = (b - n * blocks_per_image) * 8 + cgi;
+        const int n = b / passes, cg0 = (b - n * passes) * CGP, cg = cg0 + cgl;
         float acc[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) acc[j] = 0.f;
-        if (cg < cgs)
-            for (int p = pl; p < hw; p += 64) {
+        const int base = (n * cgs + cg) * hw;
+        for (int p0 = pl; p0 < hw; p0 += 8 * PLN) {
+            uint4 v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int p = p0 + u * PLN;
+                v[u] = act_ld16<LD>(rx, cg < cgs && p < hw ? (base + p) * 16 : (int)OOB_OFFSET);  // (else zeros)
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
                 float xv[8];
-                unpack8(act_ld16<LD>(rx, ((n * cgs + cg) * hw + p) * 16), xv);
+                unpack8(v[u], xv);
 #pragma unroll
                 for (int j = 0; j < 8; ++j) acc[j] += xv[j];
             }
-#pragma unroll
-        for (int j = 0; j < 8; ++j) part[pl][cgi][j] = acc[j];
-        __syncthreads();
-        for (int s = 32; s > 0; s >>= 1) {
-            if (pl < s)
-#pragma unroll
-                for (int j = 0; j < 8; ++j) part[pl][cgi][j] += part[pl + s][cgi][j];
-            __syncthreads();
         }
-        if (pl == 0 && cg < cgs) {
-            float o[8];
-            const float inv = 1.0f / (float)hw;
-#pragma unroll
-            for (int j = 0; j < 8; ++j) o[j] = part[0][cgi][j] * inv;
+        float4 *dst = reinterpret_cast<float4 *>(lds + cgl * cstride + pl * 8);
+        dst[0] = make_float4(acc[0], acc[1], acc[2], acc[3]);
+        dst[1] = make_float4(acc[4], acc[5], acc[6], acc[7]);
+        __syncthreads();
+        if (t < CGP && cg0 + t < cgs) {
+            const float4 *src = reinterpret_cast<const float4 *>(lds + t * cstride);
+            float4 lo = make_float4(0.f, 0.f, 0.f, 0.f), hi = lo;
+            for (int q = 0; q < PLN; ++q) {
+                const float4 x0 = src[q * 2], x1 = src[q * 2 + 1];
+                lo.x += x0.x, lo.y += x0.y, lo.z += x0.z, lo.w += x0.w;
+                hi.x += x1.x, hi.y += x1.y, hi.z += x1.z, hi.w += x1.w;
+            }
+            float o[8] = {lo.x * inv, lo.y * inv, lo.z * inv, lo.w * inv, hi.x * inv, hi.y * inv, hi.z * inv, hi.w * inv};
+            const int c = (cg0 + t) * 8;
             if (a.out_f32) {  // (per-image vectors stay float32: the layers they feed split them into two bf16 terms)
-                act_st16<ST>(ry, (n * a.C + cg * 8) * 4, make_uint4(__float_as_uint(o[0]), __float_as_uint(o[1]), __float_as_uint(o[2]), __float_as_uint(o[3])));
-                act_st16<ST>(ry, (n * a.C + cg * 8) * 4 + 16, make_uint4(__float_as_uint(o[4]), __float_as_uint(o[5]), __float_as_uint(o[6]), __float_as_uint(o[7])));
+                act_st16<ST>(ry, (n * a.C + c) * 4, make_uint4(__float_as_uint(o[0]), __float_as_uint(o[1]), __float_as_uint(o[2]), __float_as_uint(o[3])));
+                act_st16<ST>(ry, (n * a.C + c) * 4 + 16, make_uint4(__float_as_uint(o[4]), __float_as_uint(o[5]), __float_as_uint(o[6]), __float_as_uint(o[7])));
             } else {
-                act_st16<ST>(ry, (n * a.C + cg * 8) * 2, pack8(o));
+                act_st16<ST>(ry, (n * a.C + c) * 2, pack8(o));
             }
         }
         __syncthreads();
