@@ -202,6 +202,31 @@ int sushi_subnet_layers(const sushi_arch *arch, const sushi_subnet_cfg *cfg, sus
 int sushi_subgraph_overlap(const sushi_layer_dims *subnet, const sushi_layer_dims *subgraph, int n, int bytes_per_weight,
                            uint64_t *subnet_bytes, uint64_t *common_bytes, double *hit_ratio);
 
+/* Where one weight-bearing layer sits in the packed image of the SuperNet's weights (sushi_pack_supernet). */
+typedef struct sushi_packed_layer {
+    uint64_t offset;      /* element offset of the layer's packed weights */
+    int32_t depthwise;    /* 1: [tap in ring order][filter < Kpad]; 0: [tap][channel group < CG][filter < Kpad][8 channels] */
+    int32_t K, C, R;      /* the SuperNet layer: filters, input channels (1 for depthwise), taps per side */
+    int32_t Kpad, CG;     /* filters padded to a multiple of 16; channel groups of 8 (0 for depthwise) */
+} sushi_packed_layer;
+
+/* The weight packer on its own (Section 2.1: a SubNet is a slice of the SuperNet's weights; the packed layout makes
+ * every slice a set of contiguous prefixes).  Host only.  Produces the image that sushi_load_supernet copies to the
+ * device for compute_dtype SUSHI_BF16 (uint16 bit patterns, values rounded to nearest even) or SUSHI_FP32 (float32):
+ *   dense / FC layer  element ((tap * CG + c / 8) * Kpad + k) * 8 + c % 8 holds W[k][c][tap]: for every tap and channel
+ *                     group below C' / 8 the slice (K', C') is the run of the first K' * 8 elements
+ *   depthwise layer   element t * Kpad + k holds W[k][tap t], the taps in ring order: the 9 taps of the centre 3 x 3,
+ *                     then the 16 of the 5 x 5 ring, then the 24 of the 7 x 7 ring, so that a centred r x r crop is the
+ *                     first r * r taps
+ * Elements the SuperNet does not define (filters K .. Kpad - 1, channels beyond C in the last group, gaps between
+ * layers) are zero.  weights / nbytes: as for sushi_load_supernet.  packed: HOST buffer of cap_bytes bytes, may be NULL
+ * with cap_bytes = 0; *n_bytes receives the image's size.  layers: HOST array of cap_layers entries (may be NULL with
+ * cap_layers = 0), one per weight-bearing layer in the order of sushi_subnet_layers; *n_layers receives their number.
+ * SUSHI_EINVAL for an inconsistent arch, a blob of the wrong size, an unknown dtype or a packed buffer that is too
+ * small (sizes are still reported). */
+int sushi_pack_supernet(const sushi_arch *arch, const void *weights, size_t nbytes, int compute_dtype, void *packed,
+                        size_t cap_bytes, size_t *n_bytes, sushi_packed_layer *layers, int cap_layers, int *n_layers);
+
 /* How exec mode 3 cuts one op of a SubNet's per-query plan (Section 3.1: a query activates one SubNet; Section 4.2:
  * its layers run one after the other) into units for a team of workgroups.  kind: 0 dense conv, 1 depthwise conv,
  * 2 max-pool, 3 global average pool, 4 fully connected, 5 channel gate; 6 a whole squeeze-excite block (pooling, two

@@ -62,6 +62,10 @@ class CTeamOp(C.Structure):
                                           "ft", "pt", "wk", "n_units", "n_p", "lds_bytes", "res", "out_f32")]
 
 
+class CPackedLayer(C.Structure):
+    _fields_ = [("offset", C.c_uint64)] + [(n, C.c_int32) for n in ("depthwise", "K", "C", "R", "Kpad", "CG")]
+
+
 class CSubgraphCfg(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("layers", C.POINTER(CLayerDims))]
 
@@ -109,6 +113,8 @@ def lib():
     L.sushi_describe_supernet.argtypes = [C.POINTER(CArch), C.POINTER(CTensorDesc), C.c_int, ip]
     L.sushi_subnet_layers.argtypes = [C.POINTER(CArch), C.POINTER(CSubnetCfg), C.POINTER(CLayerDims), C.c_int, ip]
     L.sushi_team_plan.argtypes = [C.POINTER(CArch), C.POINTER(CSubnetCfg), C.c_int, C.c_int, C.POINTER(CTeamOp), C.c_int, ip]
+    L.sushi_pack_supernet.argtypes = [C.POINTER(CArch), vp, C.c_size_t, C.c_int, vp, C.c_size_t, C.POINTER(C.c_size_t),
+                                      C.POINTER(CPackedLayer), C.c_int, ip]
     L.sushi_subgraph_overlap.argtypes = [C.POINTER(CLayerDims), C.POINTER(CLayerDims), C.c_int, C.c_int,
                                          C.POINTER(C.c_uint64), C.POINTER(C.c_uint64), C.POINTER(C.c_double)]
     L.sushi_create.argtypes = [C.POINTER(vp), C.c_int, vp]
@@ -195,6 +201,20 @@ def sushi_subnet_layers(arch, cfg):
     buf = (CLayerDims * 256)()
     _check(lib().sushi_subnet_layers(C.byref(a), C.byref(s), buf, 256, C.byref(n)))
     return [(buf[i].K, buf[i].C, buf[i].r) for i in range(n.value)]
+
+
+def sushi_pack_supernet(arch, weights, compute_dtype):
+    """(packed image as a numpy array of uint16 (BF16) or float32 (FP32), [dict per weight-bearing layer]) - host only."""
+    a = c_arch(arch)
+    w = np.ascontiguousarray(weights, dtype=np.float32)
+    nb, nl = C.c_size_t(0), C.c_int(0)
+    _check(lib().sushi_pack_supernet(C.byref(a), w.ctypes.data_as(C.c_void_p), w.nbytes, int(compute_dtype), None, 0,
+                                     C.byref(nb), None, 0, C.byref(nl)))
+    out = np.zeros(nb.value // (2 if compute_dtype == BF16 else 4), dtype=np.uint16 if compute_dtype == BF16 else np.float32)
+    layers = (CPackedLayer * nl.value)()
+    _check(lib().sushi_pack_supernet(C.byref(a), w.ctypes.data_as(C.c_void_p), w.nbytes, int(compute_dtype),
+                                     out.ctypes.data_as(C.c_void_p), out.nbytes, C.byref(nb), layers, nl.value, C.byref(nl)))
+    return out, [{f: getattr(layers[i], f) for f, _ in CPackedLayer._fields_} for i in range(nl.value)]
 
 
 def sushi_team_plan(arch, cfg, batch, team_wgs):

@@ -1220,6 +1220,42 @@ int sushi_subgraph_overlap(const sushi_layer_dims *sn, const sushi_layer_dims *g
     return SUSHI_OK;
 }
 
+int sushi_pack_supernet(const sushi_arch *arch, const void *weights, size_t nbytes, int dtype, void *packed,
+                        size_t cap_bytes, size_t *n_bytes, sushi_packed_layer *layers, int cap_layers, int *n_layers) {
+    if (!arch || !weights || !n_bytes || !n_layers || (cap_bytes > 0 && !packed) || cap_layers < 0 ||
+        (cap_layers > 0 && !layers) || (dtype != SUSHI_FP32 && dtype != SUSHI_BF16))
+        return SUSHI_EINVAL;
+    SuperNet sn;
+    std::string err;
+    int rc = build_supernet(*arch, sn, err);
+    if (rc) return rc;
+    if (nbytes != sn.blob_floats * sizeof(float)) return SUSHI_EINVAL;
+    const float *blob = static_cast<const float *>(weights);
+    std::vector<float> params;
+    std::vector<uint16_t> w16;
+    std::vector<float> w32;
+    const void *src = nullptr;
+    try {
+        if (dtype == SUSHI_BF16) {
+            pack_weights<uint16_t>(sn, blob, w16, params, to_bf16);
+            *n_bytes = w16.size() * 2, src = w16.data();
+        } else {
+            pack_weights<float>(sn, blob, w32, params, [](float f) { return f; });
+            *n_bytes = w32.size() * 4, src = w32.data();
+        }
+    } catch (const std::bad_alloc &) {
+        return SUSHI_ENOMEM;
+    }
+    *n_layers = (int)sn.layers.size();
+    for (int i = 0; i < *n_layers && i < cap_layers; ++i) {
+        const SuperLayer &L = sn.layers[i];
+        layers[i] = sushi_packed_layer{(uint64_t)L.pk_w, L.type == L_DW ? 1 : 0, L.Kmax, L.Cmax, L.Rmax, L.Kpad, L.CG};
+    }
+    if (cap_bytes < *n_bytes) return packed || cap_bytes ? SUSHI_EINVAL : SUSHI_OK;
+    std::memcpy(packed, src, *n_bytes);
+    return SUSHI_OK;
+}
+
 int sushi_team_plan(const sushi_arch *arch, const sushi_subnet_cfg *cfg, int batch, int team_wgs, sushi_team_op *out,
                     int cap, int *n_out) {
     if (!arch || !cfg || !n_out || cap < 0 || (cap > 0 && !out) || batch < 1 || team_wgs < 1 || team_wgs > 32)

@@ -14,6 +14,7 @@ from oracle.sched_ref import STRICT_ACCURACY, STRICT_LATENCY, SchedRef
 from paper_2306_17266_amd import binding
 from workloads import arch as A
 from workloads import streams
+from workloads import tensors as T
 from workloads.rng import Stream
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
@@ -321,3 +322,72 @@ def test_subgraph_overlap_matches_the_oracle(mk):
             want = E.hit_ratio(E.encode_vector(arch, cfg), [v for (k, c, r) in g for v in (k if k else 0, c if k else 0)])
             assert abs(hit - want) < 1e-12
     assert S.sushi_subgraph_overlap(boxes[0], boxes[1], 2)[2] == 1.0      # G ⊇ SN
+
+
+# ---------------------------------------------------------------- weight packer (host side of sushi_load_supernet)
+
+def _bf16_bits(a):
+    """float32 -> bf16 bit patterns, round to nearest even (written here, not taken from the generators)."""
+    b = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    return (((b + 0x7FFF + ((b >> 16) & 1)) >> 16) & 0xFFFF).astype(np.uint16)
+
+
+@pytest.mark.parametrize("mk", [A.tiny_arch, A.small_resnet_arch, A.small_mbv3_arch])
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+def test_packer_round_trip_and_slices_are_prefixes(mk, dtype):
+    """Unpacking the packed image by the layout the header states gives back every weight bit for bit (bf16: rounded
+    to nearest even); everything else in the image is zero; a SubNet's slice (K', C') of a dense layer is, per tap and
+    channel group, the first K' * 8 elements of that group's run; a centred r x r crop of a depthwise layer is its
+    first r * r taps."""
+    arch = mk()
+    table = S.sushi_describe_supernet(arch)
+    tensors = T.make_weights([(s, k) for _, s, k in table], 77, False)       # (not pre-rounded: the packer rounds)
+    img, layers = S.sushi_pack_supernet(arch, T.flatten(tensors), S.BF16 if dtype == "bf16" else S.FP32)
+    conv = lambda a: _bf16_bits(a) if dtype == "bf16" else np.ascontiguousarray(a, dtype=np.float32)
+    wts = [(n, t) for (n, _, k), t in zip(table, tensors) if k in (T.KIND_CONV, T.KIND_DWCONV, T.KIND_FC)]
+    assert len(wts) == len(layers)
+    covered = np.zeros(img.size, dtype=bool)
+    st = Stream(5)
+    for (name, w), L in zip(wts, layers):
+        K, Cc, R, Kpad, CG, off = L["K"], L["C"], L["R"], L["Kpad"], L["CG"], L["offset"]
+        assert Kpad % 16 == 0 and Kpad >= K and Kpad - K < 16, name
+        w4 = w.reshape(K, Cc, R, R) if w.ndim != 2 else w.reshape(K, Cc, 1, 1)
+        want = conv(w4)
+        if L["depthwise"]:
+            assert Cc == 1 and CG == 0, name
+            block = img[off:off + R * R * Kpad].reshape(R * R, Kpad)
+            covered[off:off + R * R * Kpad] = True
+            assert not block[:, K:].any(), name
+            for r in (3, 5, 7):
+                if r > R:
+                    break
+                o = (R - r) // 2
+                crop = want[:, 0, o:o + r, o:o + r].reshape(K, r * r)
+                got = block[:r * r, :K].T                                 # [filter][first r*r taps]
+                # the same values, tap for tap, in whatever order the ring layout lists them
+                np.testing.assert_array_equal(np.sort(got, axis=1), np.sort(crop, axis=1), err_msg="%s crop %d" % (name, r))
+            # and the full kernel tap by tap: every packed tap row is one (dr, ds) plane of the tensor, each used once
+            planes = {want[:, 0, r, s].tobytes(): (r, s) for r in range(R) for s in range(R)}
+            seen = {planes[block[t, :K].tobytes()] for t in range(R * R)}
+            assert len(planes) == R * R and len(seen) == R * R, name
+        else:
+            assert CG == _ceil(Cc, 8), name
+            n = R * R * CG * Kpad * 8
+            block = img[off:off + n].reshape(R * R, CG, Kpad, 8)
+            covered[off:off + n] = True
+            full = np.zeros((R * R, CG * 8, Kpad), dtype=img.dtype)          # [tap][channel][filter]
+            full[:, :Cc, :K] = want.reshape(K, Cc, R * R).transpose(2, 1, 0)
+            np.testing.assert_array_equal(block, full.reshape(R * R, CG, 8, Kpad).transpose(0, 1, 3, 2), err_msg=name)
+            # a slice as the kernels address it: per (tap, group) one run of K' * 8 elements from the group's start
+            for _ in range(3):
+                k1 = 1 + st.randint(K)
+                c1 = 8 * (1 + st.randint(max(1, Cc // 8))) if Cc >= 8 else Cc
+                c1 = min(c1, Cc)
+                flat = img[off:off + n]
+                for tap in range(R * R):
+                    for g in range(_ceil(c1, 8)):
+                        start = ((tap * CG + g) * Kpad) * 8
+                        run = flat[start:start + k1 * 8].reshape(k1, 8)
+                        ch = min(8, Cc - g * 8)
+                        np.testing.assert_array_equal(run[:, :ch], want.reshape(K, Cc, R * R)[:k1, g * 8:g * 8 + ch, tap])
+    assert not img[~covered].any()                                          # gaps between layers
