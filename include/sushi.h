@@ -333,7 +333,7 @@ int sushi_quiesce(sushi_ctx *ctx);
 
 /* Team-kernel diagnostics.  enable = 1: from the next start of the team kernel, each team leader
  * stamps a 100 MHz clock before the first op of a query and after the barrier of every op
- * (slot 0, then slot i+1 for op i; 256 slots per team, 64 teams).  Each call first waits for all
+ * (slot 0, then slot i+1 for op i; 256 slots per team, 128 teams: team = XCD * teams per XCD + its number there).  Each call first waits for all
  * queries, stops the team kernel and, if out is not null, copies up to cap stamps to out (HOST). */
 int sushi_team_trace(sushi_ctx *ctx, int enable, uint64_t *out, int cap);
 
@@ -357,9 +357,9 @@ typedef enum {
                                    2 = stream kernel: one launch per query, layers separated by grid
                                    barriers (bf16 mode only; a barrier wait that runs out is reported
                                    by the next sushi_infer as SUSHI_EDEVICE),
-                                   3 = team kernel: a persistent kernel whose workgroups form one team per
-                                   XCD; each team serves one query at a time inside its XCD, so up to
-                                   eight queries are in flight.  bf16 mode only.  sushi_infer then waits
+                                   3 = team kernel: a persistent kernel whose workgroups form 1 to 16 teams per
+                                   XCD (SUSHI_OPT_TEAMS_PER_XCD); each team serves one query at a time inside
+                                   its XCD, so 8 to 128 queries are in flight.  bf16 mode only.  sushi_infer then waits
                                    for the context's stream (the input must be complete), posts the
                                    query to a team and returns; the logits are valid after
                                    sushi_synchronize.  The kernel runs on a private stream and leaves by

@@ -367,9 +367,9 @@ class Sushi:
         _check(lib().sushi_quiesce(self._h), self._h)
 
     def sushi_team_trace(self, enable):
-        buf = (C.c_uint64 * (64 * 256))()
-        _check(lib().sushi_team_trace(self._h, int(enable), buf, 64 * 256), self._h)
-        return np.array(buf[:], dtype=np.uint64).reshape(64, 256)
+        buf = (C.c_uint64 * (128 * 256))()
+        _check(lib().sushi_team_trace(self._h, int(enable), buf, 128 * 256), self._h)
+        return np.array(buf[:], dtype=np.uint64).reshape(128, 256)
 
     def sushi_sched_init(self, subnet_vecs, accuracy, subgraph_vecs, table, Q, policy, initial_cache=-1):
         sv = np.ascontiguousarray(subnet_vecs, dtype=np.int32)

@@ -79,10 +79,10 @@ struct StreamArgs {
 };
 
 // ---------------------------------------------------------------------------------------------
-// The team kernel: a persistent kernel in which the workgroups running on one XCD form a team.
+// The team kernel: a persistent kernel in which the workgroups running on one XCD form one to sixteen teams.
 // A team serves one query at a time, entirely inside its XCD: activations go through that XCD's L2
-// (ordinary stores; loads that skip the vector L1, which is emptied once per query), layers are separated by a team barrier (32 arrivals instead of 256),
-// and up to eight queries are in flight on the chip.  Queries arrive through per-team mailboxes in
+// (ordinary stores; loads that skip the vector L1, which is emptied once per query), layers are separated by a
+// team barrier (2 to 32 arrivals instead of 256), and 8 to 128 queries are in flight on the chip.  Queries arrive through per-team mailboxes in
 // pinned host memory; a team leader that finds no post for `idle_ticks` (or sees `stop`) makes its
 // team leave, so the kernel always ends by itself.
 constexpr int MAX_XCDS = 8;
